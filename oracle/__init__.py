@@ -1,0 +1,16 @@
+"""CPU oracle for the ternary 3D convolution (test infrastructure, not the product).
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this package.
+"""
+from .tern_oracle import (  # noqa: F401
+    ConvGeom,
+    conv3d,
+    conv3d_points,
+    fcn_forward,
+    max_threads,
+    out_dims,
+    pack,
+    set_threads,
+    threshold,
+    unpack,
+)
