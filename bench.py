@@ -1,0 +1,142 @@
+#!/usr/bin/env python3
+"""Benchmark of the ternary 3D convolution on one MI355X.
+
+One step = one call of the fused ternary convolution (halo staging, masked-Hamming contraction,
+threshold + re-pack epilogue) on BASELINE config[1]: batch 1, C_in = C_out = 64, 64^3 volume, 3^3
+kernel, stride 1, pad 1, seeded synthetic ternary data already resident in HBM and already packed
+(as it is between layers of a network).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Roofline constants: 256 compute units x 64 32-bit integer lanes per clock x 2.4 GHz.
+PEAK_LANE_OPS = 256 * 64 * 2.4e9          # 39.32e12 lane-ops/s
+OPS_PER_MAC = 5.0 / 32.0                  # and, xor, and, 2 x popcount-accumulate per 32 MACs
+HBM_PEAK = 8.0e12
+
+
+def timed(fn, steps, warmup, stream_sync):
+    """Average milliseconds per call by events on the current stream, plus wall time."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        fn()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return ev0.elapsed_time(ev1) / steps, wall
+
+
+def cpu_baseline(case, target_seconds=12.0):
+    """The oracle, as it stands, timed on the host cores on a z-slab of the same workload sized
+    to about target_seconds."""
+    import numpy as np
+    import oracle
+    from oracle import ConvGeom
+    g = ConvGeom(case.k, case.stride, case.pad, case.dil)
+    d = case.act.shape[2]
+    probe = min(d, 4)
+    sub = np.ascontiguousarray(case.act[:, :, :probe])
+    t0 = time.perf_counter()
+    oracle.conv3d(sub, case.wgt, g)
+    dt = time.perf_counter() - t0
+    per_plane = dt / probe
+    planes = int(max(probe, min(d, target_seconds / max(per_plane, 1e-9))))
+    sub = np.ascontiguousarray(case.act[:, :, :planes])
+    t0 = time.perf_counter()
+    acc = oracle.conv3d(sub, case.wgt, g)
+    dt = time.perf_counter() - t0
+    macs = acc.size * case.act.shape[1] * case.k[0] * case.k[1] * case.k[2]
+    return {
+        "value": macs / dt / 1e12, "unit": "TMAC/s", "cores": oracle.max_threads(), "kind": "oracle",
+        "sample": f"z-slab of {planes} of {d} input planes of config[1] (same channels and kernel), "
+                  f"1 repetition, {dt:.2f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true", help="also time the other entry points")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is "
+              "described in DESIGN.md but not built.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1801_09449_amd as T
+    import synth
+
+    T.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    case = synth.config1()
+    c_in, c_out = case.act.shape[1], case.wgt.shape[0]
+    act_i8 = dev(case.act)
+    act = T.tern_pack(act_i8)
+    bank = T.tern_pack_filters(dev(case.wgt))
+    lo, hi = dev(case.lo), dev(case.hi)
+    out_packed = torch.empty_like(act)
+    out_acc = torch.empty((1, c_out) + case.out_spatial, dtype=torch.int32, device="cuda")
+    geom = dict(k=case.k, stride=case.stride, pad=case.pad, dil=case.dil)
+
+    def step():
+        T.tern_conv3d(act, c_in, bank, c_out, thr_lo=lo, thr_hi=hi, out=out_packed, **geom)
+
+    ms, wall_ms = timed(step, args.steps, args.warmup, None)
+    macs = case.macs
+    tmacs = macs / (ms * 1e-3) / 1e12
+    lane_ops = OPS_PER_MAC * macs / (ms * 1e-3)
+
+    result = {
+        "metric": "ternary MAC/s (TMAC/s) + ms per volume; % of int/popcount peak",
+        "value": tmacs, "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+        "config": {"workload": "config[1]: fused ternary conv3d, N=1, C_in=C_out=64, 64^3, k=3^3, "
+                               "s=1, p=1, packed in -> packed out", "gmac": macs / 1e9,
+                   "wall_ms_per_step": wall_ms},
+        "roofline": {"bound": "alu", "achieved": lane_ops / 1e12, "peak": PEAK_LANE_OPS / 1e12,
+                     "unit": "T lane-op/s (algorithmic: 5 int32 VALU lane-ops per 32 MACs)",
+                     "frac": lane_ops / PEAK_LANE_OPS, "traffic": None},
+    }
+
+    if args.extras:
+        ex = {}
+        ms_acc, _ = timed(lambda: T.tern_conv3d(act, c_in, bank, c_out, out=out_acc, **geom), 50, 5, None)
+        ex["conv3d_int32_out_ms"] = ms_acc
+        ms_pack, _ = timed(lambda: T.tern_pack(act_i8, out=act), 50, 5, None)
+        ex["pack_i8_ms"] = ms_pack
+        ex["pack_i8_GBps"] = (act_i8.numel() + act.numel() * 4) / (ms_pack * 1e-3) / 1e9
+        ms_thr, _ = timed(lambda: T.tern_threshold_pack(out_acc, lo, hi, out=out_packed), 50, 5, None)
+        ex["threshold_pack_i32_ms"] = ms_thr
+        ex["threshold_pack_i32_GBps"] = (out_acc.numel() * 4 + out_packed.numel() * 4) / (ms_thr * 1e-3) / 1e9
+        result["extras"] = ex
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(case)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,182 @@
+/*
+ * tern.h -- C ABI of the MI355X (gfx950) ternary 3D convolution library.
+ *
+ * The library implements the inference hot path of TernaryNet (Heinrich, Blendowski, Oktay,
+ * "TernaryNet: Faster Deep Model Inference without GPUs for Medical 3D Segmentation using Sparse
+ * and Binary Convolutions", arXiv 1801.09449): a convolution whose weights and activations are
+ * both restricted to {-1, 0, +1}, evaluated as a masked Hamming distance on bit-planes (section 2,
+ * Eq. 9), followed by the hard ternary activation (Eq. 6) and re-packing to 2 bits per value
+ * (Fig. 3) so that modules can be chained (section 2, last paragraph).
+ *
+ * General rules
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless a comment says "host".
+ *     The library never allocates, frees or retains caller memory and keeps no state between
+ *     calls except the last HIP error code (tern_last_hip_error).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     on that stream and return without synchronising.
+ *   - Return value: TERN_OK (0) or a negative tern_status.  No call throws or aborts.  Arguments
+ *     are validated on the host before anything is launched; a failing call launches nothing.
+ *   - Tensors with zero elements are rejected with TERN_ESHAPE.
+ *
+ * Unpacked tensors are contiguous NCDHW (W fastest).
+ *
+ * Packed ternary tensors ("bit-planes packed along channels", Fig. 3 / section 2):
+ *     uint32 [N][D][H][W][2][Wd],   Wd = tern_words(C) = ceil(C/32)
+ *   plane 0 = nonzero mask, plane 1 = sign.  Bit j of word q describes channel 32q + j:
+ *     value +1 -> mask 1, sign 0;   value -1 -> mask 1, sign 1;   value 0 -> mask 0, sign 0.
+ *   Bits of channels >= C are 0 in both planes.  Producers in this library always emit this
+ *   canonical form; consumers ignore sign bits under a clear mask bit.
+ *   (The figure draws the complementary convention -- first bit set for +1, second bit a zero
+ *   flag; the convolution result does not depend on the choice.)
+ *   Packed buffers must be 16-byte aligned (any hipMalloc / torch allocation is).
+ *
+ * Filter banks (the ternary weights of one layer, "2 bits per weight", section 2) hold the same
+ * two bit-planes but ordered for the convolution kernels, which fetch filter words through the
+ * scalar cache one kernel tap at a time:
+ *     uint32 [T * nchunk][co_pad][2][wc]
+ *   T = kd*kh*kw taps in (a, b, c) order; Wd = ceil(C_in/32); wc = 2 if Wd is even, else 1;
+ *   nchunk = Wd / wc; co_pad = C_out rounded up to a multiple of 32.  Entry [tap*nchunk + ch]
+ *   [co][p][q] is plane p (0 mask, 1 sign) of input-channel word ch*wc + q of filter co at that
+ *   tap; channels co >= C_out are all-zero.  Built by tern_pack_filters.
+ */
+#ifndef TERN_H
+#define TERN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TERN_OK = 0,
+    TERN_ENULL = -1,        /* a required pointer is NULL                                   */
+    TERN_ESHAPE = -2,       /* non-positive extent, empty output, or sizes beyond the limits */
+    TERN_EARG = -3,         /* invalid combination of arguments                              */
+    TERN_EWORKSPACE = -4,   /* workspace too small or misaligned                             */
+    TERN_EHIP = -5          /* a HIP call failed; see tern_last_hip_error()                  */
+} tern_status;
+
+typedef struct { int32_t n, c, d, h, w; } tern_dims;          /* logical NCDHW extents */
+
+/* Kernel extent, stride, zero padding (both sides) and dilation per axis, order (d, h, w).
+ * Output extent per axis: floor((X + 2*pad - dil*(k-1) - 1)/stride) + 1; TERN_ESHAPE if < 1.
+ * Limits: k >= 1, stride >= 1, dil >= 1, pad >= 0; k[0]*k[1]*k[2]*C_in < 2^24. */
+typedef struct { int32_t k[3], stride[3], pad[3], dil[3]; } tern_conv_geom;
+
+typedef enum { TERN_SRC_I8 = 0, TERN_SRC_I32 = 1, TERN_SRC_F32 = 2 } tern_src_type;
+
+/* ceil(c/32): 32-bit words per plane per voxel. */
+int32_t tern_words(int32_t c);
+/* Bytes of a packed tensor with these logical dims (0 if dims are invalid). */
+size_t tern_packed_bytes(tern_dims dims);
+/* Bytes of the filter bank of a layer (0 if the shape is invalid or beyond the limits). */
+size_t tern_filter_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw);
+/* Output extents of a convolution; TERN_ESHAPE if the geometry does not fit. */
+int tern_conv_out_dims(tern_dims in_dims, int32_t c_out, tern_conv_geom g, tern_dims* out_dims);
+/* Raw hipError_t value recorded by the most recent call (on this host thread) that returned
+ * TERN_EHIP. */
+int tern_last_hip_error(void);
+/* Human-readable name of a tern_status. */
+const char* tern_status_string(int status);
+
+/*
+ * tern_pack -- 2-bit encoding of a ternary tensor (Fig. 3; section 2: "store ternary tensors
+ * using 2 bits per entry").
+ *   src        : int8 values in {-1, 0, +1}, contiguous [N][C][D][H][W].  Other values are not
+ *                detected: a nonzero byte sets the mask bit and a negative one the sign bit.
+ *   dst_packed : packed layout described above, tern_packed_bytes(dims) bytes.
+ */
+int tern_pack(const int8_t* src, tern_dims dims, uint32_t* dst_packed, void* stream);
+
+/*
+ * tern_pack_filters -- 2-bit encoding of a layer's ternary weights (section 2: "a trained model
+ * can be stored using only 2 bits per weight") in the filter-bank layout described above.
+ *   w    : int8 values in {-1, 0, +1}, contiguous [C_out][C_in][kd][kh][kw] (other values are
+ *          treated as in tern_pack).
+ *   bank : tern_filter_bank_bytes(...) bytes, 16-byte aligned.
+ * Done once per layer; the bank is then passed to tern_conv3d / tern_fcn_forward.
+ */
+int tern_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                      int32_t kw, uint32_t* bank, void* stream);
+
+/*
+ * tern_conv3d -- ternary convolution (cross-correlation) as a masked Hamming distance, Eq. 9:
+ *   acc[n][co][z][y][x] = sum over taps (a,b,c) and channel words q of
+ *        popcount(M) - 2*popcount(M & (sign_w ^ sign_a)),   M = mask_w & mask_a,
+ *   with the activation voxel at (z*s - p + a*dil, ...) and all-zero words outside the volume
+ *   (zero padding is the ternary value 0, which the mask excludes).  This equals the integer
+ *   inner product of the ternary patch and filter.
+ *
+ *   in_packed : packed activations, logical dims in_dims (in_dims.c = C_in).
+ *   w_bank    : filter bank of the layer (tern_pack_filters) for (c_out, C_in, g.k).
+ *   Exactly one output mode per call:
+ *     out_acc != NULL, out_packed == NULL : raw accumulators, int32 [N][c_out][Do][Ho][Wo];
+ *                                           thr_lo / thr_hi are ignored.
+ *     out_packed != NULL, out_acc == NULL : fused activation + re-pack (Eq. 6 with the
+ *         per-channel scale and batch-norm folded into two integer cut points):
+ *         code = +1 if acc > thr_hi[co]; -1 if acc < thr_lo[co]; else 0, written in the packed
+ *         layout with logical dims {N, c_out, Do, Ho, Wo}.  thr_lo, thr_hi: int32[c_out] on the
+ *         device, required, with thr_lo[co] <= thr_hi[co] (not checked -- the values live on the
+ *         device; if violated, +1 takes precedence where both comparisons hold).
+ *   Both non-NULL or both NULL -> TERN_EARG.  Buffers must not overlap.
+ */
+int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims,
+                const uint32_t* w_bank, int32_t c_out, tern_conv_geom g,
+                const int32_t* thr_lo, const int32_t* thr_hi,
+                int32_t* out_acc, uint32_t* out_packed, void* stream);
+
+/*
+ * tern_threshold_pack -- the hard ternary activation of Eq. 6 followed by 2-bit packing, on a
+ * tensor that is already in memory:  code = +1 if v > hi[c]; -1 if v < lo[c]; else 0.
+ *   src    : contiguous [N][C][D][H][W] of type t (TERN_SRC_I32: int32 accumulators with int32
+ *            cut points; TERN_SRC_F32: float values with float cut points, e.g. raw intensities
+ *            at -0.5 / +0.5; a NaN becomes 0).  TERN_SRC_I8 is not accepted here (TERN_EARG).
+ *   thr_lo, thr_hi : C entries of the source type, device memory, lo[c] <= hi[c] (not checked).
+ */
+int tern_threshold_pack(const void* src, tern_src_type t, tern_dims dims,
+                        const void* thr_lo, const void* thr_hi,
+                        uint32_t* dst_packed, void* stream);
+
+/* One TernaryNet module (section 2, last paragraph: ternary convolution, batch-norm, ternary
+ * activation).  The struct lives in HOST memory; the pointers inside are DEVICE pointers. */
+typedef struct {
+    int32_t c_in, c_out;
+    tern_conv_geom g;
+    const uint32_t* w_bank;     /* filter bank from tern_pack_filters       */
+    const int32_t* thr_lo;      /* [c_out] */
+    const int32_t* thr_hi;      /* [c_out] */
+} tern_layer;
+
+/* Bytes of scratch that tern_fcn_forward needs for this chain (0 if the chain is invalid:
+ * channel mismatch between consecutive layers or a geometry that does not fit). */
+size_t tern_fcn_workspace_bytes(tern_dims in_dims, const tern_layer* layers /* host */,
+                                int32_t n_layers);
+
+/*
+ * tern_fcn_forward -- a chain of modules with activations kept packed between layers.
+ *   in        : float [N][C0][D][H][W] raw intensities, ternarised per channel at
+ *               (in_lo[c], in_hi[c]) (device float[C0]; Eq. 6 uses -0.5 / +0.5) and packed;
+ *   layers    : host array of n_layers >= 1 modules, layers[0].c_in == in_dims.c and
+ *               layers[i].c_in == layers[i-1].c_out;
+ *   workspace : device scratch of at least tern_fcn_workspace_bytes() bytes, 16-byte aligned;
+ *               holds the packed activations of the input and of every layer but the last.
+ *               When layer_out (host array of n_layers pointers, may be NULL) is given,
+ *               layer_out[i] receives the device address of layer i's packed output (inside
+ *               workspace, or out_packed for the last layer) so that callers can inspect every
+ *               layer; nothing is overwritten within one call.
+ *   out_packed: packed output of the last layer; out_dims (host, may be NULL) receives its
+ *               logical dims.
+ * All kernels are enqueued on `stream` in order; there is no host synchronisation.
+ */
+int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
+                     const tern_layer* layers /* host */, int32_t n_layers,
+                     void* workspace, size_t workspace_bytes,
+                     uint32_t* out_packed, tern_dims* out_dims /* host */,
+                     uint32_t** layer_out /* host, optional */, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TERN_H */

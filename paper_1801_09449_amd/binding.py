@@ -1,0 +1,337 @@
+"""ctypes binding of libtern.so (the C ABI of include/tern.h) for torch device tensors.
+
+Each function mirrors the C entry point of the same name: it checks tensor dtype / device /
+contiguity, allocates the output tensor when the caller does not pass one, and forwards raw device
+pointers plus the current torch stream.  No arithmetic happens here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libtern.so"
+_lib = None
+
+
+class TernError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        msg = lib().tern_status_string(status).decode() if _lib is not None else str(status)
+        if status == -5:
+            msg += f" (hipError_t {lib().tern_last_hip_error()})"
+        super().__init__(f"{what}: {msg}")
+
+
+class Dims(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("n", "c", "d", "h", "w")]
+
+
+class Geom(C.Structure):
+    _fields_ = [("k", C.c_int32 * 3), ("stride", C.c_int32 * 3), ("pad", C.c_int32 * 3),
+                ("dil", C.c_int32 * 3)]
+
+
+class Layer(C.Structure):
+    _fields_ = [("c_in", C.c_int32), ("c_out", C.c_int32), ("g", Geom),
+                ("w_bank", C.c_void_p), ("thr_lo", C.c_void_p), ("thr_hi", C.c_void_p)]
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def lib():
+    """Load libtern.so (built in-tree by paper_1801_09449_amd/build.py).  Raises if missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise RuntimeError(
+            f"{path} is missing: build it with `python -m paper_1801_09449_amd.build` "
+            "(there is no fallback implementation)")
+    L = C.CDLL(path)
+    P, I, S = C.c_void_p, C.c_int32, C.c_size_t
+    L.tern_words.argtypes = [I]; L.tern_words.restype = I
+    L.tern_packed_bytes.argtypes = [Dims]; L.tern_packed_bytes.restype = S
+    L.tern_filter_bank_bytes.argtypes = [I] * 5; L.tern_filter_bank_bytes.restype = S
+    L.tern_conv_out_dims.argtypes = [Dims, I, Geom, C.POINTER(Dims)]; L.tern_conv_out_dims.restype = C.c_int
+    L.tern_last_hip_error.argtypes = []; L.tern_last_hip_error.restype = C.c_int
+    L.tern_status_string.argtypes = [C.c_int]; L.tern_status_string.restype = C.c_char_p
+    L.tern_pack.argtypes = [P, Dims, P, P]; L.tern_pack.restype = C.c_int
+    L.tern_pack_filters.argtypes = [P, I, I, I, I, I, P, P]; L.tern_pack_filters.restype = C.c_int
+    L.tern_conv3d.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d.restype = C.c_int
+    L.tern_threshold_pack.argtypes = [P, C.c_int, Dims, P, P, P, P]; L.tern_threshold_pack.restype = C.c_int
+    L.tern_fcn_workspace_bytes.argtypes = [Dims, C.POINTER(Layer), I]; L.tern_fcn_workspace_bytes.restype = S
+    L.tern_fcn_forward.argtypes = [P, Dims, P, P, C.POINTER(Layer), I, P, S, P, C.POINTER(Dims),
+                                   C.POINTER(C.c_void_p), P]
+    L.tern_fcn_forward.restype = C.c_int
+    _lib = L
+    return L
+
+
+# ---- helpers -----------------------------------------------------------------------------------
+def _t3(v) -> Tuple[int, int, int]:
+    if isinstance(v, int):
+        return (v, v, v)
+    v = tuple(int(x) for x in v)
+    if len(v) != 3:
+        raise ValueError("expected an int or three ints")
+    return v
+
+
+def _geom(k, stride, pad, dil) -> Geom:
+    g = Geom()
+    for name, val in (("k", k), ("stride", stride), ("pad", pad), ("dil", dil)):
+        t = _t3(val)
+        for i in range(3):
+            getattr(g, name)[i] = t[i]
+    return g
+
+
+def _dims(shape) -> Dims:
+    n, c, d, h, w = (int(x) for x in shape)
+    return Dims(n, c, d, h, w)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name} must be a torch tensor")
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (there is no CPU path)")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t
+
+
+def _stream(t: torch.Tensor) -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream(t.device).cuda_stream)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise TernError(rc, what)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> C.c_void_p:
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+# torch has no uint32 arithmetic worth the name; packed words are carried as int32 tensors (same
+# bits) and viewed as uint32 by whoever inspects them on the host.
+PACKED_DTYPE = torch.int32
+
+
+def tern_words(c: int) -> int:
+    return int(lib().tern_words(int(c)))
+
+
+def tern_packed_bytes(shape) -> int:
+    return int(lib().tern_packed_bytes(_dims(shape)))
+
+
+def tern_filter_bank_bytes(c_out: int, c_in: int, k) -> int:
+    kd, kh, kw = _t3(k)
+    return int(lib().tern_filter_bank_bytes(int(c_out), int(c_in), kd, kh, kw))
+
+
+def tern_conv_out_dims(in_shape, c_out: int, k=3, stride=1, pad=1, dil=1) -> Tuple[int, ...]:
+    o = Dims()
+    _check(lib().tern_conv_out_dims(_dims(in_shape), int(c_out), _geom(k, stride, pad, dil), C.byref(o)),
+           "tern_conv_out_dims")
+    return (o.n, o.c, o.d, o.h, o.w)
+
+
+def _empty_packed(shape, device) -> torch.Tensor:
+    n, c, d, h, w = (int(x) for x in shape)
+    return torch.empty((n, d, h, w, 2, tern_words(c)), dtype=PACKED_DTYPE, device=device)
+
+
+# ---- entry points ------------------------------------------------------------------------------
+def tern_pack(src: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """int8 ternary [N][C][D][H][W] -> packed planes [N][D][H][W][2][ceil(C/32)] (int32 bits)."""
+    _dev(src, torch.int8, "src")
+    if src.dim() != 5:
+        raise ValueError("src must be [N][C][D][H][W]")
+    if out is None:
+        out = _empty_packed(src.shape, src.device)
+    _dev(out, PACKED_DTYPE, "out")
+    if out.numel() * 4 != tern_packed_bytes(src.shape):
+        raise ValueError("out has the wrong size")
+    _check(lib().tern_pack(_ptr(src), _dims(src.shape), _ptr(out), _stream(src)), "tern_pack")
+    return out
+
+
+def tern_pack_filters(w: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """int8 ternary [C_out][C_in][kd][kh][kw] -> filter bank (flat int32 tensor)."""
+    _dev(w, torch.int8, "w")
+    if w.dim() != 5:
+        raise ValueError("w must be [C_out][C_in][kd][kh][kw]")
+    co, ci, kd, kh, kw = (int(x) for x in w.shape)
+    nbytes = tern_filter_bank_bytes(co, ci, (kd, kh, kw))
+    if nbytes == 0:
+        raise TernError(-2, "tern_pack_filters")
+    if out is None:
+        out = torch.empty((nbytes // 4,), dtype=PACKED_DTYPE, device=w.device)
+    _dev(out, PACKED_DTYPE, "out")
+    if out.numel() * 4 != nbytes:
+        raise ValueError("out has the wrong size")
+    _check(lib().tern_pack_filters(_ptr(w), co, ci, kd, kh, kw, _ptr(out), _stream(w)), "tern_pack_filters")
+    return out
+
+
+def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out: int,
+                k=3, stride=1, pad=1, dil=1,
+                thr_lo: Optional[torch.Tensor] = None, thr_hi: Optional[torch.Tensor] = None,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Ternary convolution.  Without cut points: int32 accumulators [N][C_out][Do][Ho][Wo].
+    With thr_lo / thr_hi (int32 [C_out]): fused activation + re-pack, packed output."""
+    _dev(in_packed, PACKED_DTYPE, "in_packed")
+    _dev(w_bank, PACKED_DTYPE, "w_bank")
+    if in_packed.dim() != 6 or in_packed.shape[4] != 2 or in_packed.shape[5] != tern_words(c_in):
+        raise ValueError("in_packed must be [N][D][H][W][2][ceil(C_in/32)]")
+    n, d, h, w = (int(x) for x in in_packed.shape[:4])
+    in_dims = Dims(n, int(c_in), d, h, w)
+    g = _geom(k, stride, pad, dil)
+    if w_bank.numel() * 4 != tern_filter_bank_bytes(c_out, c_in, (g.k[0], g.k[1], g.k[2])):
+        raise ValueError("w_bank size does not match (c_out, c_in, k)")
+    o = Dims()
+    _check(lib().tern_conv_out_dims(in_dims, int(c_out), g, C.byref(o)), "tern_conv3d")
+    fused = thr_lo is not None or thr_hi is not None
+    if fused:
+        if thr_lo is None or thr_hi is None:
+            raise ValueError("thr_lo and thr_hi must be given together")
+        _dev(thr_lo, torch.int32, "thr_lo"); _dev(thr_hi, torch.int32, "thr_hi")
+        if thr_lo.numel() != c_out or thr_hi.numel() != c_out:
+            raise ValueError("cut points must have c_out entries")
+        if out is None:
+            out = _empty_packed((o.n, o.c, o.d, o.h, o.w), in_packed.device)
+        _dev(out, PACKED_DTYPE, "out")
+        if out.numel() * 4 != tern_packed_bytes((o.n, o.c, o.d, o.h, o.w)):
+            raise ValueError("out has the wrong size")
+        rc = lib().tern_conv3d(_ptr(in_packed), in_dims, _ptr(w_bank), int(c_out), g, _ptr(thr_lo),
+                               _ptr(thr_hi), None, _ptr(out), _stream(in_packed))
+    else:
+        if out is None:
+            out = torch.empty((o.n, o.c, o.d, o.h, o.w), dtype=torch.int32, device=in_packed.device)
+        _dev(out, torch.int32, "out")
+        if tuple(out.shape) != (o.n, o.c, o.d, o.h, o.w):
+            raise ValueError("out has the wrong shape")
+        rc = lib().tern_conv3d(_ptr(in_packed), in_dims, _ptr(w_bank), int(c_out), g, None, None,
+                               _ptr(out), None, _stream(in_packed))
+    _check(rc, "tern_conv3d")
+    return out
+
+
+def tern_threshold_pack(src: torch.Tensor, thr_lo: torch.Tensor, thr_hi: torch.Tensor,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """int32 or float32 [N][C][D][H][W] -> packed ternary codes (+1 if v > hi[c], -1 if v < lo[c])."""
+    if not isinstance(src, torch.Tensor) or src.dtype not in (torch.int32, torch.float32):
+        raise TypeError("src must be an int32 or float32 torch tensor")
+    _dev(src, src.dtype, "src")
+    if src.dim() != 5:
+        raise ValueError("src must be [N][C][D][H][W]")
+    _dev(thr_lo, src.dtype, "thr_lo"); _dev(thr_hi, src.dtype, "thr_hi")
+    if thr_lo.numel() != src.shape[1] or thr_hi.numel() != src.shape[1]:
+        raise ValueError("cut points must have C entries")
+    if out is None:
+        out = _empty_packed(src.shape, src.device)
+    _dev(out, PACKED_DTYPE, "out")
+    if out.numel() * 4 != tern_packed_bytes(src.shape):
+        raise ValueError("out has the wrong size")
+    t = 1 if src.dtype == torch.int32 else 2
+    _check(lib().tern_threshold_pack(_ptr(src), t, _dims(src.shape), _ptr(thr_lo), _ptr(thr_hi),
+                                     _ptr(out), _stream(src)), "tern_threshold_pack")
+    return out
+
+
+@dataclass
+class FcnLayer:
+    """One module of the chain: filter bank + geometry + integer cut points (device tensors)."""
+    c_in: int
+    c_out: int
+    w_bank: torch.Tensor
+    thr_lo: torch.Tensor
+    thr_hi: torch.Tensor
+    k: Tuple[int, int, int] = (3, 3, 3)
+    stride: Tuple[int, int, int] = (1, 1, 1)
+    pad: Tuple[int, int, int] = (1, 1, 1)
+    dil: Tuple[int, int, int] = (1, 1, 1)
+
+
+def _layer_array(layers: Sequence[FcnLayer]):
+    arr = (Layer * len(layers))()
+    for i, L in enumerate(layers):
+        _dev(L.w_bank, PACKED_DTYPE, "w_bank"); _dev(L.thr_lo, torch.int32, "thr_lo")
+        _dev(L.thr_hi, torch.int32, "thr_hi")
+        g = _geom(L.k, L.stride, L.pad, L.dil)
+        if L.w_bank.numel() * 4 != tern_filter_bank_bytes(L.c_out, L.c_in, (g.k[0], g.k[1], g.k[2])):
+            raise ValueError(f"layer {i}: w_bank size does not match (c_out, c_in, k)")
+        if L.thr_lo.numel() != L.c_out or L.thr_hi.numel() != L.c_out:
+            raise ValueError(f"layer {i}: cut points must have c_out entries")
+        arr[i] = Layer(int(L.c_in), int(L.c_out), g, L.w_bank.data_ptr(), L.thr_lo.data_ptr(),
+                       L.thr_hi.data_ptr())
+    return arr
+
+
+def tern_fcn_workspace_bytes(in_shape, layers: Sequence[FcnLayer]) -> int:
+    arr = _layer_array(layers)
+    return int(lib().tern_fcn_workspace_bytes(_dims(in_shape), arr, len(layers)))
+
+
+def tern_fcn_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor,
+                     layers: Sequence[FcnLayer], workspace: Optional[torch.Tensor] = None,
+                     out: Optional[torch.Tensor] = None, return_layers: bool = False):
+    """float32 [N][C0][D][H][W] -> packed output of the last module.  With return_layers, also a
+    list of (packed tensor view, logical dims) for every module's output."""
+    _dev(x, torch.float32, "x")
+    if x.dim() != 5:
+        raise ValueError("x must be [N][C0][D][H][W]")
+    _dev(in_lo, torch.float32, "in_lo"); _dev(in_hi, torch.float32, "in_hi")
+    if in_lo.numel() != x.shape[1] or in_hi.numel() != x.shape[1]:
+        raise ValueError("input cut points must have C0 entries")
+    arr = _layer_array(layers)
+    need = int(lib().tern_fcn_workspace_bytes(_dims(x.shape), arr, len(layers)))
+    if need == 0:
+        raise TernError(-3, "tern_fcn_forward (invalid chain)")
+    if workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    # logical dims of every layer output
+    dims_list: List[Tuple[int, ...]] = []
+    cur = tuple(int(v) for v in x.shape)
+    for L in layers:
+        cur = tern_conv_out_dims(cur, L.c_out, L.k, L.stride, L.pad, L.dil)
+        dims_list.append(cur)
+    if out is None:
+        out = _empty_packed(dims_list[-1], x.device)
+    _dev(out, PACKED_DTYPE, "out")
+    if out.numel() * 4 != tern_packed_bytes(dims_list[-1]):
+        raise ValueError("out has the wrong size")
+    od = Dims()
+    ptrs = (C.c_void_p * len(layers))()
+    rc = lib().tern_fcn_forward(_ptr(x), _dims(x.shape), _ptr(in_lo), _ptr(in_hi), arr, len(layers),
+                                _ptr(workspace), workspace.numel(), _ptr(out), C.byref(od), ptrs,
+                                _stream(x))
+    _check(rc, "tern_fcn_forward")
+    if not return_layers:
+        return out
+    views = []
+    base = workspace.data_ptr()
+    for i, dm in enumerate(dims_list):
+        if i + 1 == len(layers):
+            views.append((out, dm))
+        else:
+            off = int(ptrs[i]) - base
+            nwords = tern_packed_bytes(dm) // 4
+            v = workspace[off: off + nwords * 4].view(PACKED_DTYPE).view(
+                dm[0], dm[2], dm[3], dm[4], 2, tern_words(dm[1]))
+            views.append((v, dm))
+    return out, views

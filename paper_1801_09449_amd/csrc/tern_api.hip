@@ -1,0 +1,262 @@
+// Host side of the C ABI declared in include/tern.h: argument validation and dispatch.
+// Every entry point validates on the host, launches on the caller's stream and returns without
+// synchronising.  Nothing here allocates device memory.
+#include <limits.h>
+
+#include "tern_internal.h"
+
+namespace tern {
+
+static thread_local int g_last_hip_error = 0;
+
+int record_hip_error(hipError_t e)
+{
+    g_last_hip_error = static_cast<int>(e);
+    return TERN_EHIP;
+}
+
+static bool dims_ok(const tern_dims& d)
+{
+    return d.n > 0 && d.c > 0 && d.d > 0 && d.h > 0 && d.w > 0;
+}
+
+static int64_t voxels(const tern_dims& d)
+{
+    return (int64_t)d.n * d.d * d.h * d.w;
+}
+
+// Limits that keep every device-side index inside int32/uint32 where the kernels use them.
+static bool sizes_ok(const tern_dims& d)
+{
+    if (!dims_ok(d)) return false;
+    const int64_t vox = voxels(d);
+    if (vox > (int64_t)INT32_MAX) return false;
+    const int64_t wd = (d.c + 31) / 32;
+    if (vox * 2 * wd > (int64_t)1 << 40) return false;
+    if ((int64_t)d.c * (int64_t)d.d * d.h * d.w > (int64_t)1 << 40) return false;
+    return true;
+}
+
+static int out_extent(int x, int k, int s, int p, int dil)
+{
+    const int64_t span = (int64_t)x + 2 * (int64_t)p - (int64_t)dil * (k - 1) - 1;
+    if (span < 0) return 0;
+    const int64_t o = span / s + 1;
+    return o > INT32_MAX ? 0 : (int)o;
+}
+
+static bool filter_shape_ok(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw)
+{
+    if (c_out <= 0 || c_in <= 0 || kd < 1 || kh < 1 || kw < 1) return false;
+    if (kd > 1024 || kh > 1024 || kw > 1024) return false;
+    const int64_t taps = (int64_t)kd * kh * kw;
+    if (taps * c_in >= (int64_t)1 << 24) return false;
+    if (taps * ((c_in + 31) / 32) * ((int64_t)c_out + 31) >= (int64_t)1 << 31) return false;
+    return true;
+}
+
+static int geom_check(const tern_dims& in, int32_t c_out, const tern_conv_geom& g, tern_dims* out)
+{
+    if (!sizes_ok(in) || c_out <= 0) return TERN_ESHAPE;
+    for (int a = 0; a < 3; ++a) {
+        if (g.k[a] < 1 || g.stride[a] < 1 || g.dil[a] < 1 || g.pad[a] < 0) return TERN_EARG;
+        if (g.k[a] > 1024 || g.stride[a] > 1024 || g.dil[a] > 1024 || g.pad[a] > (1 << 20))
+            return TERN_EARG;
+    }
+    if (!filter_shape_ok(c_out, in.c, g.k[0], g.k[1], g.k[2])) return TERN_ESHAPE;
+    tern_dims o;
+    o.n = in.n;
+    o.c = c_out;
+    o.d = out_extent(in.d, g.k[0], g.stride[0], g.pad[0], g.dil[0]);
+    o.h = out_extent(in.h, g.k[1], g.stride[1], g.pad[1], g.dil[1]);
+    o.w = out_extent(in.w, g.k[2], g.stride[2], g.pad[2], g.dil[2]);
+    if (o.d < 1 || o.h < 1 || o.w < 1) return TERN_ESHAPE;
+    if (!sizes_ok(o)) return TERN_ESHAPE;
+    if (out) *out = o;
+    return TERN_OK;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace tern
+
+using namespace tern;
+
+extern "C" {
+
+int32_t tern_words(int32_t c) { return c > 0 ? (c + 31) / 32 : 0; }
+
+size_t tern_packed_bytes(tern_dims dims)
+{
+    if (!sizes_ok(dims)) return 0;
+    return (size_t)voxels(dims) * 2u * (size_t)tern_words(dims.c) * sizeof(uint32_t);
+}
+
+int tern_conv_out_dims(tern_dims in_dims, int32_t c_out, tern_conv_geom g, tern_dims* out_dims)
+{
+    if (!out_dims) return TERN_ENULL;
+    return geom_check(in_dims, c_out, g, out_dims);
+}
+
+int tern_last_hip_error(void) { return g_last_hip_error; }
+
+const char* tern_status_string(int status)
+{
+    switch (status) {
+        case TERN_OK: return "TERN_OK";
+        case TERN_ENULL: return "TERN_ENULL: a required pointer is NULL";
+        case TERN_ESHAPE: return "TERN_ESHAPE: invalid or unsupported tensor extents";
+        case TERN_EARG: return "TERN_EARG: invalid argument combination";
+        case TERN_EWORKSPACE: return "TERN_EWORKSPACE: workspace too small or misaligned";
+        case TERN_EHIP: return "TERN_EHIP: a HIP call failed";
+        default: return "unknown tern_status";
+    }
+}
+
+int tern_pack(const int8_t* src, tern_dims dims, uint32_t* dst_packed, void* stream)
+{
+    if (!src || !dst_packed) return TERN_ENULL;
+    if (!sizes_ok(dims)) return TERN_ESHAPE;
+    if (!aligned16(dst_packed)) return TERN_EARG;
+    return launch_pack_i8(src, dims, dst_packed, (hipStream_t)stream);
+}
+
+size_t tern_filter_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw)
+{
+    if (!filter_shape_ok(c_out, c_in, kd, kh, kw)) return 0;
+    const size_t co_pad = (size_t)(c_out + 31) / 32 * 32;
+    return (size_t)kd * kh * kw * (size_t)tern_words(c_in) * co_pad * 2u * sizeof(uint32_t);
+}
+
+int tern_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                      int32_t kw, uint32_t* bank, void* stream)
+{
+    if (!w || !bank) return TERN_ENULL;
+    if (!filter_shape_ok(c_out, c_in, kd, kh, kw)) return TERN_ESHAPE;
+    if (!aligned16(bank)) return TERN_EARG;
+    return launch_pack_filters(w, c_out, c_in, kd, kh, kw, bank, (hipStream_t)stream);
+}
+
+int tern_threshold_pack(const void* src, tern_src_type t, tern_dims dims, const void* thr_lo,
+                        const void* thr_hi, uint32_t* dst_packed, void* stream)
+{
+    if (!src || !thr_lo || !thr_hi || !dst_packed) return TERN_ENULL;
+    if (t != TERN_SRC_I32 && t != TERN_SRC_F32) return TERN_EARG;
+    if (!sizes_ok(dims)) return TERN_ESHAPE;
+    if (!aligned16(dst_packed) || ((uintptr_t)src & 3u)) return TERN_EARG;
+    if (t == TERN_SRC_I32)
+        return launch_threshold_pack_i32((const int32_t*)src, dims, (const int32_t*)thr_lo,
+                                         (const int32_t*)thr_hi, dst_packed, (hipStream_t)stream);
+    return launch_threshold_pack_f32((const float*)src, dims, (const float*)thr_lo,
+                                     (const float*)thr_hi, dst_packed, (hipStream_t)stream);
+}
+
+int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_bank,
+                int32_t c_out, tern_conv_geom g, const int32_t* thr_lo, const int32_t* thr_hi,
+                int32_t* out_acc, uint32_t* out_packed, void* stream)
+{
+    if (!in_packed || !w_bank) return TERN_ENULL;
+    if ((out_acc == nullptr) == (out_packed == nullptr)) return TERN_EARG;
+    if (out_packed && (!thr_lo || !thr_hi)) return TERN_ENULL;
+    tern_dims o;
+    int rc = geom_check(in_dims, c_out, g, &o);
+    if (rc != TERN_OK) return rc;
+    if (!aligned16(in_packed) || !aligned16(w_bank)) return TERN_EARG;
+    if (out_packed && !aligned16(out_packed)) return TERN_EARG;
+    if (out_acc && ((uintptr_t)out_acc & 3u)) return TERN_EARG;
+
+    ConvParams p;
+    p.in = in_packed;
+    p.wgt = w_bank;
+    p.lo = thr_lo;
+    p.hi = thr_hi;
+    p.out_acc = out_acc;
+    p.out_packed = out_packed;
+    p.n = in_dims.n; p.c_in = in_dims.c; p.d = in_dims.d; p.h = in_dims.h; p.w = in_dims.w;
+    p.c_out = c_out; p.od = o.d; p.oh = o.h; p.ow = o.w;
+    p.kd = g.k[0]; p.kh = g.k[1]; p.kw = g.k[2];
+    p.sd = g.stride[0]; p.sh = g.stride[1]; p.sw = g.stride[2];
+    p.pd = g.pad[0]; p.ph = g.pad[1]; p.pw = g.pad[2];
+    p.dd = g.dil[0]; p.dh = g.dil[1]; p.dw = g.dil[2];
+    p.wd_in = tern_words(in_dims.c);
+    p.wd_out = tern_words(c_out);
+    p.wc = (p.wd_in % 2 == 0) ? 2 : 1;
+    p.co_pad = (c_out + 31) / 32 * 32;
+    return launch_conv3d(p, (hipStream_t)stream);
+}
+
+// Walks the chain once: validates channel continuity and geometry, and reports the packed size
+// of the input and of every layer output.  Returns TERN_OK or the first error.
+static int fcn_plan(tern_dims in_dims, const tern_layer* layers, int32_t n_layers,
+                    size_t* ws_bytes, tern_dims* last)
+{
+    if (!layers) return TERN_ENULL;
+    if (n_layers < 1 || n_layers > 1024) return TERN_EARG;
+    if (!sizes_ok(in_dims)) return TERN_ESHAPE;
+    size_t total = (tern_packed_bytes(in_dims) + 255u) & ~(size_t)255u;
+    tern_dims cur = in_dims;
+    for (int i = 0; i < n_layers; ++i) {
+        if (layers[i].c_in != cur.c) return TERN_EARG;
+        tern_dims o;
+        int rc = geom_check(cur, layers[i].c_out, layers[i].g, &o);
+        if (rc != TERN_OK) return rc;
+        if (i + 1 < n_layers) total += (tern_packed_bytes(o) + 255u) & ~(size_t)255u;
+        cur = o;
+    }
+    if (ws_bytes) *ws_bytes = total;
+    if (last) *last = cur;
+    return TERN_OK;
+}
+
+size_t tern_fcn_workspace_bytes(tern_dims in_dims, const tern_layer* layers, int32_t n_layers)
+{
+    size_t b = 0;
+    if (fcn_plan(in_dims, layers, n_layers, &b, nullptr) != TERN_OK) return 0;
+    return b;
+}
+
+int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
+                     const tern_layer* layers, int32_t n_layers, void* workspace,
+                     size_t workspace_bytes, uint32_t* out_packed, tern_dims* out_dims,
+                     uint32_t** layer_out, void* stream)
+{
+    if (!in || !in_lo || !in_hi || !layers || !workspace || !out_packed) return TERN_ENULL;
+    size_t need = 0;
+    tern_dims last;
+    int rc = fcn_plan(in_dims, layers, n_layers, &need, &last);
+    if (rc != TERN_OK) return rc;
+    for (int i = 0; i < n_layers; ++i)
+        if (!layers[i].w_bank || !layers[i].thr_lo || !layers[i].thr_hi) return TERN_ENULL;
+    if (workspace_bytes < need || !aligned16(workspace)) return TERN_EWORKSPACE;
+    if (!aligned16(out_packed)) return TERN_EARG;
+
+    char* ws = (char*)workspace;
+    uint32_t* cur_buf = (uint32_t*)ws;
+    ws += (tern_packed_bytes(in_dims) + 255u) & ~(size_t)255u;
+    // First step: Eq. 6 on the raw intensities, packed.
+    rc = tern_threshold_pack(in, TERN_SRC_F32, in_dims, in_lo, in_hi, cur_buf, stream);
+    if (rc != TERN_OK) return rc;
+    tern_dims cur = in_dims;
+    for (int i = 0; i < n_layers; ++i) {
+        tern_dims o;
+        rc = geom_check(cur, layers[i].c_out, layers[i].g, &o);
+        if (rc != TERN_OK) return rc;
+        uint32_t* dst;
+        if (i + 1 < n_layers) {
+            dst = (uint32_t*)ws;
+            ws += (tern_packed_bytes(o) + 255u) & ~(size_t)255u;
+        } else {
+            dst = out_packed;
+        }
+        rc = tern_conv3d(cur_buf, cur, layers[i].w_bank, layers[i].c_out, layers[i].g,
+                         layers[i].thr_lo, layers[i].thr_hi, nullptr, dst, stream);
+        if (rc != TERN_OK) return rc;
+        if (layer_out) layer_out[i] = dst;
+        cur_buf = dst;
+        cur = o;
+    }
+    if (out_dims) *out_dims = last;
+    return TERN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "tern.h"
+
+namespace tern {
+
+// Records a failing HIP call for tern_last_hip_error() and maps it to TERN_EHIP.
+int record_hip_error(hipError_t e);
+
+#define TERN_HIP_CHECK(expr)                                        \
+    do {                                                            \
+        hipError_t e__ = (expr);                                    \
+        if (e__ != hipSuccess) return ::tern::record_hip_error(e__); \
+    } while (0)
+
+// Geometry of one convolution launch, passed to kernels by value.
+struct ConvParams {
+    const uint32_t* in;     // packed activations [N][D][H][W][2][Wd]
+    const uint32_t* wgt;    // filter bank [T*nchunk][co_pad][2][wc] (see tern_pack_filters)
+    const int32_t* lo;      // [Co] (packed output mode)
+    const int32_t* hi;      // [Co]
+    int32_t* out_acc;       // [N][Co][Do][Ho][Wo] or null
+    uint32_t* out_packed;   // [N][Do][Ho][Wo][2][Wdo] or null
+    int32_t n, c_in, d, h, w;
+    int32_t c_out, od, oh, ow;
+    int32_t kd, kh, kw;
+    int32_t sd, sh, sw;
+    int32_t pd, ph, pw;
+    int32_t dd, dh, dw;
+    int32_t wd_in;          // ceil(c_in/32)
+    int32_t wd_out;         // ceil(c_out/32)
+    int32_t wc;             // filter-bank chunk width in words: 2 if wd_in is even, else 1
+    int32_t co_pad;         // c_out rounded up to a multiple of 32
+};
+
+// Launchers implemented in the kernel translation units.  Each validates nothing (the entry
+// points did) and returns a tern_status.
+int launch_pack_i8(const int8_t* src, tern_dims dims, uint32_t* dst, hipStream_t s);
+int launch_threshold_pack_i32(const int32_t* src, tern_dims dims, const int32_t* lo,
+                              const int32_t* hi, uint32_t* dst, hipStream_t s);
+int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo, const float* hi,
+                              uint32_t* dst, hipStream_t s);
+int launch_conv3d(const ConvParams& p, hipStream_t s);
+int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                        int32_t kw, uint32_t* bank, hipStream_t s);
+
+}  // namespace tern

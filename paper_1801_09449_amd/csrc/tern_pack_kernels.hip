@@ -1,0 +1,186 @@
+// Streaming kernels that turn an unpacked NCDHW tensor into channel-packed bit-planes
+// (mask plane, sign plane; the 2-bit storage of the paper's Fig. 3):
+//   - int8 ternary values                       (tern_pack)
+//   - int32 accumulators against integer cut points, or float values against float cut points:
+//     the hard activation of Eq. 6               (tern_threshold_pack)
+// All three are HBM-bound streams.  A thread owns VPT consecutive voxels of one batch item and
+// walks the channel words; for a fixed channel the lanes of a wave read consecutive addresses.
+#include "tern_internal.h"
+
+namespace tern {
+namespace {
+
+constexpr int kBlock = 256;
+
+// VPT voxels of type T starting at p (p is aligned to VPT*sizeof(T) when VPT > 1).
+template <typename T, int VPT>
+struct Vec {
+    T v[VPT];
+    __device__ void load(const T* p)
+    {
+        if constexpr (VPT == 1) {
+            v[0] = *p;
+        } else if constexpr (sizeof(T) * VPT == 4) {
+            uint32_t raw = *reinterpret_cast<const uint32_t*>(p);
+            __builtin_memcpy(v, &raw, 4);
+        } else {
+            static_assert(sizeof(T) * VPT == 16, "unsupported vector width");
+            uint4 raw = *reinterpret_cast<const uint4*>(p);
+            __builtin_memcpy(v, &raw, 16);
+        }
+    }
+};
+
+// MODE 0: int8 ternary input.  MODE 1: thresholds (T = int32_t or float).
+template <typename T, int VPT, int MODE>
+__global__ __launch_bounds__(kBlock) void pack_kernel(const T* __restrict__ src,
+                                                      uint32_t* __restrict__ dst,
+                                                      const T* __restrict__ lo,
+                                                      const T* __restrict__ hi, int32_t C,
+                                                      int32_t Wd, int64_t spatial,
+                                                      int64_t groups_per_n, int64_t total_groups)
+{
+    const int64_t gid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (gid >= total_groups) return;
+    const int64_t n = gid / groups_per_n;
+    const int64_t v0 = (gid - n * groups_per_n) * VPT;  // first voxel (within batch item n)
+    const T* base = src + (size_t)n * C * spatial + v0;
+    uint32_t* out = dst + ((size_t)n * spatial + v0) * 2u * Wd;
+
+    for (int q = 0; q < Wd; ++q) {
+        uint32_t m[VPT], s[VPT];
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) m[i] = s[i] = 0u;
+        const int cmax = min(32, C - 32 * q);
+#pragma unroll 8
+        for (int j = 0; j < cmax; ++j) {
+            const int c = 32 * q + j;
+            Vec<T, VPT> x;
+            x.load(base + (size_t)c * spatial);
+            T tl = T(0), th = T(0);
+            if constexpr (MODE == 1) { tl = lo[c]; th = hi[c]; }
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) {
+                bool nz, neg;
+                if constexpr (MODE == 0) {
+                    nz = x.v[i] != 0;
+                    neg = x.v[i] < 0;
+                } else {
+                    const bool pos = x.v[i] > th;
+                    neg = (x.v[i] < tl) && !pos;
+                    nz = pos || neg;
+                }
+                m[i] |= (nz ? 1u : 0u) << j;
+                s[i] |= (neg ? 1u : 0u) << j;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            out[(size_t)i * 2u * Wd + q] = m[i];
+            out[(size_t)i * 2u * Wd + Wd + q] = s[i];
+        }
+    }
+}
+
+template <typename T, int MODE>
+int launch_pack_any(const T* src, tern_dims dims, const T* lo, const T* hi, uint32_t* dst,
+                    hipStream_t s)
+{
+    const int64_t spatial = (int64_t)dims.d * dims.h * dims.w;
+    const int32_t Wd = (dims.c + 31) / 32;
+    constexpr int VPT = 4;
+    const bool vec_ok = (spatial % VPT == 0) && (((uintptr_t)src % (VPT * sizeof(T))) == 0);
+    if (vec_ok) {
+        const int64_t gpn = spatial / VPT;
+        const int64_t total = gpn * dims.n;
+        const int64_t blocks = (total + kBlock - 1) / kBlock;
+        if (blocks > 0x7fffffff) return TERN_ESHAPE;
+        hipLaunchKernelGGL((pack_kernel<T, VPT, MODE>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                           src, dst, lo, hi, dims.c, Wd, spatial, gpn, total);
+    } else {
+        const int64_t total = spatial * dims.n;
+        const int64_t blocks = (total + kBlock - 1) / kBlock;
+        if (blocks > 0x7fffffff) return TERN_ESHAPE;
+        hipLaunchKernelGGL((pack_kernel<T, 1, MODE>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
+                           src, dst, lo, hi, dims.c, Wd, spatial, spatial, total);
+    }
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
+
+}  // namespace
+
+int launch_pack_i8(const int8_t* src, tern_dims dims, uint32_t* dst, hipStream_t s)
+{
+    return launch_pack_any<int8_t, 0>(src, dims, nullptr, nullptr, dst, s);
+}
+
+int launch_threshold_pack_i32(const int32_t* src, tern_dims dims, const int32_t* lo,
+                              const int32_t* hi, uint32_t* dst, hipStream_t s)
+{
+    return launch_pack_any<int32_t, 1>(src, dims, lo, hi, dst, s);
+}
+
+int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo, const float* hi,
+                              uint32_t* dst, hipStream_t s)
+{
+    return launch_pack_any<float, 1>(src, dims, lo, hi, dst, s);
+}
+
+// ---- filter bank ------------------------------------------------------------------------------
+// Layout consumed by the convolution kernels: uint32 [T * nchunk][co_pad][2][wc], where
+// T = kd*kh*kw taps in (a, b, c) order, wc = 2 if ceil(C_in/32) is even else 1 words per chunk,
+// nchunk = ceil(C_in/32) / wc, co_pad = C_out rounded up to a multiple of 32 (padding channels
+// are all-zero filters).  Step s = tap * nchunk + chunk holds, for every channel, wc mask words
+// then wc sign words of input-channel words [chunk*wc, chunk*wc + wc).
+namespace {
+
+__global__ __launch_bounds__(256) void pack_filters_kernel(const int8_t* __restrict__ w,
+                                                           uint32_t* __restrict__ bank, int c_out,
+                                                           int c_in, int T, int wc, int nchunk,
+                                                           int co_pad, int64_t total)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    // one thread per (step, channel, word-in-chunk)
+    int64_t r = gid;
+    const int q = (int)(r % wc); r /= wc;
+    const int co = (int)(r % co_pad); r /= co_pad;
+    const int step = (int)r;
+    const int tap = step / nchunk, chunk = step - tap * nchunk;
+    const int word = chunk * wc + q;
+    uint32_t m = 0u, s = 0u;
+    if (co < c_out) {
+        for (int j = 0; j < 32; ++j) {
+            const int ci = 32 * word + j;
+            if (ci >= c_in) break;
+            const int8_t v = w[((size_t)co * c_in + ci) * T + tap];
+            m |= (v != 0 ? 1u : 0u) << j;
+            s |= (v < 0 ? 1u : 0u) << j;
+        }
+    }
+    uint32_t* o = bank + ((size_t)step * co_pad + co) * 2u * wc;
+    o[q] = m;
+    o[wc + q] = s;
+}
+
+}  // namespace
+
+int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                        int32_t kw, uint32_t* bank, hipStream_t s)
+{
+    const int wd = (c_in + 31) / 32;
+    const int wc = (wd % 2 == 0) ? 2 : 1;
+    const int nchunk = wd / wc;
+    const int co_pad = (c_out + 31) / 32 * 32;
+    const int T = kd * kh * kw;
+    const int64_t total = (int64_t)T * nchunk * co_pad * wc;
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffff) return TERN_ESHAPE;
+    hipLaunchKernelGGL(pack_filters_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, bank, c_out,
+                       c_in, T, wc, nchunk, co_pad, total);
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
+
+}  // namespace tern

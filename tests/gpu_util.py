@@ -1,0 +1,46 @@
+"""Helpers shared by the GPU parity tests: move synthetic cases to the device, call the library
+through its binding, and bring results back as numpy arrays for comparison with the oracle."""
+import numpy as np
+import torch
+
+import paper_1801_09449_amd as T
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def words(t: torch.Tensor) -> np.ndarray:
+    """Packed device tensor -> uint32 numpy array."""
+    return t.cpu().numpy().view(np.uint32)
+
+
+def run_case(case, want_acc=True, want_packed=True):
+    """Run one single-layer case on the GPU.  Returns (acc int32 array or None, packed uint32
+    array or None)."""
+    act = T.tern_pack(dev(case.act))
+    bank = T.tern_pack_filters(dev(case.wgt))
+    c_in, c_out = case.act.shape[1], case.wgt.shape[0]
+    acc = packed = None
+    if want_acc:
+        acc = T.tern_conv3d(act, c_in, bank, c_out, case.k, case.stride, case.pad, case.dil)
+    if want_packed:
+        packed = T.tern_conv3d(act, c_in, bank, c_out, case.k, case.stride, case.pad, case.dil,
+                               thr_lo=dev(case.lo), thr_hi=dev(case.hi))
+    torch.cuda.synchronize()
+    return (None if acc is None else acc.cpu().numpy(),
+            None if packed is None else words(packed))
+
+
+def bank_layout(w_packed: np.ndarray, c_out: int, c_in: int) -> np.ndarray:
+    """Expected filter bank from plane-packed filters [C_out][kd][kh][kw][2][Wd] by pure
+    re-indexing: [T*nchunk][co_pad][2][wc] with wc = 2 if Wd even else 1, zero padding channels."""
+    wd = (c_in + 31) // 32
+    wc = 2 if wd % 2 == 0 else 1
+    nchunk = wd // wc
+    taps = int(np.prod(w_packed.shape[1:4]))
+    co_pad = (c_out + 31) // 32 * 32
+    flat = w_packed.reshape(c_out, taps, 2, nchunk, wc)            # [co][tap][plane][chunk][q]
+    bank = np.zeros((taps, nchunk, co_pad, 2, wc), dtype=np.uint32)
+    bank[:, :, :c_out] = np.transpose(flat, (1, 3, 0, 2, 4))
+    return bank.reshape(-1)

@@ -1,0 +1,98 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects invalid arguments before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_1801_09449_amd as T
+    if not os.path.exists(T.lib_path()):
+        from paper_1801_09449_amd import build
+        build.build()
+    return T
+
+
+def test_every_declared_symbol_is_exported(T):
+    hdr = open(os.path.join(ROOT, "include", "tern.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(tern_[a-z0-9_]+)\s*\(", hdr))
+    assert {"tern_pack", "tern_conv3d", "tern_threshold_pack", "tern_fcn_forward",
+            "tern_pack_filters"} <= names
+    L = T.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), f"{n} declared in tern.h but not exported"
+
+
+def test_size_helpers(T):
+    assert T.tern_words(1) == 1 and T.tern_words(32) == 1 and T.tern_words(33) == 2
+    assert T.tern_words(0) == 0
+    assert T.tern_packed_bytes((1, 64, 64, 64, 64)) == 64 ** 3 * 16
+    assert T.tern_packed_bytes((2, 1, 3, 4, 5)) == 2 * 60 * 8
+    assert T.tern_packed_bytes((1, 0, 3, 4, 5)) == 0
+    # filter bank: taps * words * co_pad * 8 bytes
+    assert T.tern_filter_bank_bytes(64, 64, 3) == 27 * 2 * 64 * 8
+    assert T.tern_filter_bank_bytes(33, 1, (1, 3, 2)) == 6 * 1 * 64 * 8
+    assert T.tern_filter_bank_bytes(0, 4, 3) == 0
+
+
+def test_out_dims_formula(T):
+    assert T.tern_conv_out_dims((1, 64, 64, 64, 64), 64) == (1, 64, 64, 64, 64)
+    assert T.tern_conv_out_dims((1, 16, 128, 128, 64), 32, 3, 2, 1, 1) == (1, 32, 64, 64, 32)
+    assert T.tern_conv_out_dims((2, 3, 7, 9, 5), 4, 3, 2, 1, 1) == (2, 4, 4, 5, 3)
+    assert T.tern_conv_out_dims((1, 8, 96, 96, 96), 8, 3, 1, 3, 3) == (1, 8, 96, 96, 96)
+    assert T.tern_conv_out_dims((1, 8, 9, 9, 9), 8, 1, 1, 0, 1) == (1, 8, 9, 9, 9)
+    with pytest.raises(T.TernError) as e:
+        T.tern_conv_out_dims((1, 8, 2, 2, 2), 8, 3, 1, 0, 1)      # kernel does not fit
+    assert e.value.status == -2
+    with pytest.raises(T.TernError) as e:
+        T.tern_conv_out_dims((1, 8, 8, 8, 8), 8, 3, 0, 1, 1)      # stride 0
+    assert e.value.status == -3
+
+
+def test_null_and_bad_arguments_are_rejected_before_launch(T):
+    from paper_1801_09449_amd.binding import Dims, Geom, Layer, _geom
+    L = T.lib()
+    d = Dims(1, 32, 4, 4, 4)
+    g = _geom(3, 1, 1, 1)
+    fake = C.c_void_p(0x1000)   # never dereferenced: validation fails first
+    assert L.tern_pack(None, d, fake, None) == -1
+    assert L.tern_pack(fake, d, None, None) == -1
+    assert L.tern_pack(fake, Dims(1, 0, 4, 4, 4), fake, None) == -2
+    assert L.tern_pack(fake, d, C.c_void_p(0x1004), None) == -3            # misaligned
+    assert L.tern_pack_filters(None, 4, 4, 3, 3, 3, fake, None) == -1
+    assert L.tern_pack_filters(fake, 4, 4, 0, 3, 3, fake, None) == -2
+    assert L.tern_threshold_pack(fake, 0, d, fake, fake, fake, None) == -3  # int8 source not accepted
+    assert L.tern_threshold_pack(fake, 1, d, None, fake, fake, None) == -1
+    # conv: both or neither output, missing cut points, bad geometry
+    assert L.tern_conv3d(fake, d, fake, 8, g, None, None, None, None, None) == -3
+    assert L.tern_conv3d(fake, d, fake, 8, g, fake, fake, fake, fake, None) == -3
+    assert L.tern_conv3d(fake, d, fake, 8, g, None, fake, None, fake, None) == -1
+    assert L.tern_conv3d(None, d, fake, 8, g, None, None, fake, None, None) == -1
+    assert L.tern_conv3d(fake, d, fake, 0, g, None, None, fake, None, None) == -2
+    assert L.tern_conv3d(fake, d, fake, 8, _geom(3, 1, 1, 0), None, None, fake, None, None) == -3
+    assert L.tern_conv3d(fake, d, fake, 8, _geom(9, 1, 0, 1), None, None, fake, None, None) == -2
+    # fcn: channel mismatch between layers, workspace too small
+    arr = (Layer * 2)()
+    arr[0] = Layer(32, 16, g, 0x1000, 0x1000, 0x1000)
+    arr[1] = Layer(8, 16, g, 0x1000, 0x1000, 0x1000)
+    assert L.tern_fcn_workspace_bytes(d, arr, 2) == 0
+    arr[1] = Layer(16, 16, g, 0x1000, 0x1000, 0x1000)
+    need = L.tern_fcn_workspace_bytes(d, arr, 2)
+    assert need >= 64 * 8 + 64 * 8
+    od = Dims()
+    assert L.tern_fcn_forward(fake, d, fake, fake, arr, 2, fake, need - 1, fake, C.byref(od), None, None) == -4
+    assert L.tern_fcn_forward(fake, d, fake, fake, arr, 0, fake, need, fake, C.byref(od), None, None) == -3
+    assert L.tern_fcn_forward(fake, d, fake, fake, arr, 2, None, need, fake, C.byref(od), None, None) == -1
+    assert b"TERN_ESHAPE" in L.tern_status_string(-2)
+
+
+def test_binding_refuses_cpu_tensors(T):
+    import torch
+    with pytest.raises(ValueError):
+        T.tern_pack(torch.zeros((1, 4, 2, 2, 2), dtype=torch.int8))

@@ -1,0 +1,306 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, bit-exact, on the same
+seeded inputs.  Integer accumulators and ternary codes must match exactly."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from oracle import ConvGeom
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    import paper_1801_09449_amd as T
+    from tests import gpu_util
+    T.lib()          # fail loudly if the HIP library is not built
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+def geom_of(c):
+    return ConvGeom(c.k, c.stride, c.pad, c.dil)
+
+
+def expect(c):
+    acc = oracle.conv3d(c.act, c.wgt, geom_of(c))
+    packed = oracle.pack(oracle.threshold(acc, c.lo, c.hi))
+    return acc, packed
+
+
+def check_case(G, c):
+    acc, packed = G.run_case(c)
+    want_acc, want_packed = expect(c)
+    assert acc.shape == want_acc.shape
+    np.testing.assert_array_equal(acc, want_acc)
+    assert packed.shape == want_packed.shape
+    np.testing.assert_array_equal(packed, want_packed)
+
+
+# ---- a1: tern_pack --------------------------------------------------------------------------
+@pytest.mark.parametrize("c,vol", [(1, (3, 5, 7)), (5, (4, 4, 4)), (31, (2, 3, 8)), (32, (8, 8, 8)),
+                                   (33, (5, 5, 5)), (64, (8, 12, 16)), (70, (3, 3, 3)), (256, (4, 6, 8))])
+def test_pack_matches_oracle(G, c, vol):
+    import paper_1801_09449_amd as T
+    x = synth.ternary((2, c) + vol, 0.4, 31, synth.T_ACT)
+    got = G.words(T.tern_pack(G.dev(x)))
+    np.testing.assert_array_equal(got, oracle.pack(x))
+
+
+def test_pack_unaligned_source_and_all_code_points(G):
+    import torch
+    import paper_1801_09449_amd as T
+    x = np.array([1, -1, 0, 0, -1, 1, 1, 0], np.int8).reshape(1, 2, 1, 1, 4)
+    got = G.words(T.tern_pack(G.dev(x)))
+    np.testing.assert_array_equal(got, oracle.pack(x))
+    # a source that is not 4-byte aligned takes the byte path
+    big = synth.ternary((1, 40, 4, 4, 8), 0.5, 37, synth.T_ACT)
+    buf = torch.zeros(big.size + 1, dtype=torch.int8, device="cuda")
+    buf[1:] = G.dev(big).reshape(-1)
+    got = G.words(T.tern_pack(buf[1:].view(big.shape)))
+    np.testing.assert_array_equal(got, oracle.pack(big))
+
+
+# ---- a6: tern_threshold_pack ----------------------------------------------------------------
+@pytest.mark.parametrize("c,vol", [(3, (3, 5, 7)), (32, (4, 4, 4)), (45, (4, 6, 8)), (64, (5, 5, 5))])
+def test_threshold_pack_i32(G, c, vol):
+    import paper_1801_09449_amd as T
+    v = synth.uniform_int(2 * c * int(np.prod(vol)), -12, 12, 41, synth.T_ACT).astype(np.int32)
+    v = v.reshape((2, c) + vol)
+    lo, hi = synth.threshold_pair(c, 41)
+    got = G.words(T.tern_threshold_pack(G.dev(v), G.dev(lo), G.dev(hi)))
+    np.testing.assert_array_equal(got, oracle.pack(oracle.threshold(v, lo, hi)))
+
+
+def test_threshold_pack_i32_extreme_cut_points(G):
+    import paper_1801_09449_amd as T
+    v = synth.uniform_int(4 * 16, -5, 5, 43, synth.T_ACT).astype(np.int32).reshape(1, 4, 1, 4, 4)
+    i32 = np.iinfo(np.int32)
+    lo = np.array([i32.min, i32.min, i32.max, 0], np.int32)
+    hi = np.array([i32.max, i32.min, i32.max, 0], np.int32)
+    got = G.words(T.tern_threshold_pack(G.dev(v), G.dev(lo), G.dev(hi)))
+    want_code = oracle.threshold(v, lo, hi)
+    assert not want_code[0, 0].any() and (want_code[0, 1] == 1).all() and (want_code[0, 2] == -1).all()
+    np.testing.assert_array_equal(got, oracle.pack(want_code))
+
+
+def test_threshold_pack_f32_eq6_and_ties(G):
+    import paper_1801_09449_amd as T
+    x = synth.gaussian((2, 3, 4, 6, 8), 47, synth.T_F32)
+    x.reshape(-1)[:6] = [0.5, -0.5, np.nextafter(np.float32(0.5), np.float32(1)),
+                         np.nextafter(np.float32(-0.5), np.float32(-1)), np.nan, 0.0]
+    lo = np.full(3, -0.5, np.float32); hi = np.full(3, 0.5, np.float32)
+    got = G.words(T.tern_threshold_pack(G.dev(x), G.dev(lo), G.dev(hi)))
+    np.testing.assert_array_equal(got, oracle.pack(oracle.threshold(x, lo, hi)))
+
+
+# ---- filter bank ----------------------------------------------------------------------------
+@pytest.mark.parametrize("co,ci,k", [(32, 32, (3, 3, 3)), (5, 1, (3, 3, 3)), (33, 70, (1, 3, 2)),
+                                     (64, 64, (3, 3, 3)), (40, 96, (1, 1, 1)), (16, 256, (3, 3, 3))])
+def test_filter_bank_layout(G, co, ci, k):
+    import paper_1801_09449_amd as T
+    w = synth.ternary((co, ci) + k, 0.5, 53, synth.T_WGT)
+    got = G.words(T.tern_pack_filters(G.dev(w)))
+    want = G.bank_layout(oracle.pack(w), co, ci)
+    np.testing.assert_array_equal(got, want)
+
+
+# ---- a2-a5: tern_conv3d on small shapes that span tiles and ragged tails --------------------
+SMALL = [
+    # name, n, c_in, c_out, vol, k, stride, pad, dil
+    ("c1",        1,   1,   5, (9, 10, 11), 3, 1, 1, 1),
+    ("c3",        2,   3,   7, (5, 7, 9),   3, 1, 1, 1),
+    ("c16",       1,  16,  32, (8, 8, 8),   3, 1, 1, 1),
+    ("c31",       1,  31,  33, (6, 9, 17),  3, 1, 1, 1),
+    ("c33",       1,  33,  40, (10, 9, 8),  3, 1, 1, 1),
+    ("c64",       1,  64,  64, (9, 17, 10), 3, 1, 1, 1),
+    ("c96",       1,  96,  70, (5, 8, 9),   3, 1, 1, 1),
+    ("c128",      2, 128,  32, (4, 9, 8),   3, 1, 1, 1),
+    ("c256",      1, 256,  48, (5, 6, 9),   3, 1, 1, 1),
+    ("tiny_vol",  1,  32,  32, (2, 3, 2),   3, 1, 1, 1),
+    ("s2_odd",    1,  32,  32, (9, 11, 13), 3, 2, 1, 1),
+    ("s2_even",   2,  16,  32, (8, 12, 16), 3, 2, 1, 1),
+    ("dil2",      1,  32,  16, (9, 10, 11), 3, 1, 2, 2),
+    ("dil3",      1,  64,  32, (10, 9, 12), 3, 1, 3, 3),
+    ("k1",        1,  64,  64, (5, 9, 11),  1, 1, 0, 1),
+    ("valid",     1,  32,  32, (7, 9, 11),  3, 1, 0, 1),
+    ("aniso",     1,  40,  24, (6, 11, 12), (1, 3, 2), (1, 2, 1), (0, 2, 1), (1, 2, 1)),
+    ("k5_s3",     1,   8,  16, (11, 12, 13), (5, 3, 1), (3, 1, 2), (2, 1, 0), (1, 1, 1)),
+    ("batch3",    3,  32,  64, (4, 8, 8),   3, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("spec", SMALL, ids=[s[0] for s in SMALL])
+def test_conv_small_shapes(G, spec):
+    name, n, ci, co, vol, k, s, p, d = spec
+    c = synth.conv_case(name, n, ci, co, vol, k, s, p, d, p0_w=0.5, p0_a=0.4, seed=61)
+    check_case(G, c)
+
+
+def test_conv_no_zeros_and_all_zero_inputs(G):
+    # binary special case (Eq. 8): no zeros anywhere
+    c = synth.conv_case("binary", 1, 64, 32, (6, 8, 8), p0_w=0.0, p0_a=0.0, seed=67)
+    check_case(G, c)
+    # all-zero weights / activations give all-zero accumulators
+    z = synth.conv_case("zeros", 1, 32, 32, (4, 8, 8), p0_w=1.0, p0_a=0.4, seed=67)
+    acc, packed = G.run_case(z)
+    assert not acc.any()
+    want_acc, want_packed = expect(z)
+    np.testing.assert_array_equal(packed, want_packed)
+
+
+def test_conv_ignores_sign_bits_under_clear_mask(G):
+    import torch
+    import paper_1801_09449_amd as T
+    c = synth.conv_case("noncanon", 1, 64, 32, (5, 8, 9), seed=71)
+    act = T.tern_pack(G.dev(c.act))
+    dirty = act.clone()
+    dirty[..., 1, :] = -1          # set every sign bit, also where the mask is clear
+    bank = T.tern_pack_filters(G.dev(c.wgt))
+    a = T.tern_conv3d(act, 64, bank, 32)
+    # a set sign under a set mask flips the value, so compare against the oracle on flipped data
+    flipped = np.where(c.act != 0, -np.abs(c.act), 0).astype(np.int8)
+    b = T.tern_conv3d(dirty, 64, bank, 32)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(a.cpu().numpy(), oracle.conv3d(c.act, c.wgt, geom_of(c)))
+    np.testing.assert_array_equal(b.cpu().numpy(), oracle.conv3d(flipped, c.wgt, geom_of(c)))
+
+
+def test_conv_extreme_cut_points(G):
+    import paper_1801_09449_amd as T
+    c = synth.conv_case("extreme", 1, 32, 32, (4, 8, 8), seed=73)
+    i32 = np.iinfo(np.int32)
+    c.lo = np.where(np.arange(32) % 4 == 0, i32.min, np.where(np.arange(32) % 4 == 1, i32.max, c.lo)).astype(np.int32)
+    c.hi = np.where(np.arange(32) % 4 == 0, i32.max, np.where(np.arange(32) % 4 == 1, i32.max,
+                    np.where(np.arange(32) % 4 == 2, i32.min, c.hi))).astype(np.int32)
+    c.lo = np.minimum(c.lo, c.hi)
+    check_case(G, c)
+
+
+def test_fused_equals_unfused_and_deterministic(G):
+    import torch
+    import paper_1801_09449_amd as T
+    c = synth.conv_case("p12", 1, 64, 64, (10, 16, 16), seed=79)
+    act = T.tern_pack(G.dev(c.act)); bank = T.tern_pack_filters(G.dev(c.wgt))
+    lo, hi = G.dev(c.lo), G.dev(c.hi)
+    acc = T.tern_conv3d(act, 64, bank, 64)
+    unfused = T.tern_threshold_pack(acc, lo, hi)
+    fused1 = T.tern_conv3d(act, 64, bank, 64, thr_lo=lo, thr_hi=hi)
+    fused2 = T.tern_conv3d(act, 64, bank, 64, thr_lo=lo, thr_hi=hi)
+    torch.cuda.synchronize()
+    assert torch.equal(fused1, unfused) and torch.equal(fused1, fused2)
+
+
+def test_generic_fallback_for_oversized_halo(G):
+    # dilation so large that no halo tile fits in LDS: the library falls back to the direct kernel
+    c = synth.conv_case("fallback", 1, 40, 33, (20, 21, 22), k=3, stride=1, pad=60, dil=60, seed=83)
+    check_case(G, c)
+    c2 = synth.conv_case("fallback2", 1, 8, 8, (70, 9, 9), k=(2, 1, 1), stride=1, pad=(0, 0, 0),
+                         dil=(64, 1, 1), seed=83)
+    check_case(G, c2)
+
+
+# ---- BASELINE configurations -----------------------------------------------------------------
+def test_config0_full(G):
+    check_case(G, synth.config0())
+
+
+def test_config1_full(G):
+    check_case(G, synth.config1())
+
+
+def sample_points(shape, count, seed):
+    n, co, d, h, w = shape
+    u = synth.uniform01(5 * count, seed, 9).reshape(count, 5)
+    pts = np.floor(u * np.array([n, co, d, h, w])).astype(np.int32)
+    # always include the corners and the last element
+    extra = np.array([[0, 0, 0, 0, 0], [n - 1, co - 1, d - 1, h - 1, w - 1], [0, co - 1, 0, h - 1, 0],
+                      [n - 1, 0, d - 1, 0, w - 1]], np.int32)
+    return np.concatenate([pts, extra])
+
+
+def check_sampled(G, c, count=20000):
+    """Full-size run; the oracle computes a random sample of outputs one by one."""
+    acc, packed = G.run_case(c)
+    pts = sample_points(acc.shape, count, 97)
+    want = oracle.conv3d_points(c.act, c.wgt, geom_of(c), pts)
+    got = acc[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3], pts[:, 4]]
+    np.testing.assert_array_equal(got, want)
+    # codes at the same points, decoded from the packed words
+    co = pts[:, 1]
+    mw = packed[pts[:, 0], pts[:, 2], pts[:, 3], pts[:, 4], 0, co // 32]
+    sw = packed[pts[:, 0], pts[:, 2], pts[:, 3], pts[:, 4], 1, co // 32]
+    m = (mw >> (co % 32).astype(np.uint32)) & 1
+    s = (sw >> (co % 32).astype(np.uint32)) & 1
+    code = m.astype(np.int8) * (1 - 2 * s.astype(np.int8))
+    want_code = np.where(want > c.hi[co], 1, np.where(want < c.lo[co], -1, 0))
+    np.testing.assert_array_equal(code, want_code)
+    # properties that hold everywhere: canonical packing, bounded accumulators
+    assert not (packed[..., 1, :] & ~packed[..., 0, :]).any()
+    bound = c.act.shape[1] * int(np.prod(c.k))
+    assert np.abs(acc).max() <= bound
+    # and the fused output equals thresholding the accumulator tensor everywhere
+    np.testing.assert_array_equal(packed, oracle.pack(oracle.threshold(acc, c.lo, c.hi)))
+
+
+def test_config3_reduced_full_and_full_size_sampled(G):
+    check_case(G, synth.config3(vol=(6, 9, 10), n=2))
+    check_sampled(G, synth.config3())
+
+
+def test_config4_reduced_full(G):
+    for c in synth.config4_cases(vol=(12, 13, 20)):
+        check_case(G, c)
+
+
+def test_config4_full_size_sampled(G):
+    cases = synth.config4_cases()
+    for c in cases:
+        if c.name in ("cfg4_k3_d1_pw0.5", "cfg4_k3_d3_pw0.7", "cfg4_k3_d2_pw0.3", "cfg4_k1_pw0.5"):
+            check_sampled(G, c, count=8000)
+
+
+def fcn_run(G, f):
+    import paper_1801_09449_amd as T
+    layers = []
+    for L in f.layers:
+        layers.append(T.FcnLayer(c_in=L["w"].shape[1], c_out=L["w"].shape[0],
+                                 w_bank=T.tern_pack_filters(G.dev(L["w"])),
+                                 thr_lo=G.dev(L["lo"]), thr_hi=G.dev(L["hi"]),
+                                 k=L["k"], stride=L["stride"], pad=L["pad"], dil=L["dil"]))
+    out, views = T.tern_fcn_forward(G.dev(f.x), G.dev(f.in_lo), G.dev(f.in_hi), layers, return_layers=True)
+    import torch
+    torch.cuda.synchronize()
+    return [(G.words(v), dm) for v, dm in views]
+
+
+def fcn_expect(f):
+    layers = [dict(w=L["w"], geom=ConvGeom(L["k"], L["stride"], L["pad"], L["dil"]), lo=L["lo"], hi=L["hi"])
+              for L in f.layers]
+    return oracle.fcn_forward(f.x, f.in_lo, f.in_hi, layers)
+
+
+def test_config2_fcn_reduced(G):
+    f = synth.config2(seed=3, vol=(16, 24, 16))
+    got = fcn_run(G, f)
+    want = fcn_expect(f)
+    assert len(got) == 6
+    for (w, dm), code in zip(got, want):
+        assert tuple(dm) == code.shape
+        np.testing.assert_array_equal(w, oracle.pack(code))
+    assert got[-1][1] == (1, 128, 2, 3, 2)
+
+
+def test_config2_fcn_full(G):
+    f = synth.config2()
+    got = fcn_run(G, f)
+    want = fcn_expect(f)
+    for i, ((w, dm), code) in enumerate(zip(got, want)):
+        assert tuple(dm) == code.shape, f"layer {i + 1}"
+        np.testing.assert_array_equal(w, oracle.pack(code), err_msg=f"layer {i + 1}")
+    assert got[-1][1] == (1, 128, 16, 16, 8)
+    # the synthetic cut points keep the activations from collapsing
+    zero_frac = float(np.mean(want[-1] == 0))
+    assert 0.15 < zero_frac < 0.7
