@@ -121,6 +121,15 @@ def main():
                      "frac": lane_ops / PEAK_LANE_OPS, "traffic": None},
     }
 
+    # Sustained issue rate of the same instruction mix with no memory traffic (measured ceiling).
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    p_blocks, p_threads, p_iters = 8192, 256, 2000
+    ms_probe, _ = timed(lambda: T.tern_probe_valu(p_blocks, p_threads, p_iters, sink), 3, 1, None)
+    probe_rate = p_blocks * p_threads * p_iters * 65.0 / (ms_probe * 1e-3)
+    result["roofline"]["measured_peak"] = probe_rate / 1e12
+    result["roofline"]["frac_of_measured_peak"] = (lane_ops / probe_rate) if probe_rate > 0 else None
+    result["roofline"]["issued_frac_of_measured_peak"] = (0.8 * lane_ops / probe_rate) if probe_rate > 0 else None
+
     if args.extras:
         ex = {}
         ms_acc, _ = timed(lambda: T.tern_conv3d(act, c_in, bank, c_out, out=out_acc, **geom), 50, 5, None)

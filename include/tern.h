@@ -176,6 +176,16 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
                      uint32_t* out_packed, tern_dims* out_dims /* host */,
                      uint32_t** layer_out /* host, optional */, void* stream);
 
+/*
+ * tern_probe_valu -- diagnostic, no counterpart in the paper: runs `iters` rounds of the
+ * convolution's instruction mix (16 word pairs = 64 integer vector instructions plus one add per
+ * round and lane) on blocks x threads lanes with no memory traffic.  Timing it gives the sustained
+ * lane-operation rate of the device, the measured ceiling for section 2's bit-count argument on
+ * this hardware.  sink: device int32[1] (practically never written).  threads: multiple of 64,
+ * at most 512.
+ */
+int tern_probe_valu(int32_t blocks, int32_t threads, int32_t iters, int32_t* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     tern_pack,
     tern_pack_filters,
     tern_packed_bytes,
+    tern_probe_valu,
     tern_threshold_pack,
     tern_words,
     FcnLayer,

@@ -71,6 +71,7 @@ def lib():
     L.tern_fcn_forward.argtypes = [P, Dims, P, P, C.POINTER(Layer), I, P, S, P, C.POINTER(Dims),
                                    C.POINTER(C.c_void_p), P]
     L.tern_fcn_forward.restype = C.c_int
+    L.tern_probe_valu.argtypes = [I, I, I, P, P]; L.tern_probe_valu.restype = C.c_int
     _lib = L
     return L
 
@@ -335,3 +336,10 @@ def tern_fcn_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor,
                 dm[0], dm[2], dm[3], dm[4], 2, tern_words(dm[1]))
             views.append((v, dm))
     return out, views
+
+
+def tern_probe_valu(blocks: int, threads: int, iters: int, sink: torch.Tensor) -> None:
+    """Diagnostic: enqueue the instruction-mix probe (65 * iters vector instructions per lane)."""
+    _dev(sink, torch.int32, "sink")
+    _check(lib().tern_probe_valu(int(blocks), int(threads), int(iters), _ptr(sink), _stream(sink)),
+           "tern_probe_valu")

@@ -27,6 +27,22 @@ namespace {
 constexpr int kMaxThreads = 512;         // 8 waves: at most 2 waves per SIMD, <= 256 VGPRs
 constexpr int kLdsLimit = 160 * 1024;    // LDS per compute unit / per workgroup on gfx950
 
+// Largest dynamic LDS allocation the current device grants one workgroup (queried once per
+// device; 0 on error).
+int lds_limit_for_current_device()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess)
+            return 0;
+        cached[dev] = v < kLdsLimit ? v : kLdsLimit;
+    }
+    return cached[dev];
+}
+
 struct TileParams {
     int32_t nwx, nwy, nwz;        // waves per workgroup along x, y, z
     int32_t hx, hy, hz;           // halo tile extents in voxels
@@ -363,7 +379,8 @@ int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, d
         TERN_HIP_CHECK(hipGetDevice(&dev));
         if (raised_on_device != dev) {
             TERN_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLimit));
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               lds_limit_for_current_device()));
             raised_on_device = dev;
         }
     }
@@ -414,7 +431,7 @@ int launch_conv3d(const ConvParams& p, hipStream_t s)
         t = best;
     }
     const int64_t lds_bytes = lds_for(t);
-    if (lds_bytes > kLdsLimit) return launch_conv3d_generic(p, s);
+    if (lds_bytes > lds_limit_for_current_device()) return launch_conv3d_generic(p, s);
 
     t.hx = halo(8 * t.nwx, p.sw, p.kw, p.dw);
     t.hy = halo(8 * t.nwy, p.sh, p.kh, p.dh);
