@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", action="store_true", help="also time the other entry points")
+    ap.add_argument("--lane-depth", type=int, default=0, help="tuning override: 0 auto, 2 or 4")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is "
@@ -86,6 +87,7 @@ def main():
     import synth
 
     T.lib()
+    T.tern_set_option(1, args.lane_depth)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()

@@ -176,6 +176,13 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
                      uint32_t* out_packed, tern_dims* out_dims /* host */,
                      uint32_t** layer_out /* host, optional */, void* stream);
 
+/* Tuning overrides (process-wide, not thread-safe against concurrent launches; defaults are
+ * chosen per call from the problem size).  TERN_OPT_LANE_DEPTH: output voxels per lane along z in
+ * the tiled convolution kernel, 0 = choose automatically, 2 or 4 = force.  Results never depend
+ * on options.  Returns TERN_EARG for an unknown option or value. */
+typedef enum { TERN_OPT_LANE_DEPTH = 1 } tern_option;
+int tern_set_option(int option, int value);
+
 /*
  * tern_probe_valu -- diagnostic, no counterpart in the paper: runs `iters` rounds of the
  * convolution's instruction mix (16 word pairs = 64 integer vector instructions plus one add per

@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     tern_pack_filters,
     tern_packed_bytes,
     tern_probe_valu,
+    tern_set_option,
     tern_threshold_pack,
     tern_words,
     FcnLayer,

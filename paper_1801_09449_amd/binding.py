@@ -71,6 +71,7 @@ def lib():
     L.tern_fcn_forward.argtypes = [P, Dims, P, P, C.POINTER(Layer), I, P, S, P, C.POINTER(Dims),
                                    C.POINTER(C.c_void_p), P]
     L.tern_fcn_forward.restype = C.c_int
+    L.tern_set_option.argtypes = [C.c_int, C.c_int]; L.tern_set_option.restype = C.c_int
     L.tern_probe_valu.argtypes = [I, I, I, P, P]; L.tern_probe_valu.restype = C.c_int
     _lib = L
     return L
@@ -343,3 +344,8 @@ def tern_probe_valu(blocks: int, threads: int, iters: int, sink: torch.Tensor) -
     _dev(sink, torch.int32, "sink")
     _check(lib().tern_probe_valu(int(blocks), int(threads), int(iters), _ptr(sink), _stream(sink)),
            "tern_probe_valu")
+
+
+def tern_set_option(option: int, value: int) -> None:
+    """Tuning override (1 = lane depth: 0 auto, 2, 4).  Results never depend on options."""
+    _check(lib().tern_set_option(int(option), int(value)), "tern_set_option")

@@ -113,6 +113,16 @@ const char* tern_status_string(int status)
     }
 }
 
+int tern_set_option(int option, int value)
+{
+    if (option == TERN_OPT_LANE_DEPTH) {
+        if (value != 0 && value != 2 && value != 4) return TERN_EARG;
+        set_lane_depth(value);
+        return TERN_OK;
+    }
+    return TERN_EARG;
+}
+
 int tern_pack(const int8_t* src, tern_dims dims, uint32_t* dst_packed, void* stream)
 {
     if (!src || !dst_packed) return TERN_ENULL;

@@ -73,15 +73,29 @@ __device__ __forceinline__ ActChunk<WC> lds_read_chunk(const uint32_t* p)
     return a;
 }
 
-// Filter words are read through the constant address space so that the wave-uniform loads go
-// through the scalar cache (s_load) into SGPRs; the filter bank is never written by these
-// kernels.
+// Filter words and cut points are read through the constant address space so that the
+// wave-uniform loads go through the scalar cache (s_load) into SGPRs; neither is written by
+// these kernels.
 typedef const uint32_t __attribute__((address_space(4)))* scalar_ptr;
 
 // acc += popcount(x) as the single instruction the hardware has for it.
 __device__ __forceinline__ void popc_acc(int32_t& acc, uint32_t x)
 {
     asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
+}
+
+// word = (word << 1) | (thr < d): the comparison result goes through the carry flag into the
+// low bit, two instructions per decision and no overflow cases.
+__device__ __forceinline__ void shift_in_gt(uint32_t& word, int32_t d, int32_t thr)
+{
+    asm("v_cmp_lt_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+        : "+v"(word) : "v"(d), "s"(thr) : "vcc");
+}
+// word = (word << 1) | (d < thr)
+__device__ __forceinline__ void shift_in_lt(uint32_t& word, int32_t d, int32_t thr)
+{
+    asm("v_cmp_gt_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+        : "+v"(word) : "v"(d), "s"(thr) : "vcc");
 }
 
 constexpr int kGroup = 8;  // output channels whose filter words are fetched together
@@ -145,6 +159,69 @@ __device__ __forceinline__ void mac_group(const ActChunk<WC> (&A)[V], const WGro
                 popc_acc(acc_m[v][j0 + j], M);
                 popc_acc(acc_n[v][j0 + j], N);
             }
+}
+
+// Scalar walk over (tap, chunk) steps.
+struct StepCursor {
+    int tb, tc, ch;   // kernel row, column and channel chunk of the current step
+    int toff;         // LDS word offset of its tap
+};
+
+// Loop-invariant scalars of the walk.
+struct StepConsts {
+    int kw, kh, nchunk;
+    int inc_c, inc_b, inc_a;   // LDS offset increments: next column / next row / next plane
+    int step_words;            // filter-bank words per step
+    int vstep;                 // LDS words between a lane's consecutive voxels
+};
+
+// One step: accumulate CO_BLK channels from A0 (this step's activations) while fetching the next
+// step's activations into A1.  Software pipeline: while a channel group is being accumulated,
+// the scalar loads of the following group and the LDS reads of the next step are in flight.
+template <int WC, int V, int CO_BLK>
+__device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<WC> (&A1)[V], bool last,
+                                          StepCursor& cur, const StepConsts& sc, WGroup<WC>& g0,
+                                          WGroup<WC>& g1, scalar_ptr& wcur, scalar_ptr wblk,
+                                          const uint32_t* lane_lds, int32_t (&acc_m)[V][CO_BLK],
+                                          int32_t (&acc_n)[V][CO_BLK])
+{
+    constexpr int NG = CO_BLK / kGroup;
+    // LDS offset of the following step (after the last step: step 0 again, whose prefetched
+    // data is not used; this keeps every address in bounds)
+    int nch = cur.ch + 1, ntoff = cur.toff;
+    if (nch == sc.nchunk) {
+        nch = 0;
+        if (++cur.tc == sc.kw) {
+            cur.tc = 0;
+            if (++cur.tb == sc.kh) { cur.tb = 0; ntoff += sc.inc_a; }
+            else ntoff += sc.inc_b;
+        } else ntoff += sc.inc_c;
+    }
+    if (last) { nch = 0; ntoff = 0; }
+    scalar_ptr wnext = last ? wblk : wcur + sc.step_words;
+#pragma unroll
+    for (int gi = 0; gi < NG; gi += 2) {
+        settle<WC>(g0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (gi == 0) {
+            // issued behind the wait so that they complete under the first group's arithmetic
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+                A1[v] = lds_read_chunk<WC>(lane_lds + v * sc.vstep + ntoff + nch * 2 * WC);
+        }
+        load_wgroup<WC>(g1, wcur + (gi + 1) * kGroup * 2 * WC);
+        __builtin_amdgcn_sched_barrier(0);
+        mac_group<WC, V, CO_BLK>(A0, g0, gi * kGroup, acc_m, acc_n);
+        __builtin_amdgcn_sched_barrier(0);
+        settle<WC>(g1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (gi + 2 < NG) load_wgroup<WC>(g0, wcur + (gi + 2) * kGroup * 2 * WC);
+        else load_wgroup<WC>(g0, wnext);
+        __builtin_amdgcn_sched_barrier(0);
+        mac_group<WC, V, CO_BLK>(A0, g1, (gi + 1) * kGroup, acc_m, acc_n);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    cur.ch = nch; cur.toff = ntoff; wcur = wnext;
 }
 
 template <int WC, int V, int CO_BLK, bool PACKED>
@@ -223,16 +300,20 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int nsteps = T * t.nchunk;
     // scalar increments of the LDS offset when the tap advances along x / wraps to the next
     // row / wraps to the next plane
-    const int inc_c = p.dw * t.vstride;
-    const int inc_b = p.dh * row_words - (p.kw - 1) * inc_c;
-    const int inc_a = p.dd * plane_words - (p.kh - 1) * p.dh * row_words - (p.kw - 1) * inc_c;
-    const int step_words = p.co_pad * 2 * WC;  // filter-bank words per step
+    StepConsts sc;
+    sc.kw = p.kw; sc.kh = p.kh; sc.nchunk = t.nchunk;
+    sc.inc_c = p.dw * t.vstride;
+    sc.inc_b = p.dh * row_words - (p.kw - 1) * sc.inc_c;
+    sc.inc_a = p.dd * plane_words - (p.kh - 1) * p.dh * row_words - (p.kw - 1) * sc.inc_c;
+    sc.step_words = p.co_pad * 2 * WC;
+    sc.vstep = vstep;
     constexpr int NG = CO_BLK / kGroup;
     static_assert(NG >= 2 && NG % 2 == 0, "CO_BLK must be a multiple of 2*kGroup");
+    static_assert(CO_BLK <= 32 && 32 % CO_BLK == 0, "CO_BLK must divide 32");
 
-    uint32_t out_m[V], out_s[V];  // packed mode: words being assembled
+    uint32_t pos_w[V], neg_w[V];  // packed mode: decision bits of the 32-channel word in progress
 #pragma unroll
-    for (int v = 0; v < V; ++v) out_m[v] = out_s[v] = 0u;
+    for (int v = 0; v < V; ++v) pos_w[v] = neg_w[v] = 0u;
 
     // The filter bank is padded with all-zero channels up to a multiple of 32, so a channel
     // block may run past c_out: the surplus accumulators stay 0 and are dropped below.
@@ -243,99 +324,64 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
 #pragma unroll
             for (int j = 0; j < CO_BLK; ++j) acc_m[v][j] = acc_n[v][j] = 0;
 
-        const int co_left = co_end - cb;
         scalar_ptr wblk = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC;
 
-        // Software pipeline: while a channel group of step i is being accumulated, the scalar
-        // loads of the following group and the LDS reads of step i+1 are in flight.
-        ActChunk<WC> A[V];
         WGroup<WC> g0, g1;
+        scalar_ptr wcur = wblk;  // filter words of the current step
+        StepCursor cur = {0, 0, 0, 0};
+
+        ActChunk<WC> Aa[V], Ab[V];
 #pragma unroll
-        for (int v = 0; v < V; ++v) A[v] = lds_read_chunk<WC>(lane_lds + v * vstep);
+        for (int v = 0; v < V; ++v) Aa[v] = lds_read_chunk<WC>(lane_lds + v * vstep);
         load_wgroup<WC>(g0, wblk);
-
-        int tb = 0, tc = 0, ch = 0;  // row / column / chunk of the step being accumulated
-        int toff = 0;                // its LDS word offset (tap part)
-        scalar_ptr wcur = wblk;      // its filter words
-        for (int step = 0; step < nsteps; ++step) {
-            // LDS offset of the following step (after the last step: step 0 again, whose
-            // prefetched data is not used; this keeps every address in bounds)
-            int nch = ch + 1, ntoff = toff;
-            if (nch == t.nchunk) {
-                nch = 0;
-                if (++tc == p.kw) {
-                    tc = 0;
-                    if (++tb == p.kh) { tb = 0; ntoff += inc_a; }
-                    else ntoff += inc_b;
-                } else ntoff += inc_c;
-            }
-            const bool last = step + 1 == nsteps;
-            if (last) { nch = 0; ntoff = 0; }
-            scalar_ptr wnext = last ? wblk : wcur + step_words;
-
-            ActChunk<WC> An[V];
-#pragma unroll
-            for (int gi = 0; gi < NG; gi += 2) {
-                settle<WC>(g0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (gi == 0) {
-                    // LDS reads of the following step, issued behind the wait so that they
-                    // complete under the arithmetic of the first group
-#pragma unroll
-                    for (int v = 0; v < V; ++v)
-                        An[v] = lds_read_chunk<WC>(lane_lds + v * vstep + ntoff + nch * 2 * WC);
-                }
-                load_wgroup<WC>(g1, wcur + (gi + 1) * kGroup * 2 * WC);
-                __builtin_amdgcn_sched_barrier(0);
-                mac_group<WC, V, CO_BLK>(A, g0, gi * kGroup, acc_m, acc_n);
-                __builtin_amdgcn_sched_barrier(0);
-                settle<WC>(g1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (gi + 2 < NG) load_wgroup<WC>(g0, wcur + (gi + 2) * kGroup * 2 * WC);
-                else load_wgroup<WC>(g0, wnext);
-                __builtin_amdgcn_sched_barrier(0);
-                mac_group<WC, V, CO_BLK>(A, g1, (gi + 1) * kGroup, acc_m, acc_n);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int v = 0; v < V; ++v) A[v] = An[v];
-            ch = nch; toff = ntoff; wcur = wnext;
+        int step = 0;
+        for (; step + 2 <= nsteps; step += 2) {   // two steps per trip: no register copies
+            conv_step<WC, V, CO_BLK>(Aa, Ab, false, cur, sc, g0, g1, wcur, wblk, lane_lds, acc_m, acc_n);
+            conv_step<WC, V, CO_BLK>(Ab, Aa, step + 2 == nsteps, cur, sc, g0, g1, wcur, wblk, lane_lds,
+                                     acc_m, acc_n);
         }
+        if (step < nsteps)
+            conv_step<WC, V, CO_BLK>(Aa, Ab, true, cur, sc, g0, g1, wcur, wblk, lane_lds, acc_m, acc_n);
 
         // ---- epilogue ----------------------------------------------------------------------
+        const int co_left = co_end - cb;
         if constexpr (PACKED) {
+            // Cut points of this block: one bulk scalar fetch, then two decisions per
+            // (voxel, channel), highest channel first so that channel j ends up in bit j.
             scalar_ptr thr_lo = (scalar_ptr)(uintptr_t)p.lo;
             scalar_ptr thr_hi = (scalar_ptr)(uintptr_t)p.hi;
-            // Shift one decision bit per channel into a partial word, highest channel first.
-            uint32_t pm[V], ps[V];
+            int32_t lo[CO_BLK], hi[CO_BLK];
+            if (co_left >= CO_BLK) {
 #pragma unroll
-            for (int v = 0; v < V; ++v) pm[v] = ps[v] = 0u;
+                for (int j = 0; j < CO_BLK; ++j) {
+                    lo[j] = (int32_t)thr_lo[cb + j];
+                    hi[j] = (int32_t)thr_hi[cb + j];
+                }
+            } else {
 #pragma unroll
-            for (int j = CO_BLK - 1; j >= 0; --j) {
-                const bool live = j < co_left;
-                const int cj = min(cb + j, p.c_out - 1);
-                // |acc| < 2^24, so cut points beyond +-2^30 decide like +-infinity and the
-                // differences below cannot overflow.  Channels past c_out get cut points that
-                // never fire, i.e. zero bits.
-                int32_t hi = (int32_t)thr_hi[cj];
-                int32_t lo = (int32_t)thr_lo[cj];
-                hi = live ? max(min(hi, 1 << 30), -(1 << 30)) : (1 << 30);
-                lo = live ? max(min(lo, 1 << 30), -(1 << 30)) : -(1 << 30);
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    const int32_t acc = acc_m[v][j] - 2 * acc_n[v][j];
-                    const uint32_t pos = (uint32_t)(hi - acc) >> 31;            // acc > hi
-                    const uint32_t neg = ((uint32_t)(acc - lo) >> 31) & ~pos;   // acc < lo
-                    pm[v] = (pm[v] << 1) | (pos | neg);
-                    ps[v] = (ps[v] << 1) | neg;
+                for (int j = 0; j < CO_BLK; ++j) {
+                    const int cj = min(cb + j, p.c_out - 1);
+                    const int32_t l = (int32_t)thr_lo[cj], h = (int32_t)thr_hi[cj];
+                    // channels past c_out: cut points that never fire, i.e. zero bits
+                    lo[j] = j < co_left ? l : INT32_MIN;
+                    hi[j] = j < co_left ? h : INT32_MAX;
                 }
             }
-            const int sh = cb & 31;  // CO_BLK divides 32 or is a multiple of it
+            uint32_t pp[V], pn[V];
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                if constexpr (CO_BLK >= 32) { out_m[v] = pm[v]; out_s[v] = ps[v]; }
-                else { out_m[v] |= pm[v] << sh; out_s[v] |= ps[v] << sh; }
+            for (int v = 0; v < V; ++v) pp[v] = pn[v] = 0u;
+#pragma unroll
+            for (int j = CO_BLK - 1; j >= 0; --j) {
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const int32_t d = acc_m[v][j] - 2 * acc_n[v][j];
+                    shift_in_gt(pp[v], d, hi[j]);   // +1 if acc > hi
+                    shift_in_lt(pn[v], d, lo[j]);   // -1 if acc < lo
+                }
             }
+            const int sh = cb & 31;
+#pragma unroll
+            for (int v = 0; v < V; ++v) { pos_w[v] |= pp[v] << sh; neg_w[v] |= pn[v] << sh; }
             const bool flush = ((cb + CO_BLK) & 31) == 0 || cb + CO_BLK >= co_end;
             if (flush) {
                 const int q = cb >> 5;
@@ -345,10 +391,10 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
                     if (ox < p.ow && oy < p.oh && oz < p.od) {
                         uint32_t* o = p.out_packed +
                                       ((((size_t)n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
-                        o[q] = out_m[v];
-                        o[p.wd_out + q] = out_s[v];
+                        o[q] = pos_w[v] | neg_w[v];               // nonzero mask
+                        o[p.wd_out + q] = neg_w[v] & ~pos_w[v];   // sign; +1 wins if lo > hi
                     }
-                    out_m[v] = out_s[v] = 0u;
+                    pos_w[v] = neg_w[v] = 0u;
                 }
             }
         } else {
@@ -391,32 +437,23 @@ int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, d
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-}  // namespace
-
-int launch_conv3d(const ConvParams& p, hipStream_t s)
+// Tile plan for a voxel depth V per lane; returns false if no halo tile fits in LDS.
+bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_t& lds_bytes)
 {
-    const bool packed = p.out_packed != nullptr;
     const int wd = p.wd_in;
-    const int WC = p.wc;
-    const int V = 2, CO_BLK = 32;
-
-    TileParams t;
-    t.nchunk = wd / WC;
+    t.nchunk = wd / p.wc;
     t.vstride = 2 * wd + (wd >= 4 ? 4 : 0);
-
-    // Workgroup shape: start from one wave per workgroup and stack waves along z while the
-    // halo tile stays small and there are plenty of workgroups; dilated kernels amortise their
-    // wide halo better over larger tiles.
     t.nwx = 1; t.nwy = 1; t.nwz = 1;
-    auto halo = [&](int tiles_out, int stride, int k, int dil) { return (tiles_out - 1) * stride + (k - 1) * dil + 1; };
+    auto halo = [](int tiles_out, int stride, int k, int dil) { return (tiles_out - 1) * stride + (k - 1) * dil + 1; };
     auto lds_for = [&](const TileParams& q) {
         const int64_t hx = halo(8 * q.nwx, p.sw, p.kw, p.dw);
         const int64_t hy = halo(8 * q.nwy, p.sh, p.kh, p.dh);
         const int64_t hz = halo(V * q.nwz, p.sd, p.kd, p.dd);
         return hx * hy * hz * q.vstride * 4;
     };
-    // Grow the tile while the per-wave LDS share is too large for two waves per SIMD
-    // (8 waves per compute unit => 20 KB per wave of the 160 KB).
+    // Start from one wave per workgroup; grow the tile (stacking waves along the axis that
+    // lowers LDS per wave the most) while the per-wave LDS share is too large for eight waves
+    // per compute unit (20 KB per wave of the 160 KB).
     for (int it = 0; it < 6; ++it) {
         const int waves = t.nwx * t.nwy * t.nwz;
         if (lds_for(t) <= (int64_t)waves * 20 * 1024 || waves >= 8) break;
@@ -430,37 +467,67 @@ int launch_conv3d(const ConvParams& p, hipStream_t s)
         }
         t = best;
     }
-    const int64_t lds_bytes = lds_for(t);
-    if (lds_bytes > lds_limit_for_current_device()) return launch_conv3d_generic(p, s);
-
+    lds_bytes = lds_for(t);
+    if (lds_bytes > lds_limit) return false;
     t.hx = halo(8 * t.nwx, p.sw, p.kw, p.dw);
     t.hy = halo(8 * t.nwy, p.sh, p.kh, p.dh);
     t.hz = halo(V * t.nwz, p.sd, p.kd, p.dd);
     t.tiles_x = cdiv(p.ow, 8 * t.nwx);
     t.tiles_y = cdiv(p.oh, 8 * t.nwy);
     t.tiles_z = cdiv(p.od, V * t.nwz);
+    return true;
+}
+
+int g_lane_depth = 0;   // tuning override: 0 = choose, 2 or 4 = force that voxel depth per lane
+
+}  // namespace
+
+void set_lane_depth(int v) { g_lane_depth = (v == 2 || v == 4) ? v : 0; }
+
+int launch_conv3d(const ConvParams& p, hipStream_t s)
+{
+    const bool packed = p.out_packed != nullptr;
+    const int lds_limit = lds_limit_for_current_device();
+    constexpr int kWaveSlots = 2048;   // 256 compute units x 4 SIMDs x 2 waves
+
+    // Deeper lanes (V = 4, 16 channels per pass) halve the scalar-cache traffic per instruction
+    // and double the arithmetic that hides each scalar fetch; they are used when the volume
+    // still yields enough waves to occupy the chip, otherwise V = 2 with 32 channels per pass.
+    const int co_groups = cdiv(p.c_out, 32);
+    auto waves_for = [&](const TileParams& t) {
+        return (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n * t.nwx * t.nwy * t.nwz;
+    };
+    TileParams t4, t2;
+    int64_t lds4 = 0, lds2 = 0;
+    const bool ok4 = plan_tiles(p, 4, lds_limit, t4, lds4);
+    const bool ok2 = plan_tiles(p, 2, lds_limit, t2, lds2);
+    if (!ok4 && !ok2) return launch_conv3d_generic(p, s);
+    bool use4 = ok4 && (!ok2 || waves_for(t4) * co_groups >= kWaveSlots);
+    if (g_lane_depth == 4 && ok4) use4 = true;
+    if (g_lane_depth == 2 && ok2) use4 = false;
+    TileParams t = use4 ? t4 : t2;
+    const int64_t lds_bytes = use4 ? lds4 : lds2;
     const int64_t spatial_tiles = (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n;
     if (spatial_tiles > 0x7fffffff) return TERN_ESHAPE;
 
-    // Split output channels over blockIdx.y when there are too few spatial tiles to fill the
-    // chip (2048 wave slots at two waves per SIMD).  Packed output needs whole 32-channel words.
+    // Split output channels over blockIdx.y (in whole 32-channel words) when there are too few
+    // spatial tiles to fill the chip.
     const int waves_per_wg = t.nwx * t.nwy * t.nwz;
-    const int co_gran = packed ? 32 : CO_BLK;
-    int co_groups = cdiv(p.c_out, co_gran);
     int split = 1;
-    while (split < co_groups && spatial_tiles * waves_per_wg * split < 2048) split *= 2;
+    while (split < co_groups && spatial_tiles * waves_per_wg * split < kWaveSlots) split *= 2;
     split = split < co_groups ? split : co_groups;
-    t.co_per_wg = cdiv(co_groups, split) * co_gran;
+    t.co_per_wg = cdiv(co_groups, split) * 32;
     const int grid_y = cdiv(p.c_out, t.co_per_wg);
 
     const dim3 grid((unsigned)spatial_tiles, (unsigned)grid_y);
     const int threads = 64 * waves_per_wg;
-    if (WC == 2) {
-        return packed ? launch_variant<2, 2, 32, true>(p, t, (size_t)lds_bytes, grid, threads, s)
-                      : launch_variant<2, 2, 32, false>(p, t, (size_t)lds_bytes, grid, threads, s);
-    }
-    return packed ? launch_variant<1, 2, 32, true>(p, t, (size_t)lds_bytes, grid, threads, s)
-                  : launch_variant<1, 2, 32, false>(p, t, (size_t)lds_bytes, grid, threads, s);
+    const size_t lb = (size_t)lds_bytes;
+#define TERN_LAUNCH(WC_, V_, CB_)                                                            \
+    (packed ? launch_variant<WC_, V_, CB_, true>(p, t, lb, grid, threads, s)                 \
+            : launch_variant<WC_, V_, CB_, false>(p, t, lb, grid, threads, s))
+    if (p.wc == 2) return use4 ? TERN_LAUNCH(2, 4, 16) : TERN_LAUNCH(2, 2, 32);
+    return use4 ? TERN_LAUNCH(1, 4, 16) : TERN_LAUNCH(1, 2, 32);
+#undef TERN_LAUNCH
 }
 
 }  // namespace tern
