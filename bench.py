@@ -66,6 +66,72 @@ def cpu_baseline(case, target_seconds=12.0):
     }
 
 
+def conv_times(T, dev, c, steps=30, warmup=5):
+    """(fused ms, int32-output ms) of one single-layer case."""
+    import torch
+    c_in, c_out = c.act.shape[1], c.wgt.shape[0]
+    a = T.tern_pack(dev(c.act))
+    bank = T.tern_pack_filters(dev(c.wgt))
+    lo, hi = dev(c.lo), dev(c.hi)
+    g = dict(k=c.k, stride=c.stride, pad=c.pad, dil=c.dil)
+    outp = T.tern_conv3d(a, c_in, bank, c_out, thr_lo=lo, thr_hi=hi, **g)
+    outa = T.tern_conv3d(a, c_in, bank, c_out, **g)
+    ms_f, _ = timed(lambda: T.tern_conv3d(a, c_in, bank, c_out, thr_lo=lo, thr_hi=hi, out=outp, **g), steps, warmup, None)
+    ms_a, _ = timed(lambda: T.tern_conv3d(a, c_in, bank, c_out, out=outa, **g), steps, warmup, None)
+    del a, bank, outp, outa
+    torch.cuda.empty_cache()
+    return ms_f, ms_a
+
+
+def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, geom):
+    """Timings of the other entry points and of the other BASELINE configurations."""
+    import torch
+    c_in, c_out = case.act.shape[1], case.wgt.shape[0]
+    ex = {}
+    ms_acc, _ = timed(lambda: T.tern_conv3d(act, c_in, bank, c_out, out=out_acc, **geom), 50, 5, None)
+    ex["cfg1_conv3d_int32_out_ms"] = ms_acc
+    ms_pack, _ = timed(lambda: T.tern_pack(act_i8, out=act), 50, 5, None)
+    ex["cfg1_pack_i8_ms"] = ms_pack
+    ex["cfg1_pack_i8_GBps"] = (act_i8.numel() + act.numel() * 4) / (ms_pack * 1e-3) / 1e9
+    ms_thr, _ = timed(lambda: T.tern_threshold_pack(out_acc, lo, hi, out=out_packed), 50, 5, None)
+    ex["cfg1_threshold_pack_i32_ms"] = ms_thr
+    ex["cfg1_threshold_pack_i32_GBps"] = (out_acc.numel() * 4 + out_packed.numel() * 4) / (ms_thr * 1e-3) / 1e9
+
+    def row(c):
+        f, a = conv_times(T, dev, c)
+        return {"gmac": c.macs / 1e9, "fused_ms": f, "int32_ms": a, "fused_TMACs": c.macs / (f * 1e-3) / 1e12,
+                "int32_TMACs": c.macs / (a * 1e-3) / 1e12}
+    ex["cfg0"] = row(synth.config0())
+    ex["cfg3"] = row(synth.config3())
+    for c in synth.config4_cases():
+        if c.meta["p0_w"] == 0.5:
+            ex[c.name] = row(c)
+
+    f = synth.config2()
+    layers = [T.FcnLayer(L["w"].shape[1], L["w"].shape[0], T.tern_pack_filters(dev(L["w"])),
+                         dev(L["lo"]), dev(L["hi"]), L["k"], L["stride"], L["pad"], L["dil"])
+              for L in f.layers]
+    x, ilo, ihi = dev(f.x), dev(f.in_lo), dev(f.in_hi)
+    ws = torch.empty((T.tern_fcn_workspace_bytes(x.shape, layers),), dtype=torch.uint8, device="cuda")
+    out = T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws)
+    ms_fcn, _ = timed(lambda: T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws, out=out), 30, 5, None)
+    ex["cfg2_fcn"] = {"gmac": f.macs / 1e9, "ms": ms_fcn, "TMACs": f.macs / (ms_fcn * 1e-3) / 1e12}
+    # per layer
+    cur = tuple(x.shape)
+    a_in = T.tern_threshold_pack(x, ilo, ihi)
+    per = []
+    for L in layers:
+        o = T.tern_conv3d(a_in, L.c_in, L.w_bank, L.c_out, L.k, L.stride, L.pad, L.dil, thr_lo=L.thr_lo, thr_hi=L.thr_hi)
+        ms_l, _ = timed(lambda: T.tern_conv3d(a_in, L.c_in, L.w_bank, L.c_out, L.k, L.stride, L.pad, L.dil,
+                                              thr_lo=L.thr_lo, thr_hi=L.thr_hi, out=o), 30, 5, None)
+        per.append(round(ms_l, 5))
+        a_in = o
+    ex["cfg2_fcn"]["layer_ms"] = per
+    ms_in, _ = timed(lambda: T.tern_threshold_pack(x, ilo, ihi), 30, 5, None)
+    ex["cfg2_fcn"]["input_threshold_pack_ms"] = ms_in
+    return ex
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +140,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", action="store_true", help="also time the other entry points")
     ap.add_argument("--lane-depth", type=int, default=0, help="tuning override: 0 auto, 2 or 4")
+    ap.add_argument("--waves-z", type=int, default=0, help="tuning override: 0 auto, 1, 2, 4, 8")
+    ap.add_argument("--co-block", type=int, default=0, help="tuning override: 0 auto, 16, 32")
+    ap.add_argument("--co-per-wave", type=int, default=0, help="tuning override: 0 auto, multiple of 16")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is "
@@ -88,6 +157,9 @@ def main():
 
     T.lib()
     T.tern_set_option(1, args.lane_depth)
+    T.tern_set_option(2, args.waves_z)
+    T.tern_set_option(3, args.co_block)
+    T.tern_set_option(4, args.co_per_wave)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
@@ -133,16 +205,7 @@ def main():
     result["roofline"]["issued_frac_of_measured_peak"] = (0.8 * lane_ops / probe_rate) if probe_rate > 0 else None
 
     if args.extras:
-        ex = {}
-        ms_acc, _ = timed(lambda: T.tern_conv3d(act, c_in, bank, c_out, out=out_acc, **geom), 50, 5, None)
-        ex["conv3d_int32_out_ms"] = ms_acc
-        ms_pack, _ = timed(lambda: T.tern_pack(act_i8, out=act), 50, 5, None)
-        ex["pack_i8_ms"] = ms_pack
-        ex["pack_i8_GBps"] = (act_i8.numel() + act.numel() * 4) / (ms_pack * 1e-3) / 1e9
-        ms_thr, _ = timed(lambda: T.tern_threshold_pack(out_acc, lo, hi, out=out_packed), 50, 5, None)
-        ex["threshold_pack_i32_ms"] = ms_thr
-        ex["threshold_pack_i32_GBps"] = (out_acc.numel() * 4 + out_packed.numel() * 4) / (ms_thr * 1e-3) / 1e9
-        result["extras"] = ex
+        result["extras"] = extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, geom)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(case)

@@ -178,9 +178,14 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
 
 /* Tuning overrides (process-wide, not thread-safe against concurrent launches; defaults are
  * chosen per call from the problem size).  TERN_OPT_LANE_DEPTH: output voxels per lane along z in
- * the tiled convolution kernel, 0 = choose automatically, 2 or 4 = force.  Results never depend
- * on options.  Returns TERN_EARG for an unknown option or value. */
-typedef enum { TERN_OPT_LANE_DEPTH = 1 } tern_option;
+ * the tiled convolution kernel, 0 = choose automatically, 2 or 4 = force.  TERN_OPT_WAVES_Z: waves
+ * stacked along z in one workgroup (sharing one LDS halo tile), 0 = choose, 1, 2, 4 or 8 = start
+ * from that value.  TERN_OPT_CO_BLOCK: output channels per accumulation pass, 0 = choose, 16 or 32.
+ * TERN_OPT_CO_PER_WAVE: output channels handled by one wave, 0 = choose, else a multiple of 16.
+ * Results never depend on options.  Returns TERN_EARG for an unknown option or
+ * value. */
+typedef enum { TERN_OPT_LANE_DEPTH = 1, TERN_OPT_WAVES_Z = 2, TERN_OPT_CO_BLOCK = 3,
+               TERN_OPT_CO_PER_WAVE = 4 } tern_option;
 int tern_set_option(int option, int value);
 
 /*

@@ -120,6 +120,21 @@ int tern_set_option(int option, int value)
         set_lane_depth(value);
         return TERN_OK;
     }
+    if (option == TERN_OPT_CO_BLOCK) {
+        if (value != 0 && value != 16 && value != 32) return TERN_EARG;
+        set_co_block(value);
+        return TERN_OK;
+    }
+    if (option == TERN_OPT_CO_PER_WAVE) {
+        if (value < 0 || value % 16 != 0 || value > (1 << 20)) return TERN_EARG;
+        set_co_per_wave(value);
+        return TERN_OK;
+    }
+    if (option == TERN_OPT_WAVES_Z) {
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return TERN_EARG;
+        set_waves_z(value);
+        return TERN_OK;
+    }
     return TERN_EARG;
 }
 

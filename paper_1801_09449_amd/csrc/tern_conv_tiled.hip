@@ -49,7 +49,8 @@ struct TileParams {
     int32_t tiles_x, tiles_y, tiles_z;
     int32_t vstride;              // LDS words per voxel (2*Wd plus padding)
     int32_t nchunk;               // Wd / WC
-    int32_t co_per_wg;            // output channels handled by one workgroup (blockIdx.y)
+    int32_t nwc;                  // waves per workgroup along the output-channel axis
+    int32_t co_per_wave;          // output channels handled by one wave (multiple of 16)
 };
 
 template <int WC>
@@ -244,33 +245,50 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int ox0 = tix * TX, oy0 = tiy * TY, oz0 = tiz * TZ;
 
     // ---- stage the halo tile -------------------------------------------------------------
+    // A thread owns plane positions i = tid, tid + nthreads, ... of the (hy, hx) halo plane and
+    // walks the hz planes in batches: all global loads of a batch are issued before the first
+    // LDS write, so a wave pays one memory round trip per batch instead of one per voxel.
     {
+        constexpr int FB = 8;
         const int gx0 = ox0 * p.sw - p.pw, gy0 = oy0 * p.sh - p.ph, gz0 = oz0 * p.sd - p.pd;
         const int plane = t.hy * t.hx;
         const int wd = p.wd_in;
         const uint32_t* in_n = p.in + (size_t)n * p.d * p.h * p.w * 2u * wd;
-        for (int hz = 0; hz < t.hz; ++hz) {
-            const int gz = gz0 + hz;
-            const bool zin = gz >= 0 && gz < p.d;
-            for (int i = tid; i < plane; i += nthreads) {
-                const int hy = i / t.hx;
-                const int hxx = i - hy * t.hx;
-                const int gy = gy0 + hy, gx = gx0 + hxx;
-                const bool inb = zin && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
-                const uint32_t* src = in_n + (((size_t)gz * p.h + gy) * p.w + gx) * 2u * wd;
-                uint32_t* dst = lds + (size_t)(hz * plane + i) * t.vstride;
-                for (int ch = 0; ch < t.nchunk; ++ch) {
-                    if constexpr (WC == 2) {
-                        uint2 m = make_uint2(0u, 0u), s = make_uint2(0u, 0u);
+        const size_t zstride = (size_t)p.h * p.w * 2u * wd;   // words between input planes
+        for (int i = tid; i < plane; i += nthreads) {
+            const int hy = i / t.hx;
+            const int hxx = i - hy * t.hx;
+            const int gy = gy0 + hy, gx = gx0 + hxx;
+            const bool xy_in = gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
+            const uint32_t* src_xy = in_n + ((size_t)(xy_in ? gy : 0) * p.w + (xy_in ? gx : 0)) * 2u * wd;
+            uint32_t* dst_xy = lds + (size_t)i * t.vstride;
+            for (int ch = 0; ch < t.nchunk; ++ch) {
+                for (int hz0 = 0; hz0 < t.hz; hz0 += FB) {
+                    uint4 r[FB];
+#pragma unroll
+                    for (int j = 0; j < FB; ++j) {
+                        const int gz = gz0 + hz0 + j;
+                        const bool inb = xy_in && hz0 + j < t.hz && gz >= 0 && gz < p.d;
+                        r[j] = make_uint4(0u, 0u, 0u, 0u);
                         if (inb) {
-                            m = *reinterpret_cast<const uint2*>(src + 2 * ch);
-                            s = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
+                            const uint32_t* src = src_xy + (size_t)gz * zstride;
+                            if constexpr (WC == 2) {
+                                const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
+                                const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
+                                r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
+                            } else {
+                                r[j].x = src[ch];
+                                r[j].y = src[wd + ch];
+                            }
                         }
-                        *reinterpret_cast<uint4*>(dst + 4 * ch) = make_uint4(m.x, m.y, s.x, s.y);
-                    } else {
-                        uint32_t m = 0u, s = 0u;
-                        if (inb) { m = src[ch]; s = src[wd + ch]; }
-                        *reinterpret_cast<uint2*>(dst + 2 * ch) = make_uint2(m, s);
+                    }
+#pragma unroll
+                    for (int j = 0; j < FB; ++j) {
+                        if (hz0 + j < t.hz) {
+                            uint32_t* dst = dst_xy + (size_t)(hz0 + j) * plane * t.vstride;
+                            if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst + 4 * ch) = r[j];
+                            else *reinterpret_cast<uint2*>(dst + 2 * ch) = make_uint2(r[j].x, r[j].y);
+                        }
                     }
                 }
             }
@@ -281,7 +299,8 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     // ---- this wave's voxels --------------------------------------------------------------
     const int wx = wave % t.nwx;
     const int wy = (wave / t.nwx) % t.nwy;
-    const int wz = wave / (t.nwx * t.nwy);
+    const int wz = (wave / (t.nwx * t.nwy)) % t.nwz;
+    const int wch = wave / (t.nwx * t.nwy * t.nwz);   // channel slice of this wave
     const int lx = lane & 7, ly = lane >> 3;
     const int ox = ox0 + wx * 8 + lx;
     const int oy = oy0 + wy * 8 + ly;
@@ -295,8 +314,8 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const uint32_t* lane_lds = lds + lane_base;
 
     const int T = p.kd * p.kh * p.kw;
-    const int co_begin = blockIdx.y * t.co_per_wg;
-    const int co_end = min(p.c_out, co_begin + t.co_per_wg);
+    const int co_begin = (blockIdx.y * t.nwc + wch) * t.co_per_wave;
+    const int co_end = min(p.c_out, co_begin + t.co_per_wave);
     const int nsteps = T * t.nchunk;
     // scalar increments of the LDS offset when the tap advances along x / wraps to the next
     // row / wraps to the next plane
@@ -384,15 +403,30 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
             for (int v = 0; v < V; ++v) { pos_w[v] |= pp[v] << sh; neg_w[v] |= pn[v] << sh; }
             const bool flush = ((cb + CO_BLK) & 31) == 0 || cb + CO_BLK >= co_end;
             if (flush) {
+                // This wave's bits of word q are [b0, b1).  A wave that owns only half of the
+                // word stores that half (16-bit store) so that the wave owning the other half can
+                // store its own without a read-modify-write; the low-half owner also stores the
+                // (zero) high half when no channel exists there.
                 const int q = cb >> 5;
+                const int b0 = max(co_begin, q * 32) - q * 32;
+                const int b1 = min(co_begin + t.co_per_wave, q * 32 + 32) - q * 32;
+                const bool whole = b0 == 0 && (b1 == 32 || p.c_out <= q * 32 + 16);
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     const int oz = ozb + v;
                     if (ox < p.ow && oy < p.oh && oz < p.od) {
                         uint32_t* o = p.out_packed +
                                       ((((size_t)n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
-                        o[q] = pos_w[v] | neg_w[v];               // nonzero mask
-                        o[p.wd_out + q] = neg_w[v] & ~pos_w[v];   // sign; +1 wins if lo > hi
+                        const uint32_t mk = pos_w[v] | neg_w[v];      // nonzero mask
+                        const uint32_t sg = neg_w[v] & ~pos_w[v];     // sign; +1 wins if lo > hi
+                        if (whole) {
+                            o[q] = mk;
+                            o[p.wd_out + q] = sg;
+                        } else {
+                            const int half = b0 >> 4;
+                            reinterpret_cast<uint16_t*>(o + q)[half] = (uint16_t)(mk >> b0);
+                            reinterpret_cast<uint16_t*>(o + p.wd_out + q)[half] = (uint16_t)(sg >> b0);
+                        }
                     }
                     pos_w[v] = neg_w[v] = 0u;
                 }
@@ -437,13 +471,18 @@ int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, d
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
+int g_lane_depth = 0;   // tuning override: 0 = choose, 2 or 4 = force that voxel depth per lane
+int g_waves_z = 0;      // tuning override: 0 = choose, else waves stacked along z per workgroup
+int g_co_block = 0;     // tuning override: 0 = choose, 16 or 32 = channels per accumulation pass
+int g_co_per_wave = 0;  // tuning override: 0 = choose, else channels per wave (multiple of 16)
+
 // Tile plan for a voxel depth V per lane; returns false if no halo tile fits in LDS.
 bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_t& lds_bytes)
 {
     const int wd = p.wd_in;
     t.nchunk = wd / p.wc;
     t.vstride = 2 * wd + (wd >= 4 ? 4 : 0);
-    t.nwx = 1; t.nwy = 1; t.nwz = 1;
+    t.nwx = 1; t.nwy = 1; t.nwz = g_waves_z > 0 ? g_waves_z : 1;
     auto halo = [](int tiles_out, int stride, int k, int dil) { return (tiles_out - 1) * stride + (k - 1) * dil + 1; };
     auto lds_for = [&](const TileParams& q) {
         const int64_t hx = halo(8 * q.nwx, p.sw, p.kw, p.dw);
@@ -478,55 +517,68 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     return true;
 }
 
-int g_lane_depth = 0;   // tuning override: 0 = choose, 2 or 4 = force that voxel depth per lane
-
 }  // namespace
 
 void set_lane_depth(int v) { g_lane_depth = (v == 2 || v == 4) ? v : 0; }
+void set_waves_z(int v) { g_waves_z = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
+void set_co_block(int v) { g_co_block = (v == 16 || v == 32) ? v : 0; }
+void set_co_per_wave(int v) { g_co_per_wave = (v > 0 && v % 16 == 0) ? v : 0; }
 
 int launch_conv3d(const ConvParams& p, hipStream_t s)
 {
     const bool packed = p.out_packed != nullptr;
     const int lds_limit = lds_limit_for_current_device();
-    constexpr int kWaveSlots = 2048;   // 256 compute units x 4 SIMDs x 2 waves
 
-    // Deeper lanes (V = 4, 16 channels per pass) halve the scalar-cache traffic per instruction
-    // and double the arithmetic that hides each scalar fetch; they are used when the volume
-    // still yields enough waves to occupy the chip, otherwise V = 2 with 32 channels per pass.
-    const int co_groups = cdiv(p.c_out, 32);
-    auto waves_for = [&](const TileParams& t) {
-        return (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n * t.nwx * t.nwy * t.nwz;
-    };
-    TileParams t4, t2;
-    int64_t lds4 = 0, lds2 = 0;
-    const bool ok4 = plan_tiles(p, 4, lds_limit, t4, lds4);
-    const bool ok2 = plan_tiles(p, 2, lds_limit, t2, lds2);
-    if (!ok4 && !ok2) return launch_conv3d_generic(p, s);
-    bool use4 = ok4 && (!ok2 || waves_for(t4) * co_groups >= kWaveSlots);
-    if (g_lane_depth == 4 && ok4) use4 = true;
-    if (g_lane_depth == 2 && ok2) use4 = false;
-    TileParams t = use4 ? t4 : t2;
-    const int64_t lds_bytes = use4 ? lds4 : lds2;
+    // Kernel variants (voxels per lane V x channels per pass CO_BLK):
+    //   V=2, CO_BLK=16:  64 accumulator pairs -> up to 5 waves per SIMD; the finest work split;
+    //   V=2, CO_BLK=32:  128 accumulator pairs -> 3 waves per SIMD, half the passes over the
+    //                    LDS tile and half the per-wave prologue/epilogue;
+    //   V=4, CO_BLK=16:  half the scalar-cache traffic per instruction (tuning option only).
+    // Waves of 32 channels are used when that still gives every SIMD about four of them;
+    // smaller problems are cut into 16-channel waves.
+    int V = 2, co_blk = 16;
+    if (g_lane_depth == 4) { V = 4; co_blk = 16; }
+    else if (g_co_block == 32) { V = 2; co_blk = 32; }
+    else if (g_co_block == 0) {
+        const int64_t tiles2 = (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, 2) * p.n;
+        if (tiles2 * cdiv(p.c_out, 32) >= 4096) co_blk = 32;
+    }
+    TileParams t;
+    int64_t lds_bytes = 0;
+    if (!plan_tiles(p, V, lds_limit, t, lds_bytes)) {
+        if (V == 4 && plan_tiles(p, 2, lds_limit, t, lds_bytes)) V = 2;
+        else return launch_conv3d_generic(p, s);
+    }
     const int64_t spatial_tiles = (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n;
     if (spatial_tiles > 0x7fffffff) return TERN_ESHAPE;
-
-    // Split output channels over blockIdx.y (in whole 32-channel words) when there are too few
-    // spatial tiles to fill the chip.
-    const int waves_per_wg = t.nwx * t.nwy * t.nwz;
-    int split = 1;
-    while (split < co_groups && spatial_tiles * waves_per_wg * split < kWaveSlots) split *= 2;
-    split = split < co_groups ? split : co_groups;
-    t.co_per_wg = cdiv(co_groups, split) * 32;
-    const int grid_y = cdiv(p.c_out, t.co_per_wg);
+    // Output channels are cut into slices of co_per_wave (one accumulation pass by default:
+    // many short waves keep every SIMD supplied with several resident waves, and a single wave
+    // cannot issue a vector instruction every cycle by itself).  Up to 8 waves of one workgroup
+    // take consecutive slices of the same spatial tile and share its LDS halo; further slices
+    // go to blockIdx.y.
+    const int nsp = t.nwx * t.nwy * t.nwz;
+    int co_per_wave = g_co_per_wave > 0 ? g_co_per_wave : co_blk;
+    co_per_wave = cdiv(co_per_wave, co_blk) * co_blk;
+    const int slices = cdiv(p.c_out, co_per_wave);
+    int nwc = 8 / nsp;
+    if (nwc > slices) nwc = slices;
+    if (nwc < 1) nwc = 1;
+    t.nwc = nwc;
+    t.co_per_wave = co_per_wave;
+    const int grid_y = cdiv(slices, nwc);
 
     const dim3 grid((unsigned)spatial_tiles, (unsigned)grid_y);
-    const int threads = 64 * waves_per_wg;
+    const int threads = 64 * nsp * nwc;
     const size_t lb = (size_t)lds_bytes;
 #define TERN_LAUNCH(WC_, V_, CB_)                                                            \
     (packed ? launch_variant<WC_, V_, CB_, true>(p, t, lb, grid, threads, s)                 \
             : launch_variant<WC_, V_, CB_, false>(p, t, lb, grid, threads, s))
-    if (p.wc == 2) return use4 ? TERN_LAUNCH(2, 4, 16) : TERN_LAUNCH(2, 2, 32);
-    return use4 ? TERN_LAUNCH(1, 4, 16) : TERN_LAUNCH(1, 2, 32);
+    if (p.wc == 2) {
+        if (V == 4) return TERN_LAUNCH(2, 4, 16);
+        return co_blk == 32 ? TERN_LAUNCH(2, 2, 32) : TERN_LAUNCH(2, 2, 16);
+    }
+    if (V == 4) return TERN_LAUNCH(1, 4, 16);
+    return co_blk == 32 ? TERN_LAUNCH(1, 2, 32) : TERN_LAUNCH(1, 2, 16);
 #undef TERN_LAUNCH
 }
 

@@ -46,6 +46,9 @@ int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo,
                               uint32_t* dst, hipStream_t s);
 int launch_conv3d(const ConvParams& p, hipStream_t s);
 void set_lane_depth(int v);
+void set_waves_z(int v);
+void set_co_block(int v);
+void set_co_per_wave(int v);
 int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
                         int32_t kw, uint32_t* bank, hipStream_t s);
 
