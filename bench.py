@@ -139,6 +139,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", action="store_true", help="also time the other entry points")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (reference for HBM counters)")
     ap.add_argument("--lane-depth", type=int, default=0, help="tuning override: 0 auto, 2 or 4")
     ap.add_argument("--waves-z", type=int, default=0, help="tuning override: 0 auto, 1, 2, 4, 8")
     ap.add_argument("--co-block", type=int, default=0, help="tuning override: 0 auto, 16, 32")
@@ -194,6 +196,13 @@ def main():
                      "unit": "T lane-op/s (algorithmic: 5 int32 VALU lane-ops per 32 MACs)",
                      "frac": lane_ops / PEAK_LANE_OPS, "traffic": None},
     }
+
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # Sustained issue rate of the same instruction mix with no memory traffic (measured ceiling).
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")

@@ -236,7 +236,13 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // ---- which tile ------------------------------------------------------------------------
+    // Workgroups are handed to the 8 XCDs round-robin by index; give each XCD a contiguous run
+    // of tiles so that neighbouring tiles (which share halo voxels) meet in the same L2.
     int bid = blockIdx.x;
+    {
+        const int per_xcd = gridDim.x >> 3;
+        if (bid < (per_xcd << 3)) bid = (bid & 7) * per_xcd + (bid >> 3);
+    }
     const int tix = bid % t.tiles_x; bid /= t.tiles_x;
     const int tiy = bid % t.tiles_y; bid /= t.tiles_y;
     const int tiz = bid % t.tiles_z;
