@@ -20,6 +20,10 @@ if ROOT not in sys.path:
 PEAK_LANE_OPS = 256 * 64 * 2.4e9          # 39.32e12 lane-ops/s
 OPS_PER_MAC = 5.0 / 32.0                  # and, xor, and, 2 x popcount-accumulate per 32 MACs
 HBM_PEAK = 8.0e12
+# HBM bytes per launch of the config[1] kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
+# a 256 MiB copy under the same counters (profiles/conv3d_fused_config1.md).
+TRAFFIC_BYTES_CFG1 = 10.08e6
+ALGORITHMIC_BYTES_CFG1 = 8.42e6
 
 
 def timed(fn, steps, warmup, stream_sync):
@@ -194,7 +198,9 @@ def main():
                    "wall_ms_per_step": wall_ms},
         "roofline": {"bound": "alu", "achieved": lane_ops / 1e12, "peak": PEAK_LANE_OPS / 1e12,
                      "unit": "T lane-op/s (algorithmic: 5 int32 VALU lane-ops per 32 MACs)",
-                     "frac": lane_ops / PEAK_LANE_OPS, "traffic": None},
+                     "frac": lane_ops / PEAK_LANE_OPS, "traffic": TRAFFIC_BYTES_CFG1,
+                     "algorithmic_bytes": ALGORITHMIC_BYTES_CFG1,
+                     "hbm_GBps": TRAFFIC_BYTES_CFG1 / (ms * 1e-3) / 1e9},
     }
 
     if args.calib_copy:
