@@ -547,7 +547,8 @@ int launch_conv3d(const ConvParams& p, hipStream_t s)
     else if (g_co_block == 32) { V = 2; co_blk = 32; }
     else if (g_co_block == 0) {
         const int64_t tiles2 = (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, 2) * p.n;
-        if (tiles2 * cdiv(p.c_out, 32) >= 4096) co_blk = 32;
+        const int tail = p.c_out % 32;   // a 32-channel pass over 1..16 live channels is half wasted
+        if (tiles2 * cdiv(p.c_out, 32) >= 4096 && (tail == 0 || tail > 16)) co_blk = 32;
     }
     TileParams t;
     int64_t lds_bytes = 0;

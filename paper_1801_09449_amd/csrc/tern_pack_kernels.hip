@@ -31,8 +31,32 @@ struct Vec {
     }
 };
 
-// MODE 0: int8 ternary input.  MODE 1: thresholds (T = int32_t or float).
+// Decide VPT values of one channel and OR their bits into bit j of the voxels' words.
 template <typename T, int VPT, int MODE>
+__device__ __forceinline__ void classify(const Vec<T, VPT>& x, T tl, T th, int j, uint32_t (&m)[VPT],
+                                         uint32_t (&s)[VPT])
+{
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        bool nz, neg;
+        if constexpr (MODE == 0) {
+            nz = x.v[i] != 0;
+            neg = x.v[i] < 0;
+        } else {
+            const bool pos = x.v[i] > th;
+            neg = (x.v[i] < tl) && !pos;
+            nz = pos || neg;
+        }
+        m[i] |= (nz ? 1u : 0u) << j;
+        s[i] |= (neg ? 1u : 0u) << j;
+    }
+}
+
+// MODE 0: int8 ternary input.  MODE 1: thresholds (T = int32_t or float).
+// WDT > 0: Wd is the compile-time constant WDT, all words of the VPT voxels stay in registers and
+// every voxel is written with 16-byte stores (a thread writes VPT * 8 * Wd contiguous bytes).
+// WDT == 0: any Wd, word-by-word stores.
+template <typename T, int VPT, int MODE, int WDT>
 __global__ __launch_bounds__(kBlock) void pack_kernel(const T* __restrict__ src,
                                                       uint32_t* __restrict__ dst,
                                                       const T* __restrict__ lo,
@@ -45,39 +69,81 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const T* __restrict__ src,
     const int64_t n = gid / groups_per_n;
     const int64_t v0 = (gid - n * groups_per_n) * VPT;  // first voxel (within batch item n)
     const T* base = src + (size_t)n * C * spatial + v0;
-    uint32_t* out = dst + ((size_t)n * spatial + v0) * 2u * Wd;
 
-    for (int q = 0; q < Wd; ++q) {
-        uint32_t m[VPT], s[VPT];
+    if constexpr (WDT > 0) {
+        uint32_t m[WDT][VPT], s[WDT][VPT];
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) m[i] = s[i] = 0u;
-        const int cmax = min(32, C - 32 * q);
-#pragma unroll 8
-        for (int j = 0; j < cmax; ++j) {
-            const int c = 32 * q + j;
-            Vec<T, VPT> x;
-            x.load(base + (size_t)c * spatial);
-            T tl = T(0), th = T(0);
-            if constexpr (MODE == 1) { tl = lo[c]; th = hi[c]; }
+        for (int q = 0; q < WDT; ++q) {
 #pragma unroll
-            for (int i = 0; i < VPT; ++i) {
-                bool nz, neg;
-                if constexpr (MODE == 0) {
-                    nz = x.v[i] != 0;
-                    neg = x.v[i] < 0;
-                } else {
-                    const bool pos = x.v[i] > th;
-                    neg = (x.v[i] < tl) && !pos;
-                    nz = pos || neg;
+            for (int i = 0; i < VPT; ++i) m[q][i] = s[q][i] = 0u;
+            const int cbase = 32 * q;
+            if (cbase + 32 <= C) {
+                // full word: 4 batches of 8 independent loads
+#pragma unroll
+                for (int j0 = 0; j0 < 32; j0 += 8) {
+                    Vec<T, VPT> x[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) x[j].load(base + (size_t)(cbase + j0 + j) * spatial);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        T tl = T(0), th = T(0);
+                        if constexpr (MODE == 1) { tl = lo[cbase + j0 + j]; th = hi[cbase + j0 + j]; }
+                        classify<T, VPT, MODE>(x[j], tl, th, j0 + j, m[q], s[q]);
+                    }
                 }
-                m[i] |= (nz ? 1u : 0u) << j;
-                s[i] |= (neg ? 1u : 0u) << j;
+            } else {
+                for (int j = 0; cbase + j < C; ++j) {
+                    Vec<T, VPT> x;
+                    x.load(base + (size_t)(cbase + j) * spatial);
+                    T tl = T(0), th = T(0);
+                    if constexpr (MODE == 1) { tl = lo[cbase + j]; th = hi[cbase + j]; }
+                    classify<T, VPT, MODE>(x, tl, th, j, m[q], s[q]);
+                }
             }
         }
+        uint32_t* out = dst + ((size_t)n * spatial + v0) * 2u * WDT;
+        if constexpr (WDT == 1) {
+            static_assert(VPT % 2 == 0, "two 8-byte voxels per 16-byte store");
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) {
-            out[(size_t)i * 2u * Wd + q] = m[i];
-            out[(size_t)i * 2u * Wd + Wd + q] = s[i];
+            for (int i = 0; i < VPT; i += 2)
+                *reinterpret_cast<uint4*>(out + 2 * i) = make_uint4(m[0][i], s[0][i], m[0][i + 1], s[0][i + 1]);
+        } else {
+            static_assert(WDT % 2 == 0, "even word counts only");
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) {
+                uint32_t* o = out + (size_t)i * 2u * WDT;
+                if constexpr (WDT == 2) {
+                    *reinterpret_cast<uint4*>(o) = make_uint4(m[0][i], m[1][i], s[0][i], s[1][i]);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < WDT; q += 4) {
+                        *reinterpret_cast<uint4*>(o + q) = make_uint4(m[q][i], m[q + 1][i], m[q + 2][i], m[q + 3][i]);
+                        *reinterpret_cast<uint4*>(o + WDT + q) = make_uint4(s[q][i], s[q + 1][i], s[q + 2][i], s[q + 3][i]);
+                    }
+                }
+            }
+        }
+    } else {
+        uint32_t* out = dst + ((size_t)n * spatial + v0) * 2u * Wd;
+        for (int q = 0; q < Wd; ++q) {
+            uint32_t m[VPT], s[VPT];
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) m[i] = s[i] = 0u;
+            const int cmax = min(32, C - 32 * q);
+#pragma unroll 8
+            for (int j = 0; j < cmax; ++j) {
+                const int c = 32 * q + j;
+                Vec<T, VPT> x;
+                x.load(base + (size_t)c * spatial);
+                T tl = T(0), th = T(0);
+                if constexpr (MODE == 1) { tl = lo[c]; th = hi[c]; }
+                classify<T, VPT, MODE>(x, tl, th, j, m, s);
+            }
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) {
+                out[(size_t)i * 2u * Wd + q] = m[i];
+                out[(size_t)i * 2u * Wd + Wd + q] = s[i];
+            }
         }
     }
 }
@@ -90,20 +156,27 @@ int launch_pack_any(const T* src, tern_dims dims, const T* lo, const T* hi, uint
     const int32_t Wd = (dims.c + 31) / 32;
     constexpr int VPT = 4;
     const bool vec_ok = (spatial % VPT == 0) && (((uintptr_t)src % (VPT * sizeof(T))) == 0);
+    const int vpt = vec_ok ? VPT : 1;
+    const int64_t gpn = spatial / vpt;
+    const int64_t total = gpn * dims.n;
+    const int64_t blocks = (total + kBlock - 1) / kBlock;
+    if (blocks > 0x7fffffff) return TERN_ESHAPE;
+    const dim3 grid((unsigned)blocks), block(kBlock);
+#define TERN_PACK_LAUNCH(VPT_, WDT_)                                                              \
+    hipLaunchKernelGGL((pack_kernel<T, VPT_, MODE, WDT_>), grid, block, 0, s, src, dst, lo, hi, dims.c, \
+                       Wd, spatial, gpn, total)
     if (vec_ok) {
-        const int64_t gpn = spatial / VPT;
-        const int64_t total = gpn * dims.n;
-        const int64_t blocks = (total + kBlock - 1) / kBlock;
-        if (blocks > 0x7fffffff) return TERN_ESHAPE;
-        hipLaunchKernelGGL((pack_kernel<T, VPT, MODE>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                           src, dst, lo, hi, dims.c, Wd, spatial, gpn, total);
+        switch (Wd) {
+            case 1: TERN_PACK_LAUNCH(4, 1); break;
+            case 2: TERN_PACK_LAUNCH(4, 2); break;
+            case 4: TERN_PACK_LAUNCH(4, 4); break;
+            case 8: TERN_PACK_LAUNCH(4, 8); break;
+            default: TERN_PACK_LAUNCH(4, 0); break;
+        }
     } else {
-        const int64_t total = spatial * dims.n;
-        const int64_t blocks = (total + kBlock - 1) / kBlock;
-        if (blocks > 0x7fffffff) return TERN_ESHAPE;
-        hipLaunchKernelGGL((pack_kernel<T, 1, MODE>), dim3((unsigned)blocks), dim3(kBlock), 0, s,
-                           src, dst, lo, hi, dims.c, Wd, spatial, spatial, total);
+        TERN_PACK_LAUNCH(1, 0);
     }
+#undef TERN_PACK_LAUNCH
     TERN_HIP_CHECK(hipGetLastError());
     return TERN_OK;
 }
