@@ -148,6 +148,7 @@ def main():
     ap.add_argument("--lane-depth", type=int, default=0, help="tuning override: 0 auto, 2 or 4")
     ap.add_argument("--waves-z", type=int, default=0, help="tuning override: 0 auto, 1, 2, 4, 8")
     ap.add_argument("--co-block", type=int, default=0, help="tuning override: 0 auto, 16, 32")
+    ap.add_argument("--tap-split", type=int, default=0, help="tuning override: 0 auto, 1, 2, 4, 8")
     ap.add_argument("--co-per-wave", type=int, default=0, help="tuning override: 0 auto, multiple of 16")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -166,6 +167,7 @@ def main():
     T.tern_set_option(2, args.waves_z)
     T.tern_set_option(3, args.co_block)
     T.tern_set_option(4, args.co_per_wave)
+    T.tern_set_option(5, args.tap_split)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()

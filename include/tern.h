@@ -38,6 +38,12 @@
  *   nchunk = Wd / wc; co_pad = C_out rounded up to a multiple of 32.  Entry [tap*nchunk + ch]
  *   [co][p][q] is plane p (0 mask, 1 sign) of input-channel word ch*wc + q of filter co at that
  *   tap; channels co >= C_out are all-zero.  Built by tern_pack_filters.
+ *   Tap-packed variant, used when C_in <= 16 and T > 1 (a voxel's word would otherwise be mostly
+ *   empty): shift = smallest power of two >= C_in, slots = min(32 / shift, T);
+ *     uint32 [ceil(T / slots)][co_pad][2][1]
+ *   and the word of row r holds taps r*slots .. r*slots + slots - 1, tap i of the row in bits
+ *   [i*shift, i*shift + C_in).  The kernels build the matching activation word from the voxels of
+ *   those taps, so one word pair covers up to 32 (tap, channel) products of Eq. 9.
  */
 #ifndef TERN_H
 #define TERN_H
@@ -182,10 +188,12 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
  * stacked along z in one workgroup (sharing one LDS halo tile), 0 = choose, 1, 2, 4 or 8 = start
  * from that value.  TERN_OPT_CO_BLOCK: output channels per accumulation pass, 0 = choose, 16 or 32.
  * TERN_OPT_CO_PER_WAVE: output channels handled by one wave, 0 = choose, else a multiple of 16.
+ * TERN_OPT_TAP_SPLIT: waves of one workgroup that share the kernel taps of one channel slice and
+ * add their partial sums in LDS, 0 = choose, 1, 2, 4 or 8.
  * Results never depend on options.  Returns TERN_EARG for an unknown option or
  * value. */
 typedef enum { TERN_OPT_LANE_DEPTH = 1, TERN_OPT_WAVES_Z = 2, TERN_OPT_CO_BLOCK = 3,
-               TERN_OPT_CO_PER_WAVE = 4 } tern_option;
+               TERN_OPT_CO_PER_WAVE = 4, TERN_OPT_TAP_SPLIT = 5 } tern_option;
 int tern_set_option(int option, int value);
 
 /*

@@ -130,6 +130,11 @@ int tern_set_option(int option, int value)
         set_co_per_wave(value);
         return TERN_OK;
     }
+    if (option == TERN_OPT_TAP_SPLIT) {
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return TERN_EARG;
+        set_tap_split(value);
+        return TERN_OK;
+    }
     if (option == TERN_OPT_WAVES_Z) {
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return TERN_EARG;
         set_waves_z(value);
@@ -150,7 +155,8 @@ size_t tern_filter_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t k
 {
     if (!filter_shape_ok(c_out, c_in, kd, kh, kw)) return 0;
     const size_t co_pad = (size_t)(c_out + 31) / 32 * 32;
-    return (size_t)kd * kh * kw * (size_t)tern_words(c_in) * co_pad * 2u * sizeof(uint32_t);
+    const BankShape b = bank_shape(c_in, kd * kh * kw);
+    return (size_t)b.nsteps * co_pad * 2u * (size_t)b.wc * sizeof(uint32_t);
 }
 
 int tern_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
@@ -205,8 +211,11 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_
     p.dd = g.dil[0]; p.dh = g.dil[1]; p.dw = g.dil[2];
     p.wd_in = tern_words(in_dims.c);
     p.wd_out = tern_words(c_out);
-    p.wc = (p.wd_in % 2 == 0) ? 2 : 1;
+    const BankShape bs = bank_shape(in_dims.c, g.k[0] * g.k[1] * g.k[2]);
+    p.wc = bs.wc;
     p.co_pad = (c_out + 31) / 32 * 32;
+    p.tp_slots = bs.tp_slots;
+    p.tp_shift = bs.tp_shift;
     return launch_conv3d(p, (hipStream_t)stream);
 }
 

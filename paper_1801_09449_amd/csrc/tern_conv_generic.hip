@@ -25,6 +25,18 @@ __device__ __forceinline__ int32_t dot_at(const ConvParams& p, int n, int co, in
                 const uint32_t* av =
                     p.in + ((((size_t)n * p.d + iz) * p.h + iy) * p.w + ix) * 2u * Wd;
                 const int tap = (a * p.kh + b) * p.kw + c;
+                if (p.tp_slots) {
+                    // tap-packed bank: [tap / slots][co_pad][2][1], this tap's bits start at
+                    // bit (tap % slots) * shift; the activation word has bits only below C_in
+                    const int step = tap / p.tp_slots, sh = (tap - step * p.tp_slots) * p.tp_shift;
+                    const uint32_t* wv = p.wgt + ((size_t)step * p.co_pad + co) * 2u;
+                    const uint32_t live = (1u << p.c_in) - 1u;
+                    const uint32_t M = av[0] & live & (wv[0] >> sh);
+                    const uint32_t N = M & (av[1] ^ (wv[1] >> sh));
+                    acc_m += __builtin_popcount(M);
+                    acc_n += __builtin_popcount(N);
+                    continue;
+                }
                 for (int q = 0; q < Wd; ++q) {
                     // filter bank: [tap * nchunk + chunk][co_pad][2][wc]
                     const uint32_t* wv =

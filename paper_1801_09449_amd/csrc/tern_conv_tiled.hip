@@ -51,6 +51,8 @@ struct TileParams {
     int32_t nchunk;               // Wd / WC
     int32_t nwc;                  // waves per workgroup along the output-channel axis
     int32_t co_per_wave;          // output channels handled by one wave (multiple of 16)
+    int32_t nks;                  // waves per workgroup that split the kernel taps of one slice
+    int32_t red_off;              // LDS word offset of the partial-sum area (nks > 1)
 };
 
 template <int WC>
@@ -83,6 +85,16 @@ typedef const uint32_t __attribute__((address_space(4)))* scalar_ptr;
 __device__ __forceinline__ void popc_acc(int32_t& acc, uint32_t x)
 {
     asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
+}
+
+// m & (sa ^ sw) as one three-input bit operation (truth-table index = sa<<2 | m<<1 | sw).
+// Spelled out because the compiler otherwise sometimes forms (sa ^ sw) on its own and spends a
+// fifth instruction per word pair.
+__device__ __forceinline__ uint32_t and_xor(uint32_t m, uint32_t sa, uint32_t sw)
+{
+    uint32_t r;
+    asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x48" : "=v"(r) : "v"(sa), "v"(m), "s"(sw));
+    return r;
 }
 
 // word = (word << 1) | (thr < d): the comparison result goes through the carry flag into the
@@ -156,60 +168,98 @@ __device__ __forceinline__ void mac_group(const ActChunk<WC> (&A)[V], const WGro
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const uint32_t M = A[v].m[q] & g.m[j][q];
-                const uint32_t N = M & (A[v].s[q] ^ g.s[j][q]);
+                const uint32_t N = and_xor(M, A[v].s[q], g.s[j][q]);
                 popc_acc(acc_m[v][j0 + j], M);
                 popc_acc(acc_n[v][j0 + j], N);
             }
 }
 
-// Scalar walk over (tap, chunk) steps.
+// Scalar walk over the kernel taps.  Plain mode: one step = one (tap, channel chunk) and the
+// cursor is the step whose activations were fetched last.  Tap-packed mode (C_in <= 16, one
+// word per voxel): one step = up to `slots` consecutive taps whose channel bits are shifted into
+// disjoint slots of a single word, and the cursor is the next tap to fetch.
 struct StepCursor {
-    int tb, tc, ch;   // kernel row, column and channel chunk of the current step
-    int toff;         // LDS word offset of its tap
+    int tb, tc, ch;   // kernel row, column and channel chunk
+    int toff;         // LDS word offset of the tap
+    int tap;          // linear tap index
 };
 
+// (The LDS offset increments for "next column / next row / next plane" travel as three separate
+// by-value ints, not as members: as struct members the compiler turns the choice between them
+// into an indexed load from a stack copy of the struct.)
 // Loop-invariant scalars of the walk.
 struct StepConsts {
     int kw, kh, nchunk;
-    int inc_c, inc_b, inc_a;   // LDS offset increments: next column / next row / next plane
     int step_words;            // filter-bank words per step
     int vstep;                 // LDS words between a lane's consecutive voxels
+    int slots, shift;          // tap-packed mode: taps per word, bits per slot
+    uint32_t slot_mask;        // tap-packed mode: (1 << C_in) - 1
+    int tap_end;               // tap-packed mode: first tap this wave does not own
 };
+
+__device__ __forceinline__ void next_tap(StepCursor& c, const StepConsts& sc, int inc_c, int inc_b,
+                                         int inc_a)
+{
+    ++c.tap;
+    int inc = inc_c;
+    if (++c.tc == sc.kw) {
+        c.tc = 0;
+        inc = inc_b;
+        if (++c.tb == sc.kh) { c.tb = 0; inc = inc_a; }
+    }
+    c.toff += inc;
+}
+
+// Fetch the activations of one step into A.  Plain mode: advance to the following step unless
+// `stay` (used for the prefetch after a wave's last step, which is discarded), then read.
+template <int WC, int V, bool TP>
+__device__ __forceinline__ void fetch_step(ActChunk<WC> (&A)[V], StepCursor& c, const StepConsts& sc,
+                                           int inc_c, int inc_b, int inc_a,
+                                           const uint32_t* lane_lds, bool advance)
+{
+    if constexpr (!TP) {
+        if (advance) {
+            if (++c.ch == sc.nchunk) { c.ch = 0; next_tap(c, sc, inc_c, inc_b, inc_a); }
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+            A[v] = lds_read_chunk<WC>(lane_lds + v * sc.vstep + c.toff + c.ch * 2 * WC);
+    } else {
+        static_assert(WC == 1 || !TP, "tap packing uses one word per voxel");
+#pragma unroll
+        for (int v = 0; v < V; ++v) A[v].m[0] = A[v].s[0] = 0u;
+        for (int i = 0; i < sc.slots && c.tap < sc.tap_end; ++i) {
+            const int sh = i * sc.shift;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const uint2 r = *reinterpret_cast<const uint2*>(lane_lds + v * sc.vstep + c.toff);
+                A[v].m[0] |= (r.x & sc.slot_mask) << sh;
+                A[v].s[0] |= (r.y & sc.slot_mask) << sh;
+            }
+            next_tap(c, sc, inc_c, inc_b, inc_a);
+        }
+    }
+}
 
 // One step: accumulate CO_BLK channels from A0 (this step's activations) while fetching the next
 // step's activations into A1.  Software pipeline: while a channel group is being accumulated,
 // the scalar loads of the following group and the LDS reads of the next step are in flight.
-template <int WC, int V, int CO_BLK>
+template <int WC, int V, int CO_BLK, bool TP>
 __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<WC> (&A1)[V], bool last,
-                                          StepCursor& cur, const StepConsts& sc, WGroup<WC>& g0,
-                                          WGroup<WC>& g1, scalar_ptr& wcur, scalar_ptr wblk,
-                                          const uint32_t* lane_lds, int32_t (&acc_m)[V][CO_BLK],
-                                          int32_t (&acc_n)[V][CO_BLK])
+                                          StepCursor& cur, const StepConsts& sc, int inc_c, int inc_b,
+                                          int inc_a, WGroup<WC>& g0,
+                                          WGroup<WC>& g1, scalar_ptr& wcur, const uint32_t* lane_lds,
+                                          int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK])
 {
     constexpr int NG = CO_BLK / kGroup;
-    // LDS offset of the following step (after the last step: step 0 again, whose prefetched
-    // data is not used; this keeps every address in bounds)
-    int nch = cur.ch + 1, ntoff = cur.toff;
-    if (nch == sc.nchunk) {
-        nch = 0;
-        if (++cur.tc == sc.kw) {
-            cur.tc = 0;
-            if (++cur.tb == sc.kh) { cur.tb = 0; ntoff += sc.inc_a; }
-            else ntoff += sc.inc_b;
-        } else ntoff += sc.inc_c;
-    }
-    if (last) { nch = 0; ntoff = 0; }
-    scalar_ptr wnext = last ? wblk : wcur + sc.step_words;
+    // after a wave's last step the prefetches re-read the same (valid) addresses and are dropped
+    scalar_ptr wnext = last ? wcur : wcur + sc.step_words;
 #pragma unroll
     for (int gi = 0; gi < NG; gi += 2) {
         settle<WC>(g0);
         __builtin_amdgcn_sched_barrier(0);
-        if (gi == 0) {
-            // issued behind the wait so that they complete under the first group's arithmetic
-#pragma unroll
-            for (int v = 0; v < V; ++v)
-                A1[v] = lds_read_chunk<WC>(lane_lds + v * sc.vstep + ntoff + nch * 2 * WC);
-        }
+        // issued behind the wait so that the LDS reads complete under the first group's arithmetic
+        if (gi == 0) fetch_step<WC, V, TP>(A1, cur, sc, inc_c, inc_b, inc_a, lane_lds, !last);
         load_wgroup<WC>(g1, wcur + (gi + 1) * kGroup * 2 * WC);
         __builtin_amdgcn_sched_barrier(0);
         mac_group<WC, V, CO_BLK>(A0, g0, gi * kGroup, acc_m, acc_n);
@@ -222,10 +272,10 @@ __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<
         mac_group<WC, V, CO_BLK>(A0, g1, (gi + 1) * kGroup, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
     }
-    cur.ch = nch; cur.toff = ntoff; wcur = wnext;
+    wcur = wnext;
 }
 
-template <int WC, int V, int CO_BLK, bool PACKED>
+template <int WC, int V, int CO_BLK, bool PACKED, bool TP>
 __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, TileParams t)
 {
     extern __shared__ __align__(16) uint32_t lds[];
@@ -303,10 +353,13 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     __syncthreads();
 
     // ---- this wave's voxels --------------------------------------------------------------
-    const int wx = wave % t.nwx;
-    const int wy = (wave / t.nwx) % t.nwy;
-    const int wz = (wave / (t.nwx * t.nwy)) % t.nwz;
-    const int wch = wave / (t.nwx * t.nwy * t.nwz);   // channel slice of this wave
+    const int nsp = t.nwx * t.nwy * t.nwz;
+    const int wslot = wave % (nsp * t.nwc);           // (spatial, channel-slice) position
+    const int ks = wave / (nsp * t.nwc);              // which share of the kernel taps
+    const int wx = wslot % t.nwx;
+    const int wy = (wslot / t.nwx) % t.nwy;
+    const int wz = (wslot / (t.nwx * t.nwy)) % t.nwz;
+    const int wch = wslot / nsp;                      // channel slice of this wave
     const int lx = lane & 7, ly = lane >> 3;
     const int ox = ox0 + wx * 8 + lx;
     const int oy = oy0 + wy * 8 + ly;
@@ -322,16 +375,33 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int T = p.kd * p.kh * p.kw;
     const int co_begin = (blockIdx.y * t.nwc + wch) * t.co_per_wave;
     const int co_end = min(p.c_out, co_begin + t.co_per_wave);
-    const int nsteps = T * t.nchunk;
-    // scalar increments of the LDS offset when the tap advances along x / wraps to the next
-    // row / wraps to the next plane
+    const int nsteps = TP ? (T + p.tp_slots - 1) / p.tp_slots : T * t.nchunk;
+    // this wave's share of the steps (all of them unless the taps are split over nks waves)
+    const int steps_per_wave = (nsteps + t.nks - 1) / t.nks;
+    const int s_begin = ks * steps_per_wave;
+    const int s_end = min(nsteps, s_begin + steps_per_wave);
     StepConsts sc;
     sc.kw = p.kw; sc.kh = p.kh; sc.nchunk = t.nchunk;
-    sc.inc_c = p.dw * t.vstride;
-    sc.inc_b = p.dh * row_words - (p.kw - 1) * sc.inc_c;
-    sc.inc_a = p.dd * plane_words - (p.kh - 1) * p.dh * row_words - (p.kw - 1) * sc.inc_c;
+    const int inc_c = p.dw * t.vstride;
+    const int inc_b = p.dh * row_words - (p.kw - 1) * inc_c;
+    const int inc_a = p.dd * plane_words - (p.kh - 1) * p.dh * row_words - (p.kw - 1) * inc_c;
     sc.step_words = p.co_pad * 2 * WC;
     sc.vstep = vstep;
+    sc.slots = p.tp_slots; sc.shift = p.tp_shift;
+    sc.slot_mask = TP ? ((1u << p.c_in) - 1u) : 0xffffffffu;
+    sc.tap_end = TP ? min(T, s_end * p.tp_slots) : T;
+    // cursor at this wave's first step
+    StepCursor cur0;
+    {
+        const int tap0 = TP ? s_begin * p.tp_slots : s_begin / t.nchunk;
+        cur0.ch = TP ? 0 : s_begin - tap0 * t.nchunk;
+        cur0.tap = tap0;
+        cur0.tc = tap0 % p.kw;
+        const int r = tap0 / p.kw;
+        cur0.tb = r % p.kh;
+        const int ta = r / p.kh;
+        cur0.toff = ta * p.dd * plane_words + cur0.tb * p.dh * row_words + cur0.tc * inc_c;
+    }
     constexpr int NG = CO_BLK / kGroup;
     static_assert(NG >= 2 && NG % 2 == 0, "CO_BLK must be a multiple of 2*kGroup");
     static_assert(CO_BLK <= 32 && 32 % CO_BLK == 0, "CO_BLK must divide 32");
@@ -342,31 +412,66 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
 
     // The filter bank is padded with all-zero channels up to a multiple of 32, so a channel
     // block may run past c_out: the surplus accumulators stay 0 and are dropped below.
-    for (int cb = co_begin; cb < co_end; cb += CO_BLK) {
-        int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];
+    // With split taps (nks > 1) a wave makes exactly one pass (co_per_wave == CO_BLK) and every
+    // wave of the workgroup, with or without channels of its own, meets at the barrier below.
+    for (int cb = co_begin;; cb += CO_BLK) {
+        const bool active = cb < co_end;
+        if (!active && t.nks == 1) break;
+        int32_t d[V][CO_BLK];   // accumulators of this pass
+        if (active) {
+            int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];
 #pragma unroll
-        for (int v = 0; v < V; ++v)
+            for (int v = 0; v < V; ++v)
 #pragma unroll
-            for (int j = 0; j < CO_BLK; ++j) acc_m[v][j] = acc_n[v][j] = 0;
+                for (int j = 0; j < CO_BLK; ++j) acc_m[v][j] = acc_n[v][j] = 0;
 
-        scalar_ptr wblk = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC;
-
-        WGroup<WC> g0, g1;
-        scalar_ptr wcur = wblk;  // filter words of the current step
-        StepCursor cur = {0, 0, 0, 0};
-
-        ActChunk<WC> Aa[V], Ab[V];
+            if (s_begin < s_end) {
+                scalar_ptr wcur = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC +
+                                  (size_t)s_begin * sc.step_words;
+                WGroup<WC> g0, g1;
+                StepCursor cur = cur0;
+                ActChunk<WC> Aa[V], Ab[V];
+                fetch_step<WC, V, TP>(Aa, cur, sc, inc_c, inc_b, inc_a, lane_lds, false);
+                load_wgroup<WC>(g0, wcur);
+                int step = s_begin;
+                for (; step + 2 <= s_end; step += 2) {   // two steps per trip: no register copies
+                    conv_step<WC, V, CO_BLK, TP>(Aa, Ab, false, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
+                                                 acc_m, acc_n);
+                    conv_step<WC, V, CO_BLK, TP>(Ab, Aa, step + 2 == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                                 lane_lds, acc_m, acc_n);
+                }
+                if (step < s_end)
+                    conv_step<WC, V, CO_BLK, TP>(Aa, Ab, true, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
+                                                 acc_m, acc_n);
+            }
 #pragma unroll
-        for (int v = 0; v < V; ++v) Aa[v] = lds_read_chunk<WC>(lane_lds + v * vstep);
-        load_wgroup<WC>(g0, wblk);
-        int step = 0;
-        for (; step + 2 <= nsteps; step += 2) {   // two steps per trip: no register copies
-            conv_step<WC, V, CO_BLK>(Aa, Ab, false, cur, sc, g0, g1, wcur, wblk, lane_lds, acc_m, acc_n);
-            conv_step<WC, V, CO_BLK>(Ab, Aa, step + 2 == nsteps, cur, sc, g0, g1, wcur, wblk, lane_lds,
-                                     acc_m, acc_n);
+            for (int v = 0; v < V; ++v)
+#pragma unroll
+                for (int j = 0; j < CO_BLK; ++j) d[v][j] = acc_m[v][j] - 2 * acc_n[v][j];
         }
-        if (step < nsteps)
-            conv_step<WC, V, CO_BLK>(Aa, Ab, true, cur, sc, g0, g1, wcur, wblk, lane_lds, acc_m, acc_n);
+
+        if (t.nks > 1) {
+            // Partial sums of the tap shares meet in LDS: shares 1.. store, share 0 adds them up
+            // and carries on to the epilogue.
+            int32_t* red = reinterpret_cast<int32_t*>(lds) + t.red_off;
+            const int nslots = nsp * t.nwc;
+            if (active && ks > 0) {
+                int32_t* mine = red + (size_t)((ks - 1) * nslots + wslot) * (V * CO_BLK * 64) + lane;
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+#pragma unroll
+                    for (int j = 0; j < CO_BLK; ++j) mine[(v * CO_BLK + j) * 64] = d[v][j];
+            }
+            __syncthreads();
+            if (!active || ks > 0) break;
+            for (int k = 1; k < t.nks; ++k) {
+                const int32_t* theirs = red + (size_t)((k - 1) * nslots + wslot) * (V * CO_BLK * 64) + lane;
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+#pragma unroll
+                    for (int j = 0; j < CO_BLK; ++j) d[v][j] += theirs[(v * CO_BLK + j) * 64];
+            }
+        }
 
         // ---- epilogue ----------------------------------------------------------------------
         const int co_left = co_end - cb;
@@ -399,9 +504,8 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
             for (int j = CO_BLK - 1; j >= 0; --j) {
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
-                    const int32_t d = acc_m[v][j] - 2 * acc_n[v][j];
-                    shift_in_gt(pp[v], d, hi[j]);   // +1 if acc > hi
-                    shift_in_lt(pn[v], d, lo[j]);   // -1 if acc < lo
+                    shift_in_gt(pp[v], d[v][j], hi[j]);   // +1 if acc > hi
+                    shift_in_lt(pn[v], d[v][j], lo[j]);   // -1 if acc < lo
                 }
             }
             const int sh = cb & 31;
@@ -447,18 +551,19 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
                                  ((size_t)oz * p.oh + oy) * p.ow + ox;
 #pragma unroll
                     for (int j = 0; j < CO_BLK; ++j)
-                        if (j < co_left) o[(size_t)(cb + j) * cstride] = acc_m[v][j] - 2 * acc_n[v][j];
+                        if (j < co_left) o[(size_t)(cb + j) * cstride] = d[v][j];
                 }
             }
         }
+        if (t.nks > 1) break;
     }
 }
 
-template <int WC, int V, int CO_BLK, bool PACKED>
+template <int WC, int V, int CO_BLK, bool PACKED, bool TP>
 int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, dim3 grid,
                    int threads, hipStream_t s)
 {
-    auto kern = conv_tiled_kernel<WC, V, CO_BLK, PACKED>;
+    auto kern = conv_tiled_kernel<WC, V, CO_BLK, PACKED, TP>;
     if (lds_bytes > 64 * 1024) {
         static thread_local int raised_on_device = -1;
         int dev = 0;
@@ -481,6 +586,7 @@ int g_lane_depth = 0;   // tuning override: 0 = choose, 2 or 4 = force that voxe
 int g_waves_z = 0;      // tuning override: 0 = choose, else waves stacked along z per workgroup
 int g_co_block = 0;     // tuning override: 0 = choose, 16 or 32 = channels per accumulation pass
 int g_co_per_wave = 0;  // tuning override: 0 = choose, else channels per wave (multiple of 16)
+int g_tap_split = 0;    // tuning override: 0 = choose, else waves sharing the taps of one slice
 
 // Tile plan for a voxel depth V per lane; returns false if no halo tile fits in LDS.
 bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_t& lds_bytes)
@@ -529,6 +635,7 @@ void set_lane_depth(int v) { g_lane_depth = (v == 2 || v == 4) ? v : 0; }
 void set_waves_z(int v) { g_waves_z = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
 void set_co_block(int v) { g_co_block = (v == 16 || v == 32) ? v : 0; }
 void set_co_per_wave(int v) { g_co_per_wave = (v > 0 && v % 16 == 0) ? v : 0; }
+void set_tap_split(int v) { g_tap_split = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
 
 int launch_conv3d(const ConvParams& p, hipStream_t s)
 {
@@ -543,7 +650,7 @@ int launch_conv3d(const ConvParams& p, hipStream_t s)
     // Waves of 32 channels are used when that still gives every SIMD about four of them;
     // smaller problems are cut into 16-channel waves.
     int V = 2, co_blk = 16;
-    if (g_lane_depth == 4) { V = 4; co_blk = 16; }
+    if (g_lane_depth == 4 && p.tp_slots == 0) { V = 4; co_blk = 16; }
     else if (g_co_block == 32) { V = 2; co_blk = 32; }
     else if (g_co_block == 0) {
         const int64_t tiles2 = (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, 2) * p.n;
@@ -566,26 +673,53 @@ int launch_conv3d(const ConvParams& p, hipStream_t s)
     const int nsp = t.nwx * t.nwy * t.nwz;
     int co_per_wave = g_co_per_wave > 0 ? g_co_per_wave : co_blk;
     co_per_wave = cdiv(co_per_wave, co_blk) * co_blk;
-    const int slices = cdiv(p.c_out, co_per_wave);
-    int nwc = 8 / nsp;
+    int slices = cdiv(p.c_out, co_per_wave);
+
+    // Small problems: when even 16-channel slices leave most SIMDs without a wave, the kernel
+    // taps of one (tile, slice) are split over nks waves of the same workgroup, which add their
+    // partial sums through LDS.
+    const bool tp = p.tp_slots > 0;
+    const int T = p.kd * p.kh * p.kw;
+    const int nsteps = tp ? cdiv(T, p.tp_slots) : T * t.nchunk;
+    int nks = 1;
+    if (g_tap_split > 0) nks = g_tap_split;
+    else {
+        const int64_t waves0 = spatial_tiles * nsp * slices;
+        while (nks * 2 * nsp <= 8 && waves0 * nks < 2048 && nsteps >= 4 * nks) nks *= 2;
+    }
+    if (nks * nsp > 8) nks = 8 / nsp;
+    if (nks < 1) nks = 1;
+    if (nks > 1) { co_per_wave = co_blk; slices = cdiv(p.c_out, co_per_wave); }
+    int nwc = 8 / (nsp * nks);
     if (nwc > slices) nwc = slices;
     if (nwc < 1) nwc = 1;
     t.nwc = nwc;
     t.co_per_wave = co_per_wave;
+    t.nks = nks;
+    t.red_off = (int32_t)(lds_bytes / 4);
+    if (nks > 1) {
+        lds_bytes += (int64_t)(nks - 1) * nsp * nwc * V * co_blk * 64 * 4;
+        if (lds_bytes > lds_limit) {   // no room for the partial sums: do without the split
+            lds_bytes = (int64_t)t.red_off * 4;
+            t.nks = nks = 1;
+            t.nwc = nwc = (8 / nsp < slices) ? 8 / nsp : slices;
+        }
+    }
     const int grid_y = cdiv(slices, nwc);
 
     const dim3 grid((unsigned)spatial_tiles, (unsigned)grid_y);
-    const int threads = 64 * nsp * nwc;
+    const int threads = 64 * nsp * nwc * nks;
     const size_t lb = (size_t)lds_bytes;
-#define TERN_LAUNCH(WC_, V_, CB_)                                                            \
-    (packed ? launch_variant<WC_, V_, CB_, true>(p, t, lb, grid, threads, s)                 \
-            : launch_variant<WC_, V_, CB_, false>(p, t, lb, grid, threads, s))
+#define TERN_LAUNCH(WC_, V_, CB_, TP_)                                                       \
+    (packed ? launch_variant<WC_, V_, CB_, true, TP_>(p, t, lb, grid, threads, s)            \
+            : launch_variant<WC_, V_, CB_, false, TP_>(p, t, lb, grid, threads, s))
+    if (tp) return co_blk == 32 ? TERN_LAUNCH(1, 2, 32, true) : TERN_LAUNCH(1, 2, 16, true);
     if (p.wc == 2) {
-        if (V == 4) return TERN_LAUNCH(2, 4, 16);
-        return co_blk == 32 ? TERN_LAUNCH(2, 2, 32) : TERN_LAUNCH(2, 2, 16);
+        if (V == 4) return TERN_LAUNCH(2, 4, 16, false);
+        return co_blk == 32 ? TERN_LAUNCH(2, 2, 32, false) : TERN_LAUNCH(2, 2, 16, false);
     }
-    if (V == 4) return TERN_LAUNCH(1, 4, 16);
-    return co_blk == 32 ? TERN_LAUNCH(1, 2, 32) : TERN_LAUNCH(1, 2, 16);
+    if (V == 4) return TERN_LAUNCH(1, 4, 16, false);
+    return co_blk == 32 ? TERN_LAUNCH(1, 2, 32, false) : TERN_LAUNCH(1, 2, 16, false);
 #undef TERN_LAUNCH
 }
 

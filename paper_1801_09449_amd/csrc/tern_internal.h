@@ -35,7 +35,34 @@ struct ConvParams {
     int32_t wd_out;         // ceil(c_out/32)
     int32_t wc;             // filter-bank chunk width in words: 2 if wd_in is even, else 1
     int32_t co_pad;         // c_out rounded up to a multiple of 32
+    int32_t tp_slots;       // tap-packed filter bank: taps per word (0 = plain layout)
+    int32_t tp_shift;       // tap-packed filter bank: bits per tap slot
 };
+
+// Filter-bank geometry for (c_in, taps): tap packing applies when a voxel is one word with at
+// most 16 live channels and the kernel has more than one tap.
+struct BankShape {
+    int32_t wd, wc, nchunk;     // words per plane, words per chunk, chunks per tap
+    int32_t tp_slots, tp_shift; // 0, 0 for the plain layout
+    int32_t nsteps;             // rows of the bank
+};
+inline BankShape bank_shape(int32_t c_in, int32_t taps)
+{
+    BankShape b;
+    b.wd = (c_in + 31) / 32;
+    b.wc = (b.wd % 2 == 0) ? 2 : 1;
+    b.nchunk = b.wd / b.wc;
+    b.tp_slots = 0; b.tp_shift = 0;
+    if (c_in <= 16 && taps > 1) {
+        int sh = 1;
+        while (sh < c_in) sh *= 2;
+        b.tp_shift = sh;
+        b.tp_slots = 32 / sh;
+        if (b.tp_slots > taps) b.tp_slots = taps;
+    }
+    b.nsteps = b.tp_slots ? (taps + b.tp_slots - 1) / b.tp_slots : taps * b.nchunk;
+    return b;
+}
 
 // Launchers implemented in the kernel translation units.  Each validates nothing (the entry
 // points did) and returns a tern_status.
@@ -49,6 +76,7 @@ void set_lane_depth(int v);
 void set_waves_z(int v);
 void set_co_block(int v);
 void set_co_per_wave(int v);
+void set_tap_split(int v);
 int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
                         int32_t kw, uint32_t* bank, hipStream_t s);
 

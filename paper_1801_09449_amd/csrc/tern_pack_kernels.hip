@@ -201,40 +201,52 @@ int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo,
 }
 
 // ---- filter bank ------------------------------------------------------------------------------
-// Layout consumed by the convolution kernels: uint32 [T * nchunk][co_pad][2][wc], where
-// T = kd*kh*kw taps in (a, b, c) order, wc = 2 if ceil(C_in/32) is even else 1 words per chunk,
-// nchunk = ceil(C_in/32) / wc, co_pad = C_out rounded up to a multiple of 32 (padding channels
-// are all-zero filters).  Step s = tap * nchunk + chunk holds, for every channel, wc mask words
-// then wc sign words of input-channel words [chunk*wc, chunk*wc + wc).
+// Layout consumed by the convolution kernels (documented in include/tern.h).
+// Plain: uint32 [T * nchunk][co_pad][2][wc]; step s = tap * nchunk + chunk holds, for every
+// channel, wc mask words then wc sign words of input-channel words [chunk*wc, chunk*wc + wc).
+// Tap-packed (C_in <= 16, T > 1): uint32 [ceil(T / slots)][co_pad][2][1]; the word of step s
+// carries taps s*slots .. s*slots + slots - 1, tap i of the step in bits [i*shift, i*shift + C_in).
 namespace {
 
 __global__ __launch_bounds__(256) void pack_filters_kernel(const int8_t* __restrict__ w,
                                                            uint32_t* __restrict__ bank, int c_out,
-                                                           int c_in, int T, int wc, int nchunk,
-                                                           int co_pad, int64_t total)
+                                                           int c_in, int T, BankShape b, int co_pad,
+                                                           int64_t total)
 {
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (gid >= total) return;
     // one thread per (step, channel, word-in-chunk)
     int64_t r = gid;
-    const int q = (int)(r % wc); r /= wc;
+    const int q = (int)(r % b.wc); r /= b.wc;
     const int co = (int)(r % co_pad); r /= co_pad;
     const int step = (int)r;
-    const int tap = step / nchunk, chunk = step - tap * nchunk;
-    const int word = chunk * wc + q;
     uint32_t m = 0u, s = 0u;
     if (co < c_out) {
-        for (int j = 0; j < 32; ++j) {
-            const int ci = 32 * word + j;
-            if (ci >= c_in) break;
-            const int8_t v = w[((size_t)co * c_in + ci) * T + tap];
-            m |= (v != 0 ? 1u : 0u) << j;
-            s |= (v < 0 ? 1u : 0u) << j;
+        if (b.tp_slots) {
+            for (int i = 0; i < b.tp_slots; ++i) {
+                const int tap = step * b.tp_slots + i;
+                if (tap >= T) break;
+                for (int ci = 0; ci < c_in; ++ci) {
+                    const int8_t v = w[((size_t)co * c_in + ci) * T + tap];
+                    m |= (v != 0 ? 1u : 0u) << (i * b.tp_shift + ci);
+                    s |= (v < 0 ? 1u : 0u) << (i * b.tp_shift + ci);
+                }
+            }
+        } else {
+            const int tap = step / b.nchunk, chunk = step - tap * b.nchunk;
+            const int word = chunk * b.wc + q;
+            for (int j = 0; j < 32; ++j) {
+                const int ci = 32 * word + j;
+                if (ci >= c_in) break;
+                const int8_t v = w[((size_t)co * c_in + ci) * T + tap];
+                m |= (v != 0 ? 1u : 0u) << j;
+                s |= (v < 0 ? 1u : 0u) << j;
+            }
         }
     }
-    uint32_t* o = bank + ((size_t)step * co_pad + co) * 2u * wc;
+    uint32_t* o = bank + ((size_t)step * co_pad + co) * 2u * b.wc;
     o[q] = m;
-    o[wc + q] = s;
+    o[b.wc + q] = s;
 }
 
 }  // namespace
@@ -242,16 +254,14 @@ __global__ __launch_bounds__(256) void pack_filters_kernel(const int8_t* __restr
 int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
                         int32_t kw, uint32_t* bank, hipStream_t s)
 {
-    const int wd = (c_in + 31) / 32;
-    const int wc = (wd % 2 == 0) ? 2 : 1;
-    const int nchunk = wd / wc;
-    const int co_pad = (c_out + 31) / 32 * 32;
     const int T = kd * kh * kw;
-    const int64_t total = (int64_t)T * nchunk * co_pad * wc;
+    const BankShape b = bank_shape(c_in, T);
+    const int co_pad = (c_out + 31) / 32 * 32;
+    const int64_t total = (int64_t)b.nsteps * co_pad * b.wc;
     const int64_t blocks = (total + 255) / 256;
     if (blocks > 0x7fffffff) return TERN_ESHAPE;
     hipLaunchKernelGGL(pack_filters_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, bank, c_out,
-                       c_in, T, wc, nchunk, co_pad, total);
+                       c_in, T, b, co_pad, total);
     TERN_HIP_CHECK(hipGetLastError());
     return TERN_OK;
 }

@@ -34,12 +34,24 @@ def run_case(case, want_acc=True, want_packed=True):
 
 def bank_layout(w_packed: np.ndarray, c_out: int, c_in: int) -> np.ndarray:
     """Expected filter bank from plane-packed filters [C_out][kd][kh][kw][2][Wd] by pure
-    re-indexing: [T*nchunk][co_pad][2][wc] with wc = 2 if Wd even else 1, zero padding channels."""
+    re-indexing.  Plain: [T*nchunk][co_pad][2][wc] with wc = 2 if Wd even else 1.  Tap-packed
+    (C_in <= 16, T > 1): [ceil(T/slots)][co_pad][2][1], tap i of a row shifted left by i*shift."""
     wd = (c_in + 31) // 32
-    wc = 2 if wd % 2 == 0 else 1
-    nchunk = wd // wc
     taps = int(np.prod(w_packed.shape[1:4]))
     co_pad = (c_out + 31) // 32 * 32
+    if c_in <= 16 and taps > 1:
+        shift = 1
+        while shift < c_in:
+            shift *= 2
+        slots = min(32 // shift, taps)
+        rows = (taps + slots - 1) // slots
+        flat = w_packed.reshape(c_out, taps, 2).astype(np.uint64)       # one word per plane
+        bank = np.zeros((rows, co_pad, 2), dtype=np.uint64)
+        for t in range(taps):
+            bank[t // slots, :c_out] |= flat[:, t] << np.uint64((t % slots) * shift)
+        return bank.astype(np.uint32).reshape(-1)
+    wc = 2 if wd % 2 == 0 else 1
+    nchunk = wd // wc
     flat = w_packed.reshape(c_out, taps, 2, nchunk, wc)            # [co][tap][plane][chunk][q]
     bank = np.zeros((taps, nchunk, co_pad, 2, wc), dtype=np.uint32)
     bank[:, :, :c_out] = np.transpose(flat, (1, 3, 0, 2, 4))

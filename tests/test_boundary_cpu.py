@@ -37,7 +37,10 @@ def test_size_helpers(T):
     assert T.tern_packed_bytes((1, 0, 3, 4, 5)) == 0
     # filter bank: taps * words * co_pad * 8 bytes
     assert T.tern_filter_bank_bytes(64, 64, 3) == 27 * 2 * 64 * 8
-    assert T.tern_filter_bank_bytes(33, 1, (1, 3, 2)) == 6 * 1 * 64 * 8
+    assert T.tern_filter_bank_bytes(33, 1, (1, 3, 2)) == 1 * 64 * 8      # 6 taps packed into one word
+    assert T.tern_filter_bank_bytes(32, 16, 3) == 14 * 32 * 8           # two taps per word
+    assert T.tern_filter_bank_bytes(32, 17, 3) == 27 * 32 * 8           # plain layout above 16 channels
+    assert T.tern_filter_bank_bytes(32, 8, 1) == 1 * 32 * 8             # single tap: plain
     assert T.tern_filter_bank_bytes(0, 4, 3) == 0
 
 

@@ -193,6 +193,37 @@ def test_fused_equals_unfused_and_deterministic(G):
     assert torch.equal(fused1, unfused) and torch.equal(fused1, fused2)
 
 
+VARIANTS = [
+    # (lane depth, waves z, channels per pass, channels per wave, tap split)
+    (0, 0, 0, 0, 0), (2, 0, 16, 16, 1), (2, 0, 32, 32, 1), (4, 0, 0, 16, 1), (2, 2, 16, 48, 1),
+    (2, 4, 32, 64, 1), (2, 0, 16, 0, 2), (2, 0, 16, 0, 4), (2, 0, 32, 0, 8), (4, 0, 0, 0, 2),
+    (2, 2, 16, 0, 4),
+]
+
+
+@pytest.mark.parametrize("opts", VARIANTS, ids=["-".join(map(str, v)) for v in VARIANTS])
+def test_conv_kernel_variants_agree_with_oracle(G, opts):
+    """Every launch shape the tuning options can force (lane depth, stacked waves, channels per
+    pass / per wave, taps split over waves) on cases with one and two words per voxel, a
+    tap-packed small-C_in case and a ragged channel count."""
+    import paper_1801_09449_amd as T
+    cases = [
+        synth.conv_case("v_c64", 1, 64, 80, (6, 17, 9), seed=101),
+        synth.conv_case("v_c32", 2, 32, 33, (5, 9, 10), stride=2, seed=102),
+        synth.conv_case("v_c16", 1, 16, 48, (7, 9, 12), seed=103),
+        synth.conv_case("v_c3_dil", 1, 3, 20, (9, 8, 11), pad=2, dil=2, seed=104),
+        synth.conv_case("v_c256", 1, 256, 32, (4, 8, 8), seed=105),
+    ]
+    try:
+        for key, val in zip((1, 2, 3, 4, 5), opts):
+            T.tern_set_option(key, val)
+        for c in cases:
+            check_case(G, c)
+    finally:
+        for key in (1, 2, 3, 4, 5):
+            T.tern_set_option(key, 0)
+
+
 def test_generic_fallback_for_oversized_halo(G):
     # dilation so large that no halo tile fits in LDS: the library falls back to the direct kernel
     c = synth.conv_case("fallback", 1, 40, 33, (20, 21, 22), k=3, stride=1, pad=60, dil=60, seed=83)
