@@ -111,7 +111,10 @@ __device__ __forceinline__ void shift_in_lt(uint32_t& word, int32_t d, int32_t t
         : "+v"(word) : "v"(d), "s"(thr) : "vcc");
 }
 
-constexpr int kGroup = 8;  // output channels whose filter words are fetched together
+// Output channels whose filter words are fetched together.  Two groups are in flight (one being
+// used, one arriving); 4 channels x up to 4 words x 2 groups keeps the filter words within 32
+// SGPRs, which leaves room for the loop's own scalars (8 per group made the compiler spill them).
+constexpr int kGroup = 4;
 
 template <int WC>
 struct WGroup {
@@ -391,8 +394,8 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     sc.slot_mask = TP ? ((1u << p.c_in) - 1u) : 0xffffffffu;
     sc.tap_end = TP ? min(T, s_end * p.tp_slots) : T;
     // cursor at this wave's first step
-    StepCursor cur0;
-    {
+    StepCursor cur0 = {0, 0, 0, 0, 0};
+    if (s_begin > 0) {
         const int tap0 = TP ? s_begin * p.tp_slots : s_begin / t.nchunk;
         cur0.ch = TP ? 0 : s_begin - tap0 * t.nchunk;
         cur0.tap = tap0;
