@@ -12,7 +12,7 @@ namespace {
 
 constexpr int kBlock = 256;
 
-// VPT voxels of type T starting at p (p is aligned to VPT*sizeof(T) when VPT > 1).
+// VPT voxels of type T starting at p (4 or 16 bytes, naturally aligned, when VPT > 1).
 template <typename T, int VPT>
 struct Vec {
     T v[VPT];
@@ -78,14 +78,15 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const T* __restrict__ src,
             for (int i = 0; i < VPT; ++i) m[q][i] = s[q][i] = 0u;
             const int cbase = 32 * q;
             if (cbase + 32 <= C) {
-                // full word: 4 batches of 8 independent loads
+                // full word: batches of independent loads, at least 128 bytes in flight per lane
+                constexpr int B = (sizeof(T) * VPT >= 16) ? 8 : 32;
 #pragma unroll
-                for (int j0 = 0; j0 < 32; j0 += 8) {
-                    Vec<T, VPT> x[8];
+                for (int j0 = 0; j0 < 32; j0 += B) {
+                    Vec<T, VPT> x[B];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) x[j].load(base + (size_t)(cbase + j0 + j) * spatial);
+                    for (int j = 0; j < B; ++j) x[j].load(base + (size_t)(cbase + j0 + j) * spatial);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
+                    for (int j = 0; j < B; ++j) {
                         T tl = T(0), th = T(0);
                         if constexpr (MODE == 1) { tl = lo[cbase + j0 + j]; th = hi[cbase + j0 + j]; }
                         classify<T, VPT, MODE>(x[j], tl, th, j0 + j, m[q], s[q]);
@@ -154,9 +155,14 @@ int launch_pack_any(const T* src, tern_dims dims, const T* lo, const T* hi, uint
 {
     const int64_t spatial = (int64_t)dims.d * dims.h * dims.w;
     const int32_t Wd = (dims.c + 31) / 32;
-    constexpr int VPT = 4;
-    const bool vec_ok = (spatial % VPT == 0) && (((uintptr_t)src % (VPT * sizeof(T))) == 0);
-    const int vpt = vec_ok ? VPT : 1;
+    // Voxels per thread: 4, or 16 for int8 when that still leaves a few thousand waves (a 16-byte
+    // load per lane instead of a 4-byte one).
+    constexpr bool kByte = sizeof(T) == 1;
+    const bool ok4 = (spatial % 4 == 0) && (((uintptr_t)src % (4 * sizeof(T))) == 0);
+    const bool ok16 = kByte && (spatial % 16 == 0) && (((uintptr_t)src % 16) == 0) &&
+                      spatial * dims.n / 16 >= (int64_t)4096 * 64;
+    const int vpt = ok16 ? 16 : (ok4 ? 4 : 1);
+    const bool vec_ok = vpt > 1;
     const int64_t gpn = spatial / vpt;
     const int64_t total = gpn * dims.n;
     const int64_t blocks = (total + kBlock - 1) / kBlock;
@@ -166,12 +172,23 @@ int launch_pack_any(const T* src, tern_dims dims, const T* lo, const T* hi, uint
     hipLaunchKernelGGL((pack_kernel<T, VPT_, MODE, WDT_>), grid, block, 0, s, src, dst, lo, hi, dims.c, \
                        Wd, spatial, gpn, total)
     if (vec_ok) {
-        switch (Wd) {
-            case 1: TERN_PACK_LAUNCH(4, 1); break;
-            case 2: TERN_PACK_LAUNCH(4, 2); break;
-            case 4: TERN_PACK_LAUNCH(4, 4); break;
-            case 8: TERN_PACK_LAUNCH(4, 8); break;
-            default: TERN_PACK_LAUNCH(4, 0); break;
+        if (vpt == 16) {
+            if constexpr (kByte) {
+                switch (Wd) {   // 16 voxels x 2*Wd words stay in registers
+                    case 1: TERN_PACK_LAUNCH(16, 1); break;
+                    case 2: TERN_PACK_LAUNCH(16, 2); break;
+                    case 4: TERN_PACK_LAUNCH(16, 4); break;
+                    default: TERN_PACK_LAUNCH(16, 0); break;
+                }
+            }
+        } else {
+            switch (Wd) {
+                case 1: TERN_PACK_LAUNCH(4, 1); break;
+                case 2: TERN_PACK_LAUNCH(4, 2); break;
+                case 4: TERN_PACK_LAUNCH(4, 4); break;
+                case 8: TERN_PACK_LAUNCH(4, 8); break;
+                default: TERN_PACK_LAUNCH(4, 0); break;
+            }
         }
     } else {
         TERN_PACK_LAUNCH(1, 0);
