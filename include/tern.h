@@ -124,8 +124,9 @@ int tern_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, 
  *         per-channel scale and batch-norm folded into two integer cut points):
  *         code = +1 if acc > thr_hi[co]; -1 if acc < thr_lo[co]; else 0, written in the packed
  *         layout with logical dims {N, c_out, Do, Ho, Wo}.  thr_lo, thr_hi: int32[c_out] on the
- *         device, required, with thr_lo[co] <= thr_hi[co] (not checked -- the values live on the
- *         device; if violated, +1 takes precedence where both comparisons hold).
+ *         device, required, with thr_lo[co] <= thr_hi[co] + 1 (lo = hi + 1 is an empty zero
+ *         band; not checked -- the values live on the device; if violated, +1 takes precedence
+ *         where both comparisons hold).
  *   Both non-NULL or both NULL -> TERN_EARG.  Buffers must not overlap.
  */
 int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims,
@@ -139,7 +140,8 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims,
  *   src    : contiguous [N][C][D][H][W] of type t (TERN_SRC_I32: int32 accumulators with int32
  *            cut points; TERN_SRC_F32: float values with float cut points, e.g. raw intensities
  *            at -0.5 / +0.5; a NaN becomes 0).  TERN_SRC_I8 is not accepted here (TERN_EARG).
- *   thr_lo, thr_hi : C entries of the source type, device memory, lo[c] <= hi[c] (not checked).
+ *   thr_lo, thr_hi : C entries of the source type, device memory, lo[c] <= hi[c] (int32:
+ *            lo[c] <= hi[c] + 1); not checked.
  */
 int tern_threshold_pack(const void* src, tern_src_type t, tern_dims dims,
                         const void* thr_lo, const void* thr_hi,
@@ -181,6 +183,37 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
                      void* workspace, size_t workspace_bytes,
                      uint32_t* out_packed, tern_dims* out_dims /* host */,
                      uint32_t** layer_out /* host, optional */, void* stream);
+
+/*
+ * Host-side model preparation.  These three run on the CPU on HOST arrays and launch nothing.
+ *
+ * tern_ternarize_filters -- ternary weight approximation W ~ alpha * W~ (Eq. 4), per output
+ * filter: Delta = 0.7/n * sum|W_i|;  W~_i = +1 if W_i > Delta, 0 if |W_i| <= Delta, -1 otherwise;
+ * alpha = mean of |W_i| over the nonzero W~_i (0 if there are none).  Sums in double.
+ *   w      : float [c_out][per_filter]  (per_filter = C_in*kd*kh*kw, the filter's own order)
+ *   codes  : int8  [c_out][per_filter]  (ready for tern_pack_filters once copied to the device)
+ *   alpha  : double[c_out]
+ *
+ * tern_fold_thresholds -- integer cut points for the activation of Eq. 6 applied to
+ * y = scale[c]*acc + shift[c] (scale and shift collect alpha and the batch-norm affine, which sit
+ * between convolution and activation in a TernaryNet module, section 2).  For every integer acc
+ * with |acc| <= acc_bound:  (+1 if acc > hi[c]; -1 if acc < lo[c]; else 0) equals the
+ * double-precision evaluation (+1 if y > 0.5; 0 if |y| <= 0.5; else -1), ties included.
+ * A channel with negative scale gets negate[c] = 1 and cut points for |scale|: the caller must
+ * negate that filter's ternary codes (conv(-w) = -conv(w)).  scale = 0 gives a constant channel.
+ * acc_bound: 1 .. 2^24-1, normally C_in*kd*kh*kw.  Non-finite scale/shift -> TERN_EARG.
+ *
+ * tern_fold_batchnorm -- the same with scale = alpha*gamma/sqrt(var+eps) and
+ * shift = beta - gamma*mean/sqrt(var+eps) computed in double.
+ */
+int tern_ternarize_filters(const float* w /* host */, int32_t c_out, int64_t per_filter,
+                           int8_t* codes /* host */, double* alpha /* host */);
+int tern_fold_thresholds(const double* scale /* host */, const double* shift /* host */, int32_t c,
+                         int32_t acc_bound, int32_t* lo /* host */, int32_t* hi /* host */,
+                         uint8_t* negate /* host */);
+int tern_fold_batchnorm(const double* alpha, const double* gamma, const double* beta,
+                        const double* mean, const double* var, double eps, int32_t c,
+                        int32_t acc_bound, int32_t* lo, int32_t* hi, uint8_t* negate);
 
 /* Tuning overrides (process-wide, not thread-safe against concurrent launches; defaults are
  * chosen per call from the problem size).  TERN_OPT_LANE_DEPTH: output voxels per lane along z in

@@ -14,3 +14,4 @@ from .tern_oracle import (  # noqa: F401
     threshold,
     unpack,
 )
+from .prepare_oracle import activation_code, bn_affine, ternarize_filters  # noqa: F401,E402

@@ -1,0 +1,44 @@
+"""Oracle for the host-side model preparation (test infrastructure, not the product).
+
+Two small definitions from the paper, written out plainly in float64 numpy:
+
+* ternary weights (Eq. 4): Delta = 0.7/n * sum|W_i|;  W~_i = +1 if W_i > Delta, 0 if |W_i| <= Delta,
+  -1 otherwise;  alpha = (sum over nonzero W~ of |W_i|) / n_Delta.  Taken per output filter: the
+  paper stores "one scalar weighting value per feature channel" (section 2, last paragraph).
+* the activation of Eq. 6 applied to y = a*acc + b, where a and b collect the weight scale alpha
+  and the batch-norm affine (section 2: batch-norm sits between the ternary convolution and the
+  activation):  code(acc) = +1 if y > 0.5, 0 if |y| <= 0.5, -1 otherwise, evaluated in float64.
+
+Pins: tests/test_prepare.py (hand-worked vectors, scale equivariance, Gaussian zero fraction,
+exhaustive agreement of integer cut points with the float64 evaluation).
+"""
+import numpy as np
+
+
+def ternarize_filters(w: np.ndarray):
+    """w: float [C_out][...].  Returns (int8 codes of the same shape, float64 alpha[C_out])."""
+    w64 = np.asarray(w, dtype=np.float64)
+    flat = w64.reshape(w64.shape[0], -1)
+    codes = np.zeros(flat.shape, dtype=np.int8)
+    alpha = np.zeros(flat.shape[0], dtype=np.float64)
+    for co in range(flat.shape[0]):
+        row = flat[co]
+        delta = 0.7 * np.sum(np.abs(row)) / row.size
+        t = np.where(row > delta, 1, np.where(np.abs(row) <= delta, 0, -1)).astype(np.int8)
+        n_delta = int(np.count_nonzero(t))
+        alpha[co] = (np.sum(np.abs(row)[t != 0]) / n_delta) if n_delta else 0.0
+        codes[co] = t
+    return codes.reshape(w64.shape), alpha
+
+
+def bn_affine(alpha, gamma, beta, mean, var, eps):
+    """y = a*acc + b for conv scale alpha followed by batch-norm (gamma, beta, mean, var, eps)."""
+    alpha, gamma, beta, mean, var = (np.asarray(v, dtype=np.float64) for v in (alpha, gamma, beta, mean, var))
+    inv = 1.0 / np.sqrt(var + eps)
+    return alpha * gamma * inv, beta - gamma * mean * inv
+
+
+def activation_code(acc, a, b):
+    """Eq. 6 on y = a*acc + b in float64, for integer acc (any shape) and scalars a, b."""
+    y = np.float64(a) * np.asarray(acc, dtype=np.float64) + np.float64(b)
+    return np.where(y > 0.5, 1, np.where(np.abs(y) <= 0.5, 0, -1)).astype(np.int8)

@@ -22,7 +22,7 @@
  *   - the hard activation tern(x) of Eq. 6 (+1 if x > 0.5, 0 if |x| <= 0.5, -1 else) with the
  *     per-channel scale alpha (below Eq. 4) and batch-norm (section 2, last paragraph) folded
  *     into two integer cut points per channel: code = +1 if acc > hi, -1 if acc < lo, else 0,
- *     strict comparisons, inclusive zero band, lo <= hi;
+ *     strict comparisons, inclusive zero band, lo <= hi + 1 (lo = hi + 1: empty zero band);
  *   - the 2-bit storage of Fig. 3 as two bit-planes packed along channels: bit j of word q of a
  *     voxel's mask plane is 1 iff channel 32q+j is nonzero; the same bit of the sign plane is 1
  *     iff that channel is -1 (and 0 when the value is 0).  The figure's caption draws the first
@@ -166,8 +166,11 @@ int oracle_threshold_i32(const int32_t* v, int n, int c, int64_t spatial,
                          const int32_t* lo, const int32_t* hi, int8_t* code)
 {
     if (!v || !lo || !hi || !code || n <= 0 || c <= 0 || spatial <= 0) return ORACLE_EARG;
+    /* lo = hi + 1 is allowed: when the scale folded into the cut points exceeds 1, the zero band
+     * |y| <= 0.5 of Eq. 6 may contain no integer, and the -1 and +1 ranges are then adjacent.
+     * Beyond that the two ranges would overlap, which Eq. 6 cannot produce. */
     for (int ch = 0; ch < c; ++ch)
-        if (lo[ch] > hi[ch]) return ORACLE_EARG;
+        if ((int64_t)lo[ch] > (int64_t)hi[ch] + 1) return ORACLE_EARG;
 #pragma omp parallel for collapse(2) schedule(static)
     for (int b = 0; b < n; ++b)
         for (int ch = 0; ch < c; ++ch)

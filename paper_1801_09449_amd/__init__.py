@@ -14,6 +14,9 @@ from .binding import (  # noqa: F401
     tern_fcn_forward,
     tern_fcn_workspace_bytes,
     tern_filter_bank_bytes,
+    tern_fold_batchnorm,
+    tern_fold_thresholds,
+    tern_ternarize_filters,
     tern_pack,
     tern_pack_filters,
     tern_packed_bytes,

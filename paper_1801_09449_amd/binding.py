@@ -71,6 +71,10 @@ def lib():
     L.tern_fcn_forward.argtypes = [P, Dims, P, P, C.POINTER(Layer), I, P, S, P, C.POINTER(Dims),
                                    C.POINTER(C.c_void_p), P]
     L.tern_fcn_forward.restype = C.c_int
+    L.tern_ternarize_filters.argtypes = [P, I, C.c_int64, P, P]; L.tern_ternarize_filters.restype = C.c_int
+    L.tern_fold_thresholds.argtypes = [P, P, I, I, P, P, P]; L.tern_fold_thresholds.restype = C.c_int
+    L.tern_fold_batchnorm.argtypes = [P, P, P, P, P, C.c_double, I, I, P, P, P]
+    L.tern_fold_batchnorm.restype = C.c_int
     L.tern_set_option.argtypes = [C.c_int, C.c_int]; L.tern_set_option.restype = C.c_int
     L.tern_probe_valu.argtypes = [I, I, I, P, P]; L.tern_probe_valu.restype = C.c_int
     _lib = L
@@ -349,3 +353,47 @@ def tern_probe_valu(blocks: int, threads: int, iters: int, sink: torch.Tensor) -
 def tern_set_option(option: int, value: int) -> None:
     """Tuning override (1 = lane depth: 0 auto, 2, 4).  Results never depend on options."""
     _check(lib().tern_set_option(int(option), int(value)), "tern_set_option")
+
+
+# ---- host-side model preparation (numpy arrays in, numpy arrays out; no GPU involved) ----------
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def tern_ternarize_filters(w):
+    """float32 [C_out][...] host array -> (int8 codes of the same shape, float64 alpha[C_out])."""
+    import numpy as np
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    if w.ndim < 2:
+        raise ValueError("w must be [C_out][...]")
+    codes = np.empty(w.shape, dtype=np.int8)
+    alpha = np.empty(w.shape[0], dtype=np.float64)
+    _check(lib().tern_ternarize_filters(_np_ptr(w), w.shape[0], w.size // w.shape[0], _np_ptr(codes),
+                                        _np_ptr(alpha)), "tern_ternarize_filters")
+    return codes, alpha
+
+
+def tern_fold_thresholds(scale, shift, acc_bound: int):
+    """Per-channel y = scale*acc + shift -> (lo int32[C], hi int32[C], negate uint8[C])."""
+    import numpy as np
+    scale = np.ascontiguousarray(scale, dtype=np.float64)
+    shift = np.ascontiguousarray(shift, dtype=np.float64)
+    if scale.ndim != 1 or scale.shape != shift.shape:
+        raise ValueError("scale and shift must be 1-D arrays of the same length")
+    c = scale.shape[0]
+    lo = np.empty(c, np.int32); hi = np.empty(c, np.int32); neg = np.empty(c, np.uint8)
+    _check(lib().tern_fold_thresholds(_np_ptr(scale), _np_ptr(shift), c, int(acc_bound), _np_ptr(lo),
+                                      _np_ptr(hi), _np_ptr(neg)), "tern_fold_thresholds")
+    return lo, hi, neg
+
+
+def tern_fold_batchnorm(alpha, gamma, beta, mean, var, eps: float, acc_bound: int):
+    import numpy as np
+    arrs = [np.ascontiguousarray(v, dtype=np.float64) for v in (alpha, gamma, beta, mean, var)]
+    c = arrs[0].shape[0]
+    if any(a.ndim != 1 or a.shape[0] != c for a in arrs):
+        raise ValueError("all per-channel arrays must be 1-D of the same length")
+    lo = np.empty(c, np.int32); hi = np.empty(c, np.int32); neg = np.empty(c, np.uint8)
+    _check(lib().tern_fold_batchnorm(*[_np_ptr(a) for a in arrs], float(eps), c, int(acc_bound),
+                                     _np_ptr(lo), _np_ptr(hi), _np_ptr(neg)), "tern_fold_batchnorm")
+    return lo, hi, neg

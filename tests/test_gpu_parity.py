@@ -176,6 +176,7 @@ def test_conv_extreme_cut_points(G):
     c.hi = np.where(np.arange(32) % 4 == 0, i32.max, np.where(np.arange(32) % 4 == 1, i32.max,
                     np.where(np.arange(32) % 4 == 2, i32.min, c.hi))).astype(np.int32)
     c.lo = np.minimum(c.lo, c.hi)
+    c.lo[3::4] = c.hi[3::4] + 1          # empty zero band: every accumulator maps to -1 or +1
     check_case(G, c)
 
 

@@ -194,8 +194,11 @@ def test_threshold_strict_outside_inclusive_band():
     # lo == hi: only that value maps to 0
     code = oracle.threshold(v, np.array([0], np.int32), np.array([0], np.int32))
     np.testing.assert_array_equal(code.reshape(-1), [-1] * 4 + [0] + [1] * 4)
+    # lo == hi + 1: empty zero band (a folded scale above 1 leaves no integer inside |y| <= 0.5)
+    code = oracle.threshold(v, np.array([1], np.int32), np.array([0], np.int32))
+    np.testing.assert_array_equal(code.reshape(-1), [-1] * 5 + [1] * 4)
     with pytest.raises(ValueError):
-        oracle.threshold(v, np.array([1], np.int32), np.array([0], np.int32))
+        oracle.threshold(v, np.array([2], np.int32), np.array([0], np.int32))
     # float form of Eq. 6 at the paper's cut points: x > 0.5 -> +1, |x| <= 0.5 -> 0, else -1
     x = np.array([-0.75, -0.5, -0.25, 0.0, 0.5, 0.5000001, 2.0, np.nan], np.float32).reshape(1, 1, -1)
     code = oracle.threshold(x, np.array([-0.5], np.float32), np.array([0.5], np.float32))
