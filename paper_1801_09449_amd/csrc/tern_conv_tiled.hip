@@ -111,25 +111,30 @@ __device__ __forceinline__ void shift_in_lt(uint32_t& word, int32_t d, int32_t t
         : "+v"(word) : "v"(d), "s"(thr) : "vcc");
 }
 
-// Output channels whose filter words are fetched together.  Two groups are in flight (one being
-// used, one arriving); 4 channels x up to 4 words x 2 groups keeps the filter words within 32
-// SGPRs, which leaves room for the loop's own scalars (8 per group made the compiler spill them).
-constexpr int kGroup = 4;
-
-template <int WC>
-struct WGroup {
-    uint32_t m[kGroup][WC];
-    uint32_t s[kGroup][WC];
+// KG = output channels whose filter words are fetched together.  Two groups are in flight (one
+// being used, one arriving).  With 32 channels per pass KG = 4 keeps the filter words within 32
+// SGPRs, which leaves room for the loop's own scalars (8 per group made the compiler spill them);
+// with 16 channels per pass KG = 8 fits and halves the number of waits, which matters when a
+// SIMD holds a single wave and nothing else hides the scalar-cache latency.
+template <int CO_BLK>
+struct GroupOf {
+    static constexpr int value = CO_BLK >= 32 ? 4 : 8;
 };
 
-// Fetch the filter words of kGroup consecutive channels of one step.  In the filter bank the
+template <int WC, int KG>
+struct WGroup {
+    uint32_t m[KG][WC];
+    uint32_t s[KG][WC];
+};
+
+// Fetch the filter words of KG consecutive channels of one step.  In the filter bank the
 // channels of a step are contiguous (2*WC words each), so this is one contiguous block that
 // the compiler turns into wide scalar loads with immediate offsets.
-template <int WC>
-__device__ __forceinline__ void load_wgroup(WGroup<WC>& g, scalar_ptr wp)
+template <int WC, int KG>
+__device__ __forceinline__ void load_wgroup(WGroup<WC, KG>& g, scalar_ptr wp)
 {
 #pragma unroll
-    for (int j = 0; j < kGroup; ++j)
+    for (int j = 0; j < KG; ++j)
 #pragma unroll
         for (int q = 0; q < WC; ++q) {
             g.m[j][q] = wp[j * 2 * WC + q];
@@ -141,11 +146,12 @@ __device__ __forceinline__ void load_wgroup(WGroup<WC>& g, scalar_ptr wp)
 // registers here makes the compiler place that wait at this point, i.e. before the loads of the
 // following group are issued, so that those overlap the arithmetic on this group instead of
 // being waited for together with it.
-template <int WC>
-__device__ __forceinline__ void settle(const WGroup<WC>& g)
+template <int WC, int KG>
+__device__ __forceinline__ void settle(const WGroup<WC, KG>& g)
 {
+    static_assert(KG % 4 == 0, "groups of 4 channels per asm statement");
 #pragma unroll
-    for (int j = 0; j < kGroup; j += 4) {
+    for (int j = 0; j < KG; j += 4) {
         if constexpr (WC == 2) {
             asm volatile("" ::"s"(g.m[j][0]), "s"(g.m[j][1]), "s"(g.s[j][0]), "s"(g.s[j][1]),
                          "s"(g.m[j + 1][0]), "s"(g.m[j + 1][1]), "s"(g.s[j + 1][0]), "s"(g.s[j + 1][1]),
@@ -160,12 +166,12 @@ __device__ __forceinline__ void settle(const WGroup<WC>& g)
 
 // Four VALU instructions per (word pair, voxel): and, popcount-accumulate, and-xor,
 // popcount-accumulate (Eq. 9 as popcount(M) - 2 popcount(M & X), the subtraction deferred).
-template <int WC, int V, int CO_BLK>
-__device__ __forceinline__ void mac_group(const ActChunk<WC> (&A)[V], const WGroup<WC>& g, int j0,
+template <int WC, int V, int CO_BLK, int KG>
+__device__ __forceinline__ void mac_group(const ActChunk<WC> (&A)[V], const WGroup<WC, KG>& g, int j0,
                                           int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK])
 {
 #pragma unroll
-    for (int j = 0; j < kGroup; ++j)
+    for (int j = 0; j < KG; ++j)
 #pragma unroll
         for (int q = 0; q < WC; ++q)
 #pragma unroll
@@ -250,29 +256,31 @@ __device__ __forceinline__ void fetch_step(ActChunk<WC> (&A)[V], StepCursor& c, 
 template <int WC, int V, int CO_BLK, bool TP>
 __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<WC> (&A1)[V], bool last,
                                           StepCursor& cur, const StepConsts& sc, int inc_c, int inc_b,
-                                          int inc_a, WGroup<WC>& g0,
-                                          WGroup<WC>& g1, scalar_ptr& wcur, const uint32_t* lane_lds,
+                                          int inc_a, WGroup<WC, GroupOf<CO_BLK>::value>& g0,
+                                          WGroup<WC, GroupOf<CO_BLK>::value>& g1, scalar_ptr& wcur,
+                                          const uint32_t* lane_lds,
                                           int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK])
 {
-    constexpr int NG = CO_BLK / kGroup;
+    constexpr int KG = GroupOf<CO_BLK>::value;
+    constexpr int NG = CO_BLK / KG;
     // after a wave's last step the prefetches re-read the same (valid) addresses and are dropped
     scalar_ptr wnext = last ? wcur : wcur + sc.step_words;
 #pragma unroll
     for (int gi = 0; gi < NG; gi += 2) {
-        settle<WC>(g0);
+        settle<WC, KG>(g0);
         __builtin_amdgcn_sched_barrier(0);
         // issued behind the wait so that the LDS reads complete under the first group's arithmetic
         if (gi == 0) fetch_step<WC, V, TP>(A1, cur, sc, inc_c, inc_b, inc_a, lane_lds, !last);
-        load_wgroup<WC>(g1, wcur + (gi + 1) * kGroup * 2 * WC);
+        load_wgroup<WC, KG>(g1, wcur + (gi + 1) * KG * 2 * WC);
         __builtin_amdgcn_sched_barrier(0);
-        mac_group<WC, V, CO_BLK>(A0, g0, gi * kGroup, acc_m, acc_n);
+        mac_group<WC, V, CO_BLK, KG>(A0, g0, gi * KG, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
-        settle<WC>(g1);
+        settle<WC, KG>(g1);
         __builtin_amdgcn_sched_barrier(0);
-        if (gi + 2 < NG) load_wgroup<WC>(g0, wcur + (gi + 2) * kGroup * 2 * WC);
-        else load_wgroup<WC>(g0, wnext);
+        if (gi + 2 < NG) load_wgroup<WC, KG>(g0, wcur + (gi + 2) * KG * 2 * WC);
+        else load_wgroup<WC, KG>(g0, wnext);
         __builtin_amdgcn_sched_barrier(0);
-        mac_group<WC, V, CO_BLK>(A0, g1, (gi + 1) * kGroup, acc_m, acc_n);
+        mac_group<WC, V, CO_BLK, KG>(A0, g1, (gi + 1) * KG, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
     }
     wcur = wnext;
@@ -405,8 +413,9 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
         const int ta = r / p.kh;
         cur0.toff = ta * p.dd * plane_words + cur0.tb * p.dh * row_words + cur0.tc * inc_c;
     }
-    constexpr int NG = CO_BLK / kGroup;
-    static_assert(NG >= 2 && NG % 2 == 0, "CO_BLK must be a multiple of 2*kGroup");
+    constexpr int KG = GroupOf<CO_BLK>::value;
+    constexpr int NG = CO_BLK / KG;
+    static_assert(NG >= 2 && NG % 2 == 0, "CO_BLK must be a multiple of twice the group size");
     static_assert(CO_BLK <= 32 && 32 % CO_BLK == 0, "CO_BLK must divide 32");
 
     uint32_t pos_w[V], neg_w[V];  // packed mode: decision bits of the 32-channel word in progress
@@ -431,11 +440,11 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
             if (s_begin < s_end) {
                 scalar_ptr wcur = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC +
                                   (size_t)s_begin * sc.step_words;
-                WGroup<WC> g0, g1;
+                WGroup<WC, KG> g0, g1;
                 StepCursor cur = cur0;
                 ActChunk<WC> Aa[V], Ab[V];
                 fetch_step<WC, V, TP>(Aa, cur, sc, inc_c, inc_b, inc_a, lane_lds, false);
-                load_wgroup<WC>(g0, wcur);
+                load_wgroup<WC, KG>(g0, wcur);
                 int step = s_begin;
                 for (; step + 2 <= s_end; step += 2) {   // two steps per trip: no register copies
                     conv_step<WC, V, CO_BLK, TP>(Aa, Ab, false, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
@@ -606,11 +615,16 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
         return hx * hy * hz * q.vstride * 4;
     };
     // Start from one wave per workgroup; grow the tile (stacking waves along the axis that
-    // lowers LDS per wave the most) while the per-wave LDS share is too large for eight waves
-    // per compute unit (20 KB per wave of the 160 KB).
+    // lowers LDS per wave the most) while the per-wave LDS share is too large for the waves a
+    // compute unit is expected to hold: eight (20 KB each of the 160 KB) on a large problem,
+    // fewer on a small one, where small tiles matter more because they give more workgroups.
+    const int64_t waves1 = (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, V) * p.n * cdiv(p.c_out, 16);
+    int per_cu = (int)((waves1 + 255) / 256);
+    per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
+    const int64_t share_budget = (int64_t)(160 * 1024) / per_cu;
     for (int it = 0; it < 6; ++it) {
         const int waves = t.nwx * t.nwy * t.nwz;
-        if (lds_for(t) <= (int64_t)waves * 20 * 1024 || waves >= 8) break;
+        if (lds_for(t) <= (int64_t)waves * share_budget || waves >= 8) break;
         TileParams best = t;
         double best_share = 1e30;
         TileParams cand[3] = {t, t, t};
