@@ -152,8 +152,8 @@ def main():
     ap.add_argument("--co-per-wave", type=int, default=0, help="tuning override: 0 auto, multiple of 16")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (--gpus 1); multi-GPU sharding is "
-              "described in DESIGN.md but not built.", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); sharding over several "
+              "GPUs is not built.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -64,11 +64,14 @@ typedef enum {
     TERN_EHIP = -5          /* a HIP call failed; see tern_last_hip_error()                  */
 } tern_status;
 
-typedef struct { int32_t n, c, d, h, w; } tern_dims;          /* logical NCDHW extents */
+/* Logical NCDHW extents.  Limits: every extent >= 1; N*D*H*W <= 2^31 - 1 voxels per tensor (the
+ * kernels count voxels in 32 bits; byte offsets are 64-bit, so tensors may exceed 4 GiB). */
+typedef struct { int32_t n, c, d, h, w; } tern_dims;
 
 /* Kernel extent, stride, zero padding (both sides) and dilation per axis, order (d, h, w).
  * Output extent per axis: floor((X + 2*pad - dil*(k-1) - 1)/stride) + 1; TERN_ESHAPE if < 1.
- * Limits: k >= 1, stride >= 1, dil >= 1, pad >= 0; k[0]*k[1]*k[2]*C_in < 2^24. */
+ * Limits: 1 <= k, stride, dil <= 1024 and 0 <= pad <= 2^20 per axis (else TERN_EARG);
+ * k[0]*k[1]*k[2]*C_in < 2^24, which bounds |accumulator|, and C_out <= 2^19 (else TERN_ESHAPE). */
 typedef struct { int32_t k[3], stride[3], pad[3], dil[3]; } tern_conv_geom;
 
 typedef enum { TERN_SRC_I8 = 0, TERN_SRC_I32 = 1, TERN_SRC_F32 = 2 } tern_src_type;

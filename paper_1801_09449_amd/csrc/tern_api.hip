@@ -47,7 +47,7 @@ static int out_extent(int x, int k, int s, int p, int dil)
 
 static bool filter_shape_ok(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw)
 {
-    if (c_out <= 0 || c_in <= 0 || kd < 1 || kh < 1 || kw < 1) return false;
+    if (c_out <= 0 || c_out > (1 << 19) || c_in <= 0 || kd < 1 || kh < 1 || kw < 1) return false;
     if (kd > 1024 || kh > 1024 || kw > 1024) return false;
     const int64_t taps = (int64_t)kd * kh * kw;
     if (taps * c_in >= (int64_t)1 << 24) return false;

@@ -723,6 +723,7 @@ int launch_conv3d(const ConvParams& p, hipStream_t s)
         }
     }
     const int grid_y = cdiv(slices, nwc);
+    if (grid_y > 65535) return TERN_ESHAPE;
 
     const dim3 grid((unsigned)spatial_tiles, (unsigned)grid_y);
     const int threads = 64 * nsp * nwc * nks;

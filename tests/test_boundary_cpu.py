@@ -99,3 +99,31 @@ def test_binding_refuses_cpu_tensors(T):
     import torch
     with pytest.raises(ValueError):
         T.tern_pack(torch.zeros((1, 4, 2, 2, 2), dtype=torch.int8))
+
+
+def test_maximum_sizes_are_enforced(T):
+    """The kernels index voxels with 32-bit integers and accumulate in int32: extents beyond
+    those limits must be refused, extents just inside accepted (no launch: helpers only)."""
+    from paper_1801_09449_amd.binding import Dims, _geom
+    L = T.lib()
+    fake = C.c_void_p(0x1000)
+    # 2^31 - 1 voxels is the most a tensor may hold
+    assert T.tern_packed_bytes((1, 1, 1, 1, 2 ** 31 - 1)) == (2 ** 31 - 1) * 8
+    assert T.tern_packed_bytes((1, 1, 2, 2 ** 15, 2 ** 15)) == 0           # 2^31 voxels
+    assert T.tern_packed_bytes((2 ** 16, 1, 2 ** 15, 1, 1)) == 0           # batch counts too
+    assert L.tern_pack(fake, Dims(1, 1, 2, 2 ** 15, 2 ** 15), fake, None) == -2
+    # output extents are checked as well as input extents (padding grows the output)
+    with pytest.raises(T.TernError) as e:
+        T.tern_conv_out_dims((1, 1, 1, 1, 2 ** 31 - 2), 1, (1, 1, 1), 1, (0, 0, 1), 1)
+    assert e.value.status == -2
+    # kernel volume x C_in bounds |accumulator|: it must stay below 2^24
+    assert T.tern_filter_bank_bytes(1, 2 ** 14, (16, 8, 8)) == 0           # 2^24
+    assert T.tern_filter_bank_bytes(1, 2 ** 14 - 1, (16, 8, 8)) > 0
+    assert L.tern_conv3d(fake, Dims(1, 2 ** 14, 16, 8, 8), fake, 1, _geom((16, 8, 8), 1, 0, 1),
+                         None, None, fake, None, None) == -2
+    # kernel, stride, dilation extents above 1024 are rejected as arguments
+    assert L.tern_conv3d(fake, Dims(1, 1, 2000, 4, 4), fake, 1, _geom((1025, 1, 1), 1, 0, 1),
+                         None, None, fake, None, None) == -3
+    # output channel count
+    assert T.tern_filter_bank_bytes(2 ** 19, 1, 1) > 0
+    assert T.tern_filter_bank_bytes(2 ** 19 + 1, 1, 1) == 0

@@ -336,3 +336,71 @@ def test_config2_fcn_full(G):
     # the synthetic cut points keep the activations from collapsing
     zero_frac = float(np.mean(want[-1] == 0))
     assert 0.15 < zero_frac < 0.7
+
+
+# ---- tensors above 4 GiB: byte offsets need 64 bits, voxel indices still fit 32 ---------------
+@pytest.mark.parametrize("c_in,c_out", [(1, 33), (17, 8)], ids=["tap-packed", "plain"])
+def test_volume_above_4gib_sampled(G, c_in, c_out):
+    """576 Mi voxels: the packed input (4.5 GiB) and output (4.5 or 9 GiB) exceed 32-bit byte
+    offsets.  The volume is one seeded 64 Mi-voxel block repeated nine times along D (drawing
+    every element separately would take minutes); the oracle evaluates sampled outputs, which
+    include the last voxel, on the very same array."""
+    import torch
+    import paper_1801_09449_amd as T
+    block = synth.ternary((1, c_in, 64, 1024, 1024), 1.0 / 3.0, 41, synth.T_ACT)
+    act = np.tile(block, (1, 1, 9, 1, 1))
+    del block
+    wgt = synth.ternary((c_out, c_in, 3, 3, 3), 0.5, 41, synth.T_WGT)
+    lo, hi = synth.threshold_pair(c_out, 41, lo=-2, hi=2)
+    packed_in = T.tern_pack(G.dev(act))
+    assert packed_in.numel() * 4 > 2 ** 32
+    out = T.tern_conv3d(packed_in, c_in, T.tern_pack_filters(G.dev(wgt)), c_out, 3, 1, 1, 1,
+                        thr_lo=G.dev(lo), thr_hi=G.dev(hi))
+    torch.cuda.synchronize()
+    del packed_in
+    assert out.numel() * 4 > 2 ** 32
+    pts = sample_points((1, c_out) + act.shape[2:], 3000, 43)
+    pts = np.concatenate([pts, pts[:200] * np.array([0, 1, 0, 1, 1]) + np.array([0, 0, 575, 0, 0])]
+                         ).astype(np.int32)                      # and the last plane
+    want = oracle.conv3d_points(act, wgt, ConvGeom((3,) * 3, (1,) * 3, (1,) * 3, (1,) * 3), pts)
+    idx = [torch.from_numpy(pts[:, a].astype(np.int64)).cuda() for a in (0, 2, 3, 4)]
+    co = pts[:, 1]
+    wsel = torch.from_numpy((co // 32).astype(np.int64)).cuda()
+    mw = out[idx[0], idx[1], idx[2], idx[3], 0, wsel].cpu().numpy().view(np.uint32)
+    sw = out[idx[0], idx[1], idx[2], idx[3], 1, wsel].cpu().numpy().view(np.uint32)
+    m = (mw >> (co % 32).astype(np.uint32)) & 1
+    s = (sw >> (co % 32).astype(np.uint32)) & 1
+    code = m.astype(np.int8) * (1 - 2 * s.astype(np.int8))
+    want_code = np.where(want > hi[co], 1, np.where(want < lo[co], -1, 0))
+    np.testing.assert_array_equal(code, want_code)
+    assert len(np.unique(want_code)) == 3
+    # canonical packing everywhere, no bits above the channel count (checked on the device)
+    assert not bool((out[..., 1, :] & ~out[..., 0, :]).any())
+    if c_out % 32:
+        assert not bool((out[..., 0, -1] >> (c_out % 32)).any())
+
+
+def test_calls_follow_the_callers_stream(G):
+    """Every entry point enqueues on the stream it is given: a chain issued on a side stream,
+    with no synchronisation between the calls, gives the oracle's result, and work on the default
+    stream in between does not disturb it."""
+    import torch
+    import paper_1801_09449_amd as T
+    c = synth.conv_case("stream", 1, 40, 24, (10, 18, 20), seed=77)
+    want_acc, want_packed = expect(c)
+    side = torch.cuda.Stream()
+    act8, wgt8, lo, hi = G.dev(c.act), G.dev(c.wgt), G.dev(c.lo), G.dev(c.hi)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        a = T.tern_pack(act8)
+        b = T.tern_pack_filters(wgt8)
+        acc = T.tern_conv3d(a, 40, b, 24, c.k, c.stride, c.pad, c.dil)
+        fused = T.tern_conv3d(a, 40, b, 24, c.k, c.stride, c.pad, c.dil, thr_lo=lo, thr_hi=hi)
+        two_step = T.tern_threshold_pack(acc, lo, hi)
+    noise = torch.zeros(1 << 20, device="cuda").add_(1.0)      # default stream, unrelated
+    side.synchronize()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(acc.cpu().numpy(), want_acc)
+    np.testing.assert_array_equal(G.words(fused), want_packed)
+    np.testing.assert_array_equal(G.words(two_step), want_packed)
+    assert float(noise.sum()) == float(1 << 20)
