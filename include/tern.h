@@ -188,7 +188,61 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
                      uint32_t** layer_out /* host, optional */, void* stream);
 
 /*
- * Host-side model preparation.  These three run on the CPU on HOST arrays and launch nothing.
+ * U-Net plumbing on packed activations (section 3, Table 1: the Upsample2D rows, the "Skip"
+ * column, the AvgPool2D rows and the Prediction row; section 2 notes that skip connections and
+ * feature concatenation are usable with ternary convolutions).
+ *
+ * tern_concat -- output voxel (n, z, y, x) takes, from every source i in turn, the channels of
+ * source voxel (n, (z + first[0]) / up[0], (y + first[1]) / up[1], (x + first[2]) / up[2])
+ * (integer division: nearest-neighbour upsampling by `up`, then a crop that starts at `first`
+ * in upsampled coordinates) and lays them side by side: source 0 fills channels
+ * [0, c0), source 1 [c0, c0 + c1), ...  One source with up = 1 is a crop, with up = 2 an
+ * upsampling; two sources are a decoder step (upsampled tensor + cropped skip tensor).
+ *   srcs      : host array of n_src (1 .. TERN_MAX_SOURCES) descriptors; `packed` are device
+ *               pointers in the packed layout of `dims`; dims.n == out_dims.n;
+ *               1 <= up <= 1024, first >= 0, first + out extent <= dims extent * up per axis;
+ *   out_dims  : out_dims.c must equal the sum of the sources' channel counts (any counts: bits
+ *               are shifted across word boundaries when a count is not a multiple of 32);
+ *   out_packed: packed output, must not overlap a source.
+ * Errors: TERN_EARG for a violated constraint, TERN_ESHAPE for invalid extents.
+ *
+ * tern_conv3d_real -- the full-precision output layer: cross-correlation of packed ternary codes
+ * with float weights w [c_out][C_in][kd][kh][kw] plus bias [c_out] (NULL = none), zero padding,
+ * float output [N][c_out][Do][Ho][Wo].  Each term is +-w exactly; they are added in fp32 in the
+ * order taps (d, h, w), then ascending input channel, starting from the bias, so the result
+ * differs from exact arithmetic by at most (terms) * 2^-24 * (|bias| + sum |w| over the filter).
+ * Meant for a handful of output channels (Table 1: 2); one thread per output element.
+ *
+ * tern_fold_avgpool (host arrays, launches nothing) -- average pooling between two ternary
+ * modules, done exactly: pooling with window = stride = pool followed by a convolution with
+ * kernel k, stride s, padding p, dilation 1 equals, up to the constant factor
+ * P = pool[0]*pool[1]*pool[2], a convolution of the unpooled tensor with kernel k*pool (every
+ * tap repeated pool times along each axis), stride s*pool and padding p*pool.  The helper
+ * writes those repeated filters, w_out int8 [c_out][c_in][kd*pool[0]][kh*pool[1]][kw*pool[2]];
+ * the accumulator of the folded convolution is P times that of the pooled one, so pass
+ * scale/P to tern_fold_thresholds.  Without padding the output extents and values are identical
+ * to pool-then-convolve for any input extent (trailing voxels that do not fill a pooling window
+ * are never reached); with padding p > 0 the input extents must be multiples of the pooling
+ * window, otherwise the folded convolution would read those trailing voxels where the pooled
+ * one reads padding.
+ */
+#define TERN_MAX_SOURCES 8
+typedef struct {
+    const uint32_t* packed;     /* device: packed activations of this source           */
+    tern_dims dims;             /* its logical extents                                  */
+    int32_t up[3];              /* nearest-neighbour upsampling factor per axis (d,h,w) */
+    int32_t first[3];           /* upsampled coordinate that lands on output voxel 0    */
+} tern_source;
+int tern_concat(const tern_source* srcs /* host */, int32_t n_src, tern_dims out_dims,
+                uint32_t* out_packed, void* stream);
+int tern_conv3d_real(const uint32_t* in_packed, tern_dims in_dims, const float* w,
+                     const float* bias, int32_t c_out, tern_conv_geom g, float* out,
+                     void* stream);
+int tern_fold_avgpool(const int8_t* w /* host */, int32_t c_out, int32_t c_in, int32_t kd,
+                      int32_t kh, int32_t kw, const int32_t pool[3], int8_t* w_out /* host */);
+
+/*
+ * Host-side model preparation.  These run on the CPU on HOST arrays and launch nothing.
  *
  * tern_ternarize_filters -- ternary weight approximation W ~ alpha * W~ (Eq. 4), per output
  * filter: Delta = 0.7/n * sum|W_i|;  W~_i = +1 if W_i > Delta, 0 if |W_i| <= Delta, -1 otherwise;

@@ -15,3 +15,11 @@ from .tern_oracle import (  # noqa: F401
     unpack,
 )
 from .prepare_oracle import activation_code, bn_affine, ternarize_filters  # noqa: F401,E402
+from .unet_oracle import (  # noqa: F401,E402
+    centre_crop,
+    concat_channels,
+    conv3d_real,
+    pool_sum,
+    unet_forward,
+    upsample_nearest,
+)

@@ -9,7 +9,10 @@ from .binding import (  # noqa: F401
     TernError,
     lib,
     lib_path,
+    tern_concat,
     tern_conv3d,
+    tern_conv3d_real,
+    tern_fold_avgpool,
     tern_conv_out_dims,
     tern_fcn_forward,
     tern_fcn_workspace_bytes,

@@ -41,6 +41,11 @@ class Layer(C.Structure):
                 ("w_bank", C.c_void_p), ("thr_lo", C.c_void_p), ("thr_hi", C.c_void_p)]
 
 
+class Source(C.Structure):
+    _fields_ = [("packed", C.c_void_p), ("dims", Dims), ("up", C.c_int32 * 3),
+                ("first", C.c_int32 * 3)]
+
+
 def lib_path() -> str:
     return os.path.join(_HERE, _LIB_NAME)
 
@@ -75,6 +80,10 @@ def lib():
     L.tern_fold_thresholds.argtypes = [P, P, I, I, P, P, P]; L.tern_fold_thresholds.restype = C.c_int
     L.tern_fold_batchnorm.argtypes = [P, P, P, P, P, C.c_double, I, I, P, P, P]
     L.tern_fold_batchnorm.restype = C.c_int
+    L.tern_concat.argtypes = [C.POINTER(Source), I, Dims, P, P]; L.tern_concat.restype = C.c_int
+    L.tern_conv3d_real.argtypes = [P, Dims, P, P, I, Geom, P, P]; L.tern_conv3d_real.restype = C.c_int
+    L.tern_fold_avgpool.argtypes = [P, I, I, I, I, I, C.POINTER(C.c_int32), P]
+    L.tern_fold_avgpool.restype = C.c_int
     L.tern_set_option.argtypes = [C.c_int, C.c_int]; L.tern_set_option.restype = C.c_int
     L.tern_probe_valu.argtypes = [I, I, I, P, P]; L.tern_probe_valu.restype = C.c_int
     _lib = L
@@ -355,6 +364,78 @@ def tern_set_option(option: int, value: int) -> None:
     _check(lib().tern_set_option(int(option), int(value)), "tern_set_option")
 
 
+# ---- U-Net plumbing ------------------------------------------------------------------------------
+def _logical_dims(t: torch.Tensor, c: int):
+    """Logical (n, c, d, h, w) of a packed tensor [N][D][H][W][2][Wd] holding c channels."""
+    _dev(t, PACKED_DTYPE, "packed tensor")
+    if t.dim() != 6 or t.shape[4] != 2 or t.shape[5] != tern_words(c):
+        raise ValueError("packed tensor must be [N][D][H][W][2][ceil(C/32)]")
+    return (int(t.shape[0]), int(c), int(t.shape[1]), int(t.shape[2]), int(t.shape[3]))
+
+
+def tern_concat(sources, out_spatial=None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Gather-and-concatenate on packed tensors.  sources: sequence of (packed, channels[, up[,
+    first]]) with up/first an int or three ints (defaults 1 and 0).  out_spatial: (d, h, w) of the
+    output; default = the first source's upsampled extent minus its `first`.  Channels are laid
+    out in the order of the sources."""
+    srcs = []
+    for s in sources:
+        t, c = s[0], int(s[1])
+        up = _t3(s[2]) if len(s) > 2 else (1, 1, 1)
+        first = _t3(s[3]) if len(s) > 3 else (0, 0, 0)
+        srcs.append((t, _logical_dims(t, c), up, first))
+    if not srcs:
+        raise ValueError("at least one source")
+    if out_spatial is None:
+        _, d0, up0, first0 = srcs[0]
+        out_spatial = tuple(d0[2 + a] * up0[a] - first0[a] for a in range(3))
+    n = srcs[0][1][0]
+    c_total = sum(d[1] for _, d, _, _ in srcs)
+    odims = (n, c_total) + tuple(int(v) for v in out_spatial)
+    arr = (Source * len(srcs))()
+    for i, (t, d, up, first) in enumerate(srcs):
+        arr[i].packed = t.data_ptr()
+        arr[i].dims = _dims(d)
+        for a in range(3):
+            arr[i].up[a] = up[a]
+            arr[i].first[a] = first[a]
+    if out is None:
+        out = _empty_packed(odims, srcs[0][0].device)
+    _dev(out, PACKED_DTYPE, "out")
+    if out.numel() * 4 != tern_packed_bytes(odims):
+        raise ValueError("out has the wrong size")
+    _check(lib().tern_concat(arr, len(srcs), _dims(odims), _ptr(out), _stream(out)), "tern_concat")
+    return out
+
+
+def tern_conv3d_real(in_packed: torch.Tensor, c_in: int, w: torch.Tensor,
+                     bias: Optional[torch.Tensor] = None, stride=1, pad=0, dil=1,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Packed ternary codes x float32 weights [C_out][C_in][kd][kh][kw] (+ bias) -> float32
+    [N][C_out][Do][Ho][Wo]."""
+    idims = _logical_dims(in_packed, c_in)
+    _dev(w, torch.float32, "w")
+    if w.dim() != 5 or w.shape[1] != c_in:
+        raise ValueError("w must be [C_out][C_in][kd][kh][kw]")
+    c_out = int(w.shape[0])
+    k = tuple(int(x) for x in w.shape[2:])
+    if bias is not None:
+        _dev(bias, torch.float32, "bias")
+        if bias.numel() != c_out:
+            raise ValueError("bias must have C_out entries")
+    odims = tern_conv_out_dims(idims, c_out, k, stride, pad, dil)
+    if out is None:
+        out = torch.empty(odims, dtype=torch.float32, device=w.device)
+    _dev(out, torch.float32, "out")
+    if tuple(out.shape) != tuple(odims):
+        raise ValueError("out has the wrong shape")
+    _check(lib().tern_conv3d_real(_ptr(in_packed), _dims(idims), _ptr(w),
+                                  _ptr(bias) if bias is not None else None, c_out,
+                                  _geom(k, stride, pad, dil), _ptr(out), _stream(out)),
+           "tern_conv3d_real")
+    return out
+
+
 # ---- host-side model preparation (numpy arrays in, numpy arrays out; no GPU involved) ----------
 def _np_ptr(a):
     return a.ctypes.data_as(C.c_void_p)
@@ -397,3 +478,19 @@ def tern_fold_batchnorm(alpha, gamma, beta, mean, var, eps: float, acc_bound: in
     _check(lib().tern_fold_batchnorm(*[_np_ptr(a) for a in arrs], float(eps), c, int(acc_bound),
                                      _np_ptr(lo), _np_ptr(hi), _np_ptr(neg)), "tern_fold_batchnorm")
     return lo, hi, neg
+
+
+def tern_fold_avgpool(w, pool):
+    """int8 ternary filters [C_out][C_in][kd][kh][kw] -> filters with every tap repeated pool
+    times per axis, [C_out][C_in][kd*pd][kh*ph][kw*pw] (host arrays)."""
+    import numpy as np
+    w = np.ascontiguousarray(w, dtype=np.int8)
+    if w.ndim != 5:
+        raise ValueError("w must be [C_out][C_in][kd][kh][kw]")
+    pool = _t3(pool)
+    co, ci, kd, kh, kw = (int(x) for x in w.shape)
+    out = np.empty((co, ci, kd * pool[0], kh * pool[1], kw * pool[2]), dtype=np.int8)
+    parr = (C.c_int32 * 3)(*pool)
+    _check(lib().tern_fold_avgpool(_np_ptr(w), co, ci, kd, kh, kw, parr, _np_ptr(out)),
+           "tern_fold_avgpool")
+    return out

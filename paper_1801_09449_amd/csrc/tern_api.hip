@@ -219,6 +219,69 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_
     return launch_conv3d(p, (hipStream_t)stream);
 }
 
+int tern_concat(const tern_source* srcs, int32_t n_src, tern_dims out_dims, uint32_t* out_packed,
+                void* stream)
+{
+    if (!srcs || !out_packed) return TERN_ENULL;
+    if (n_src < 1 || n_src > TERN_MAX_SOURCES) return TERN_EARG;
+    if (!sizes_ok(out_dims)) return TERN_ESHAPE;
+    if (!aligned16(out_packed)) return TERN_EARG;
+    ConcatParams p;
+    int64_t channels = 0;
+    const int32_t oext[3] = {out_dims.d, out_dims.h, out_dims.w};
+    for (int i = 0; i < n_src; ++i) {
+        const tern_source& s = srcs[i];
+        if (!s.packed) return TERN_ENULL;
+        if (!sizes_ok(s.dims)) return TERN_ESHAPE;
+        if (s.dims.n != out_dims.n) return TERN_EARG;
+        if (!aligned16(s.packed)) return TERN_EARG;
+        const int32_t sext[3] = {s.dims.d, s.dims.h, s.dims.w};
+        for (int a = 0; a < 3; ++a) {
+            if (s.up[a] < 1 || s.up[a] > 1024 || s.first[a] < 0) return TERN_EARG;
+            if ((int64_t)s.first[a] + oext[a] > (int64_t)sext[a] * s.up[a]) return TERN_EARG;
+        }
+        ConcatSrc& c = p.s[i];
+        c.p = s.packed;
+        c.d = s.dims.d; c.h = s.dims.h; c.w = s.dims.w;
+        c.wd = tern_words(s.dims.c);
+        c.bit0 = (int32_t)channels;
+        for (int a = 0; a < 3; ++a) { c.up[a] = s.up[a]; c.first[a] = s.first[a]; }
+        channels += s.dims.c;
+        if (channels > out_dims.c) return TERN_EARG;
+    }
+    if (channels != out_dims.c) return TERN_EARG;
+    for (int i = n_src; i < TERN_MAX_SOURCES; ++i) p.s[i] = p.s[0];
+    p.n_src = n_src;
+    p.od = out_dims.d; p.oh = out_dims.h; p.ow = out_dims.w;
+    p.wd_out = tern_words(out_dims.c);
+    p.total = voxels(out_dims) * p.wd_out;
+    p.out = out_packed;
+    return launch_concat(p, (hipStream_t)stream);
+}
+
+int tern_conv3d_real(const uint32_t* in_packed, tern_dims in_dims, const float* w,
+                     const float* bias, int32_t c_out, tern_conv_geom g, float* out, void* stream)
+{
+    if (!in_packed || !w || !out) return TERN_ENULL;
+    tern_dims o;
+    int rc = geom_check(in_dims, c_out, g, &o);
+    if (rc != TERN_OK) return rc;
+    if (!aligned16(in_packed) || ((uintptr_t)w & 3u) || ((uintptr_t)out & 3u) ||
+        ((uintptr_t)bias & 3u))
+        return TERN_EARG;
+    RealConvParams p;
+    p.in = in_packed; p.wgt = w; p.bias = bias; p.out = out;
+    p.c_in = in_dims.c; p.d = in_dims.d; p.h = in_dims.h; p.w = in_dims.w;
+    p.wd_in = tern_words(in_dims.c);
+    p.c_out = c_out; p.od = o.d; p.oh = o.h; p.ow = o.w;
+    p.kd = g.k[0]; p.kh = g.k[1]; p.kw = g.k[2];
+    p.sd = g.stride[0]; p.sh = g.stride[1]; p.sw = g.stride[2];
+    p.pd = g.pad[0]; p.ph = g.pad[1]; p.pw = g.pad[2];
+    p.dd = g.dil[0]; p.dh = g.dil[1]; p.dw = g.dil[2];
+    p.total = voxels(o) * c_out;
+    return launch_real_conv(p, (hipStream_t)stream);
+}
+
 // Walks the chain once: validates channel continuity and geometry, and reports the packed size
 // of the input and of every layer output.  Returns TERN_OK or the first error.
 static int fcn_plan(tern_dims in_dims, const tern_layer* layers, int32_t n_layers,

@@ -53,6 +53,8 @@ struct TileParams {
     int32_t co_per_wave;          // output channels handled by one wave (multiple of 16)
     int32_t nks;                  // waves per workgroup that split the kernel taps of one slice
     int32_t red_off;              // LDS word offset of the partial-sum area (nks > 1)
+    int32_t vy;                   // 1: a lane's V voxels are 8 rows apart along y (single-plane
+                                  // outputs); 0: consecutive along z
 };
 
 template <int WC>
@@ -308,7 +310,9 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int tiy = bid % t.tiles_y; bid /= t.tiles_y;
     const int tiz = bid % t.tiles_z;
     const int n = bid / t.tiles_z;
-    const int TX = 8 * t.nwx, TY = 8 * t.nwy, TZ = V * t.nwz;
+    // A lane's V output voxels are stacked along z, or (vy: single-plane outputs) along y.
+    const int ywave = t.vy ? 8 * V : 8, zwave = t.vy ? 1 : V;   // output extent of one wave
+    const int TX = 8 * t.nwx, TY = ywave * t.nwy, TZ = zwave * t.nwz;
     const int ox0 = tix * TX, oy0 = tiy * TY, oz0 = tiz * TZ;
 
     // ---- stage the halo tile -------------------------------------------------------------
@@ -373,14 +377,14 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int wch = wslot / nsp;                      // channel slice of this wave
     const int lx = lane & 7, ly = lane >> 3;
     const int ox = ox0 + wx * 8 + lx;
-    const int oy = oy0 + wy * 8 + ly;
-    const int ozb = oz0 + wz * V;
+    const int oy = oy0 + wy * ywave + ly;
+    const int ozb = oz0 + wz * zwave;
     const int row_words = t.hx * t.vstride;
     const int plane_words = t.hy * row_words;
     // LDS word offset of the tap-(0,0,0) input voxel of this lane's output voxel v = 0
-    const int lane_base = (wz * V * p.sd) * plane_words + (wy * 8 + ly) * p.sh * row_words +
+    const int lane_base = (wz * zwave * p.sd) * plane_words + (wy * ywave + ly) * p.sh * row_words +
                           (wx * 8 + lx) * p.sw * t.vstride;
-    const int vstep = p.sd * plane_words;  // between consecutive v
+    const int vstep = t.vy ? 8 * p.sh * row_words : p.sd * plane_words;  // between consecutive v
     const uint32_t* lane_lds = lds + lane_base;
 
     const int T = p.kd * p.kh * p.kw;
@@ -535,10 +539,11 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
                 const bool whole = b0 == 0 && (b1 == 32 || p.c_out <= q * 32 + 16);
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
-                    const int oz = ozb + v;
-                    if (ox < p.ow && oy < p.oh && oz < p.od) {
+                    const int oz = t.vy ? ozb : ozb + v;
+                    const int oyv = t.vy ? oy + 8 * v : oy;
+                    if (ox < p.ow && oyv < p.oh && oz < p.od) {
                         uint32_t* o = p.out_packed +
-                                      ((((size_t)n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
+                                      ((((size_t)n * p.od + oz) * p.oh + oyv) * p.ow + ox) * 2u * p.wd_out;
                         const uint32_t mk = pos_w[v] | neg_w[v];      // nonzero mask
                         const uint32_t sg = neg_w[v] & ~pos_w[v];     // sign; +1 wins if lo > hi
                         if (whole) {
@@ -557,10 +562,11 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
             const size_t cstride = (size_t)p.od * p.oh * p.ow;
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                const int oz = ozb + v;
-                if (ox < p.ow && oy < p.oh && oz < p.od) {
+                const int oz = t.vy ? ozb : ozb + v;
+                const int oyv = t.vy ? oy + 8 * v : oy;
+                if (ox < p.ow && oyv < p.oh && oz < p.od) {
                     int32_t* o = p.out_acc + (size_t)n * p.c_out * cstride +
-                                 ((size_t)oz * p.oh + oy) * p.ow + ox;
+                                 ((size_t)oz * p.oh + oyv) * p.ow + ox;
 #pragma unroll
                     for (int j = 0; j < CO_BLK; ++j)
                         if (j < co_left) o[(size_t)(cb + j) * cstride] = d[v][j];
@@ -607,18 +613,21 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     t.nchunk = wd / p.wc;
     t.vstride = 2 * wd + (wd >= 4 ? 4 : 0);
     t.nwx = 1; t.nwy = 1; t.nwz = g_waves_z > 0 ? g_waves_z : 1;
+    // Single-plane outputs (2-D convolutions): a lane's V voxels go along y instead of z.
+    t.vy = p.od == 1 ? 1 : 0;
+    const int vyx = t.vy ? V : 1, vzx = t.vy ? 1 : V;
     auto halo = [](int tiles_out, int stride, int k, int dil) { return (tiles_out - 1) * stride + (k - 1) * dil + 1; };
     auto lds_for = [&](const TileParams& q) {
         const int64_t hx = halo(8 * q.nwx, p.sw, p.kw, p.dw);
-        const int64_t hy = halo(8 * q.nwy, p.sh, p.kh, p.dh);
-        const int64_t hz = halo(V * q.nwz, p.sd, p.kd, p.dd);
+        const int64_t hy = halo(8 * vyx * q.nwy, p.sh, p.kh, p.dh);
+        const int64_t hz = halo(vzx * q.nwz, p.sd, p.kd, p.dd);
         return hx * hy * hz * q.vstride * 4;
     };
     // Start from one wave per workgroup; grow the tile (stacking waves along the axis that
     // lowers LDS per wave the most) while the per-wave LDS share is too large for the waves a
     // compute unit is expected to hold: eight (20 KB each of the 160 KB) on a large problem,
     // fewer on a small one, where small tiles matter more because they give more workgroups.
-    const int64_t waves1 = (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, V) * p.n * cdiv(p.c_out, 16);
+    const int64_t waves1 = (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8 * vyx) * cdiv(p.od, vzx) * p.n * cdiv(p.c_out, 16);
     int per_cu = (int)((waves1 + 255) / 256);
     per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
     const int64_t share_budget = (int64_t)(160 * 1024) / per_cu;
@@ -630,6 +639,7 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
         TileParams cand[3] = {t, t, t};
         cand[0].nwz *= 2; cand[1].nwy *= 2; cand[2].nwx *= 2;
         for (const TileParams& c : cand) {
+            if (c.nwz != t.nwz && vzx * t.nwz >= p.od) continue;   // no planes left to stack
             const double share = (double)lds_for(c) / (c.nwx * c.nwy * c.nwz);
             if (share < best_share) { best_share = share; best = c; }
         }
@@ -638,11 +648,11 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     lds_bytes = lds_for(t);
     if (lds_bytes > lds_limit) return false;
     t.hx = halo(8 * t.nwx, p.sw, p.kw, p.dw);
-    t.hy = halo(8 * t.nwy, p.sh, p.kh, p.dh);
-    t.hz = halo(V * t.nwz, p.sd, p.kd, p.dd);
+    t.hy = halo(8 * vyx * t.nwy, p.sh, p.kh, p.dh);
+    t.hz = halo(vzx * t.nwz, p.sd, p.kd, p.dd);
     t.tiles_x = cdiv(p.ow, 8 * t.nwx);
-    t.tiles_y = cdiv(p.oh, 8 * t.nwy);
-    t.tiles_z = cdiv(p.od, V * t.nwz);
+    t.tiles_y = cdiv(p.oh, 8 * vyx * t.nwy);
+    t.tiles_z = cdiv(p.od, vzx * t.nwz);
     return true;
 }
 
@@ -654,9 +664,19 @@ void set_co_block(int v) { g_co_block = (v == 16 || v == 32) ? v : 0; }
 void set_co_per_wave(int v) { g_co_per_wave = (v > 0 && v % 16 == 0) ? v : 0; }
 void set_tap_split(int v) { g_tap_split = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
 
-int launch_conv3d(const ConvParams& p, hipStream_t s)
+int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 {
+    ConvParams p = p_in;
     const bool packed = p.out_packed != nullptr;
+    // A kernel of depth extent 1 with unit depth stride and no depth padding treats every input
+    // plane by itself, so batch items are just more planes: [N][D] collapses to [1][N*D] and
+    // planes of different batch items share tiles (stacks of 2-D slices have D = 1).  Packed
+    // output only: the int32 layout has the channel axis between N and D.
+    if (packed && p.n > 1 && p.kd == 1 && p.sd == 1 && p.pd == 0 && (int64_t)p.n * p.d <= INT32_MAX) {
+        p.d *= p.n;
+        p.od *= p.n;
+        p.n = 1;
+    }
     const int lds_limit = lds_limit_for_current_device();
 
     // Kernel variants (voxels per lane V x channels per pass CO_BLK):
@@ -670,7 +690,8 @@ int launch_conv3d(const ConvParams& p, hipStream_t s)
     if (g_lane_depth == 4 && p.tp_slots == 0) { V = 4; co_blk = 16; }
     else if (g_co_block == 32) { V = 2; co_blk = 32; }
     else if (g_co_block == 0) {
-        const int64_t tiles2 = (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, 2) * p.n;
+        const int64_t tiles2 = p.od == 1 ? (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 16) * p.n
+                                         : (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, 2) * p.n;
         const int tail = p.c_out % 32;   // a 32-channel pass over 1..16 live channels is half wasted
         if (tiles2 * cdiv(p.c_out, 32) >= 4096 && (tail == 0 || tail > 16)) co_blk = 32;
     }

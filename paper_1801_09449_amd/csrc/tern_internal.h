@@ -64,6 +64,34 @@ inline BankShape bank_shape(int32_t c_in, int32_t taps)
     return b;
 }
 
+// tern_concat: one source after validation, and the whole launch (passed to the kernel by value).
+struct ConcatSrc {
+    const uint32_t* p;      // packed [N][d][h][w][2][wd]
+    int32_t d, h, w, wd;
+    int32_t bit0;           // first output channel this source fills
+    int32_t up[3];          // nearest-neighbour factor per axis
+    int32_t first[3];       // upsampled coordinate that lands on output voxel 0
+};
+struct ConcatParams {
+    ConcatSrc s[TERN_MAX_SOURCES];
+    int32_t n_src;
+    int32_t od, oh, ow, wd_out;
+    int64_t total;          // output voxels x wd_out
+    uint32_t* out;
+};
+
+// tern_conv3d_real: ternary codes x float weights.
+struct RealConvParams {
+    const uint32_t* in;     // packed [N][D][H][W][2][wd_in]
+    const float* wgt;       // [c_out][c_in][kd][kh][kw]
+    const float* bias;      // [c_out] or null
+    float* out;             // [N][c_out][od][oh][ow]
+    int32_t c_in, d, h, w, wd_in;
+    int32_t c_out, od, oh, ow;
+    int32_t kd, kh, kw, sd, sh, sw, pd, ph, pw, dd, dh, dw;
+    int64_t total;          // output voxels x c_out
+};
+
 // Launchers implemented in the kernel translation units.  Each validates nothing (the entry
 // points did) and returns a tern_status.
 int launch_pack_i8(const int8_t* src, tern_dims dims, uint32_t* dst, hipStream_t s);
@@ -72,6 +100,8 @@ int launch_threshold_pack_i32(const int32_t* src, tern_dims dims, const int32_t*
 int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo, const float* hi,
                               uint32_t* dst, hipStream_t s);
 int launch_conv3d(const ConvParams& p, hipStream_t s);
+int launch_concat(const ConcatParams& p, hipStream_t s);
+int launch_real_conv(const RealConvParams& p, hipStream_t s);
 void set_lane_depth(int v);
 void set_waves_z(int v);
 void set_co_block(int v);

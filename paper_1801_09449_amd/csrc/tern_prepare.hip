@@ -124,4 +124,26 @@ int tern_fold_batchnorm(const double* alpha, const double* gamma, const double* 
     return TERN_OK;
 }
 
+int tern_fold_avgpool(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                      int32_t kw, const int32_t pool[3], int8_t* w_out)
+{
+    if (!w || !pool || !w_out) return TERN_ENULL;
+    if (c_out <= 0 || c_in <= 0 || kd < 1 || kh < 1 || kw < 1) return TERN_ESHAPE;
+    for (int a = 0; a < 3; ++a)
+        if (pool[a] < 1 || pool[a] > 1024) return TERN_EARG;
+    const int64_t fd = (int64_t)kd * pool[0], fh = (int64_t)kh * pool[1], fw = (int64_t)kw * pool[2];
+    if (fd > 1024 || fh > 1024 || fw > 1024) return TERN_ESHAPE;
+    const size_t filters = (size_t)c_out * (size_t)c_in;
+    for (size_t f = 0; f < filters; ++f) {
+        const int8_t* src = w + f * (size_t)kd * kh * kw;
+        int8_t* dst = w_out + f * (size_t)(fd * fh * fw);
+        for (int64_t a = 0; a < fd; ++a)
+            for (int64_t b = 0; b < fh; ++b)
+                for (int64_t c = 0; c < fw; ++c)
+                    dst[(a * fh + b) * fw + c] =
+                        src[((a / pool[0]) * kh + b / pool[1]) * kw + c / pool[2]];
+    }
+    return TERN_OK;
+}
+
 }  // extern "C"

@@ -205,3 +205,60 @@ def config2(seed: int = 0, vol=(128, 128, 64), channels=(16, 32, 32, 64, 64, 128
                            lo=lo, hi=hi))
         c_in = c_out
     return FcnCase("cfg2", x, np.array([-0.5], np.float32), np.array([0.5], np.float32), layers)
+
+
+@dataclass
+class UNetCase:
+    """The paper's baseline U-Net (section 3, Table 1) with synthetic ternary weights.
+
+    layers: one dict per ternary module, in order, each with
+      w (int8 [C_out][C_in][kd][kh][kw]), lo/hi (int32 [C_out], cut points on the integer
+      accumulator the module produces, pooling factor included), and what happens to the
+      module's input before the convolution:
+        pool   : (pd, ph, pw) average-pooling window applied to the incoming tensor, or None;
+        concat : name of a saved encoder tensor that is centre-cropped and appended (channel-wise)
+                 after the incoming tensor has been upsampled by `up`, or None;
+        up     : nearest-neighbour factors used with `concat`;
+      and save: name under which the module's output codes are kept for a later skip, or None.
+    head_w / head_b: float32 weights [classes][C][1][3][3] and bias of the prediction layer.
+    """
+    name: str
+    x: np.ndarray
+    in_lo: np.ndarray
+    in_hi: np.ndarray
+    layers: List[Dict]
+    head_w: np.ndarray
+    head_b: np.ndarray
+
+
+def unet_table1(seed: int = 0, n: int = 1, size=(236, 172), slices: int = 15, width_div: int = 1,
+                classes: int = 2) -> UNetCase:
+    """Layer list of Table 1: #1 is a 3x3x15 convolution over the stack of `slices` neighbouring
+    slices (one input channel, depth extent collapses to 1), #2-#14 are 2-D 3x3 (1x1 at #7, #8)
+    valid convolutions with 2x2 average pooling before #4, #6, #8 and 2x upsampling plus skip
+    concatenation (#6 -> #9, #4 -> #11, #2 -> #13) before #9, #11, #13.  Channel counts
+    32-64-64-128-128-256-256-256-256-128-128-64-64-64, divided by width_div.  Input: N(0,1)
+    intensities (zero mean, unit variance as in the paper's preprocessing) ternarised at +-0.5;
+    weights: half zeros; cut points from bn_like_thresholds with the pooling factor counted as
+    extra taps.  Spatial extents follow from valid-convolution arithmetic on `size`."""
+    ch = [max(1, c // width_div) for c in (32, 64, 64, 128, 128, 256, 256, 256, 256, 128, 128, 64, 64, 64)]
+    k2 = [3, 3, 3, 3, 3, 3, 1, 1, 3, 3, 3, 3, 3, 3]
+    pool = {4: (1, 2, 2), 6: (1, 2, 2), 8: (1, 2, 2)}
+    save = {2: "s2", 4: "s4", 6: "s6"}
+    concat = {9: "s6", 11: "s4", 13: "s2"}
+    x = gaussian((n, 1, slices) + tuple(size), seed, T_F32)
+    layers, c_in = [], 1
+    for li in range(1, 15):
+        c_out = ch[li - 1]
+        cin_l = c_in + (ch[{9: 6, 11: 4, 13: 2}[li] - 1] if li in concat else 0)
+        k = (slices, 3, 3) if li == 1 else (1, k2[li - 1], k2[li - 1])
+        w = ternary((c_out, cin_l) + k, 0.5, seed, T_WGT + 8 * li)
+        pvol = int(np.prod(pool[li])) if li in pool else 1
+        lo, hi = bn_like_thresholds(c_out, k[0] * k[1] * k[2] * pvol, cin_l, 0.5, 0.617, seed, T_THR + 8 * li)
+        layers.append(dict(w=w, k=k, lo=lo, hi=hi, pool=pool.get(li), concat=concat.get(li),
+                           up=(1, 2, 2), save=save.get(li)))
+        c_in = c_out
+    head_w = (gaussian((classes, c_in, 1, 3, 3), seed, T_F32 + 8 * 15) * 0.1).astype(np.float32)
+    head_b = (gaussian((classes,), seed, T_F32 + 8 * 16) * 0.1).astype(np.float32)
+    return UNetCase("unet_table1", x, np.array([-0.5], np.float32), np.array([0.5], np.float32),
+                    layers, head_w, head_b)

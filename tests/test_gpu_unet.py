@@ -1,0 +1,206 @@
+"""GPU parity for the U-Net pieces around the ternary convolution: gather/concat on packed
+tensors, 2-D (single-plane) convolutions, average pooling folded into the next convolution, the
+real-weight prediction layer, and the whole Table 1 network, each against the CPU oracle on the
+same seeded inputs.  Integer and bit results must match exactly; the float prediction layer
+within the bound its summation order implies."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from oracle import ConvGeom
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    import paper_1801_09449_amd as T
+    from tests import gpu_util
+    T.lib()
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+def tern(shape, seed, p0=0.35, tid=synth.T_ACT):
+    return synth.ternary(shape, p0, seed, tid)
+
+
+def gpu_pack(G, x):
+    import paper_1801_09449_amd as T
+    return T.tern_pack(G.dev(x))
+
+
+# ---- tern_concat --------------------------------------------------------------------------------
+@pytest.mark.parametrize("c,vol,up", [(5, (2, 3, 4), (1, 2, 2)), (33, (1, 5, 7), (1, 2, 2)), (64, (3, 4, 5), (2, 1, 3)),
+                                      (70, (2, 2, 2), (3, 3, 3))])
+def test_upsample_nearest(G, c, vol, up):
+    import paper_1801_09449_amd as T
+    x = tern((2, c) + vol, 5)
+    got = T.tern_concat([(gpu_pack(G, x), c, up)])
+    np.testing.assert_array_equal(G.words(got), oracle.pack(oracle.upsample_nearest(x, up)))
+
+
+def test_centre_crop(G):
+    import paper_1801_09449_amd as T
+    x = tern((2, 40, 3, 9, 12), 6)
+    want = oracle.centre_crop(x, (2, 4, 7))
+    got = T.tern_concat([(gpu_pack(G, x), 40, 1, (0, 2, 2))], out_spatial=(2, 4, 7))
+    np.testing.assert_array_equal(G.words(got), oracle.pack(np.ascontiguousarray(want)))
+
+
+@pytest.mark.parametrize("chans", [(32, 32), (64, 64), (20, 50), (1, 1), (31, 33, 7), (96, 5, 40, 3), (7,) * 8])
+def test_concat_any_channel_counts(G, chans):
+    """Word-aligned and unaligned channel counts, up to the maximum number of sources."""
+    import paper_1801_09449_amd as T
+    parts = [tern((2, c, 2, 5, 6), 10 + i) for i, c in enumerate(chans)]
+    got = T.tern_concat([(gpu_pack(G, p), p.shape[1]) for p in parts])
+    want = oracle.pack(oracle.concat_channels(parts))
+    assert got.shape[-1] == (sum(chans) + 31) // 32
+    np.testing.assert_array_equal(G.words(got), want)
+
+
+def test_decoder_step_upsample_crop_concat(G):
+    """The decoder step of the U-Net: upsampled tensor first, centre-cropped skip tensor after."""
+    import paper_1801_09449_amd as T
+    low = tern((2, 48, 1, 6, 5), 31)
+    skip = tern((2, 20, 1, 15, 13), 32)
+    up = oracle.upsample_nearest(low, (1, 2, 2))
+    want = oracle.concat_channels([up, oracle.centre_crop(skip, up.shape[2:])])
+    first = tuple((s - u) // 2 for s, u in zip(skip.shape[2:], up.shape[2:]))
+    got = T.tern_concat([(gpu_pack(G, low), 48, (1, 2, 2)), (gpu_pack(G, skip), 20, 1, first)],
+                        out_spatial=up.shape[2:])
+    np.testing.assert_array_equal(G.words(got), oracle.pack(want))
+
+
+def test_concat_rejects_bad_arguments(G):
+    import paper_1801_09449_amd as T
+    a = gpu_pack(G, tern((1, 8, 2, 4, 4), 1))
+    b = gpu_pack(G, tern((2, 8, 2, 4, 4), 2))
+    with pytest.raises(T.TernError) as e:
+        T.tern_concat([(a, 8), (b, 8)], out_spatial=(2, 4, 4))          # batch mismatch
+    assert e.value.status == -3
+    with pytest.raises(T.TernError) as e:
+        T.tern_concat([(a, 8, 1, (0, 1, 0))], out_spatial=(2, 4, 4))    # crop runs past the source
+    assert e.value.status == -3
+    with pytest.raises(T.TernError) as e:
+        T.tern_concat([(a, 8)] * 9, out_spatial=(2, 4, 4))              # too many sources
+    assert e.value.status == -3
+
+
+# ---- 2-D convolutions (single output plane) ---------------------------------------------------------
+@pytest.mark.parametrize("n,ci,co,hw,k,stride", [(1, 32, 32, (17, 23), (1, 3, 3), 1), (3, 64, 40, (20, 19), (1, 3, 3), 1),
+                                                 (2, 15, 32, (30, 26), (1, 3, 3), 1), (1, 128, 64, (33, 9), (1, 1, 1), 1),
+                                                 (4, 8, 16, (21, 22), (1, 6, 6), (1, 2, 2)),
+                                                 (5, 70, 33, (9, 40), (1, 3, 3), (1, 2, 1))])
+def test_conv2d_single_plane(G, n, ci, co, hw, k, stride):
+    """D = 1: a lane's voxels are stacked along y, and batch items are folded into planes for the
+    packed output.  Both output modes against the oracle."""
+    c = synth.conv_case("c2d", n, ci, co, (1,) + hw, k=k, stride=stride, pad=0, seed=n + ci)
+    acc, packed = G.run_case(c)
+    want = oracle.conv3d(c.act, c.wgt, ConvGeom(c.k, c.stride, c.pad, c.dil))
+    np.testing.assert_array_equal(acc, want)
+    np.testing.assert_array_equal(packed, oracle.pack(oracle.threshold(want, c.lo, c.hi)))
+
+
+def test_conv_depth_one_kernel_on_a_volume_with_batch(G):
+    """kd = 1 on D > 1 with N > 1 (planes independent: batch folded into depth), padded in-plane."""
+    c = synth.conv_case("kd1", 3, 40, 24, (5, 12, 11), k=(1, 3, 3), pad=(0, 1, 1), seed=8)
+    acc, packed = G.run_case(c)
+    want = oracle.conv3d(c.act, c.wgt, ConvGeom(c.k, c.stride, c.pad, c.dil))
+    np.testing.assert_array_equal(acc, want)
+    np.testing.assert_array_equal(packed, oracle.pack(oracle.threshold(want, c.lo, c.hi)))
+
+
+def test_first_layer_of_table1_stack_kernel(G):
+    """Row #1 of Table 1: one input channel, kernel spanning the whole stack of 15 slices."""
+    c = synth.conv_case("row1", 2, 1, 32, (15, 20, 22), k=(15, 3, 3), pad=0, seed=4)
+    acc, packed = G.run_case(c)
+    want = oracle.conv3d(c.act, c.wgt, ConvGeom(c.k, c.stride, c.pad, c.dil))
+    assert want.shape[2] == 1
+    np.testing.assert_array_equal(acc, want)
+    np.testing.assert_array_equal(packed, oracle.pack(oracle.threshold(want, c.lo, c.hi)))
+
+
+# ---- average pooling folded into the next convolution ----------------------------------------------
+@pytest.mark.parametrize("vol,k,pool", [((1, 23, 21), (1, 3, 3), (1, 2, 2)), ((6, 10, 9), (3, 3, 3), (2, 2, 2)),
+                                        ((1, 13, 11), (1, 1, 1), (1, 2, 2))])
+def test_avgpool_folded_into_conv(G, vol, k, pool):
+    import paper_1801_09449_amd as T
+    x = tern((2, 24) + vol, 17)
+    w = tern((40, 24) + k, 18, 0.5, synth.T_WGT)
+    lo, hi = synth.threshold_pair(40, 19, lo=-6, hi=6)
+    want = oracle.conv3d(oracle.pool_sum(x, pool), w, ConvGeom(k, (1, 1, 1), (0, 0, 0), (1, 1, 1)))
+    wf = T.tern_fold_avgpool(w, pool)
+    bank = T.tern_pack_filters(G.dev(wf))
+    xp = gpu_pack(G, x)
+    acc = T.tern_conv3d(xp, 24, bank, 40, wf.shape[2:], pool, 0, 1)
+    np.testing.assert_array_equal(acc.cpu().numpy(), want)
+    codes = T.tern_conv3d(xp, 24, bank, 40, wf.shape[2:], pool, 0, 1, thr_lo=G.dev(lo), thr_hi=G.dev(hi))
+    np.testing.assert_array_equal(G.words(codes), oracle.pack(oracle.threshold(want, lo, hi)))
+
+
+# ---- prediction layer ------------------------------------------------------------------------------
+def real_conv_bound(w, b):
+    """|fp32 result - exact| <= terms * 2^-24 * (|bias| + sum|w| of the filter), per output channel."""
+    terms = w[0].size + 1
+    mass = np.abs(w.astype(np.float64)).reshape(w.shape[0], -1).sum(axis=1) + np.abs(b.astype(np.float64))
+    return terms * 2.0 ** -24 * mass
+
+
+@pytest.mark.parametrize("ci,co,vol,k,stride,pad,dil", [(64, 2, (1, 20, 18), (1, 3, 3), 1, 0, 1),
+                                                        (37, 5, (4, 6, 7), (3, 3, 3), (1, 2, 1), (1, 0, 2), (1, 1, 2)),
+                                                        (8, 1, (3, 3, 3), (1, 1, 1), 1, 0, 1)])
+def test_conv3d_real(G, ci, co, vol, k, stride, pad, dil):
+    import paper_1801_09449_amd as T
+    t3 = lambda v: (v,) * 3 if isinstance(v, int) else tuple(v)
+    x = tern((2, ci) + vol, 23)
+    w = synth.gaussian((co, ci) + k, 23, synth.T_F32)
+    b = synth.gaussian((co,), 24, synth.T_F32)
+    want = oracle.conv3d_real(x, w, b, t3(stride), t3(pad), t3(dil))
+    got = T.tern_conv3d_real(gpu_pack(G, x), ci, G.dev(w), G.dev(b), stride, pad, dil).cpu().numpy()
+    assert got.shape == want.shape and got.dtype == np.float32
+    bound = real_conv_bound(w, b)[None, :, None, None, None]
+    assert (np.abs(got.astype(np.float64) - want) <= bound).all()
+    # without bias
+    got0 = T.tern_conv3d_real(gpu_pack(G, x), ci, G.dev(w), None, stride, pad, dil).cpu().numpy()
+    want0 = oracle.conv3d_real(x, w, None, t3(stride), t3(pad), t3(dil))
+    assert (np.abs(got0.astype(np.float64) - want0) <= bound).all()
+    # ternary-valued float weights: every partial sum is a small integer, the result is exact
+    wi = tern((co, ci) + k, 25, 0.5, synth.T_WGT)
+    exact = oracle.conv3d(x, wi, ConvGeom(k, t3(stride), t3(pad), t3(dil)))
+    goti = T.tern_conv3d_real(gpu_pack(G, x), ci, G.dev(wi.astype(np.float32)), None, stride, pad, dil).cpu().numpy()
+    np.testing.assert_array_equal(goti, exact.astype(np.float32))
+
+
+# ---- the whole network -----------------------------------------------------------------------------
+def run_unet(G, u):
+    import torch
+    from paper_1801_09449_amd import unet
+    plan = unet.UNetPlan(u.layers, u.head_w, u.head_b, u.in_lo, u.in_hi)
+    pred, kept = unet.unet_forward(plan, G.dev(u.x), keep_layers=True)
+    torch.cuda.synchronize()
+    return pred.cpu().numpy(), [G.words(t) for t, _ in kept]
+
+
+def check_unet(G, u):
+    pred, kept = run_unet(G, u)
+    codes, want_pred = oracle.unet_forward(u.x, u.in_lo, u.in_hi, u.layers, u.head_w, u.head_b)
+    assert len(kept) == len(codes) == 14
+    for li, (got, want) in enumerate(zip(kept, codes), start=1):
+        np.testing.assert_array_equal(got, oracle.pack(want), err_msg=f"module #{li}")
+    bound = real_conv_bound(u.head_w, u.head_b)[None, :, None, None, None]
+    assert pred.shape == want_pred.shape
+    assert (np.abs(pred.astype(np.float64) - want_pred) <= bound).all()
+
+
+def test_unet_reduced(G):
+    """Narrow network on small stacks, batch of 3: every module's packed output, bit for bit."""
+    check_unet(G, synth.unet_table1(seed=5, n=3, width_div=8, size=(84, 76), slices=5))
+    check_unet(G, synth.unet_table1(seed=6, n=1, width_div=3, size=(92, 100), slices=15))
+
+
+def test_unet_table1_full_size(G):
+    """The network at the paper's size (236 x 172 x 15 stack, full channel counts), one stack."""
+    check_unet(G, synth.unet_table1(seed=0, n=1))
