@@ -89,6 +89,7 @@ def conv_times(T, dev, c, steps=30, warmup=5):
 
 def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, geom):
     """Timings of the other entry points and of the other BASELINE configurations."""
+    import numpy as np
     import torch
     c_in, c_out = case.act.shape[1], case.wgt.shape[0]
     ex = {}
@@ -133,6 +134,29 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
     ex["cfg2_fcn"]["layer_ms"] = per
     ms_in, _ = timed(lambda: T.tern_threshold_pack(x, ilo, ihi), 30, 5, None)
     ex["cfg2_fcn"]["input_threshold_pack_ms"] = ms_in
+
+    # The paper's baseline U-Net (Table 1) on synthetic weights, whole forward pass, for one
+    # stack of slices and for a batch of 16 stacks.  MACs in the paper's convention (a pooled
+    # module counted at the pooled resolution) and as executed (pooling folded into the filters
+    # repeats every tap over the pooling window).
+    from paper_1801_09449_amd import unet
+    for n in (1, 16):
+        u = synth.unet_table1(seed=0, n=n)
+        plan = unet.UNetPlan(u.layers, u.head_w, u.head_b, u.in_lo, u.in_hi)
+        ux = dev(u.x)
+        pred, kept = unet.unet_forward(plan, ux, keep_layers=True)
+        nominal = executed = 0
+        for L, (t, c) in zip(u.layers, kept):
+            vox = t.shape[0] * t.shape[1] * t.shape[2] * t.shape[3]
+            taps = int(np.prod(L["k"]))
+            nominal += vox * c * L["w"].shape[1] * taps
+            executed += vox * c * L["w"].shape[1] * taps * (int(np.prod(L["pool"])) if L["pool"] else 1)
+        del kept
+        ms_u, _ = timed(lambda: unet.unet_forward(plan, ux), 20, 3, None)
+        ex["unet_table1_n%d" % n] = {"ms": ms_u, "gmac_table1_convention": nominal / 1e9,
+                                     "gmac_executed": executed / 1e9,
+                                     "TMACs_executed": executed / (ms_u * 1e-3) / 1e12,
+                                     "prediction_shape": list(pred.shape)}
     return ex
 
 

@@ -211,7 +211,7 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
  * float output [N][c_out][Do][Ho][Wo].  Each term is +-w exactly; they are added in fp32 in the
  * order taps (d, h, w), then ascending input channel, starting from the bias, so the result
  * differs from exact arithmetic by at most (terms) * 2^-24 * (|bias| + sum |w| over the filter).
- * Meant for a handful of output channels (Table 1: 2); one thread per output element.
+ * Meant for a handful of output channels (Table 1: 2); one thread per output voxel.
  *
  * tern_fold_avgpool (host arrays, launches nothing) -- average pooling between two ternary
  * modules, done exactly: pooling with window = stride = pool followed by a convolution with

@@ -278,7 +278,7 @@ int tern_conv3d_real(const uint32_t* in_packed, tern_dims in_dims, const float* 
     p.sd = g.stride[0]; p.sh = g.stride[1]; p.sw = g.stride[2];
     p.pd = g.pad[0]; p.ph = g.pad[1]; p.pw = g.pad[2];
     p.dd = g.dil[0]; p.dh = g.dil[1]; p.dw = g.dil[2];
-    p.total = voxels(o) * c_out;
+    p.total = voxels(o);
     return launch_real_conv(p, (hipStream_t)stream);
 }
 

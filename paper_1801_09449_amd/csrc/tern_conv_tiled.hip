@@ -640,9 +640,11 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
         cand[0].nwz *= 2; cand[1].nwy *= 2; cand[2].nwx *= 2;
         for (const TileParams& c : cand) {
             if (c.nwz != t.nwz && vzx * t.nwz >= p.od) continue;   // no planes left to stack
+            if (lds_for(c) > lds_limit) continue;                  // would not fit at all
             const double share = (double)lds_for(c) / (c.nwx * c.nwy * c.nwz);
             if (share < best_share) { best_share = share; best = c; }
         }
+        if (best_share == 1e30) break;   // nothing larger fits: keep what we have
         t = best;
     }
     lds_bytes = lds_for(t);

@@ -89,7 +89,7 @@ struct RealConvParams {
     int32_t c_in, d, h, w, wd_in;
     int32_t c_out, od, oh, ow;
     int32_t kd, kh, kw, sd, sh, sw, pd, ph, pw, dd, dh, dw;
-    int64_t total;          // output voxels x c_out
+    int64_t total;          // output voxels
 };
 
 // Launchers implemented in the kernel translation units.  Each validates nothing (the entry
