@@ -173,6 +173,11 @@ size_t tern_fcn_workspace_bytes(tern_dims in_dims, const tern_layer* layers /* h
  *               layers[i].c_in == layers[i-1].c_out;
  *   workspace : device scratch of at least tern_fcn_workspace_bytes() bytes, 16-byte aligned;
  *               holds the packed activations of the input and of every layer but the last.
+ *               (With a one-channel input and a 3x3x3 or 1x3x3 first kernel of unit depth
+ *               stride and dilation, the input region instead holds, per
+ *               output voxel of layer 0, that voxel's kernel taps gathered into one word pair:
+ *               Eq. 6 and the gathering run as one pass over the intensities and layer 0
+ *               becomes a single-tap convolution.  Results are identical either way.)
  *               When layer_out (host array of n_layers pointers, may be NULL) is given,
  *               layer_out[i] receives the device address of layer i's packed output (inside
  *               workspace, or out_packed for the last layer) so that callers can inspect every
@@ -279,11 +284,13 @@ int tern_fold_batchnorm(const double* alpha, const double* gamma, const double* 
  * from that value.  TERN_OPT_CO_BLOCK: output channels per accumulation pass, 0 = choose, 16 or 32.
  * TERN_OPT_CO_PER_WAVE: output channels handled by one wave, 0 = choose, else a multiple of 16.
  * TERN_OPT_TAP_SPLIT: waves of one workgroup that share the kernel taps of one channel slice and
- * add their partial sums in LDS, 0 = choose, 1, 2, 4 or 8.
+ * add their partial sums in LDS, 0 = choose, 1, 2, 4 or 8.  TERN_OPT_POINTWISE: 1 (default) = 1x1x1
+ * convolutions with unit stride and no padding use the pointwise kernel when the input has 1, 2,
+ * 4 or 8 words per plane, 0 = they go through the tiled kernel like any other.
  * Results never depend on options.  Returns TERN_EARG for an unknown option or
  * value. */
 typedef enum { TERN_OPT_LANE_DEPTH = 1, TERN_OPT_WAVES_Z = 2, TERN_OPT_CO_BLOCK = 3,
-               TERN_OPT_CO_PER_WAVE = 4, TERN_OPT_TAP_SPLIT = 5 } tern_option;
+               TERN_OPT_CO_PER_WAVE = 4, TERN_OPT_TAP_SPLIT = 5, TERN_OPT_POINTWISE = 6 } tern_option;
 int tern_set_option(int option, int value);
 
 /*

@@ -76,6 +76,35 @@ static int geom_check(const tern_dims& in, int32_t c_out, const tern_conv_geom& 
     return TERN_OK;
 }
 
+// Kernel parameters of one (already validated) convolution with output extents o.
+static ConvParams conv_params(const uint32_t* in_packed, const tern_dims& in_dims,
+                              const uint32_t* w_bank, int32_t c_out, const tern_conv_geom& g,
+                              const tern_dims& o, const int32_t* thr_lo, const int32_t* thr_hi,
+                              int32_t* out_acc, uint32_t* out_packed)
+{
+    ConvParams p;
+    p.in = in_packed;
+    p.wgt = w_bank;
+    p.lo = thr_lo;
+    p.hi = thr_hi;
+    p.out_acc = out_acc;
+    p.out_packed = out_packed;
+    p.n = in_dims.n; p.c_in = in_dims.c; p.d = in_dims.d; p.h = in_dims.h; p.w = in_dims.w;
+    p.c_out = c_out; p.od = o.d; p.oh = o.h; p.ow = o.w;
+    p.kd = g.k[0]; p.kh = g.k[1]; p.kw = g.k[2];
+    p.sd = g.stride[0]; p.sh = g.stride[1]; p.sw = g.stride[2];
+    p.pd = g.pad[0]; p.ph = g.pad[1]; p.pw = g.pad[2];
+    p.dd = g.dil[0]; p.dh = g.dil[1]; p.dw = g.dil[2];
+    p.wd_in = tern_words(in_dims.c);
+    p.wd_out = tern_words(c_out);
+    const BankShape bs = bank_shape(in_dims.c, g.k[0] * g.k[1] * g.k[2]);
+    p.wc = bs.wc;
+    p.co_pad = (c_out + 31) / 32 * 32;
+    p.tp_slots = bs.tp_slots;
+    p.tp_shift = bs.tp_shift;
+    return p;
+}
+
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 }  // namespace tern
@@ -133,6 +162,11 @@ int tern_set_option(int option, int value)
     if (option == TERN_OPT_TAP_SPLIT) {
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return TERN_EARG;
         set_tap_split(value);
+        return TERN_OK;
+    }
+    if (option == TERN_OPT_POINTWISE) {
+        if (value != 0 && value != 1) return TERN_EARG;
+        set_pointwise(value);
         return TERN_OK;
     }
     if (option == TERN_OPT_WAVES_Z) {
@@ -196,26 +230,8 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_
     if (out_packed && !aligned16(out_packed)) return TERN_EARG;
     if (out_acc && ((uintptr_t)out_acc & 3u)) return TERN_EARG;
 
-    ConvParams p;
-    p.in = in_packed;
-    p.wgt = w_bank;
-    p.lo = thr_lo;
-    p.hi = thr_hi;
-    p.out_acc = out_acc;
-    p.out_packed = out_packed;
-    p.n = in_dims.n; p.c_in = in_dims.c; p.d = in_dims.d; p.h = in_dims.h; p.w = in_dims.w;
-    p.c_out = c_out; p.od = o.d; p.oh = o.h; p.ow = o.w;
-    p.kd = g.k[0]; p.kh = g.k[1]; p.kw = g.k[2];
-    p.sd = g.stride[0]; p.sh = g.stride[1]; p.sw = g.stride[2];
-    p.pd = g.pad[0]; p.ph = g.pad[1]; p.pw = g.pad[2];
-    p.dd = g.dil[0]; p.dh = g.dil[1]; p.dw = g.dil[2];
-    p.wd_in = tern_words(in_dims.c);
-    p.wd_out = tern_words(c_out);
-    const BankShape bs = bank_shape(in_dims.c, g.k[0] * g.k[1] * g.k[2]);
-    p.wc = bs.wc;
-    p.co_pad = (c_out + 31) / 32 * 32;
-    p.tp_slots = bs.tp_slots;
-    p.tp_shift = bs.tp_shift;
+    const ConvParams p = conv_params(in_packed, in_dims, w_bank, c_out, g, o, thr_lo, thr_hi, out_acc,
+                                     out_packed);
     return launch_conv3d(p, (hipStream_t)stream);
 }
 
@@ -297,6 +313,12 @@ static int fcn_plan(tern_dims in_dims, const tern_layer* layers, int32_t n_layer
         tern_dims o;
         int rc = geom_check(cur, layers[i].c_out, layers[i].g, &o);
         if (rc != TERN_OK) return rc;
+        if (i == 0 && patch_pack_applies(in_dims.c, layers[0].g, o)) {
+            // the first region then holds the gathered taps (one word pair per output voxel of
+            // layer 0) instead of the packed input
+            const tern_dims patches = {o.n, 1, o.d, o.h, o.w};
+            total = (tern_packed_bytes(patches) + 255u) & ~(size_t)255u;
+        }
         if (i + 1 < n_layers) total += (tern_packed_bytes(o) + 255u) & ~(size_t)255u;
         cur = o;
     }
@@ -329,11 +351,33 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
 
     char* ws = (char*)workspace;
     uint32_t* cur_buf = (uint32_t*)ws;
-    ws += (tern_packed_bytes(in_dims) + 255u) & ~(size_t)255u;
-    // First step: Eq. 6 on the raw intensities, packed.
-    rc = tern_threshold_pack(in, TERN_SRC_F32, in_dims, in_lo, in_hi, cur_buf, stream);
-    if (rc != TERN_OK) return rc;
     tern_dims cur = in_dims;
+    tern_dims o0;
+    rc = geom_check(in_dims, layers[0].c_out, layers[0].g, &o0);
+    if (rc != TERN_OK) return rc;
+    // A one-channel input with at most 32 kernel taps: Eq. 6 and the gathering of every output
+    // voxel's taps into one word happen in one pass over the intensities, and layer 0 becomes a
+    // single-tap convolution over those words (its tap-packed filter bank is already in the
+    // matching layout).  Otherwise: Eq. 6 on the raw intensities, packed, then layer 0 as is.
+    const bool gathered = patch_pack_applies(in_dims.c, layers[0].g, o0);
+    if (gathered) {
+        const tern_dims patches = {o0.n, 1, o0.d, o0.h, o0.w};
+        ws += (tern_packed_bytes(patches) + 255u) & ~(size_t)255u;
+        const tern_conv_geom& g = layers[0].g;
+        PatchParams pp;
+        pp.src = in; pp.lo = in_lo; pp.hi = in_hi; pp.dst = cur_buf;
+        pp.d = in_dims.d; pp.h = in_dims.h; pp.w = in_dims.w;
+        pp.od = o0.d; pp.oh = o0.h; pp.ow = o0.w;
+        pp.kd = g.k[0]; pp.kh = g.k[1]; pp.kw = g.k[2];
+        pp.sh = g.stride[1]; pp.sw = g.stride[2];
+        pp.pd = g.pad[0]; pp.ph = g.pad[1]; pp.pw = g.pad[2];
+        pp.dh = g.dil[1]; pp.dw = g.dil[2];
+        rc = launch_patch_pack_f32(pp, in_dims.n, (hipStream_t)stream);
+    } else {
+        ws += (tern_packed_bytes(in_dims) + 255u) & ~(size_t)255u;
+        rc = tern_threshold_pack(in, TERN_SRC_F32, in_dims, in_lo, in_hi, cur_buf, stream);
+    }
+    if (rc != TERN_OK) return rc;
     for (int i = 0; i < n_layers; ++i) {
         tern_dims o;
         rc = geom_check(cur, layers[i].c_out, layers[i].g, &o);
@@ -345,8 +389,17 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
         } else {
             dst = out_packed;
         }
-        rc = tern_conv3d(cur_buf, cur, layers[i].w_bank, layers[i].c_out, layers[i].g,
-                         layers[i].thr_lo, layers[i].thr_hi, nullptr, dst, stream);
+        if (i == 0 && gathered) {
+            const int32_t taps = layers[0].g.k[0] * layers[0].g.k[1] * layers[0].g.k[2];
+            const tern_dims pin = {o.n, taps, o.d, o.h, o.w};
+            const tern_conv_geom unit = {{1, 1, 1}, {1, 1, 1}, {0, 0, 0}, {1, 1, 1}};
+            rc = launch_conv3d(conv_params(cur_buf, pin, layers[0].w_bank, layers[0].c_out, unit, o,
+                                           layers[0].thr_lo, layers[0].thr_hi, nullptr, dst),
+                               (hipStream_t)stream);
+        } else {
+            rc = tern_conv3d(cur_buf, cur, layers[i].w_bank, layers[i].c_out, layers[i].g,
+                             layers[i].thr_lo, layers[i].thr_hi, nullptr, dst, stream);
+        }
         if (rc != TERN_OK) return rc;
         if (layer_out) layer_out[i] = dst;
         cur_buf = dst;

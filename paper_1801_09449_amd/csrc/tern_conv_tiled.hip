@@ -16,6 +16,7 @@
 //   - Epilogue: acc = M-count - 2 * N-count; either stored as int32 (NCDHW) or compared with the
 //     per-channel cut points (Eq. 6 in integer form) and assembled into mask/sign words in-lane,
 //     so that activations go back to memory at 2 bits per value.
+#include "tern_conv_common.h"
 #include "tern_internal.h"
 
 namespace tern {
@@ -58,12 +59,6 @@ struct TileParams {
 };
 
 template <int WC>
-struct ActChunk {
-    uint32_t m[WC];
-    uint32_t s[WC];
-};
-
-template <int WC>
 __device__ __forceinline__ ActChunk<WC> lds_read_chunk(const uint32_t* p)
 {
     ActChunk<WC> a;
@@ -76,113 +71,6 @@ __device__ __forceinline__ ActChunk<WC> lds_read_chunk(const uint32_t* p)
         a.m[0] = r.x; a.m[1] = r.y; a.s[0] = r.z; a.s[1] = r.w;
     }
     return a;
-}
-
-// Filter words and cut points are read through the constant address space so that the
-// wave-uniform loads go through the scalar cache (s_load) into SGPRs; neither is written by
-// these kernels.
-typedef const uint32_t __attribute__((address_space(4)))* scalar_ptr;
-
-// acc += popcount(x) as the single instruction the hardware has for it.
-__device__ __forceinline__ void popc_acc(int32_t& acc, uint32_t x)
-{
-    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
-}
-
-// m & (sa ^ sw) as one three-input bit operation (truth-table index = sa<<2 | m<<1 | sw).
-// Spelled out because the compiler otherwise sometimes forms (sa ^ sw) on its own and spends a
-// fifth instruction per word pair.
-__device__ __forceinline__ uint32_t and_xor(uint32_t m, uint32_t sa, uint32_t sw)
-{
-    uint32_t r;
-    asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x48" : "=v"(r) : "v"(sa), "v"(m), "s"(sw));
-    return r;
-}
-
-// word = (word << 1) | (thr < d): the comparison result goes through the carry flag into the
-// low bit, two instructions per decision and no overflow cases.
-__device__ __forceinline__ void shift_in_gt(uint32_t& word, int32_t d, int32_t thr)
-{
-    asm("v_cmp_lt_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
-        : "+v"(word) : "v"(d), "s"(thr) : "vcc");
-}
-// word = (word << 1) | (d < thr)
-__device__ __forceinline__ void shift_in_lt(uint32_t& word, int32_t d, int32_t thr)
-{
-    asm("v_cmp_gt_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
-        : "+v"(word) : "v"(d), "s"(thr) : "vcc");
-}
-
-// KG = output channels whose filter words are fetched together.  Two groups are in flight (one
-// being used, one arriving).  With 32 channels per pass KG = 4 keeps the filter words within 32
-// SGPRs, which leaves room for the loop's own scalars (8 per group made the compiler spill them);
-// with 16 channels per pass KG = 8 fits and halves the number of waits, which matters when a
-// SIMD holds a single wave and nothing else hides the scalar-cache latency.
-template <int CO_BLK>
-struct GroupOf {
-    static constexpr int value = CO_BLK >= 32 ? 4 : 8;
-};
-
-template <int WC, int KG>
-struct WGroup {
-    uint32_t m[KG][WC];
-    uint32_t s[KG][WC];
-};
-
-// Fetch the filter words of KG consecutive channels of one step.  In the filter bank the
-// channels of a step are contiguous (2*WC words each), so this is one contiguous block that
-// the compiler turns into wide scalar loads with immediate offsets.
-template <int WC, int KG>
-__device__ __forceinline__ void load_wgroup(WGroup<WC, KG>& g, scalar_ptr wp)
-{
-#pragma unroll
-    for (int j = 0; j < KG; ++j)
-#pragma unroll
-        for (int q = 0; q < WC; ++q) {
-            g.m[j][q] = wp[j * 2 * WC + q];
-            g.s[j][q] = wp[j * 2 * WC + WC + q];
-        }
-}
-
-// Scalar loads return out of order, so the only safe wait is "all of them".  Naming the group's
-// registers here makes the compiler place that wait at this point, i.e. before the loads of the
-// following group are issued, so that those overlap the arithmetic on this group instead of
-// being waited for together with it.
-template <int WC, int KG>
-__device__ __forceinline__ void settle(const WGroup<WC, KG>& g)
-{
-    static_assert(KG % 4 == 0, "groups of 4 channels per asm statement");
-#pragma unroll
-    for (int j = 0; j < KG; j += 4) {
-        if constexpr (WC == 2) {
-            asm volatile("" ::"s"(g.m[j][0]), "s"(g.m[j][1]), "s"(g.s[j][0]), "s"(g.s[j][1]),
-                         "s"(g.m[j + 1][0]), "s"(g.m[j + 1][1]), "s"(g.s[j + 1][0]), "s"(g.s[j + 1][1]),
-                         "s"(g.m[j + 2][0]), "s"(g.m[j + 2][1]), "s"(g.s[j + 2][0]), "s"(g.s[j + 2][1]),
-                         "s"(g.m[j + 3][0]), "s"(g.m[j + 3][1]), "s"(g.s[j + 3][0]), "s"(g.s[j + 3][1]));
-        } else {
-            asm volatile("" ::"s"(g.m[j][0]), "s"(g.s[j][0]), "s"(g.m[j + 1][0]), "s"(g.s[j + 1][0]),
-                         "s"(g.m[j + 2][0]), "s"(g.s[j + 2][0]), "s"(g.m[j + 3][0]), "s"(g.s[j + 3][0]));
-        }
-    }
-}
-
-// Four VALU instructions per (word pair, voxel): and, popcount-accumulate, and-xor,
-// popcount-accumulate (Eq. 9 as popcount(M) - 2 popcount(M & X), the subtraction deferred).
-template <int WC, int V, int CO_BLK, int KG>
-__device__ __forceinline__ void mac_group(const ActChunk<WC> (&A)[V], const WGroup<WC, KG>& g, int j0,
-                                          int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK])
-{
-#pragma unroll
-    for (int j = 0; j < KG; ++j)
-#pragma unroll
-        for (int q = 0; q < WC; ++q)
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const uint32_t M = A[v].m[q] & g.m[j][q];
-                const uint32_t N = and_xor(M, A[v].s[q], g.s[j][q]);
-                popc_acc(acc_m[v][j0 + j], M);
-                popc_acc(acc_n[v][j0 + j], N);
-            }
 }
 
 // Scalar walk over the kernel taps.  Plain mode: one step = one (tap, channel chunk) and the
@@ -316,9 +204,11 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int ox0 = tix * TX, oy0 = tiy * TY, oz0 = tiz * TZ;
 
     // ---- stage the halo tile -------------------------------------------------------------
-    // A thread owns plane positions i = tid, tid + nthreads, ... of the (hy, hx) halo plane and
-    // walks the hz planes in batches: all global loads of a batch are issued before the first
-    // LDS write, so a wave pays one memory round trip per batch instead of one per voxel.
+    // All global loads of a batch of FB voxels are issued before the batch's first LDS write, so
+    // a wave pays one memory round trip per batch instead of one per voxel.  Deep tiles: a thread
+    // owns plane positions i = tid, tid + nthreads, ... of the (hy, hx) halo plane and a batch is
+    // FB planes of one position.  Flat tiles (few planes, many positions per thread, as for
+    // single-plane outputs): a batch is FB positions of one plane.
     {
         constexpr int FB = 8;
         const int gx0 = ox0 * p.sw - p.pw, gy0 = oy0 * p.sh - p.ph, gz0 = oz0 * p.sd - p.pd;
@@ -326,39 +216,84 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
         const int wd = p.wd_in;
         const uint32_t* in_n = p.in + (size_t)n * p.d * p.h * p.w * 2u * wd;
         const size_t zstride = (size_t)p.h * p.w * 2u * wd;   // words between input planes
-        for (int i = tid; i < plane; i += nthreads) {
-            const int hy = i / t.hx;
-            const int hxx = i - hy * t.hx;
-            const int gy = gy0 + hy, gx = gx0 + hxx;
-            const bool xy_in = gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
-            const uint32_t* src_xy = in_n + ((size_t)(xy_in ? gy : 0) * p.w + (xy_in ? gx : 0)) * 2u * wd;
-            uint32_t* dst_xy = lds + (size_t)i * t.vstride;
-            for (int ch = 0; ch < t.nchunk; ++ch) {
-                for (int hz0 = 0; hz0 < t.hz; hz0 += FB) {
-                    uint4 r[FB];
-#pragma unroll
-                    for (int j = 0; j < FB; ++j) {
-                        const int gz = gz0 + hz0 + j;
-                        const bool inb = xy_in && hz0 + j < t.hz && gz >= 0 && gz < p.d;
-                        r[j] = make_uint4(0u, 0u, 0u, 0u);
-                        if (inb) {
-                            const uint32_t* src = src_xy + (size_t)gz * zstride;
-                            if constexpr (WC == 2) {
-                                const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
-                                const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
-                                r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
-                            } else {
-                                r[j].x = src[ch];
-                                r[j].y = src[wd + ch];
+        if (t.hz >= 4) {
+            for (int i = tid; i < plane; i += nthreads) {
+                const int hy = i / t.hx;
+                const int hxx = i - hy * t.hx;
+                const int gy = gy0 + hy, gx = gx0 + hxx;
+                const bool xy_in = gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
+                const uint32_t* src_xy = in_n + ((size_t)(xy_in ? gy : 0) * p.w + (xy_in ? gx : 0)) * 2u * wd;
+                uint32_t* dst_xy = lds + (size_t)i * t.vstride;
+                for (int ch = 0; ch < t.nchunk; ++ch) {
+                    for (int hz0 = 0; hz0 < t.hz; hz0 += FB) {
+                        uint4 r[FB];
+    #pragma unroll
+                        for (int j = 0; j < FB; ++j) {
+                            const int gz = gz0 + hz0 + j;
+                            const bool inb = xy_in && hz0 + j < t.hz && gz >= 0 && gz < p.d;
+                            r[j] = make_uint4(0u, 0u, 0u, 0u);
+                            if (inb) {
+                                const uint32_t* src = src_xy + (size_t)gz * zstride;
+                                if constexpr (WC == 2) {
+                                    const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
+                                    const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
+                                    r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
+                                } else {
+                                    r[j].x = src[ch];
+                                    r[j].y = src[wd + ch];
+                                }
+                            }
+                        }
+    #pragma unroll
+                        for (int j = 0; j < FB; ++j) {
+                            if (hz0 + j < t.hz) {
+                                uint32_t* dst = dst_xy + (size_t)(hz0 + j) * plane * t.vstride;
+                                if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst + 4 * ch) = r[j];
+                                else *reinterpret_cast<uint2*>(dst + 2 * ch) = make_uint2(r[j].x, r[j].y);
                             }
                         }
                     }
+                }
+            }
+        } else {
+            // floor(i / hx) = umulhi(i, magic) for every i * hx < 2^32 (i is an LDS position)
+            const uint32_t magic = 0xffffffffu / (uint32_t)t.hx + 1u;
+            for (int hz = 0; hz < t.hz; ++hz) {
+                const int gz = gz0 + hz;
+                const bool z_in = gz >= 0 && gz < p.d;
+                const uint32_t* src_z = in_n + (size_t)(z_in ? gz : 0) * zstride;
+                uint32_t* dst_z = lds + (size_t)hz * plane * t.vstride;
+                for (int ch = 0; ch < t.nchunk; ++ch) {
+                    for (int i0 = tid; i0 < plane; i0 += FB * nthreads) {
+                        uint4 r[FB];
 #pragma unroll
-                    for (int j = 0; j < FB; ++j) {
-                        if (hz0 + j < t.hz) {
-                            uint32_t* dst = dst_xy + (size_t)(hz0 + j) * plane * t.vstride;
-                            if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst + 4 * ch) = r[j];
-                            else *reinterpret_cast<uint2*>(dst + 2 * ch) = make_uint2(r[j].x, r[j].y);
+                        for (int j = 0; j < FB; ++j) {
+                            const int i = i0 + j * nthreads;
+                            const int hy = (int)__umulhi((uint32_t)i, magic);
+                            const int hxx = i - hy * t.hx;
+                            const int gy = gy0 + hy, gx = gx0 + hxx;
+                            const bool inb = z_in && i < plane && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
+                            r[j] = make_uint4(0u, 0u, 0u, 0u);
+                            if (inb) {
+                                const uint32_t* src = src_z + ((size_t)gy * p.w + gx) * 2u * wd;
+                                if constexpr (WC == 2) {
+                                    const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
+                                    const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
+                                    r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
+                                } else {
+                                    r[j].x = src[ch];
+                                    r[j].y = src[wd + ch];
+                                }
+                            }
+                        }
+#pragma unroll
+                        for (int j = 0; j < FB; ++j) {
+                            const int i = i0 + j * nthreads;
+                            if (i < plane) {
+                                uint32_t* dst = dst_z + (size_t)i * t.vstride;
+                                if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst + 4 * ch) = r[j];
+                                else *reinterpret_cast<uint2*>(dst + 2 * ch) = make_uint2(r[j].x, r[j].y);
+                            }
                         }
                     }
                 }
@@ -605,6 +540,7 @@ int g_waves_z = 0;      // tuning override: 0 = choose, else waves stacked along
 int g_co_block = 0;     // tuning override: 0 = choose, 16 or 32 = channels per accumulation pass
 int g_co_per_wave = 0;  // tuning override: 0 = choose, else channels per wave (multiple of 16)
 int g_tap_split = 0;    // tuning override: 0 = choose, else waves sharing the taps of one slice
+int g_point = 1;        // tuning override: 0 = never use the pointwise kernel
 
 // Tile plan for a voxel depth V per lane; returns false if no halo tile fits in LDS.
 bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_t& lds_bytes)
@@ -665,9 +601,11 @@ void set_waves_z(int v) { g_waves_z = (v == 1 || v == 2 || v == 4 || v == 8) ? v
 void set_co_block(int v) { g_co_block = (v == 16 || v == 32) ? v : 0; }
 void set_co_per_wave(int v) { g_co_per_wave = (v > 0 && v % 16 == 0) ? v : 0; }
 void set_tap_split(int v) { g_tap_split = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
+void set_pointwise(int v) { g_point = v ? 1 : 0; }
 
 int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 {
+    if (g_point && conv_point_applies(p_in)) return launch_conv_point(p_in, s);
     ConvParams p = p_in;
     const bool packed = p.out_packed != nullptr;
     // A kernel of depth extent 1 with unit depth stride and no depth padding treats every input
@@ -678,6 +616,19 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         p.d *= p.n;
         p.od *= p.n;
         p.n = 1;
+    }
+    // A single tap with unit stride and no padding looks at no neighbour at all: the volume is
+    // a flat list of voxels.  Laid out as rows of 8 it makes every wave's 8 x 16 tile one
+    // contiguous run of 128 voxels, so the halo fill and the stores stream instead of touching
+    // 64-byte pieces of many rows.
+    if (p.kd * p.kh * p.kw == 1 && p.sd == 1 && p.sh == 1 && p.sw == 1 && p.pd == 0 && p.ph == 0 &&
+        p.pw == 0) {
+        const int64_t vox = (int64_t)p.d * p.h * p.w;
+        if (vox % 8 == 0) {
+            p.d = p.od = 1;
+            p.h = p.oh = (int32_t)(vox / 8);
+            p.w = p.ow = 8;
+        }
     }
     const int lds_limit = lds_limit_for_current_device();
 

@@ -92,6 +92,20 @@ struct RealConvParams {
     int64_t total;          // output voxels
 };
 
+// Gathering of the taps of a one-channel first layer (see patch_pack_f32_kernel).
+struct PatchParams {
+    const float* src;       // [N][1][d][h][w]
+    const float* lo;        // [1] cut points of the input activation
+    const float* hi;
+    uint32_t* dst;          // [N][od][oh][ow][2][1]
+    int32_t d, h, w, od, oh, ow;
+    int32_t kd, kh, kw, sh, sw, pd, ph, pw, dh, dw;
+};
+// True when a first layer with c_in input channels, geometry g and output extents `out` can take
+// that route.
+bool patch_pack_applies(int32_t c_in, const tern_conv_geom& g, const tern_dims& out);
+int launch_patch_pack_f32(const PatchParams& p, int32_t n, hipStream_t s);
+
 // Launchers implemented in the kernel translation units.  Each validates nothing (the entry
 // points did) and returns a tern_status.
 int launch_pack_i8(const int8_t* src, tern_dims dims, uint32_t* dst, hipStream_t s);
@@ -100,6 +114,9 @@ int launch_threshold_pack_i32(const int32_t* src, tern_dims dims, const int32_t*
 int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo, const float* hi,
                               uint32_t* dst, hipStream_t s);
 int launch_conv3d(const ConvParams& p, hipStream_t s);
+// 1x1x1 / stride 1 / no padding with 1, 2, 4 or 8 input words per plane: the pointwise kernel.
+bool conv_point_applies(const ConvParams& p);
+int launch_conv_point(const ConvParams& p, hipStream_t s);
 int launch_concat(const ConcatParams& p, hipStream_t s);
 int launch_real_conv(const RealConvParams& p, hipStream_t s);
 void set_lane_depth(int v);
@@ -107,6 +124,7 @@ void set_waves_z(int v);
 void set_co_block(int v);
 void set_co_per_wave(int v);
 void set_tap_split(int v);
+void set_pointwise(int v);
 int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
                         int32_t kw, uint32_t* bank, hipStream_t s);
 

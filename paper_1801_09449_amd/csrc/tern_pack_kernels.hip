@@ -217,6 +217,126 @@ int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo,
     return launch_pack_any<float, 1>(src, dims, lo, hi, dst, s);
 }
 
+// ---- first layer of a network on a scalar volume: gather the kernel taps into one word ----------
+// With one input channel a packed voxel carries a single live bit per plane, and a convolution
+// would have to collect its T <= 32 taps bit by bit for every output voxel and channel slice.
+// This kernel does that collecting once, straight from the float intensities (applying the
+// activation cut points on the way): output voxel o gets one mask word and one sign word whose
+// bit t is the code of tap t = (a*kh + b)*kw + c of o's receptive field (0 outside the volume).
+// The convolution then is a single-tap one over T "channels", and the tap-packed filter bank
+// (bit t of its one word per channel = tap t) is exactly that convolution's plain bank.
+// A thread owns one (ox, oy) column and kPatchZ consecutive output planes; with unit depth stride
+// and dilation these share input planes, so kPatchZ + KD - 1 plane parts serve kPatchZ outputs.
+// Instantiated for the usual first kernels, 3x3x3 and 1x3x3 (any in-plane stride, dilation, pad).
+namespace {
+
+constexpr int kPatchZ = 8;
+
+template <int KD, int KH, int KW>
+__global__ __launch_bounds__(256) void patch_pack_f32_kernel(PatchParams p)
+{
+    constexpr int NB = KH * KW;   // taps per input plane
+    const int ox = blockIdx.x * 64 + threadIdx.x;
+    const int oy = blockIdx.y * 4 + threadIdx.y;
+    const int nseg = (p.od + kPatchZ - 1) / kPatchZ;
+    const int seg = blockIdx.z % nseg;
+    const int n = blockIdx.z / nseg;
+    if (ox >= p.ow || oy >= p.oh) return;
+    const float lo = p.lo[0], hi = p.hi[0];
+    const float* src_n = p.src + (size_t)n * p.d * p.h * p.w;
+    const size_t plane = (size_t)p.h * p.w;
+
+    // In-plane offsets of this column's taps, fixed for the whole walk; taps outside the plane
+    // read element 0 and are masked out afterwards, so every load is unconditional.
+    int off[NB];
+    uint32_t valid = 0u;
+#pragma unroll
+    for (int b = 0; b < KH; ++b)
+#pragma unroll
+        for (int c = 0; c < KW; ++c) {
+            const int iy = oy * p.sh - p.ph + b * p.dh;
+            const int ix = ox * p.sw - p.pw + c * p.dw;
+            const bool ok = iy >= 0 && iy < p.h && ix >= 0 && ix < p.w;
+            off[b * KW + c] = ok ? iy * p.w + ix : 0;
+            valid |= (ok ? 1u : 0u) << (b * KW + c);
+        }
+
+    // All input planes this thread needs, fetched before any of them is used: one memory round
+    // trip for the whole walk.  Planes outside the volume read plane 0 and are masked out.
+    constexpr int NP = kPatchZ + KD - 1;
+    const int oz0 = seg * kPatchZ;
+    float v[NP][NB];
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+        const int iz = oz0 - p.pd + j;
+        const float* pl = src_n + (size_t)((iz >= 0 && iz < p.d) ? iz : 0) * plane;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) v[j][i] = pl[off[i]];
+    }
+    // codes of the in-plane taps of every fetched plane, tap (b, c) at bit b*KW + c
+    uint32_t m[NP], s[NP];
+#pragma unroll
+    for (int j = 0; j < NP; ++j) {
+        const int iz = oz0 - p.pd + j;
+        uint32_t P = 0u, N = 0u;
+#pragma unroll
+        for (int i = NB - 1; i >= 0; --i) {
+            // P = 2P + (hi < v), N = 2N + (v < lo): the comparison result travels through the
+            // carry flag into the low bit (ordered comparisons: false for NaN, like the C ones)
+            asm("v_cmp_lt_f32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+                : "+v"(P) : "v"(v[j][i]), "s"(hi) : "vcc");
+            asm("v_cmp_gt_f32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
+                : "+v"(N) : "v"(v[j][i]), "s"(lo) : "vcc");
+        }
+        const uint32_t vm = (iz >= 0 && iz < p.d) ? valid : 0u;
+        P &= vm;
+        N &= vm & ~P;          // +1 wins should the cut points be crossed (lo > hi)
+        m[j] = P | N;
+        s[j] = N;
+    }
+    uint32_t* out = p.dst + ((((size_t)n * p.od + oz0) * p.oh + oy) * p.ow + ox) * 2u;
+    const size_t ostep = (size_t)p.oh * p.ow * 2u;
+#pragma unroll
+    for (int t = 0; t < kPatchZ; ++t) {
+        if (oz0 + t >= p.od) break;
+        uint32_t wm = 0u, ws = 0u;
+#pragma unroll
+        for (int a = 0; a < KD; ++a) { wm |= m[t + a] << (a * NB); ws |= s[t + a] << (a * NB); }
+        *reinterpret_cast<uint2*>(out + (size_t)t * ostep) = make_uint2(wm, ws);
+    }
+}
+
+// Kernel extents the gathering kernel is instantiated for.
+inline bool patch_kernel_exists(int kd, int kh, int kw)
+{
+    return kh == 3 && kw == 3 && (kd == 3 || kd == 1);
+}
+
+}  // namespace
+
+bool patch_pack_applies(int32_t c_in, const tern_conv_geom& g, const tern_dims& out)
+{
+    if (!(c_in == 1 && patch_kernel_exists(g.k[0], g.k[1], g.k[2]) && g.stride[0] == 1 && g.dil[0] == 1))
+        return false;
+    // launch grid limits of the gathering kernel
+    const int64_t nseg = (out.d + kPatchZ - 1) / kPatchZ;
+    return nseg * out.n <= 65535 && (out.h + 3) / 4 <= 65535;
+}
+
+int launch_patch_pack_f32(const PatchParams& p, int32_t n, hipStream_t s)
+{
+    const int nseg = (p.od + kPatchZ - 1) / kPatchZ;
+    const dim3 grid((unsigned)((p.ow + 63) / 64), (unsigned)((p.oh + 3) / 4), (unsigned)(nseg * n)), block(64, 4);
+    if (p.kd == 3 && p.kh == 3 && p.kw == 3)
+        hipLaunchKernelGGL((patch_pack_f32_kernel<3, 3, 3>), grid, block, 0, s, p);
+    else if (p.kd == 1 && p.kh == 3 && p.kw == 3)
+        hipLaunchKernelGGL((patch_pack_f32_kernel<1, 3, 3>), grid, block, 0, s, p);
+    else
+        return TERN_EARG;
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
+
 // ---- filter bank ------------------------------------------------------------------------------
 // Layout consumed by the convolution kernels (documented in include/tern.h).
 // Plain: uint32 [T * nchunk][co_pad][2][wc]; step s = tap * nchunk + chunk holds, for every

@@ -338,6 +338,67 @@ def test_config2_fcn_full(G):
     assert 0.15 < zero_frac < 0.7
 
 
+POINTWISE = [(27, 16, (5, 7, 9), 1), (64, 64, (6, 5, 7), 2), (128, 40, (3, 5, 5), 3), (256, 96, (4, 4, 4), 1),
+             (32, 33, (1, 1, 130), 2), (100, 70, (2, 9, 8), 2), (8, 200, (3, 3, 3), 1), (1, 1, (1, 1, 1), 1),
+             (64, 32, (16, 32, 40), 1)]
+
+
+@pytest.mark.parametrize("ci,co,vol,n", POINTWISE, ids=[f"{a}-{b}-n{d}" for a, b, _, d in POINTWISE])
+def test_pointwise_kernel_and_tiled_route_agree_with_oracle(G, ci, co, vol, n):
+    """1x1x1 convolutions: 1, 2, 4 and 8 input words per plane, ragged voxel counts and channel
+    tails, batches; once through the pointwise kernel and once forced through the tiled one."""
+    import paper_1801_09449_amd as T
+    c = synth.conv_case("pw", n, ci, co, vol, k=1, pad=0, seed=ci + co)
+    want_acc, want_packed = expect(c)
+    try:
+        for use_point in (1, 0):
+            T.tern_set_option(6, use_point)
+            acc, packed = G.run_case(c)
+            np.testing.assert_array_equal(acc, want_acc)
+            np.testing.assert_array_equal(packed, want_packed)
+    finally:
+        T.tern_set_option(6, 1)
+
+
+FIRST_LAYERS = [
+    # (k, stride, pad, dil) of layer 0 on a one-channel input; 3x3x3 and 1x3x3 kernels with unit
+    # depth stride and dilation take the route that gathers the taps into one word per output
+    # voxel (rows 0, 1, 3), the others the ordinary one
+    ((3, 3, 3), (1, 1, 1), (1, 1, 1), (1, 1, 1)),
+    ((1, 3, 3), (1, 1, 1), (0, 1, 1), (1, 1, 1)),
+    ((2, 3, 3), (1, 2, 1), (1, 0, 1), (1, 1, 1)),
+    ((3, 3, 3), (1, 2, 2), (1, 2, 1), (1, 2, 1)),
+    ((2, 4, 4), (1, 1, 3), (0, 2, 0), (1, 1, 2)),      # 32 taps: the word is full
+    ((3, 1, 5), (1, 1, 1), (2, 0, 3), (1, 1, 1)),
+    ((3, 3, 3), (2, 1, 1), (1, 1, 1), (1, 1, 1)),      # depth stride 2
+    ((3, 3, 3), (1, 1, 1), (2, 1, 1), (2, 1, 1)),      # depth dilation 2
+    ((3, 3, 4), (1, 1, 1), (1, 1, 1), (1, 1, 1)),      # 36 taps
+]
+
+
+@pytest.mark.parametrize("k,stride,pad,dil", FIRST_LAYERS, ids=[str(i) for i in range(len(FIRST_LAYERS))])
+def test_fcn_first_layer_geometries(G, k, stride, pad, dil):
+    """One-channel float input, asymmetric input cut points, batch of 2, extents that are not
+    multiples of the kernels' block shapes; three layers so that layer 0's output feeds on."""
+    vol = (11, 70, 67)
+    x = synth.gaussian((2, 1) + vol, 61, synth.T_F32)
+    in_lo, in_hi = np.array([-0.3], np.float32), np.array([0.8], np.float32)
+    layers, c_in = [], 1
+    for li, (c_out, kk, st, pd, dl) in enumerate([(20, k, stride, pad, dil), (33, (3, 3, 3), (1, 1, 1), (1, 1, 1), (1, 1, 1)),
+                                                   (8, (1, 1, 1), (1, 1, 1), (0, 0, 0), (1, 1, 1))], start=1):
+        w = synth.ternary((c_out, c_in) + kk, 0.5, 61, synth.T_WGT + 8 * li)
+        lo, hi = synth.bn_like_thresholds(c_out, int(np.prod(kk)), c_in, 0.5, 0.6, 61, synth.T_THR + 8 * li)
+        layers.append(dict(w=w, k=kk, stride=st, pad=pd, dil=dl, lo=lo, hi=hi))
+        c_in = c_out
+    f = synth.FcnCase("first", x, in_lo, in_hi, layers)
+    got = fcn_run(G, f)
+    want = fcn_expect(f)
+    for i, ((w, dm), code) in enumerate(zip(got, want)):
+        assert tuple(dm) == code.shape, f"layer {i + 1}"
+        np.testing.assert_array_equal(w, oracle.pack(code), err_msg=f"layer {i + 1}")
+    assert len(np.unique(want[0])) == 3
+
+
 # ---- tensors above 4 GiB: byte offsets need 64 bits, voxel indices still fit 32 ---------------
 @pytest.mark.parametrize("c_in,c_out", [(1, 33), (17, 8)], ids=["tap-packed", "plain"])
 def test_volume_above_4gib_sampled(G, c_in, c_out):
