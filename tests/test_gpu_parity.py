@@ -225,6 +225,27 @@ def test_conv_kernel_variants_agree_with_oracle(G, opts):
             T.tern_set_option(key, 0)
 
 
+def random_case(i):
+    """Seeded random geometry: channels up to 300, extents up to 20, kernels up to 5 per axis with
+    random stride, padding and dilation (kept valid), batch up to 3."""
+    u = synth.uniform_int(16, 0, 10 ** 6, 9000 + i, 11)
+    pick = lambda j, lo, hi: int(lo + u[j] % (hi - lo + 1))
+    c_in = [1, 3, 8, 16, 17, 32, 33, 64, 65, 100, 128, 200, 256, 300][pick(0, 0, 13)]
+    c_out = [1, 5, 16, 17, 31, 32, 33, 48, 64, 70, 96, 129][pick(1, 0, 11)]
+    n = pick(2, 1, 3)
+    k = tuple(pick(3 + a, 1, 5 if c_in <= 64 else 3) for a in range(3))
+    dil = tuple(pick(6 + a, 1, 3) for a in range(3))
+    stride = tuple(pick(9 + a, 1, 3) for a in range(3))
+    pad = tuple(pick(12 + a, 0, dil[a] * (k[a] - 1)) for a in range(3))
+    vol = tuple(max(dil[a] * (k[a] - 1) + 1 - 2 * pad[a], 1) + pick(15, 0, 12) + 3 * a for a in range(3))
+    return synth.conv_case(f"rnd{i}", n, c_in, c_out, vol, k, stride, pad, dil, seed=7000 + i)
+
+
+@pytest.mark.parametrize("i", range(48))
+def test_random_geometries(G, i):
+    check_case(G, random_case(i))
+
+
 def test_generic_fallback_for_oversized_halo(G):
     # dilation so large that no halo tile fits in LDS: the library falls back to the direct kernel
     c = synth.conv_case("fallback", 1, 40, 33, (20, 21, 22), k=3, stride=1, pad=60, dil=60, seed=83)
