@@ -121,6 +121,12 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
     out = T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws)
     ms_fcn, _ = timed(lambda: T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws, out=out), 30, 5, None)
     ex["cfg2_fcn"] = {"gmac": f.macs / 1e9, "ms": ms_fcn, "TMACs": f.macs / (ms_fcn * 1e-3) / 1e12}
+    # the same chain recorded once into a HIP graph and replayed (no per-launch host work)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws, out=out)
+    ms_g, _ = timed(graph.replay, 30, 5, None)
+    ex["cfg2_fcn"]["graph_replay_ms"] = ms_g
     # per layer
     cur = tuple(x.shape)
     a_in = T.tern_threshold_pack(x, ilo, ihi)
@@ -153,7 +159,12 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
             executed += vox * c * L["w"].shape[1] * taps * (int(np.prod(L["pool"])) if L["pool"] else 1)
         del kept
         ms_u, _ = timed(lambda: unet.unet_forward(plan, ux), 20, 3, None)
-        ex["unet_table1_n%d" % n] = {"ms": ms_u, "gmac_table1_convention": nominal / 1e9,
+        ugraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(ugraph):
+            upred = unet.unet_forward(plan, ux)
+        ms_ug, _ = timed(ugraph.replay, 20, 3, None)
+        ex["unet_table1_n%d" % n] = {"ms": ms_u, "graph_replay_ms": ms_ug,
+                                     "gmac_table1_convention": nominal / 1e9,
                                      "gmac_executed": executed / 1e9,
                                      "TMACs_executed": executed / (ms_u * 1e-3) / 1e12,
                                      "prediction_shape": list(pred.shape)}

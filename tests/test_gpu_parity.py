@@ -486,3 +486,38 @@ def test_calls_follow_the_callers_stream(G):
     np.testing.assert_array_equal(G.words(fused), want_packed)
     np.testing.assert_array_equal(G.words(two_step), want_packed)
     assert float(noise.sum()) == float(1 << 20)
+
+
+def test_fcn_forward_replays_from_a_captured_graph(G):
+    """The entry points allocate nothing and clear nothing, so a chain of them can be recorded
+    into a HIP graph: capture tern_fcn_forward once, then replay it on new input contents, with
+    eager work and synchronisation between the replays; every replay must match the oracle."""
+    import torch
+    import paper_1801_09449_amd as T
+    f = synth.config2(seed=5, vol=(16, 24, 16))
+    layers = [T.FcnLayer(c_in=L["w"].shape[1], c_out=L["w"].shape[0], w_bank=T.tern_pack_filters(G.dev(L["w"])),
+                         thr_lo=G.dev(L["lo"]), thr_hi=G.dev(L["hi"]), k=L["k"], stride=L["stride"],
+                         pad=L["pad"], dil=L["dil"]) for L in f.layers]
+    x = G.dev(f.x)
+    ilo, ihi = G.dev(f.in_lo), G.dev(f.in_hi)
+    ws = torch.empty((T.tern_fcn_workspace_bytes(x.shape, layers),), dtype=torch.uint8, device="cuda")
+    out = T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws)      # warm-up, also sizes `out`
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws, out=out)
+    want_layers = [dict(w=L["w"], geom=ConvGeom(L["k"], L["stride"], L["pad"], L["dil"]), lo=L["lo"], hi=L["hi"])
+                   for L in f.layers]
+    for rep in range(3):
+        xi = synth.gaussian(f.x.shape, 100 + rep, synth.T_F32)
+        x.copy_(torch.from_numpy(xi))
+        out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        want = oracle.fcn_forward(xi, f.in_lo, f.in_hi, want_layers)[-1]
+        np.testing.assert_array_equal(G.words(out), oracle.pack(want), err_msg=f"replay {rep}")
+        # eager call on the same input gives the same bits
+        eager = T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(G.words(eager), G.words(out))
