@@ -127,3 +127,61 @@ def test_maximum_sizes_are_enforced(T):
     # output channel count
     assert T.tern_filter_bank_bytes(2 ** 19, 1, 1) > 0
     assert T.tern_filter_bank_bytes(2 ** 19 + 1, 1, 1) == 0
+
+
+def test_unet_entry_points_reject_bad_arguments(T):
+    """tern_concat / tern_conv3d_real validate on the host before anything is launched;
+    tern_fold_avgpool runs on the host entirely."""
+    import numpy as np
+    from paper_1801_09449_amd.binding import Dims, Source, _geom
+    L = T.lib()
+    fake = 0x1000
+
+    def src(c, d=2, h=4, w=4, n=1, up=(1, 1, 1), first=(0, 0, 0), ptr=fake):
+        s = Source()
+        s.packed = ptr
+        s.dims = Dims(n, c, d, h, w)
+        for a in range(3):
+            s.up[a] = up[a]
+            s.first[a] = first[a]
+        return s
+
+    out = C.c_void_p(fake)
+    one = (Source * 1)(src(8))
+    assert L.tern_concat(one, 1, Dims(1, 8, 2, 4, 4), None, None) == -1
+    assert L.tern_concat(None, 1, Dims(1, 8, 2, 4, 4), out, None) == -1
+    assert L.tern_concat(one, 0, Dims(1, 8, 2, 4, 4), out, None) == -3
+    assert L.tern_concat(one, 9, Dims(1, 8, 2, 4, 4), out, None) == -3
+    assert L.tern_concat(one, 1, Dims(1, 9, 2, 4, 4), out, None) == -3          # channel sum mismatch
+    assert L.tern_concat(one, 1, Dims(2, 8, 2, 4, 4), out, None) == -3          # batch mismatch
+    assert L.tern_concat(one, 1, Dims(1, 8, 2, 5, 4), out, None) == -3          # runs past the source
+    assert L.tern_concat(one, 1, Dims(1, 8, 0, 4, 4), out, None) == -2
+    assert L.tern_concat((Source * 1)(src(8, up=(1, 0, 1))), 1, Dims(1, 8, 2, 4, 4), out, None) == -3
+    assert L.tern_concat((Source * 1)(src(8, first=(0, -1, 0))), 1, Dims(1, 8, 2, 4, 4), out, None) == -3
+    assert L.tern_concat((Source * 1)(src(8, ptr=None)), 1, Dims(1, 8, 2, 4, 4), out, None) == -1
+    assert L.tern_concat((Source * 1)(src(8, ptr=0x1004)), 1, Dims(1, 8, 2, 4, 4), out, None) == -3
+    # upsampled source with crop: 2*4 - 1 = 7 rows available from first = 1
+    assert L.tern_concat((Source * 1)(src(8, up=(1, 2, 2), first=(0, 1, 1))), 1, Dims(1, 8, 2, 8, 7), out, None) == -3
+
+    g = _geom(3, 1, 0, 1)
+    d = Dims(1, 8, 4, 4, 4)
+    p = C.c_void_p(fake)
+    assert L.tern_conv3d_real(None, d, p, None, 2, g, p, None) == -1
+    assert L.tern_conv3d_real(p, d, None, None, 2, g, p, None) == -1
+    assert L.tern_conv3d_real(p, d, p, None, 2, g, None, None) == -1
+    assert L.tern_conv3d_real(p, d, p, None, 0, g, p, None) == -2
+    assert L.tern_conv3d_real(p, Dims(1, 8, 2, 2, 2), p, None, 2, g, p, None) == -2     # kernel does not fit
+    assert L.tern_conv3d_real(p, d, C.c_void_p(0x1002), None, 2, g, p, None) == -3      # misaligned weights
+
+    w = np.arange(2 * 3 * 1 * 2 * 2, dtype=np.int8).reshape(2, 3, 1, 2, 2) % 3 - 1
+    f = T.tern_fold_avgpool(w, (1, 2, 3))
+    assert f.shape == (2, 3, 1, 4, 6)
+    for a in range(4):
+        for b in range(6):
+            assert (f[:, :, 0, a, b] == w[:, :, 0, a // 2, b // 3]).all()
+    with pytest.raises(T.TernError) as e:
+        T.tern_fold_avgpool(w, (1, 0, 1))
+    assert e.value.status == -3
+    with pytest.raises(T.TernError) as e:
+        T.tern_fold_avgpool(np.zeros((1, 1, 600, 1, 1), np.int8), (2, 1, 1))    # folded extent above 1024
+    assert e.value.status == -2
