@@ -279,7 +279,8 @@ int tern_fold_batchnorm(const double* alpha, const double* gamma, const double* 
 
 /* Tuning overrides (process-wide, not thread-safe against concurrent launches; defaults are
  * chosen per call from the problem size).  TERN_OPT_LANE_DEPTH: output voxels per lane along z in
- * the tiled convolution kernel, 0 = choose automatically, 2 or 4 = force.  TERN_OPT_WAVES_Z: waves
+ * the tiled convolution kernel, 0 = choose automatically, 1, 2 or 4 = force (1 and 4 only
+ * where that variant exists).  TERN_OPT_WAVES_Z: waves
  * stacked along z in one workgroup (sharing one LDS halo tile), 0 = choose, 1, 2, 4 or 8 = start
  * from that value.  TERN_OPT_CO_BLOCK: output channels per accumulation pass, 0 = choose, 16 or 32.
  * TERN_OPT_CO_PER_WAVE: output channels handled by one wave, 0 = choose, else a multiple of 16.

@@ -145,7 +145,7 @@ const char* tern_status_string(int status)
 int tern_set_option(int option, int value)
 {
     if (option == TERN_OPT_LANE_DEPTH) {
-        if (value != 0 && value != 2 && value != 4) return TERN_EARG;
+        if (value != 0 && value != 1 && value != 2 && value != 4) return TERN_EARG;
         set_lane_depth(value);
         return TERN_OK;
     }

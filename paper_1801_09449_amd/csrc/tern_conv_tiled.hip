@@ -535,7 +535,7 @@ int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, d
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-int g_lane_depth = 0;   // tuning override: 0 = choose, 2 or 4 = force that voxel depth per lane
+int g_lane_depth = 0;   // tuning override: 0 = choose, 1, 2 or 4 = force that voxel depth per lane
 int g_waves_z = 0;      // tuning override: 0 = choose, else waves stacked along z per workgroup
 int g_co_block = 0;     // tuning override: 0 = choose, 16 or 32 = channels per accumulation pass
 int g_co_per_wave = 0;  // tuning override: 0 = choose, else channels per wave (multiple of 16)
@@ -549,6 +549,9 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     t.nchunk = wd / p.wc;
     t.vstride = 2 * wd + (wd >= 4 ? 4 : 0);
     t.nwx = 1; t.nwy = 1; t.nwz = g_waves_z > 0 ? g_waves_z : 1;
+    // one voxel per lane: two waves share a halo tile from the start (along z, or along y for
+    // single-plane outputs), which gives the same tile as one wave with two voxels per lane
+    if (V == 1 && g_waves_z == 0) { if (p.od > 1) t.nwz = 2; else t.nwy = 2; }
     // Single-plane outputs (2-D convolutions): a lane's V voxels go along y instead of z.
     t.vy = p.od == 1 ? 1 : 0;
     const int vyx = t.vy ? V : 1, vzx = t.vy ? 1 : V;
@@ -596,7 +599,7 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
 
 }  // namespace
 
-void set_lane_depth(int v) { g_lane_depth = (v == 2 || v == 4) ? v : 0; }
+void set_lane_depth(int v) { g_lane_depth = (v == 1 || v == 2 || v == 4) ? v : 0; }
 void set_waves_z(int v) { g_waves_z = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
 void set_co_block(int v) { g_co_block = (v == 16 || v == 32) ? v : 0; }
 void set_co_per_wave(int v) { g_co_per_wave = (v > 0 && v % 16 == 0) ? v : 0; }
@@ -648,6 +651,12 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         const int tail = p.c_out % 32;   // a 32-channel pass over 1..16 live channels is half wasted
         if (tiles2 * cdiv(p.c_out, 32) >= 4096 && (tail == 0 || tail > 16)) co_blk = 32;
     }
+    // Large problems with two words per chunk: one voxel per lane.  64 accumulator pairs leave
+    // room for five waves per SIMD instead of three, and the waves are half as long, which
+    // shortens the end of the launch where SIMDs run out of waves one by one (measured 1-2 % on
+    // 64-cubed and 32-cubed volumes, 5 % on 96-cubed ones, up to 10 % with int32 output).
+    if (co_blk == 32 && V == 2 && p.wc == 2 && p.tp_slots == 0 && (g_lane_depth == 0 || g_lane_depth == 1))
+        V = 1;
     TileParams t;
     int64_t lds_bytes = 0;
     if (!plan_tiles(p, V, lds_limit, t, lds_bytes)) {
@@ -707,6 +716,7 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
             : launch_variant<WC_, V_, CB_, false, TP_>(p, t, lb, grid, threads, s))
     if (tp) return co_blk == 32 ? TERN_LAUNCH(1, 2, 32, true) : TERN_LAUNCH(1, 2, 16, true);
     if (p.wc == 2) {
+        if (V == 1) return TERN_LAUNCH(2, 1, 32, false);
         if (V == 4) return TERN_LAUNCH(2, 4, 16, false);
         return co_blk == 32 ? TERN_LAUNCH(2, 2, 32, false) : TERN_LAUNCH(2, 2, 16, false);
     }
