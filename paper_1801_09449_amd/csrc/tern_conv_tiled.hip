@@ -651,12 +651,18 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         const int tail = p.c_out % 32;   // a 32-channel pass over 1..16 live channels is half wasted
         if (tiles2 * cdiv(p.c_out, 32) >= 4096 && (tail == 0 || tail > 16)) co_blk = 32;
     }
-    // Large problems with two words per chunk: one voxel per lane.  64 accumulator pairs leave
-    // room for five waves per SIMD instead of three, and the waves are half as long, which
-    // shortens the end of the launch where SIMDs run out of waves one by one (measured 1-2 % on
-    // 64-cubed and 32-cubed volumes, 5 % on 96-cubed ones, up to 10 % with int32 output).
-    if (co_blk == 32 && V == 2 && p.wc == 2 && p.tp_slots == 0 && (g_lane_depth == 0 || g_lane_depth == 1))
-        V = 1;
+    // One voxel per lane where a wave still has enough steps to amortise its fixed cost (not
+    // the tap-packed layers, whose step set-up is per voxel): half the accumulators, so more
+    // waves fit a SIMD (five instead of three with 32 channels per pass), and waves half as
+    // long, which shortens the end of the launch where SIMDs run out of waves one by one.
+    // Measured against two voxels per lane: +1-2 % on 64- and 32-cubed volumes of 64-256
+    // channels, +5 % on 96-cubed ones, up to +10 % with int32 output, +30 % on 512-channel 2-D
+    // modules; -3 % with only 9 steps per wave, hence the step limit.
+    {
+        const bool exists = p.tp_slots == 0 && (p.wc == 2 || co_blk == 32);
+        const int steps = p.kd * p.kh * p.kw * (p.wd_in / p.wc);
+        if (V == 2 && exists && (g_lane_depth == 1 || (g_lane_depth == 0 && steps >= 16))) V = 1;
+    }
     TileParams t;
     int64_t lds_bytes = 0;
     if (!plan_tiles(p, V, lds_limit, t, lds_bytes)) {
@@ -716,11 +722,12 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
             : launch_variant<WC_, V_, CB_, false, TP_>(p, t, lb, grid, threads, s))
     if (tp) return co_blk == 32 ? TERN_LAUNCH(1, 2, 32, true) : TERN_LAUNCH(1, 2, 16, true);
     if (p.wc == 2) {
-        if (V == 1) return TERN_LAUNCH(2, 1, 32, false);
+        if (V == 1) return co_blk == 32 ? TERN_LAUNCH(2, 1, 32, false) : TERN_LAUNCH(2, 1, 16, false);
         if (V == 4) return TERN_LAUNCH(2, 4, 16, false);
         return co_blk == 32 ? TERN_LAUNCH(2, 2, 32, false) : TERN_LAUNCH(2, 2, 16, false);
     }
     if (V == 4) return TERN_LAUNCH(1, 4, 16, false);
+    if (V == 1) return TERN_LAUNCH(1, 1, 32, false);
     return co_blk == 32 ? TERN_LAUNCH(1, 2, 32, false) : TERN_LAUNCH(1, 2, 16, false);
 #undef TERN_LAUNCH
 }
