@@ -243,6 +243,17 @@ int tern_concat(const tern_source* srcs /* host */, int32_t n_src, tern_dims out
 int tern_conv3d_real(const uint32_t* in_packed, tern_dims in_dims, const float* w,
                      const float* bias, int32_t c_out, tern_conv_geom g, float* out,
                      void* stream);
+/*
+ * tern_count_codes -- per-channel statistics of a packed tensor (the paper discusses how sparse
+ * the ternary weights and activations are, section 4): nonzero[c] = number of voxels (over the
+ * whole batch) whose channel c is +1 or -1, negative[c] = number whose channel c is -1; the zero
+ * fraction of channel c is 1 - nonzero[c] / (N*D*H*W).  Both arrays: device, dims.c entries of
+ * uint64, 8-byte aligned, overwritten.  Sign bits under a clear mask bit are ignored.  Exact
+ * (integer atomics); works on filter tensors too when they are packed with tern_pack as
+ * {C_out, C_in, kd, kh, kw} (statistics then are per input channel).
+ */
+int tern_count_codes(const uint32_t* in_packed, tern_dims dims, uint64_t* nonzero, uint64_t* negative,
+                     void* stream);
 int tern_fold_avgpool(const int8_t* w /* host */, int32_t c_out, int32_t c_in, int32_t kd,
                       int32_t kh, int32_t kw, const int32_t pool[3], int8_t* w_out /* host */);
 

@@ -19,6 +19,7 @@ from .unet_oracle import (  # noqa: F401,E402
     centre_crop,
     concat_channels,
     conv3d_real,
+    count_codes,
     pool_sum,
     unet_forward,
     upsample_nearest,

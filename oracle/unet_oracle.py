@@ -88,6 +88,14 @@ def conv3d_real(act: np.ndarray, wgt: np.ndarray, bias, stride=(1, 1, 1), pad=(0
     return out
 
 
+def count_codes(x: np.ndarray):
+    """Per-channel counts over batch and space of nonzero codes and of -1 codes of an integer
+    tensor [N][C][...] (the zero fraction the paper discusses in section 4 is
+    1 - nonzero / voxels).  Returns two int64 arrays [C]."""
+    axes = (0,) + tuple(range(2, x.ndim))
+    return (x != 0).sum(axis=axes).astype(np.int64), (x < 0).sum(axis=axes).astype(np.int64)
+
+
 def unet_forward(x, in_lo, in_hi, layers, head_w, head_b):
     """The U-Net of Table 1 on unpacked tensors, module by module.
 

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     lib_path,
     tern_concat,
     tern_conv3d,
+    tern_count_codes,
     tern_conv3d_real,
     tern_fold_avgpool,
     tern_conv_out_dims,

@@ -82,6 +82,7 @@ def lib():
     L.tern_fold_batchnorm.restype = C.c_int
     L.tern_concat.argtypes = [C.POINTER(Source), I, Dims, P, P]; L.tern_concat.restype = C.c_int
     L.tern_conv3d_real.argtypes = [P, Dims, P, P, I, Geom, P, P]; L.tern_conv3d_real.restype = C.c_int
+    L.tern_count_codes.argtypes = [P, Dims, P, P, P]; L.tern_count_codes.restype = C.c_int
     L.tern_fold_avgpool.argtypes = [P, I, I, I, I, I, C.POINTER(C.c_int32), P]
     L.tern_fold_avgpool.restype = C.c_int
     L.tern_set_option.argtypes = [C.c_int, C.c_int]; L.tern_set_option.restype = C.c_int
@@ -434,6 +435,16 @@ def tern_conv3d_real(in_packed: torch.Tensor, c_in: int, w: torch.Tensor,
                                   _geom(k, stride, pad, dil), _ptr(out), _stream(out)),
            "tern_conv3d_real")
     return out
+
+
+def tern_count_codes(in_packed: torch.Tensor, c: int):
+    """Per-channel (nonzero, negative) voxel counts of a packed tensor, two int64 tensors [C]."""
+    dims = _logical_dims(in_packed, c)
+    nz = torch.empty((c,), dtype=torch.int64, device=in_packed.device)
+    ng = torch.empty((c,), dtype=torch.int64, device=in_packed.device)
+    _check(lib().tern_count_codes(_ptr(in_packed), _dims(dims), _ptr(nz), _ptr(ng), _stream(in_packed)),
+           "tern_count_codes")
+    return nz, ng
 
 
 # ---- host-side model preparation (numpy arrays in, numpy arrays out; no GPU involved) ----------

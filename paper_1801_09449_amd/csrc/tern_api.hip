@@ -298,6 +298,16 @@ int tern_conv3d_real(const uint32_t* in_packed, tern_dims in_dims, const float* 
     return launch_real_conv(p, (hipStream_t)stream);
 }
 
+int tern_count_codes(const uint32_t* in_packed, tern_dims dims, uint64_t* nonzero, uint64_t* negative,
+                     void* stream)
+{
+    if (!in_packed || !nonzero || !negative) return TERN_ENULL;
+    if (!sizes_ok(dims)) return TERN_ESHAPE;
+    if (!aligned16(in_packed) || ((uintptr_t)nonzero & 7u) || ((uintptr_t)negative & 7u)) return TERN_EARG;
+    return launch_count_codes(in_packed, voxels(dims), dims.c, (unsigned long long*)nonzero,
+                              (unsigned long long*)negative, (hipStream_t)stream);
+}
+
 // Walks the chain once: validates channel continuity and geometry, and reports the packed size
 // of the input and of every layer output.  Returns TERN_OK or the first error.
 static int fcn_plan(tern_dims in_dims, const tern_layer* layers, int32_t n_layers,

@@ -119,6 +119,8 @@ bool conv_point_applies(const ConvParams& p);
 int launch_conv_point(const ConvParams& p, hipStream_t s);
 int launch_concat(const ConcatParams& p, hipStream_t s);
 int launch_real_conv(const RealConvParams& p, hipStream_t s);
+int launch_count_codes(const uint32_t* in, int64_t voxels, int32_t c, unsigned long long* nonzero,
+                       unsigned long long* negative, hipStream_t s);
 void set_lane_depth(int v);
 void set_waves_z(int v);
 void set_co_block(int v);

@@ -130,7 +130,62 @@ __global__ __launch_bounds__(kBlock) void real_conv_kernel(RealConvParams p)
     }
 }
 
+// Per-channel code statistics of a packed tensor (the paper reports how sparse weights and
+// activations become, section 4).  A wave takes 64 voxels at a time; for every channel bit the
+// wave-wide vote of "this voxel's bit is set" is counted, lane j keeping the running nonzero
+// count of channel 32q + j and lane 32 + j the count of its -1 codes.  One atomic add per
+// (wave, channel) at the end.
+__global__ __launch_bounds__(kBlock) void count_codes_kernel(const uint32_t* __restrict__ in, int64_t voxels,
+                                                             int32_t wd, int32_t c,
+                                                             unsigned long long* __restrict__ nonzero,
+                                                             unsigned long long* __restrict__ negative)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> 6;
+    const int64_t nwaves = ((int64_t)gridDim.x * kBlock) >> 6;
+    for (int q = 0; q < wd; ++q) {
+        unsigned long long mine = 0ull;
+        for (int64_t v0 = wave * 64; v0 < voxels; v0 += nwaves * 64) {
+            const int64_t vox = v0 + lane;
+            uint32_t m = 0u, sg = 0u;
+            if (vox < voxels) {
+                m = in[(size_t)vox * 2u * wd + q];
+                sg = in[(size_t)vox * 2u * wd + wd + q] & m;
+            }
+            for (int j = 0; j < 32; ++j) {
+                const unsigned long long vm = __ballot((m >> j) & 1u);
+                const unsigned long long vs = __ballot((sg >> j) & 1u);
+                if (lane == j) mine += (unsigned long long)__popcll(vm);
+                if (lane == 32 + j) mine += (unsigned long long)__popcll(vs);
+            }
+        }
+        const int ch = 32 * q + (lane & 31);
+        if (ch < c && mine != 0ull) atomicAdd(lane < 32 ? &nonzero[ch] : &negative[ch], mine);
+    }
+}
+
+__global__ void zero_counts_kernel(unsigned long long* a, unsigned long long* b, int32_t c)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < c) { a[i] = 0ull; b[i] = 0ull; }
+}
+
 }  // namespace
+
+int launch_count_codes(const uint32_t* in, int64_t voxels, int32_t c, unsigned long long* nonzero,
+                       unsigned long long* negative, hipStream_t s)
+{
+    // a small fill kernel rather than a memset, so that the call can be captured into a graph
+    hipLaunchKernelGGL(zero_counts_kernel, dim3((unsigned)((c + 255) / 256)), dim3(256), 0, s, nonzero, negative, c);
+    TERN_HIP_CHECK(hipGetLastError());
+    const int wd = (c + 31) / 32;
+    int64_t blocks = (voxels + kBlock - 1) / kBlock;
+    if (blocks > 2048) blocks = 2048;      // grid-stride: a few waves per SIMD, few atomics
+    hipLaunchKernelGGL(count_codes_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, s, in, voxels, wd, c, nonzero,
+                       negative);
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
 
 int launch_concat(const ConcatParams& p, hipStream_t s)
 {

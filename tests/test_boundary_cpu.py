@@ -173,6 +173,11 @@ def test_unet_entry_points_reject_bad_arguments(T):
     assert L.tern_conv3d_real(p, Dims(1, 8, 2, 2, 2), p, None, 2, g, p, None) == -2     # kernel does not fit
     assert L.tern_conv3d_real(p, d, C.c_void_p(0x1002), None, 2, g, p, None) == -3      # misaligned weights
 
+    assert L.tern_count_codes(None, d, p, p, None) == -1
+    assert L.tern_count_codes(p, d, None, p, None) == -1
+    assert L.tern_count_codes(p, Dims(1, 0, 4, 4, 4), p, p, None) == -2
+    assert L.tern_count_codes(p, d, C.c_void_p(0x1004), p, None) == -3          # counters need 8-byte alignment
+
     w = np.arange(2 * 3 * 1 * 2 * 2, dtype=np.int8).reshape(2, 3, 1, 2, 2) % 3 - 1
     f = T.tern_fold_avgpool(w, (1, 2, 3))
     assert f.shape == (2, 3, 1, 4, 6)

@@ -174,6 +174,32 @@ def test_conv3d_real(G, ci, co, vol, k, stride, pad, dil):
     np.testing.assert_array_equal(goti, exact.astype(np.float32))
 
 
+# ---- code statistics ---------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,c,vol", [(1, 1, (1, 1, 1)), (2, 5, (3, 5, 7)), (1, 33, (4, 9, 11)), (3, 64, (2, 8, 8)),
+                                     (1, 100, (5, 13, 6)), (2, 256, (3, 4, 5)), (1, 16, (40, 64, 70))])
+def test_count_codes(G, n, c, vol):
+    import paper_1801_09449_amd as T
+    x = tern((n, c) + vol, 71, p0=0.45)
+    nz, ng = T.tern_count_codes(gpu_pack(G, x), c)
+    want_nz, want_ng = oracle.count_codes(x)
+    np.testing.assert_array_equal(nz.cpu().numpy(), want_nz)
+    np.testing.assert_array_equal(ng.cpu().numpy(), want_ng)
+
+
+def test_count_codes_ignores_sign_under_clear_mask_and_repeats(G):
+    import torch
+    import paper_1801_09449_amd as T
+    x = tern((1, 40, 3, 6, 5), 72)
+    p = gpu_pack(G, x).clone()
+    p[..., 1, :] = -1                      # every sign bit set, also under clear mask bits
+    want_nz, _ = oracle.count_codes(x)
+    for _ in range(2):                     # the call overwrites its outputs: same answer twice
+        nz, ng = T.tern_count_codes(p, 40)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(nz.cpu().numpy(), want_nz)
+        np.testing.assert_array_equal(ng.cpu().numpy(), want_nz)     # every nonzero now reads as -1
+
+
 # ---- the whole network -----------------------------------------------------------------------------
 def run_unet(G, u):
     import torch
@@ -181,15 +207,22 @@ def run_unet(G, u):
     plan = unet.UNetPlan(u.layers, u.head_w, u.head_b, u.in_lo, u.in_hi)
     pred, kept = unet.unet_forward(plan, G.dev(u.x), keep_layers=True)
     torch.cuda.synchronize()
-    return pred.cpu().numpy(), [G.words(t) for t, _ in kept]
+    return pred.cpu().numpy(), [G.words(t) for t, _ in kept], kept
 
 
 def check_unet(G, u):
-    pred, kept = run_unet(G, u)
+    pred, kept, kept_dev = run_unet(G, u)
     codes, want_pred = oracle.unet_forward(u.x, u.in_lo, u.in_hi, u.layers, u.head_w, u.head_b)
     assert len(kept) == len(codes) == 14
     for li, (got, want) in enumerate(zip(kept, codes), start=1):
         np.testing.assert_array_equal(got, oracle.pack(want), err_msg=f"module #{li}")
+    # zero fraction per module from the library's statistics = the oracle's
+    import paper_1801_09449_amd as T
+    for (t, c), want in zip(kept_dev, codes):
+        nz, ng = T.tern_count_codes(t, c)
+        want_nz, want_ng = oracle.count_codes(want)
+        np.testing.assert_array_equal(nz.cpu().numpy(), want_nz)
+        np.testing.assert_array_equal(ng.cpu().numpy(), want_ng)
     bound = real_conv_bound(u.head_w, u.head_b)[None, :, None, None, None]
     assert pred.shape == want_pred.shape
     assert (np.abs(pred.astype(np.float64) - want_pred) <= bound).all()

@@ -114,6 +114,21 @@ def test_pool_then_conv_equals_strided_conv_with_repeated_taps(vol, k, pool, pad
     np.testing.assert_array_equal(T.tern_fold_avgpool(w, pool), rep)
 
 
+def test_count_codes_hand_example():
+    x = np.array([[[1, 0, -1], [0, 0, -1]], [[-1, 1, 1], [0, -1, 0]]], np.int8).reshape(2, 2, 1, 1, 3)
+    nz, ng = oracle.count_codes(x)
+    # channel 0: items (1,0,-1) and (-1,1,1); channel 1: (0,0,-1) and (0,-1,0)
+    np.testing.assert_array_equal(nz, [5, 2])
+    np.testing.assert_array_equal(ng, [2, 2])
+    x = rnd_tern((3, 5, 4, 6, 7), 9, p0=0.4)
+    nz, ng = oracle.count_codes(x)
+    for c in range(5):
+        assert nz[c] == sum(int(v != 0) for v in x[:, c].reshape(-1))
+        assert ng[c] == sum(int(v < 0) for v in x[:, c].reshape(-1))
+    # the generator's zero fraction shows up
+    assert abs(1 - nz.sum() / x.size - 0.4) < 0.03
+
+
 def test_unet_chain_shapes_follow_valid_arithmetic():
     u = synth.unet_table1(seed=3, width_div=16, size=(76, 68), slices=5)
     codes, pred = oracle.unet_forward(u.x, u.in_lo, u.in_hi, u.layers, u.head_w, u.head_b)
