@@ -23,6 +23,9 @@ struct Vec {
         } else if constexpr (sizeof(T) * VPT == 4) {
             uint32_t raw = *reinterpret_cast<const uint32_t*>(p);
             __builtin_memcpy(v, &raw, 4);
+        } else if constexpr (sizeof(T) * VPT == 8) {
+            uint2 raw = *reinterpret_cast<const uint2*>(p);
+            __builtin_memcpy(v, &raw, 8);
         } else {
             static_assert(sizeof(T) * VPT == 16, "unsupported vector width");
             uint4 raw = *reinterpret_cast<const uint4*>(p);
@@ -52,6 +55,82 @@ __device__ __forceinline__ void classify(const Vec<T, VPT>& x, T tl, T th, int j
     }
 }
 
+// int8 fast path.  A 32-bit word holds one channel's values of four consecutive voxels.  Per byte,
+// "nonzero" and "negative" are single bits (any bit set / bit 7), so eight channels of four voxels
+// are classified with a few word-wide operations each: flag bits land at bit 0 of every byte and
+// are shifted to bit j of the byte for channel j of the octet.  The result has voxel i's eight
+// channel bits in byte i; four octets are then transposed into the voxels' 32-channel words.
+__device__ __forceinline__ void classify_octet(const uint32_t (&w)[8], int live, uint32_t& tm, uint32_t& ts)
+{
+    tm = ts = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t x = j < live ? w[j] : 0u;
+        const uint32_t any = ((x & 0x7f7f7f7fu) + 0x7f7f7f7fu) | x;   // bit 7 of a byte: byte != 0
+        tm |= ((any >> 7) & 0x01010101u) << j;
+        ts |= ((x >> 7) & 0x01010101u) << j;
+    }
+}
+
+// byte i of t[0], t[1], t[2], t[3] -> one word (t[g] = channel octet g)
+__device__ __forceinline__ uint32_t byte_column(const uint32_t (&t)[4], int i)
+{
+    const uint32_t sel = (uint32_t)i | ((uint32_t)(4 + i) << 8) | 0x0c0c0000u;   // 0x0c selects a zero byte
+    const uint32_t lo = __builtin_amdgcn_perm(t[1], t[0], sel);
+    const uint32_t hi = __builtin_amdgcn_perm(t[3], t[2], sel);
+    return lo | (hi << 16);
+}
+
+// One 32-channel word group of VPT voxels from int8 data: channels c0 .. c0+31 (those >= C read
+// a valid address and are masked out).  NW = VPT / 4 words of voxels per channel.
+template <int VPT>
+__device__ __forceinline__ void pack_group_i8(const int8_t* base, int64_t spatial, int c0, int C,
+                                              uint32_t (&m)[VPT], uint32_t (&s)[VPT])
+{
+    constexpr int NW = VPT / 4;
+    uint32_t tm[NW][4], ts[NW][4];
+    if constexpr (NW == 1) {
+        // all 32 channel loads in flight at once (128 bytes per lane)
+        uint32_t w[4][8];
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int c = min(c0 + 8 * g + j, C - 1);
+                w[g][j] = *reinterpret_cast<const uint32_t*>(base + (size_t)c * spatial);
+            }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) classify_octet(w[g], C - (c0 + 8 * g), tm[0][g], ts[0][g]);
+    } else {
+        // 16-byte loads: one octet of channels at a time (128 bytes per lane in flight)
+        static_assert(NW == 4, "4 or 16 voxels per thread");
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t r[8][NW];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int c = min(c0 + 8 * g + j, C - 1);
+                const uint4 v = *reinterpret_cast<const uint4*>(base + (size_t)c * spatial);
+                r[j][0] = v.x; r[j][1] = v.y; r[j][2] = v.z; r[j][3] = v.w;
+            }
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                uint32_t w[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) w[j] = r[j][k];
+                classify_octet(w, C - (c0 + 8 * g), tm[k][g], ts[k][g]);
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < NW; ++k)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            m[4 * k + i] = byte_column(tm[k], i);
+            s[4 * k + i] = byte_column(ts[k], i);
+        }
+}
+
 // MODE 0: int8 ternary input.  MODE 1: thresholds (T = int32_t or float).
 // WDT > 0: Wd is the compile-time constant WDT, all words of the VPT voxels stay in registers and
 // every voxel is written with 16-byte stores (a thread writes VPT * 8 * Wd contiguous bytes).
@@ -77,7 +156,10 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const T* __restrict__ src,
 #pragma unroll
             for (int i = 0; i < VPT; ++i) m[q][i] = s[q][i] = 0u;
             const int cbase = 32 * q;
-            if (cbase + 32 <= C) {
+            if constexpr (MODE == 0 && sizeof(T) == 1 && VPT % 4 == 0) {
+                if (cbase < C)
+                    pack_group_i8<VPT>(reinterpret_cast<const int8_t*>(base), spatial, cbase, C, m[q], s[q]);
+            } else if (cbase + 32 <= C) {
                 // full word: batches of independent loads, at least 128 bytes in flight per lane
                 constexpr int B = (sizeof(T) * VPT >= 16) ? 8 : 32;
 #pragma unroll
@@ -126,11 +208,19 @@ __global__ __launch_bounds__(kBlock) void pack_kernel(const T* __restrict__ src,
         }
     } else {
         uint32_t* out = dst + ((size_t)n * spatial + v0) * 2u * Wd;
-        for (int q = 0; q < Wd; ++q) {
+        // blockIdx.y selects a slice of the channel words (one slice = all words, unless the
+        // launch split them to get more threads out of a small volume with many channels)
+        const int q_per_slice = (Wd + (int)gridDim.y - 1) / (int)gridDim.y;
+        const int q_begin = blockIdx.y * q_per_slice;
+        const int q_end = min(Wd, q_begin + q_per_slice);
+        for (int q = q_begin; q < q_end; ++q) {
             uint32_t m[VPT], s[VPT];
 #pragma unroll
             for (int i = 0; i < VPT; ++i) m[i] = s[i] = 0u;
             const int cmax = min(32, C - 32 * q);
+            if constexpr (MODE == 0 && sizeof(T) == 1 && VPT % 4 == 0)
+                pack_group_i8<VPT>(reinterpret_cast<const int8_t*>(base), spatial, 32 * q, C, m, s);
+            else
 #pragma unroll 8
             for (int j = 0; j < cmax; ++j) {
                 const int c = 32 * q + j;
@@ -167,7 +257,10 @@ int launch_pack_any(const T* src, tern_dims dims, const T* lo, const T* hi, uint
     const int64_t total = gpn * dims.n;
     const int64_t blocks = (total + kBlock - 1) / kBlock;
     if (blocks > 0x7fffffff) return TERN_ESHAPE;
-    const dim3 grid((unsigned)blocks), block(kBlock);
+    // Few voxels but many channels (e.g. 256 channels on 32-cubed): one thread per channel word
+    // instead of one per voxel group, through the word-by-word variant.
+    const bool split_words = vpt == 4 && Wd >= 4 && total < (int64_t)1024 * 64;
+    const dim3 grid((unsigned)blocks, split_words ? (unsigned)Wd : 1u), block(kBlock);
 #define TERN_PACK_LAUNCH(VPT_, WDT_)                                                              \
     hipLaunchKernelGGL((pack_kernel<T, VPT_, MODE, WDT_>), grid, block, 0, s, src, dst, lo, hi, dims.c, \
                        Wd, spatial, gpn, total)
@@ -181,6 +274,8 @@ int launch_pack_any(const T* src, tern_dims dims, const T* lo, const T* hi, uint
                     default: TERN_PACK_LAUNCH(16, 0); break;
                 }
             }
+        } else if (split_words) {
+            TERN_PACK_LAUNCH(4, 0);
         } else {
             switch (Wd) {
                 case 1: TERN_PACK_LAUNCH(4, 1); break;
