@@ -20,7 +20,7 @@
  *
  * Unpacked tensors are contiguous NCDHW (W fastest).
  *
- * Packed ternary tensors ("bit-planes packed along channels", Fig. 3 / section 2):
+ * Packed ternary tensors (two bit-planes packed along the channel axis, Fig. 3 / section 2):
  *     uint32 [N][D][H][W][2][Wd],   Wd = tern_words(C) = ceil(C/32)
  *   plane 0 = nonzero mask, plane 1 = sign.  Bit j of word q describes channel 32q + j:
  *     value +1 -> mask 1, sign 0;   value -1 -> mask 1, sign 1;   value 0 -> mask 0, sign 0.
@@ -91,8 +91,8 @@ int tern_last_hip_error(void);
 const char* tern_status_string(int status);
 
 /*
- * tern_pack -- 2-bit encoding of a ternary tensor (Fig. 3; section 2: "store ternary tensors
- * using 2 bits per entry").
+ * tern_pack -- 2-bit encoding of a ternary tensor (Fig. 3; section 2: two bits per entry, one
+ * for the value, one for the sign).
  *   src        : int8 values in {-1, 0, +1}, contiguous [N][C][D][H][W].  Other values are not
  *                detected: a nonzero byte sets the mask bit and a negative one the sign bit.
  *   dst_packed : packed layout described above, tern_packed_bytes(dims) bytes.

@@ -4,7 +4,7 @@ Two small definitions from the paper, written out plainly in float64 numpy:
 
 * ternary weights (Eq. 4): Delta = 0.7/n * sum|W_i|;  W~_i = +1 if W_i > Delta, 0 if |W_i| <= Delta,
   -1 otherwise;  alpha = (sum over nonzero W~ of |W_i|) / n_Delta.  Taken per output filter: the
-  paper stores "one scalar weighting value per feature channel" (section 2, last paragraph).
+  paper keeps a single full-precision scale per feature channel (section 2, last paragraph).
 * the activation of Eq. 6 applied to y = a*acc + b, where a and b collect the weight scale alpha
   and the batch-norm affine (section 2: batch-norm sits between the ternary convolution and the
   activation):  code(acc) = +1 if y > 0.5, 0 if |y| <= 0.5, -1 otherwise, evaluated in float64.
