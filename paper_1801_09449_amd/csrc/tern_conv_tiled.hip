@@ -16,6 +16,8 @@
 //   - Epilogue: acc = M-count - 2 * N-count; either stored as int32 (NCDHW) or compared with the
 //     per-channel cut points (Eq. 6 in integer form) and assembled into mask/sign words in-lane,
 //     so that activations go back to memory at 2 bits per value.
+#include <cmath>
+
 #include "tern_conv_common.h"
 #include "tern_internal.h"
 
@@ -642,15 +644,6 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     //   V=4, CO_BLK=16:  half the scalar-cache traffic per instruction (tuning option only).
     // Waves of 32 channels are used when that still gives every SIMD about four of them;
     // smaller problems are cut into 16-channel waves.
-    int V = 2, co_blk = 16;
-    if (g_lane_depth == 4 && p.tp_slots == 0) { V = 4; co_blk = 16; }
-    else if (g_co_block == 32) { V = 2; co_blk = 32; }
-    else if (g_co_block == 0) {
-        const int64_t tiles2 = p.od == 1 ? (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 16) * p.n
-                                         : (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, 2) * p.n;
-        const int tail = p.c_out % 32;   // a 32-channel pass over 1..16 live channels is half wasted
-        if (tiles2 * cdiv(p.c_out, 32) >= 4096 && (tail == 0 || tail > 16)) co_blk = 32;
-    }
     // One voxel per lane where a wave still has enough steps to amortise its fixed cost (not
     // the tap-packed layers, whose step set-up is per voxel): half the accumulators, so more
     // waves fit a SIMD (five instead of three with 32 channels per pass), and waves half as
@@ -658,11 +651,46 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     // Measured against two voxels per lane: +1-2 % on 64- and 32-cubed volumes of 64-256
     // channels, +5 % on 96-cubed ones, up to +10 % with int32 output, +30 % on 512-channel 2-D
     // modules; -3 % with only 9 steps per wave, hence the step limit.
-    {
-        const bool exists = p.tp_slots == 0 && (p.wc == 2 || co_blk == 32);
-        const int steps = p.kd * p.kh * p.kw * (p.wd_in / p.wc);
-        if (V == 2 && exists && (g_lane_depth == 1 || (g_lane_depth == 0 && steps >= 16))) V = 1;
+    const int steps_all = p.kd * p.kh * p.kw * (p.wd_in / p.wc);
+    auto lane_depth_for = [&](int cb) {
+        const bool exists = p.tp_slots == 0 && (p.wc == 2 || cb == 32);
+        return (exists && (g_lane_depth == 1 || (g_lane_depth == 0 && steps_all >= 16))) ? 1 : 2;
+    };
+    // Estimated launch time in vector instructions of the busiest SIMD, for cb channels per pass:
+    // workgroups are dealt to the 256 compute units whole, a workgroup puts (its waves / 4) on
+    // every SIMD, and a wave costs its contraction, its epilogue and about 560 fixed instructions.
+    auto estimate = [&](int cb) -> double {
+        const int v = lane_depth_for(cb);
+        TileParams q;
+        int64_t bytes = 0;
+        if (!plan_tiles(p, v, lds_limit, q, bytes)) return 1e300;
+        const int nsp = q.nwx * q.nwy * q.nwz;
+        const int slices = cdiv(p.c_out, cb);
+        int nwc = 8 / nsp;
+        if (nwc > slices) nwc = slices;
+        if (nwc < 1) nwc = 1;
+        const double wgs = (double)q.tiles_x * q.tiles_y * q.tiles_z * p.n * cdiv(slices, nwc);
+        const double per_simd = (nsp * nwc + 3) / 4;
+        const double per_wave = (double)steps_all * cb * p.wc * v * 4 + 5.0 * v * cb + 560.0;
+        return std::ceil(wgs / 256.0) * per_simd * per_wave;
+    };
+    int V = 2, co_blk = 16;
+    if (g_lane_depth == 4 && p.tp_slots == 0) { V = 4; co_blk = 16; }
+    else if (g_co_block == 32) { V = 2; co_blk = 32; }
+    else if (g_co_block == 0) {
+        const int64_t tiles2 = p.od == 1 ? (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 16) * p.n
+                                         : (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, 2) * p.n;
+        const int tail = p.c_out % 32;   // a 32-channel pass over 1..16 live channels is half wasted
+        const int64_t units = tiles2 * cdiv(p.c_out, 32);
+        // large launches: 32 channels per pass (half the passes over the LDS tile, half the fixed
+        // cost); tiny ones: 16 (they need every wave they can get and split the taps besides);
+        // in between the two differ in how evenly the workgroups fill the chip: estimate both
+        if (tail == 0 || tail > 16) {
+            if (units >= 4096) co_blk = 32;
+            else if (units >= 512 && p.tp_slots == 0 && estimate(32) < estimate(16)) co_blk = 32;
+        }
     }
+    if (V == 2) V = lane_depth_for(co_blk);
     TileParams t;
     int64_t lds_bytes = 0;
     if (!plan_tiles(p, V, lds_limit, t, lds_bytes)) {
