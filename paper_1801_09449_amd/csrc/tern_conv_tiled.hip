@@ -656,24 +656,29 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         const bool exists = p.tp_slots == 0 && (p.wc == 2 || cb == 32);
         return (exists && (g_lane_depth == 1 || (g_lane_depth == 0 && steps_all >= 16))) ? 1 : 2;
     };
-    // Estimated launch time in vector instructions of the busiest SIMD, for cb channels per pass:
-    // workgroups are dealt to the 256 compute units whole, a workgroup puts (its waves / 4) on
-    // every SIMD, and a wave costs its contraction, its epilogue and about 560 fixed instructions.
-    auto estimate = [&](int cb) -> double {
+    // Estimated launch time in vector instructions of the busiest SIMD, for cb channels per pass
+    // and the kernel taps split over ks waves: workgroups are dealt to the 256 compute units
+    // whole, a workgroup puts (its waves / 4) on every SIMD, and a wave costs its share of the
+    // contraction, its epilogue, about 560 fixed instructions and, with split taps, the exchange
+    // of partial sums.
+    auto estimate = [&](int cb, int ks) -> double {
         const int v = lane_depth_for(cb);
         TileParams q;
         int64_t bytes = 0;
         if (!plan_tiles(p, v, lds_limit, q, bytes)) return 1e300;
         const int nsp = q.nwx * q.nwy * q.nwz;
+        if (nsp * ks > 8 || steps_all < 4 * ks) return 1e300;
         const int slices = cdiv(p.c_out, cb);
-        int nwc = 8 / nsp;
+        int nwc = 8 / (nsp * ks);
         if (nwc > slices) nwc = slices;
         if (nwc < 1) nwc = 1;
         const double wgs = (double)q.tiles_x * q.tiles_y * q.tiles_z * p.n * cdiv(slices, nwc);
-        const double per_simd = (nsp * nwc + 3) / 4;
-        const double per_wave = (double)steps_all * cb * p.wc * v * 4 + 5.0 * v * cb + 560.0;
+        const double per_simd = (nsp * nwc * ks + 3) / 4;
+        const double per_wave = (double)steps_all / ks * cb * p.wc * v * 4 + 5.0 * v * cb + 560.0 +
+                                (ks > 1 ? 2.0 * (ks - 1) * v * cb + 300.0 : 0.0);
         return std::ceil(wgs / 256.0) * per_simd * per_wave;
     };
+    int nks_pref = 0;   // tap split chosen together with the pass width (0: decided further down)
     int V = 2, co_blk = 16;
     if (g_lane_depth == 4 && p.tp_slots == 0) { V = 4; co_blk = 16; }
     else if (g_co_block == 32) { V = 2; co_blk = 32; }
@@ -685,9 +690,18 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         // large launches: 32 channels per pass (half the passes over the LDS tile, half the fixed
         // cost); tiny ones: 16 (they need every wave they can get and split the taps besides);
         // in between the two differ in how evenly the workgroups fill the chip: estimate both
-        if (tail == 0 || tail > 16) {
-            if (units >= 4096) co_blk = 32;
-            else if (units >= 512 && p.tp_slots == 0 && estimate(32) < estimate(16)) co_blk = 32;
+        if (units >= 4096) {
+            if (tail == 0 || tail > 16) co_blk = 32;
+        } else if (units >= 512 && p.tp_slots == 0) {
+            double best = 1e300;
+            for (int cb = 16; cb <= 32; cb += 16) {
+                if (cb == 32 && !(tail == 0 || tail > 16)) continue;
+                for (int ks = 1; ks <= 2; ++ks) {
+                    if (g_tap_split > 0 && ks != g_tap_split) continue;
+                    const double e = estimate(cb, ks);
+                    if (e < best) { best = e; co_blk = cb; nks_pref = ks; }
+                }
+            }
         }
     }
     if (V == 2) V = lane_depth_for(co_blk);
@@ -717,6 +731,7 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     const int nsteps = tp ? cdiv(T, p.tp_slots) : T * t.nchunk;
     int nks = 1;
     if (g_tap_split > 0) nks = g_tap_split;
+    else if (nks_pref > 0) nks = nks_pref;
     else {
         const int64_t waves0 = spatial_tiles * nsp * slices;
         while (nks * 2 * nsp <= 8 && waves0 * nks < 2048 && nsteps >= 4 * nks) nks *= 2;
