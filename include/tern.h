@@ -244,6 +244,49 @@ int tern_conv3d_real(const uint32_t* in_packed, tern_dims in_dims, const float* 
                      const float* bias, int32_t c_out, tern_conv_geom g, float* out,
                      void* stream);
 /*
+ * tern_net_forward -- a network of ternary modules with skip connections (the baseline U-Net of
+ * section 3 / Table 1, or any encoder-decoder of that kind), run as one call: Eq. 6 on the float
+ * input, then for every module, in order, [nearest upsampling of the incoming tensor and
+ * appending of an earlier module's centre-cropped output, via the tern_concat kernel] and a
+ * fused tern_conv3d; optionally a float-weight prediction layer (tern_conv3d_real) on the last
+ * module's output.  Average pooling is expressed through the module's filters and stride
+ * (tern_fold_avgpool).  A chain without skips and upsampling is what tern_fcn_forward runs.
+ *   mods       : host array; module i reads the output of module i-1 (the packed input for
+ *                i = 0), upsampled by up[] when any factor is > 1, followed channel-wise by the
+ *                output of module skip_from (-1 = none; must be < i), centre-cropped to the
+ *                (upsampled) incoming extent: first voxel floor((X_skip - X)/2) per axis, which
+ *                must not be negative.  w_bank holds filters for that total channel count.
+ *   head_w     : float [head_c_out][C_last][k] on the device, NULL = no prediction layer (then
+ *                head_b, head_out are ignored); head_b may be NULL; head_out receives
+ *                [N][head_c_out][Do][Ho][Wo] floats, head_dims (host, optional) its extents.
+ *   workspace  : device scratch of at least tern_net_workspace_bytes() bytes, 16-byte aligned;
+ *                holds the packed input, every module's output and every concatenated tensor,
+ *                each in a region of its own (nothing is overwritten within a call).
+ *   module_out / module_dims : optional host arrays of n_mods entries that receive the device
+ *                address (inside workspace) and logical extents of every module's packed output.
+ * Errors as for the calls it is made of; TERN_EARG for an invalid skip_from or crop,
+ * TERN_EWORKSPACE for a workspace that is too small or misaligned.  Everything is enqueued on
+ * `stream` in order; no host synchronisation.
+ */
+typedef struct {
+    int32_t c_out;
+    tern_conv_geom g;
+    const uint32_t* w_bank;
+    const int32_t* thr_lo;
+    const int32_t* thr_hi;
+    int32_t skip_from;
+    int32_t up[3];
+} tern_module;
+size_t tern_net_workspace_bytes(tern_dims in_dims, const tern_module* mods /* host */, int32_t n_mods);
+int tern_net_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
+                     const tern_module* mods /* host */, int32_t n_mods,
+                     const float* head_w, const float* head_b, int32_t head_c_out, tern_conv_geom head_g,
+                     void* workspace, size_t workspace_bytes,
+                     float* head_out, tern_dims* head_dims /* host, optional */,
+                     uint32_t** module_out /* host, optional */, tern_dims* module_dims /* host, optional */,
+                     void* stream);
+
+/*
  * tern_count_codes -- per-channel statistics of a packed tensor (the paper discusses how sparse
  * the ternary weights and activations are, section 4): nonzero[c] = number of voxels (over the
  * whole batch) whose channel c is +1 or -1, negative[c] = number whose channel c is -1; the zero

@@ -100,8 +100,8 @@ def unet_forward(x, in_lo, in_hi, layers, head_w, head_b):
     """The U-Net of Table 1 on unpacked tensors, module by module.
 
     x: float32 intensities, ternarised at (in_lo, in_hi) (Eq. 6).  layers: dicts as described by
-    the synthetic recipe (w, lo, hi, pool, concat, up, save).  Every convolution is the integer
-    oracle's, valid (no padding), stride 1, and runs on the pooled sums where a pooling window is
+    the synthetic recipe (w, k, lo, hi, pool, up, concat, save; optional stride/pad, default 1/0).  Every convolution is the integer
+    oracle's (valid and stride 1 unless the layer says otherwise) and runs on the pooled sums where a pooling window is
     given.  Returns (list of per-module int8 codes, float64 prediction maps)."""
     from .tern_oracle import ConvGeom as geom, conv3d, threshold
     cur = threshold(np.ascontiguousarray(x, dtype=np.float32), in_lo, in_hi)
@@ -109,12 +109,14 @@ def unet_forward(x, in_lo, in_hi, layers, head_w, head_b):
     for L in layers:
         if L.get("pool"):
             cur = pool_sum(cur, L["pool"])
-        if L.get("concat"):
+        if L.get("up"):
             cur = upsample_nearest(cur, L["up"])
+        if L.get("concat"):
             cur = concat_channels([cur, centre_crop(saved[L["concat"]], cur.shape[2:])])
-        acc = conv3d(np.ascontiguousarray(cur), L["w"], geom(L["k"], (1, 1, 1), (0, 0, 0), (1, 1, 1)))
+        acc = conv3d(np.ascontiguousarray(cur), L["w"],
+                     geom(L["k"], L.get("stride") or (1, 1, 1), L.get("pad") or (0, 0, 0), (1, 1, 1)))
         cur = threshold(acc, L["lo"], L["hi"])
         codes.append(cur)
         if L.get("save"):
             saved[L["save"]] = cur
-    return codes, conv3d_real(cur, head_w, head_b)
+    return codes, (conv3d_real(cur, head_w, head_b) if head_w is not None else None)

@@ -16,6 +16,9 @@ from .binding import (  # noqa: F401
     tern_fold_avgpool,
     tern_conv_out_dims,
     tern_fcn_forward,
+    tern_net_forward,
+    tern_net_workspace_bytes,
+    NetModule,
     tern_fcn_workspace_bytes,
     tern_filter_bank_bytes,
     tern_fold_batchnorm,

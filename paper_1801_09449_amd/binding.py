@@ -46,6 +46,11 @@ class Source(C.Structure):
                 ("first", C.c_int32 * 3)]
 
 
+class Module(C.Structure):
+    _fields_ = [("c_out", C.c_int32), ("g", Geom), ("w_bank", C.c_void_p), ("thr_lo", C.c_void_p),
+                ("thr_hi", C.c_void_p), ("skip_from", C.c_int32), ("up", C.c_int32 * 3)]
+
+
 def lib_path() -> str:
     return os.path.join(_HERE, _LIB_NAME)
 
@@ -82,6 +87,10 @@ def lib():
     L.tern_fold_batchnorm.restype = C.c_int
     L.tern_concat.argtypes = [C.POINTER(Source), I, Dims, P, P]; L.tern_concat.restype = C.c_int
     L.tern_conv3d_real.argtypes = [P, Dims, P, P, I, Geom, P, P]; L.tern_conv3d_real.restype = C.c_int
+    L.tern_net_workspace_bytes.argtypes = [Dims, C.POINTER(Module), I]; L.tern_net_workspace_bytes.restype = S
+    L.tern_net_forward.argtypes = [P, Dims, P, P, C.POINTER(Module), I, P, P, I, Geom, P, S, P, C.POINTER(Dims),
+                                   C.POINTER(C.c_void_p), C.POINTER(Dims), P]
+    L.tern_net_forward.restype = C.c_int
     L.tern_count_codes.argtypes = [P, Dims, P, P, P]; L.tern_count_codes.restype = C.c_int
     L.tern_fold_avgpool.argtypes = [P, I, I, I, I, I, C.POINTER(C.c_int32), P]
     L.tern_fold_avgpool.restype = C.c_int
@@ -434,6 +443,112 @@ def tern_conv3d_real(in_packed: torch.Tensor, c_in: int, w: torch.Tensor,
                                   _ptr(bias) if bias is not None else None, c_out,
                                   _geom(k, stride, pad, dil), _ptr(out), _stream(out)),
            "tern_conv3d_real")
+    return out
+
+
+class NetModule:
+    """One module of tern_net_forward: a fused ternary convolution whose input is the previous
+    module's output, optionally upsampled (`up`) and followed by the centre-cropped output of
+    module `skip_from`."""
+
+    def __init__(self, c_out: int, w_bank: torch.Tensor, thr_lo: torch.Tensor, thr_hi: torch.Tensor,
+                 k=3, stride=1, pad=0, dil=1, skip_from: int = -1, up=1):
+        _dev(w_bank, PACKED_DTYPE, "w_bank")
+        _dev(thr_lo, torch.int32, "thr_lo")
+        _dev(thr_hi, torch.int32, "thr_hi")
+        self.c_out, self.w_bank, self.thr_lo, self.thr_hi = int(c_out), w_bank, thr_lo, thr_hi
+        self.k, self.stride, self.pad, self.dil = _t3(k), _t3(stride), _t3(pad), _t3(dil)
+        self.skip_from, self.up = int(skip_from), _t3(up)
+
+    def as_struct(self) -> Module:
+        m = Module(self.c_out, _geom(self.k, self.stride, self.pad, self.dil), self.w_bank.data_ptr(),
+                   self.thr_lo.data_ptr(), self.thr_hi.data_ptr(), self.skip_from)
+        for a in range(3):
+            m.up[a] = self.up[a]
+        return m
+
+
+def _module_array(mods):
+    arr = (Module * len(mods))()
+    for i, m in enumerate(mods):
+        arr[i] = m.as_struct()
+    return arr
+
+
+def tern_net_workspace_bytes(in_shape, mods) -> int:
+    return int(lib().tern_net_workspace_bytes(_dims(in_shape), _module_array(mods), len(mods)))
+
+
+def tern_net_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor, mods,
+                     head_w: Optional[torch.Tensor] = None, head_b: Optional[torch.Tensor] = None,
+                     head_stride=1, head_pad=0, head_dil=1, workspace: Optional[torch.Tensor] = None,
+                     head_out: Optional[torch.Tensor] = None, return_modules: bool = False):
+    """Float input -> Eq. 6 -> modules with skips -> optional float-weight prediction layer.
+    Returns the prediction maps (or None without a head) and, if return_modules, a list of
+    (packed module output viewing the workspace, logical dims)."""
+    _dev(x, torch.float32, "x")
+    if x.dim() != 5:
+        raise ValueError("x must be [N][C][D][H][W]")
+    _dev(in_lo, torch.float32, "in_lo")
+    _dev(in_hi, torch.float32, "in_hi")
+    arr = _module_array(mods)
+    need = int(lib().tern_net_workspace_bytes(_dims(x.shape), arr, len(mods)))
+    if need == 0:
+        raise TernError(-3, "tern_net_workspace_bytes (invalid module list)")
+    if workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    _dev(workspace, torch.uint8, "workspace")
+    mod_ptr = (C.c_void_p * len(mods))()
+    mod_dims = (Dims * len(mods))()
+    hd = Dims()
+    hk = Geom()
+    head_c_out = 0
+    if head_w is not None:
+        _dev(head_w, torch.float32, "head_w")
+        if head_w.dim() != 5:
+            raise ValueError("head_w must be [C_out][C_in][kd][kh][kw]")
+        head_c_out = int(head_w.shape[0])
+        hk = _geom(tuple(int(v) for v in head_w.shape[2:]), head_stride, head_pad, head_dil)
+        if head_b is not None:
+            _dev(head_b, torch.float32, "head_b")
+        if head_out is None:
+            # extents of the last module, then of the head
+            dims_list = _net_dims(x.shape, mods)
+            ho = tern_conv_out_dims(dims_list[-1], head_c_out, tuple(int(v) for v in head_w.shape[2:]),
+                                    head_stride, head_pad, head_dil)
+            head_out = torch.empty(ho, dtype=torch.float32, device=x.device)
+        _dev(head_out, torch.float32, "head_out")
+    _check(lib().tern_net_forward(_ptr(x), _dims(x.shape), _ptr(in_lo), _ptr(in_hi), arr, len(mods),
+                                  _ptr(head_w) if head_w is not None else None,
+                                  _ptr(head_b) if head_b is not None else None, head_c_out, hk,
+                                  _ptr(workspace), workspace.numel(),
+                                  _ptr(head_out) if head_out is not None else None, C.byref(hd),
+                                  mod_ptr, mod_dims, _stream(x)), "tern_net_forward")
+    if not return_modules:
+        return head_out
+    views = []
+    base = workspace.data_ptr()
+    for i in range(len(mods)):
+        d = mod_dims[i]
+        dm = (d.n, d.c, d.d, d.h, d.w)
+        nbytes = tern_packed_bytes(dm)
+        off = mod_ptr[i] - base
+        v = workspace[off:off + nbytes].view(PACKED_DTYPE).view(d.n, d.d, d.h, d.w, 2, tern_words(d.c))
+        views.append((v, dm))
+    return head_out, views
+
+
+def _net_dims(in_shape, mods):
+    """Logical dims of every module's output (host arithmetic mirroring the library's)."""
+    out = []
+    cur = tuple(int(v) for v in in_shape)
+    for m in mods:
+        n, c, d, h, w = cur
+        d, h, w = d * m.up[0], h * m.up[1], w * m.up[2]
+        if m.skip_from >= 0:
+            c += out[m.skip_from][1]
+        cur = tern_conv_out_dims((n, c, d, h, w), m.c_out, m.k, m.stride, m.pad, m.dil)
+        out.append(cur)
     return out
 
 

@@ -3,6 +3,8 @@
 // synchronising.  Nothing here allocates device memory.
 #include <limits.h>
 
+#include <vector>
+
 #include "tern_internal.h"
 
 namespace tern {
@@ -416,6 +418,136 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
         cur = o;
     }
     if (out_dims) *out_dims = last;
+    return TERN_OK;
+}
+
+// One walk over the modules: validates the wiring, reports extents, and lays the workspace out
+// (regions of 256-byte granularity, in the order: packed input, then per module [concatenated
+// input,] output).  With `run` the kernels are enqueued as well.
+namespace {
+struct NetWalk {
+    const float* in; const float* in_lo; const float* in_hi;
+    char* ws; hipStream_t stream; bool run;
+    uint32_t** module_out; tern_dims* module_dims;
+};
+
+inline size_t region(const tern_dims& d) { return (tern_packed_bytes(d) + 255u) & ~(size_t)255u; }
+
+int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk* w, size_t* total,
+             tern_dims* last_dims, const uint32_t** last_ptr)
+{
+    if (!mods) return TERN_ENULL;
+    if (n_mods < 1 || n_mods > 1024) return TERN_EARG;
+    if (!sizes_ok(in_dims)) return TERN_ESHAPE;
+    std::vector<tern_dims> odims((size_t)n_mods);
+    std::vector<size_t> ooff((size_t)n_mods);
+    size_t off = 0;
+    const size_t in_off = off;
+    off += region(in_dims);
+    if (w && w->run) {
+        int rc = tern_threshold_pack(w->in, TERN_SRC_F32, in_dims, w->in_lo, w->in_hi,
+                                     (uint32_t*)(w->ws + in_off), w->stream);
+        if (rc != TERN_OK) return rc;
+    }
+    tern_dims cur = in_dims;
+    size_t cur_off = in_off;
+    for (int i = 0; i < n_mods; ++i) {
+        const tern_module& m = mods[i];
+        if (m.skip_from >= i || m.skip_from < -1) return TERN_EARG;
+        for (int a = 0; a < 3; ++a)
+            if (m.up[a] < 1 || m.up[a] > 1024) return TERN_EARG;
+        const bool resample = m.up[0] > 1 || m.up[1] > 1 || m.up[2] > 1 || m.skip_from >= 0;
+        if (resample) {
+            const int64_t ud = (int64_t)cur.d * m.up[0], uh = (int64_t)cur.h * m.up[1], uw = (int64_t)cur.w * m.up[2];
+            if (ud > INT32_MAX || uh > INT32_MAX || uw > INT32_MAX) return TERN_ESHAPE;
+            tern_dims cat = {cur.n, cur.c, (int32_t)ud, (int32_t)uh, (int32_t)uw};
+            tern_source src[2];
+            src[0].packed = w && w->run ? (const uint32_t*)(w->ws + cur_off) : nullptr;
+            src[0].dims = cur;
+            for (int a = 0; a < 3; ++a) { src[0].up[a] = m.up[a]; src[0].first[a] = 0; }
+            int n_src = 1;
+            if (m.skip_from >= 0) {
+                const tern_dims& sd = odims[(size_t)m.skip_from];
+                const int32_t first[3] = {(sd.d - cat.d) / 2, (sd.h - cat.h) / 2, (sd.w - cat.w) / 2};
+                if (sd.d < cat.d || sd.h < cat.h || sd.w < cat.w) return TERN_EARG;
+                if ((int64_t)cat.c + sd.c > INT32_MAX) return TERN_ESHAPE;
+                src[1].packed = w && w->run ? (const uint32_t*)(w->ws + ooff[(size_t)m.skip_from]) : nullptr;
+                src[1].dims = sd;
+                for (int a = 0; a < 3; ++a) { src[1].up[a] = 1; src[1].first[a] = first[a]; }
+                cat.c += sd.c;
+                n_src = 2;
+            }
+            if (!sizes_ok(cat)) return TERN_ESHAPE;
+            const size_t cat_off = off;
+            off += region(cat);
+            if (w && w->run) {
+                int rc = tern_concat(src, n_src, cat, (uint32_t*)(w->ws + cat_off), w->stream);
+                if (rc != TERN_OK) return rc;
+            }
+            cur = cat;
+            cur_off = cat_off;
+        }
+        tern_dims o;
+        int rc = geom_check(cur, m.c_out, m.g, &o);
+        if (rc != TERN_OK) return rc;
+        odims[(size_t)i] = o;
+        ooff[(size_t)i] = off;
+        off += region(o);
+        if (w && w->run) {
+            if (!m.w_bank || !m.thr_lo || !m.thr_hi) return TERN_ENULL;
+            rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
+                             m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
+            if (rc != TERN_OK) return rc;
+            if (w->module_out) w->module_out[i] = (uint32_t*)(w->ws + ooff[(size_t)i]);
+            if (w->module_dims) w->module_dims[i] = o;
+        }
+        cur = o;
+        cur_off = ooff[(size_t)i];
+    }
+    if (total) *total = off;
+    if (last_dims) *last_dims = cur;
+    if (last_ptr) *last_ptr = w && w->run ? (const uint32_t*)(w->ws + cur_off) : nullptr;
+    return TERN_OK;
+}
+}  // namespace
+
+size_t tern_net_workspace_bytes(tern_dims in_dims, const tern_module* mods, int32_t n_mods)
+{
+    size_t total = 0;
+    if (net_walk(in_dims, mods, n_mods, nullptr, &total, nullptr, nullptr) != TERN_OK) return 0;
+    return total;
+}
+
+int tern_net_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
+                     const tern_module* mods, int32_t n_mods, const float* head_w, const float* head_b,
+                     int32_t head_c_out, tern_conv_geom head_g, void* workspace, size_t workspace_bytes,
+                     float* head_out, tern_dims* head_dims, uint32_t** module_out,
+                     tern_dims* module_dims, void* stream)
+{
+    if (!in || !in_lo || !in_hi || !mods || !workspace) return TERN_ENULL;
+    if (head_w && !head_out) return TERN_ENULL;
+    if (n_mods >= 1 && n_mods <= 1024)
+        for (int i = 0; i < n_mods; ++i)
+            if (!mods[i].w_bank || !mods[i].thr_lo || !mods[i].thr_hi) return TERN_ENULL;
+    size_t need = 0;
+    tern_dims last;
+    int rc = net_walk(in_dims, mods, n_mods, nullptr, &need, &last, nullptr);   // validate first
+    if (rc != TERN_OK) return rc;
+    tern_dims hd = last;
+    if (head_w) {
+        rc = geom_check(last, head_c_out, head_g, &hd);
+        if (rc != TERN_OK) return rc;
+    }
+    if (workspace_bytes < need || !aligned16(workspace)) return TERN_EWORKSPACE;
+    NetWalk w = {in, in_lo, in_hi, (char*)workspace, (hipStream_t)stream, true, module_out, module_dims};
+    const uint32_t* last_ptr = nullptr;
+    rc = net_walk(in_dims, mods, n_mods, &w, nullptr, nullptr, &last_ptr);
+    if (rc != TERN_OK) return rc;
+    if (head_w) {
+        rc = tern_conv3d_real(last_ptr, last, head_w, head_b, head_c_out, head_g, head_out, stream);
+        if (rc != TERN_OK) return rc;
+        if (head_dims) *head_dims = hd;
+    }
     return TERN_OK;
 }
 

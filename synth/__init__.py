@@ -216,9 +216,9 @@ class UNetCase:
       accumulator the module produces, pooling factor included), and what happens to the
       module's input before the convolution:
         pool   : (pd, ph, pw) average-pooling window applied to the incoming tensor, or None;
-        concat : name of a saved encoder tensor that is centre-cropped and appended (channel-wise)
-                 after the incoming tensor has been upsampled by `up`, or None;
-        up     : nearest-neighbour factors used with `concat`;
+        up     : nearest-neighbour upsampling factors applied to the incoming tensor, or None;
+        concat : name of a saved tensor that is centre-cropped to the (upsampled) incoming
+                 extent and appended channel-wise, or None;
       and save: name under which the module's output codes are kept for a later skip, or None.
     head_w / head_b: float32 weights [classes][C][1][3][3] and bias of the prediction layer.
     """
@@ -256,7 +256,7 @@ def unet_table1(seed: int = 0, n: int = 1, size=(236, 172), slices: int = 15, wi
         pvol = int(np.prod(pool[li])) if li in pool else 1
         lo, hi = bn_like_thresholds(c_out, k[0] * k[1] * k[2] * pvol, cin_l, 0.5, 0.617, seed, T_THR + 8 * li)
         layers.append(dict(w=w, k=k, lo=lo, hi=hi, pool=pool.get(li), concat=concat.get(li),
-                           up=(1, 2, 2), save=save.get(li)))
+                           up=(1, 2, 2) if li in concat else None, save=save.get(li)))
         c_in = c_out
     head_w = (gaussian((classes, c_in, 1, 3, 3), seed, T_F32 + 8 * 15) * 0.1).astype(np.float32)
     head_b = (gaussian((classes,), seed, T_F32 + 8 * 16) * 0.1).astype(np.float32)

@@ -190,3 +190,37 @@ def test_unet_entry_points_reject_bad_arguments(T):
     with pytest.raises(T.TernError) as e:
         T.tern_fold_avgpool(np.zeros((1, 1, 600, 1, 1), np.int8), (2, 1, 1))    # folded extent above 1024
     assert e.value.status == -2
+
+
+def test_net_forward_wiring_is_validated_on_the_host(T):
+    from paper_1801_09449_amd.binding import Dims, Geom, Module, _geom
+    L = T.lib()
+    fake = 0x1000
+    p = C.c_void_p(fake)
+
+    def mod(c_out, k=3, stride=1, pad=1, skip=-1, up=(1, 1, 1), bank=fake):
+        m = Module(c_out, _geom(k, stride, pad, 1), bank, fake, fake, skip)
+        for a in range(3):
+            m.up[a] = up[a]
+        return m
+
+    d = Dims(1, 4, 4, 8, 8)
+    ok = (Module * 3)(mod(8), mod(16, stride=2), mod(8, skip=0, up=(2, 2, 2)))
+    need = L.tern_net_workspace_bytes(d, ok, 3)
+    # packed input + 3 outputs + one concatenated tensor (8 + 16 channels at the input extent)
+    assert need == 256 * 8 + 256 * 8 + 32 * 8 + 256 * 8 + 256 * 8
+    assert L.tern_net_workspace_bytes(d, (Module * 1)(mod(8, skip=0)), 1) == 0          # skip from itself
+    assert L.tern_net_workspace_bytes(d, (Module * 2)(mod(8), mod(8, skip=1)), 2) == 0   # skip from later
+    assert L.tern_net_workspace_bytes(d, (Module * 2)(mod(8), mod(8, up=(0, 1, 1))), 2) == 0
+    # the skipped tensor must be at least as large as the (upsampled) incoming one
+    assert L.tern_net_workspace_bytes(d, (Module * 3)(mod(8, stride=2), mod(8), mod(8, skip=0, up=(4, 4, 4))), 3) == 0
+    hg = _geom(1, 1, 0, 1)
+    hd = Dims()
+    args = lambda mods, n, ws_bytes, ws=p, head=None, hout=None: L.tern_net_forward(
+        p, d, p, p, mods, n, head, None, 2, hg, ws, ws_bytes, hout, C.byref(hd), None, None, None)
+    assert args(ok, 3, need - 1) == -4
+    assert args(ok, 3, need, ws=C.c_void_p(0x1008)) == -4
+    assert args(ok, 3, need, ws=None) == -1
+    assert args(ok, 3, need, head=p, hout=None) == -1                                    # head without output
+    assert args((Module * 1)(mod(8, bank=None)), 1, need) == -1
+    assert args(ok, 0, need) == -3

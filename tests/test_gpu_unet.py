@@ -237,3 +237,41 @@ def test_unet_reduced(G):
 def test_unet_table1_full_size(G):
     """The network at the paper's size (236 x 172 x 15 stack, full channel counts), one stack."""
     check_unet(G, synth.unet_table1(seed=0, n=1))
+
+
+def test_net_forward_generic_wiring(G):
+    """tern_net_forward beyond the Table 1 pattern: a 3-D network with padded and strided
+    modules, upsampling without a skip, a skip without upsampling, a skip of a skip, unaligned
+    channel counts, and no prediction layer."""
+    import torch
+    from paper_1801_09449_amd import unet
+    n, vol = 2, (6, 14, 12)
+    x = synth.gaussian((n, 3) + vol, 91, synth.T_F32)
+    in_lo = np.array([-0.4, -0.5, -0.2], np.float32)
+    in_hi = np.array([0.5, 0.3, 0.6], np.float32)
+    spec = [
+        # c_out, c_in, k, stride, pad, extras
+        (20, 3, (3, 3, 3), (1, 1, 1), (1, 1, 1), dict(save="a")),
+        (33, 20, (3, 3, 3), (2, 2, 2), (1, 1, 1), dict(save="b")),
+        (16, 33, (1, 1, 1), (1, 1, 1), (0, 0, 0), dict()),
+        (24, 16 + 33, (3, 3, 3), (1, 1, 1), (1, 1, 1), dict(concat="b")),                 # skip, no upsampling
+        (12, 24, (3, 3, 3), (1, 1, 1), (1, 1, 1), dict(up=(2, 2, 2), save="c")),           # upsampling, no skip
+        (8, 12 + 20, (3, 3, 3), (1, 1, 1), (0, 0, 0), dict(concat="a")),                   # same extent as "a"
+        (5, 8 + 12, (1, 3, 3), (1, 1, 1), (0, 0, 0), dict(concat="c")),                    # "c" is larger: cropped
+    ]
+    layers = []
+    for li, (co, ci, k, st, pd, extra) in enumerate(spec, start=1):
+        w = synth.ternary((co, ci) + k, 0.5, 91, synth.T_WGT + 8 * li)
+        lo, hi = synth.bn_like_thresholds(co, int(np.prod(k)), ci, 0.5, 0.6, 91, synth.T_THR + 8 * li)
+        layers.append(dict(w=w, k=k, stride=st, pad=pd, lo=lo, hi=hi, pool=None, up=extra.get("up"),
+                           concat=extra.get("concat"), save=extra.get("save")))
+    plan = unet.UNetPlan(layers, None, None, in_lo, in_hi)
+    pred, kept = unet.unet_forward(plan, G.dev(x), keep_layers=True)
+    torch.cuda.synchronize()
+    assert pred is None
+    codes, _ = oracle.unet_forward(x, in_lo, in_hi, layers, None, None)
+    assert len(kept) == len(codes) == 7
+    for li, ((t, c), want) in enumerate(zip(kept, codes), start=1):
+        assert c == want.shape[1]
+        np.testing.assert_array_equal(G.words(t), oracle.pack(want), err_msg=f"module {li}")
+    assert len(np.unique(codes[-1])) == 3
