@@ -260,8 +260,10 @@ int tern_conv3d_real(const uint32_t* in_packed, tern_dims in_dims, const float* 
  *                head_b, head_out are ignored); head_b may be NULL; head_out receives
  *                [N][head_c_out][Do][Ho][Wo] floats, head_dims (host, optional) its extents.
  *   workspace  : device scratch of at least tern_net_workspace_bytes() bytes, 16-byte aligned;
- *                holds the packed input, every module's output and every concatenated tensor,
- *                each in a region of its own (nothing is overwritten within a call).
+ *                holds the packed input (or, as in tern_fcn_forward, the gathered taps of a
+ *                one-channel input's first module), every module's output and every
+ *                concatenated tensor, each in a region of its own (nothing is overwritten
+ *                within a call).
  *   module_out / module_dims : optional host arrays of n_mods entries that receive the device
  *                address (inside workspace) and logical extents of every module's packed output.
  * Errors as for the calls it is made of; TERN_EARG for an invalid skip_from or crop,

@@ -443,10 +443,39 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
     std::vector<size_t> ooff((size_t)n_mods);
     size_t off = 0;
     const size_t in_off = off;
-    off += region(in_dims);
+    // Module 0 on a one-channel input with a 3x3x3 / 1x3x3 kernel: the input region holds the
+    // gathered taps of every output voxel instead of the packed input (see tern_fcn_forward).
+    bool gathered = false;
+    tern_dims o0 = in_dims;
+    {
+        const tern_module& m0 = mods[0];
+        const bool plain = m0.skip_from == -1 && m0.up[0] == 1 && m0.up[1] == 1 && m0.up[2] == 1;
+        if (plain && geom_check(in_dims, m0.c_out, m0.g, &o0) == TERN_OK)
+            gathered = patch_pack_applies(in_dims.c, m0.g, o0);
+    }
+    if (gathered) {
+        const tern_dims patches = {o0.n, 1, o0.d, o0.h, o0.w};
+        off += region(patches);
+    } else {
+        off += region(in_dims);
+    }
     if (w && w->run) {
-        int rc = tern_threshold_pack(w->in, TERN_SRC_F32, in_dims, w->in_lo, w->in_hi,
+        int rc;
+        if (gathered) {
+            const tern_conv_geom& g = mods[0].g;
+            PatchParams pp;
+            pp.src = w->in; pp.lo = w->in_lo; pp.hi = w->in_hi; pp.dst = (uint32_t*)(w->ws + in_off);
+            pp.d = in_dims.d; pp.h = in_dims.h; pp.w = in_dims.w;
+            pp.od = o0.d; pp.oh = o0.h; pp.ow = o0.w;
+            pp.kd = g.k[0]; pp.kh = g.k[1]; pp.kw = g.k[2];
+            pp.sh = g.stride[1]; pp.sw = g.stride[2];
+            pp.pd = g.pad[0]; pp.ph = g.pad[1]; pp.pw = g.pad[2];
+            pp.dh = g.dil[1]; pp.dw = g.dil[2];
+            rc = launch_patch_pack_f32(pp, in_dims.n, w->stream);
+        } else {
+            rc = tern_threshold_pack(w->in, TERN_SRC_F32, in_dims, w->in_lo, w->in_hi,
                                      (uint32_t*)(w->ws + in_off), w->stream);
+        }
         if (rc != TERN_OK) return rc;
     }
     tern_dims cur = in_dims;
@@ -495,8 +524,20 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
         off += region(o);
         if (w && w->run) {
             if (!m.w_bank || !m.thr_lo || !m.thr_hi) return TERN_ENULL;
-            rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
-                             m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
+            if (i == 0 && gathered) {
+                // single-tap convolution over the gathered words
+                const int32_t taps = m.g.k[0] * m.g.k[1] * m.g.k[2];
+                const tern_dims pin = {o.n, taps, o.d, o.h, o.w};
+                const tern_conv_geom unit = {{1, 1, 1}, {1, 1, 1}, {0, 0, 0}, {1, 1, 1}};
+                if (!aligned16(m.w_bank)) return TERN_EARG;
+                rc = launch_conv3d(conv_params((const uint32_t*)(w->ws + cur_off), pin, m.w_bank, m.c_out, unit,
+                                               o, m.thr_lo, m.thr_hi, nullptr,
+                                               (uint32_t*)(w->ws + ooff[(size_t)i])),
+                                   w->stream);
+            } else {
+                rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
+                                 m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
+            }
             if (rc != TERN_OK) return rc;
             if (w->module_out) w->module_out[i] = (uint32_t*)(w->ws + ooff[(size_t)i]);
             if (w->module_dims) w->module_dims[i] = o;

@@ -275,3 +275,21 @@ def test_net_forward_generic_wiring(G):
         assert c == want.shape[1]
         np.testing.assert_array_equal(G.words(t), oracle.pack(want), err_msg=f"module {li}")
     assert len(np.unique(codes[-1])) == 3
+
+
+def test_net_forward_one_channel_first_module(G):
+    """A plain chain through tern_net_forward whose first module qualifies for the gathered-tap
+    route (one input channel, 3x3x3): same codes as the oracle's chain, module by module."""
+    import torch
+    from paper_1801_09449_amd import unet
+    f = synth.config2(seed=8, vol=(12, 20, 18))
+    layers = [dict(w=L["w"], k=L["k"], stride=L["stride"], pad=L["pad"], lo=L["lo"], hi=L["hi"], pool=None,
+                   up=None, concat=None, save=None) for L in f.layers]
+    plan = unet.UNetPlan(layers, None, None, f.in_lo, f.in_hi)
+    _, kept = unet.unet_forward(plan, G.dev(f.x), keep_layers=True)
+    torch.cuda.synchronize()
+    want = oracle.fcn_forward(f.x, f.in_lo, f.in_hi,
+                              [dict(w=L["w"], geom=ConvGeom(L["k"], L["stride"], L["pad"], L["dil"]), lo=L["lo"],
+                                    hi=L["hi"]) for L in f.layers])
+    for li, ((t, c), code) in enumerate(zip(kept, want), start=1):
+        np.testing.assert_array_equal(G.words(t), oracle.pack(code), err_msg=f"module {li}")
