@@ -637,13 +637,11 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     }
     const int lds_limit = lds_limit_for_current_device();
 
-    // Kernel variants (voxels per lane V x channels per pass CO_BLK):
-    //   V=2, CO_BLK=16:  64 accumulator pairs -> up to 5 waves per SIMD; the finest work split;
-    //   V=2, CO_BLK=32:  128 accumulator pairs -> 3 waves per SIMD, half the passes over the
-    //                    LDS tile and half the per-wave prologue/epilogue;
-    //   V=4, CO_BLK=16:  half the scalar-cache traffic per instruction (tuning option only).
-    // Waves of 32 channels are used when that still gives every SIMD about four of them;
-    // smaller problems are cut into 16-channel waves.
+    // Kernel variants: voxels per lane V x channels per pass CO_BLK = accumulator pairs per lane.
+    //   V=1, CO_BLK=32  (64 pairs, five waves per SIMD): large launches;
+    //   V=1 or 2, CO_BLK=16  (32 or 64 pairs): smaller launches, the finest work split;
+    //   V=2, CO_BLK=32  (128 pairs, three waves per SIMD): tap-packed layers and few-step kernels;
+    //   V=4, CO_BLK=16: half the scalar-cache traffic per instruction (tuning option only).
     // One voxel per lane where a wave still has enough steps to amortise its fixed cost (not
     // the tap-packed layers, whose step set-up is per voxel): half the accumulators, so more
     // waves fit a SIMD (five instead of three with 32 channels per pass), and waves half as
