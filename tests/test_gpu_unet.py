@@ -151,7 +151,9 @@ def real_conv_bound(w, b):
 
 @pytest.mark.parametrize("ci,co,vol,k,stride,pad,dil", [(64, 2, (1, 20, 18), (1, 3, 3), 1, 0, 1),
                                                         (37, 5, (4, 6, 7), (3, 3, 3), (1, 2, 1), (1, 0, 2), (1, 1, 2)),
-                                                        (8, 1, (3, 3, 3), (1, 1, 1), 1, 0, 1)])
+                                                        (8, 1, (3, 3, 3), (1, 1, 1), 1, 0, 1),
+                                                        (300, 2, (3, 4, 5), (3, 3, 3), 1, 1, 1),     # filters too large for LDS
+                                                        (130, 7, (2, 9, 70), (1, 3, 3), 1, (0, 1, 1), 1)])
 def test_conv3d_real(G, ci, co, vol, k, stride, pad, dil):
     import paper_1801_09449_amd as T
     t3 = lambda v: (v,) * 3 if isinstance(v, int) else tuple(v)
