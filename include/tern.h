@@ -173,9 +173,9 @@ size_t tern_fcn_workspace_bytes(tern_dims in_dims, const tern_layer* layers /* h
  *               layers[i].c_in == layers[i-1].c_out;
  *   workspace : device scratch of at least tern_fcn_workspace_bytes() bytes, 16-byte aligned;
  *               holds the packed activations of the input and of every layer but the last.
- *               (With a one-channel input and a 3x3x3 or 1x3x3 first kernel of unit depth
- *               stride and dilation, the input region instead holds, per
- *               output voxel of layer 0, that voxel's kernel taps gathered into one word pair:
+ *               (With a one-channel input and a 3x3x3, 1x3x3 or 15x3x3 first kernel of unit
+ *               depth stride and dilation, the input region instead holds, per
+ *               output voxel of layer 0, that voxel's kernel taps gathered into a bit string:
  *               Eq. 6 and the gathering run as one pass over the intensities and layer 0
  *               becomes a single-tap convolution.  Results are identical either way.)
  *               When layer_out (host array of n_layers pointers, may be NULL) is given,

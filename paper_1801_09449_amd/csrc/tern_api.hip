@@ -328,7 +328,7 @@ static int fcn_plan(tern_dims in_dims, const tern_layer* layers, int32_t n_layer
         if (i == 0 && patch_pack_applies(in_dims.c, layers[0].g, o)) {
             // the first region then holds the gathered taps (one word pair per output voxel of
             // layer 0) instead of the packed input
-            const tern_dims patches = {o.n, 1, o.d, o.h, o.w};
+            const tern_dims patches = {o.n, layers[0].g.k[0] * layers[0].g.k[1] * layers[0].g.k[2], o.d, o.h, o.w};
             total = (tern_packed_bytes(patches) + 255u) & ~(size_t)255u;
         }
         if (i + 1 < n_layers) total += (tern_packed_bytes(o) + 255u) & ~(size_t)255u;
@@ -367,13 +367,13 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
     tern_dims o0;
     rc = geom_check(in_dims, layers[0].c_out, layers[0].g, &o0);
     if (rc != TERN_OK) return rc;
-    // A one-channel input with at most 32 kernel taps: Eq. 6 and the gathering of every output
-    // voxel's taps into one word happen in one pass over the intensities, and layer 0 becomes a
-    // single-tap convolution over those words (its tap-packed filter bank is already in the
+    // A one-channel input with a 3x3x3, 1x3x3 or 15x3x3 first kernel: Eq. 6 and the gathering of
+    // every output voxel's taps into a bit string happen in one pass over the intensities, and
+    // layer 0 becomes a single-tap convolution over those strings (its tap-packed filter bank is already in the
     // matching layout).  Otherwise: Eq. 6 on the raw intensities, packed, then layer 0 as is.
     const bool gathered = patch_pack_applies(in_dims.c, layers[0].g, o0);
     if (gathered) {
-        const tern_dims patches = {o0.n, 1, o0.d, o0.h, o0.w};
+        const tern_dims patches = {o0.n, layers[0].g.k[0] * layers[0].g.k[1] * layers[0].g.k[2], o0.d, o0.h, o0.w};
         ws += (tern_packed_bytes(patches) + 255u) & ~(size_t)255u;
         const tern_conv_geom& g = layers[0].g;
         PatchParams pp;
@@ -454,7 +454,7 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
             gathered = patch_pack_applies(in_dims.c, m0.g, o0);
     }
     if (gathered) {
-        const tern_dims patches = {o0.n, 1, o0.d, o0.h, o0.w};
+        const tern_dims patches = {o0.n, mods[0].g.k[0] * mods[0].g.k[1] * mods[0].g.k[2], o0.d, o0.h, o0.w};
         off += region(patches);
     } else {
         off += region(in_dims);

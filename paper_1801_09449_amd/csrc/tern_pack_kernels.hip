@@ -316,21 +316,23 @@ int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo,
 // With one input channel a packed voxel carries a single live bit per plane, and a convolution
 // would have to collect its T <= 32 taps bit by bit for every output voxel and channel slice.
 // This kernel does that collecting once, straight from the float intensities (applying the
-// activation cut points on the way): output voxel o gets one mask word and one sign word whose
+// activation cut points on the way): output voxel o gets a mask string and a sign string whose
 // bit t is the code of tap t = (a*kh + b)*kw + c of o's receptive field (0 outside the volume).
 // The convolution then is a single-tap one over T "channels", and the tap-packed filter bank
 // (bit t of its one word per channel = tap t) is exactly that convolution's plain bank.
 // A thread owns one (ox, oy) column and kPatchZ consecutive output planes; with unit depth stride
 // and dilation these share input planes, so kPatchZ + KD - 1 plane parts serve kPatchZ outputs.
-// Instantiated for the usual first kernels, 3x3x3 and 1x3x3 (any in-plane stride, dilation, pad).
+// Instantiated for the usual first kernels, 3x3x3 and 1x3x3, and for the 15x3x3 stack kernel of
+// Table 1, whose 135 taps make a five-word string (any in-plane stride, dilation, pad).
 namespace {
 
-constexpr int kPatchZ = 8;
-
-template <int KD, int KH, int KW>
+// PZ = output planes per thread, WDP = words per plane of the gathered tap string.
+template <int KD, int KH, int KW, int PZ>
 __global__ __launch_bounds__(256) void patch_pack_f32_kernel(PatchParams p)
 {
+    constexpr int kPatchZ = PZ;
     constexpr int NB = KH * KW;   // taps per input plane
+    constexpr int WDP = (KD * NB + 31) / 32;
     const int ox = blockIdx.x * 64 + threadIdx.x;
     const int oy = blockIdx.y * 4 + threadIdx.y;
     const int nseg = (p.od + kPatchZ - 1) / kPatchZ;
@@ -389,45 +391,69 @@ __global__ __launch_bounds__(256) void patch_pack_f32_kernel(PatchParams p)
         m[j] = P | N;
         s[j] = N;
     }
-    uint32_t* out = p.dst + ((((size_t)n * p.od + oz0) * p.oh + oy) * p.ow + ox) * 2u;
-    const size_t ostep = (size_t)p.oh * p.ow * 2u;
+    uint32_t* out = p.dst + ((((size_t)n * p.od + oz0) * p.oh + oy) * p.ow + ox) * 2u * WDP;
+    const size_t ostep = (size_t)p.oh * p.ow * 2u * WDP;
 #pragma unroll
     for (int t = 0; t < kPatchZ; ++t) {
         if (oz0 + t >= p.od) break;
-        uint32_t wm = 0u, ws = 0u;
+        // plane a of the kernel occupies bits [a*NB, a*NB + NB) of the tap string
+        uint32_t wm[WDP], ws[WDP];
 #pragma unroll
-        for (int a = 0; a < KD; ++a) { wm |= m[t + a] << (a * NB); ws |= s[t + a] << (a * NB); }
-        *reinterpret_cast<uint2*>(out + (size_t)t * ostep) = make_uint2(wm, ws);
+        for (int q = 0; q < WDP; ++q) wm[q] = ws[q] = 0u;
+#pragma unroll
+        for (int a = 0; a < KD; ++a) {
+            constexpr int kNB = NB;
+            const int word = (a * kNB) / 32, sh = (a * kNB) % 32;
+            wm[word] |= m[t + a] << sh;
+            ws[word] |= s[t + a] << sh;
+            if (sh + kNB > 32) {
+                wm[word + 1] |= m[t + a] >> (32 - sh);
+                ws[word + 1] |= s[t + a] >> (32 - sh);
+            }
+        }
+        uint32_t* o = out + (size_t)t * ostep;
+        if constexpr (WDP == 1) {
+            *reinterpret_cast<uint2*>(o) = make_uint2(wm[0], ws[0]);
+        } else {
+#pragma unroll
+            for (int q = 0; q < WDP; ++q) { o[q] = wm[q]; o[WDP + q] = ws[q]; }
+        }
     }
 }
 
-// Kernel extents the gathering kernel is instantiated for.
-inline bool patch_kernel_exists(int kd, int kh, int kw)
+// Kernel extents the gathering kernel is instantiated for -> output planes per thread (0: none).
+// 15x3x3 is the stack-of-slices first layer of Table 1 (its output has a single plane).
+inline int patch_planes_per_thread(int kd, int kh, int kw)
 {
-    return kh == 3 && kw == 3 && (kd == 3 || kd == 1);
+    if (kh != 3 || kw != 3) return 0;
+    if (kd == 3 || kd == 1) return 8;
+    if (kd == 15) return 1;
+    return 0;
 }
 
 }  // namespace
 
 bool patch_pack_applies(int32_t c_in, const tern_conv_geom& g, const tern_dims& out)
 {
-    if (!(c_in == 1 && patch_kernel_exists(g.k[0], g.k[1], g.k[2]) && g.stride[0] == 1 && g.dil[0] == 1))
-        return false;
+    const int pz = patch_planes_per_thread(g.k[0], g.k[1], g.k[2]);
+    if (!(c_in == 1 && pz > 0 && g.stride[0] == 1 && g.dil[0] == 1)) return false;
     // launch grid limits of the gathering kernel
-    const int64_t nseg = (out.d + kPatchZ - 1) / kPatchZ;
+    const int64_t nseg = (out.d + pz - 1) / pz;
     return nseg * out.n <= 65535 && (out.h + 3) / 4 <= 65535;
 }
 
 int launch_patch_pack_f32(const PatchParams& p, int32_t n, hipStream_t s)
 {
-    const int nseg = (p.od + kPatchZ - 1) / kPatchZ;
+    const int pz = patch_planes_per_thread(p.kd, p.kh, p.kw);
+    if (pz == 0) return TERN_EARG;
+    const int nseg = (p.od + pz - 1) / pz;
     const dim3 grid((unsigned)((p.ow + 63) / 64), (unsigned)((p.oh + 3) / 4), (unsigned)(nseg * n)), block(64, 4);
-    if (p.kd == 3 && p.kh == 3 && p.kw == 3)
-        hipLaunchKernelGGL((patch_pack_f32_kernel<3, 3, 3>), grid, block, 0, s, p);
-    else if (p.kd == 1 && p.kh == 3 && p.kw == 3)
-        hipLaunchKernelGGL((patch_pack_f32_kernel<1, 3, 3>), grid, block, 0, s, p);
+    if (p.kd == 3)
+        hipLaunchKernelGGL((patch_pack_f32_kernel<3, 3, 3, 8>), grid, block, 0, s, p);
+    else if (p.kd == 1)
+        hipLaunchKernelGGL((patch_pack_f32_kernel<1, 3, 3, 8>), grid, block, 0, s, p);
     else
-        return TERN_EARG;
+        hipLaunchKernelGGL((patch_pack_f32_kernel<15, 3, 3, 1>), grid, block, 0, s, p);
     TERN_HIP_CHECK(hipGetLastError());
     return TERN_OK;
 }

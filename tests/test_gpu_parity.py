@@ -385,7 +385,8 @@ def test_pointwise_kernel_and_tiled_route_agree_with_oracle(G, ci, co, vol, n):
 FIRST_LAYERS = [
     # (k, stride, pad, dil) of layer 0 on a one-channel input; 3x3x3 and 1x3x3 kernels with unit
     # depth stride and dilation take the route that gathers the taps into one word per output
-    # voxel (rows 0, 1, 3), the others the ordinary one
+    # voxel (rows 0, 1, 3), 15x3x3 kernels the same route with five words (rows 9, 10), the others
+    # the ordinary one
     ((3, 3, 3), (1, 1, 1), (1, 1, 1), (1, 1, 1)),
     ((1, 3, 3), (1, 1, 1), (0, 1, 1), (1, 1, 1)),
     ((2, 3, 3), (1, 2, 1), (1, 0, 1), (1, 1, 1)),
@@ -395,6 +396,8 @@ FIRST_LAYERS = [
     ((3, 3, 3), (2, 1, 1), (1, 1, 1), (1, 1, 1)),      # depth stride 2
     ((3, 3, 3), (1, 1, 1), (2, 1, 1), (2, 1, 1)),      # depth dilation 2
     ((3, 3, 4), (1, 1, 1), (1, 1, 1), (1, 1, 1)),      # 36 taps
+    ((15, 3, 3), (1, 1, 1), (2, 1, 1), (1, 1, 1)),     # stack kernel: 135 taps in five words, one output plane
+    ((15, 3, 3), (1, 2, 1), (4, 0, 1), (1, 1, 1)),     # the same with five output planes
 ]
 
 
