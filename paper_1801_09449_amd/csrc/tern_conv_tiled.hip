@@ -656,7 +656,7 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     };
     // Estimated launch time in vector instructions of the busiest SIMD, for cb channels per pass
     // and the kernel taps split over ks waves: workgroups are dealt to the 256 compute units
-    // whole, a workgroup puts (its waves / 4) on every SIMD, and a wave costs its share of the
+    // whole, a unit's waves spread over its four SIMDs, and a wave costs its share of the
     // contraction, its epilogue, about 560 fixed instructions and, with split taps, the exchange
     // of partial sums.
     auto estimate = [&](int cb, int ks) -> double {
@@ -671,10 +671,14 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         if (nwc > slices) nwc = slices;
         if (nwc < 1) nwc = 1;
         const double wgs = (double)q.tiles_x * q.tiles_y * q.tiles_z * p.n * cdiv(slices, nwc);
-        const double per_simd = (nsp * nwc * ks + 3) / 4;
         const double per_wave = (double)steps_all / ks * cb * p.wc * v * 4 + 5.0 * v * cb + 560.0 +
                                 (ks > 1 ? 2.0 * (ks - 1) * v * cb + 300.0 : 0.0);
-        return std::ceil(wgs / 256.0) * per_simd * per_wave;
+        // waves of the fullest compute unit, spread over its four SIMDs
+        const double per_simd = std::ceil(std::ceil(wgs / 256.0) * (nsp * nwc * ks) / 4.0);
+        // a SIMD issues a vector instruction in 78 % of its cycles with one wave, 90 % with two,
+        // 93 % with three, 95 % with four or more (measured with the instruction-mix probe)
+        const double eff = per_simd <= 1 ? 0.78 : per_simd <= 2 ? 0.90 : per_simd <= 3 ? 0.93 : 0.95;
+        return per_simd * per_wave / eff;
     };
     int nks_pref = 0;   // tap split chosen together with the pass width (0: decided further down)
     int V = 2, co_blk = 16;
