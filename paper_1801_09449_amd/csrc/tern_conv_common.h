@@ -18,22 +18,6 @@ struct ActChunk {
 // these kernels.
 typedef const uint32_t __attribute__((address_space(4)))* scalar_ptr;
 
-// acc += popcount(x) as the single instruction the hardware has for it.
-__device__ __forceinline__ void popc_acc(int32_t& acc, uint32_t x)
-{
-    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
-}
-
-// m & (sa ^ sw) as one three-input bit operation (truth-table index = sa<<2 | m<<1 | sw).
-// Spelled out because the compiler otherwise sometimes forms (sa ^ sw) on its own and spends a
-// fifth instruction per word pair.
-__device__ __forceinline__ uint32_t and_xor(uint32_t m, uint32_t sa, uint32_t sw)
-{
-    uint32_t r;
-    asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x48" : "=v"(r) : "v"(sa), "v"(m), "s"(sw));
-    return r;
-}
-
 // word = (word << 1) | (thr < d): the comparison result goes through the carry flag into the
 // low bit, two instructions per decision and no overflow cases.
 __device__ __forceinline__ void shift_in_gt(uint32_t& word, int32_t d, int32_t thr)
@@ -46,6 +30,78 @@ __device__ __forceinline__ void shift_in_lt(uint32_t& word, int32_t d, int32_t t
 {
     asm("v_cmp_gt_i32 vcc, %2, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc"
         : "+v"(word) : "v"(d), "s"(thr) : "vcc");
+}
+
+// Cut points of Eq. 6 for kCutBatch consecutive output channels.  The epilogue walks a pass's
+// channels in such batches, two in flight (one being compared, one arriving), so that the cut
+// points never occupy more than 32 SGPRs: fetching all 2 x CO_BLK of them at once left the
+// register allocator short of SGPRs and it parked hundreds of them in VGPR lanes.
+constexpr int kCutBatch = 8;
+struct CutGroup {
+    int32_t lo[kCutBatch];
+    int32_t hi[kCutBatch];
+};
+
+// Channels c0 .. c0+7 of a pass; `valid` of them exist (channels past c_out get cut points that
+// never fire, i.e. zero bits).  The full case is two contiguous 8-word scalar loads.
+__device__ __forceinline__ void load_cuts(CutGroup& c, scalar_ptr thr_lo, scalar_ptr thr_hi, int c0,
+                                          int valid, int c_out)
+{
+    if (valid >= kCutBatch) {
+#pragma unroll
+        for (int j = 0; j < kCutBatch; ++j) {
+            c.lo[j] = (int32_t)thr_lo[c0 + j];
+            c.hi[j] = (int32_t)thr_hi[c0 + j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < kCutBatch; ++j) {
+            const int cj = min(c0 + j, c_out - 1);
+            const int32_t l = (int32_t)thr_lo[cj], h = (int32_t)thr_hi[cj];
+            c.lo[j] = j < valid ? l : INT32_MIN;
+            c.hi[j] = j < valid ? h : INT32_MAX;
+        }
+    }
+}
+
+// Same purpose as settle() for filter words: pins the wait for this batch's scalar loads here.
+__device__ __forceinline__ void settle_cuts(const CutGroup& c)
+{
+    asm volatile("" ::"s"(c.lo[0]), "s"(c.lo[1]), "s"(c.lo[2]), "s"(c.lo[3]), "s"(c.lo[4]), "s"(c.lo[5]),
+                 "s"(c.lo[6]), "s"(c.lo[7]), "s"(c.hi[0]), "s"(c.hi[1]), "s"(c.hi[2]), "s"(c.hi[3]),
+                 "s"(c.hi[4]), "s"(c.hi[5]), "s"(c.hi[6]), "s"(c.hi[7]));
+}
+
+// Eq. 6 in integer form for one pass of CO_BLK channels: two decisions per (voxel, channel),
+// highest channel first so that channel j ends up in bit j of pp (acc > hi) and pn (acc < lo).
+template <int V, int CO_BLK>
+__device__ __forceinline__ void ternarise_pass(const int32_t (&d)[V][CO_BLK], scalar_ptr thr_lo,
+                                               scalar_ptr thr_hi, int cb, int co_left, int c_out,
+                                               uint32_t (&pp)[V], uint32_t (&pn)[V])
+{
+    constexpr int NB = CO_BLK / kCutBatch;
+    static_assert(CO_BLK % kCutBatch == 0, "whole batches");
+    CutGroup cg[2];
+    load_cuts(cg[(NB - 1) & 1], thr_lo, thr_hi, cb + (NB - 1) * kCutBatch, co_left - (NB - 1) * kCutBatch, c_out);
+#pragma unroll
+    for (int v = 0; v < V; ++v) pp[v] = pn[v] = 0u;
+#pragma unroll
+    for (int b = NB - 1; b >= 0; --b) {
+        settle_cuts(cg[b & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (b > 0)
+            load_cuts(cg[(b - 1) & 1], thr_lo, thr_hi, cb + (b - 1) * kCutBatch, co_left - (b - 1) * kCutBatch, c_out);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = kCutBatch - 1; j >= 0; --j) {
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                shift_in_gt(pp[v], d[v][b * kCutBatch + j], cg[b & 1].hi[j]);   // +1 if acc > hi
+                shift_in_lt(pn[v], d[v][b * kCutBatch + j], cg[b & 1].lo[j]);   // -1 if acc < lo
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 
 // KG = output channels whose filter words are fetched together.  Two groups are in flight (one
@@ -101,23 +157,98 @@ __device__ __forceinline__ void settle(const WGroup<WC, KG>& g)
     }
 }
 
-// Four VALU instructions per (word pair, voxel): and, popcount-accumulate, and-xor,
-// popcount-accumulate (Eq. 9 as popcount(M) - 2 popcount(M & X), the subtraction deferred).
-template <int WC, int V, int CO_BLK, int KG>
+// Eq. 9 for four (word pair, voxel) combinations: acc_m += popcount(ma & mw), acc_n +=
+// popcount(ma & mw & (sa ^ sw)) -- and, popcount-accumulate, three-input bit operation (truth
+// table 0x48 = m & (sa ^ sw), index = sa<<2 | m<<1 | sw), popcount-accumulate; mw and sw are
+// wave-uniform.
+//
+// The sixteen instructions are one asm statement because their order and spacing decide the
+// issue rate on gfx950.  Measured with register-only loops of this mix (cycles per vector
+// instruction at 2.4 GHz, four waves per SIMD): any order with no scalar instruction in between
+// 3.95-4.0, also with another vector instruction between producer and popcount; one scalar
+// instruction (s_nop 0 or any other) between the bit operation and its popcount 3.4; one between
+// each producer and its popcount, as below, 3.1, a fifth less time per word pair; s_nop 1, v_nop or
+// further nops between independent instructions lose the gain again.  The s_nop behind the bit
+// operation is also the wait state the compiler itself puts between v_bitop3 and a reader of its
+// result.  The compiler assumes that an asm statement's outputs may need such a wait state and
+// puts an s_nop of its own in front of the next statement that touches one of them, which spoils
+// the spacing: hence four word pairs per statement, and two scratch registers taken in turn.
+#ifndef TERN_MAC_PATTERN
+#define TERN_MAC_PATTERN 2
+#endif
+#if TERN_MAC_PATTERN == 1
+#define TERN_MAC_PAIR(P, ADD_M, ADD_N)                                              \
+    "v_and_b32 %[t], %[mw" P "], %[ma" P "]\n\t"                                   \
+    "v_bcnt_u32_b32 %[am" P "], %[t], " ADD_M "\n\t"                               \
+    "v_bitop3_b32 %[t], %[sa" P "], %[t], %[sw" P "] bitop3:0x48\n\t"              \
+    "s_nop 0\n\t"                                                                  \
+    "v_bcnt_u32_b32 %[an" P "], %[t], " ADD_N "\n\t"
+#else
+#define TERN_MAC_PAIR(P, ADD_M, ADD_N)                                              \
+    "v_and_b32 %[t], %[mw" P "], %[ma" P "]\n\t"                                   \
+    "s_nop 0\n\t"                                                                  \
+    "v_bcnt_u32_b32 %[am" P "], %[t], " ADD_M "\n\t"                               \
+    "v_bitop3_b32 %[t], %[sa" P "], %[t], %[sw" P "] bitop3:0x48\n\t"              \
+    "s_nop 0\n\t"                                                                  \
+    "v_bcnt_u32_b32 %[an" P "], %[t], " ADD_N "\n\t"
+#endif
+#define TERN_MAC_IN(P, MA, SA, MW, SW) [ma##P] "v"(MA), [sa##P] "v"(SA), [mw##P] "s"(MW), [sw##P] "s"(SW)
+
+// Word q of channels jg .. jg+4/V-1 of group g for all V voxels of a lane (pair p = channel
+// p / V, voxel p % V).  SET: the accumulators hold nothing yet and are set instead of added to (a
+// pass's first step does that, so they are never cleared).
+template <int WC, int V, int CO_BLK, int KG, bool SET>
+__device__ __forceinline__ void mac_quad(const ActChunk<WC> (&A)[V], const WGroup<WC, KG>& g, int q, int jg,
+                                         int j0, int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK],
+                                         uint32_t& t)
+{
+    static_assert(V == 1 || V == 2 || V == 4, "four (channel, voxel) pairs per statement");
+#define TERN_C(P) (jg + (P) / V)
+#define TERN_X(P) ((P) % V)
+#define TERN_AM(P) acc_m[TERN_X(P)][j0 + TERN_C(P)]
+#define TERN_AN(P) acc_n[TERN_X(P)][j0 + TERN_C(P)]
+#define TERN_INS(P) TERN_MAC_IN(P, A[TERN_X(P)].m[q], A[TERN_X(P)].s[q], g.m[TERN_C(P)][q], g.s[TERN_C(P)][q])
+    if constexpr (SET) {
+        asm volatile(TERN_MAC_PAIR("0", "0", "0") TERN_MAC_PAIR("1", "0", "0") TERN_MAC_PAIR("2", "0", "0")
+                     TERN_MAC_PAIR("3", "0", "0")
+                     : [am0] "=&v"(TERN_AM(0)), [an0] "=&v"(TERN_AN(0)), [am1] "=&v"(TERN_AM(1)),
+                       [an1] "=&v"(TERN_AN(1)), [am2] "=&v"(TERN_AM(2)), [an2] "=&v"(TERN_AN(2)),
+                       [am3] "=&v"(TERN_AM(3)), [an3] "=&v"(TERN_AN(3)), [t] "+v"(t)
+                     : TERN_INS(0), TERN_INS(1), TERN_INS(2), TERN_INS(3));
+    } else {
+        asm volatile(TERN_MAC_PAIR("0", "%[am0]", "%[an0]") TERN_MAC_PAIR("1", "%[am1]", "%[an1]")
+                     TERN_MAC_PAIR("2", "%[am2]", "%[an2]") TERN_MAC_PAIR("3", "%[am3]", "%[an3]")
+                     : [am0] "+v"(TERN_AM(0)), [an0] "+v"(TERN_AN(0)), [am1] "+v"(TERN_AM(1)),
+                       [an1] "+v"(TERN_AN(1)), [am2] "+v"(TERN_AM(2)), [an2] "+v"(TERN_AN(2)),
+                       [am3] "+v"(TERN_AM(3)), [an3] "+v"(TERN_AN(3)), [t] "+v"(t)
+                     : TERN_INS(0), TERN_INS(1), TERN_INS(2), TERN_INS(3));
+    }
+#undef TERN_C
+#undef TERN_X
+#undef TERN_AM
+#undef TERN_AN
+#undef TERN_INS
+}
+
+// Four VALU instructions per (word pair, voxel) (Eq. 9 as popcount(M) - 2 popcount(M & X), the
+// subtraction deferred).  INIT: the accumulators of these channels hold nothing yet.
+template <int WC, int V, int CO_BLK, int KG, bool INIT = false>
 __device__ __forceinline__ void mac_group(const ActChunk<WC> (&A)[V], const WGroup<WC, KG>& g, int j0,
                                           int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK])
 {
+    // (The statements are volatile so that they stay in this order; the empty statement hands out
+    // two distinct scratch registers without an instruction.)
+    static_assert(KG % (4 / V) == 0 || V == 4, "whole statements");
+    uint32_t t[2];
+    asm volatile("" : "=v"(t[0]), "=v"(t[1]));
+    int k = 0;
 #pragma unroll
-    for (int j = 0; j < KG; ++j)
+    for (int q = 0; q < WC; ++q)
 #pragma unroll
-        for (int q = 0; q < WC; ++q)
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const uint32_t M = A[v].m[q] & g.m[j][q];
-                const uint32_t N = and_xor(M, A[v].s[q], g.s[j][q]);
-                popc_acc(acc_m[v][j0 + j], M);
-                popc_acc(acc_n[v][j0 + j], N);
-            }
+        for (int jg = 0; jg < KG; jg += (V == 4 ? 1 : 4 / V), ++k) {
+            if (INIT && q == 0) mac_quad<WC, V, CO_BLK, KG, true>(A, g, q, jg, j0, acc_m, acc_n, t[k & 1]);
+            else mac_quad<WC, V, CO_BLK, KG, false>(A, g, q, jg, j0, acc_m, acc_n, t[k & 1]);
+        }
 }
 
 }  // namespace

@@ -9,6 +9,8 @@
 // through the scalar cache -- the same four vector instructions per word pair and the same
 // epilogue as the tiled kernel, without its LDS tile, barrier and tap walk, whose fixed cost per
 // wave would dominate here (a single-tap wave has only a few hundred instructions of real work).
+#include <type_traits>
+
 #include "tern_conv_common.h"
 #include "tern_internal.h"
 
@@ -73,18 +75,13 @@ __global__ __launch_bounds__(kPointThreads) void conv_point_kernel(PointParams p
     for (int v = 0; v < V; ++v) pos_w[v] = neg_w[v] = 0u;
 
     for (int cb = co_begin; cb < co_end; cb += CO_BLK) {
-        int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];
-#pragma unroll
-        for (int v = 0; v < V; ++v)
-#pragma unroll
-            for (int j = 0; j < CO_BLK; ++j) acc_m[v][j] = acc_n[v][j] = 0;
+        int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];   // set by the first chunk, added to by the rest
 
         // (chunk, channel group) pairs in order, two filter-word groups in flight
         scalar_ptr wbase = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC;
         WGroup<WC, KG> g[2];
         load_wgroup<WC, KG>(g[0], wbase);
-#pragma unroll
-        for (int idx = 0; idx < NCH * NG; ++idx) {
+        auto group_step = [&](int idx, auto init) {
             const int ch = idx / NG, gi = idx % NG;
             settle<WC, KG>(g[idx & 1]);
             __builtin_amdgcn_sched_barrier(0);
@@ -93,9 +90,13 @@ __global__ __launch_bounds__(kPointThreads) void conv_point_kernel(PointParams p
                 load_wgroup<WC, KG>(g[(idx + 1) & 1], wbase + (size_t)nch * step_words + ngi * KG * 2 * WC);
             }
             __builtin_amdgcn_sched_barrier(0);
-            mac_group<WC, V, CO_BLK, KG>(A[ch], g[idx & 1], gi * KG, acc_m, acc_n);
+            mac_group<WC, V, CO_BLK, KG, decltype(init)::value>(A[ch], g[idx & 1], gi * KG, acc_m, acc_n);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        };
+#pragma unroll
+        for (int idx = 0; idx < NG; ++idx) group_step(idx, std::true_type{});
+#pragma unroll
+        for (int idx = NG; idx < NCH * NG; ++idx) group_step(idx, std::false_type{});
 
         int32_t d[V][CO_BLK];
 #pragma unroll
@@ -105,37 +106,9 @@ __global__ __launch_bounds__(kPointThreads) void conv_point_kernel(PointParams p
 
         const int co_left = co_end - cb;
         if constexpr (PACKED) {
-            // Eq. 6 in integer form: two decisions per (voxel, channel), highest channel first so
-            // that channel j ends up in bit j; channels past c_out get cut points that never fire.
-            scalar_ptr thr_lo = (scalar_ptr)(uintptr_t)p.lo;
-            scalar_ptr thr_hi = (scalar_ptr)(uintptr_t)p.hi;
-            int32_t lo[CO_BLK], hi[CO_BLK];
-            if (co_left >= CO_BLK) {
-#pragma unroll
-                for (int j = 0; j < CO_BLK; ++j) {
-                    lo[j] = (int32_t)thr_lo[cb + j];
-                    hi[j] = (int32_t)thr_hi[cb + j];
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < CO_BLK; ++j) {
-                    const int cj = min(cb + j, p.c_out - 1);
-                    const int32_t l = (int32_t)thr_lo[cj], h = (int32_t)thr_hi[cj];
-                    lo[j] = j < co_left ? l : INT32_MIN;
-                    hi[j] = j < co_left ? h : INT32_MAX;
-                }
-            }
             uint32_t pp[V], pn[V];
-#pragma unroll
-            for (int v = 0; v < V; ++v) pp[v] = pn[v] = 0u;
-#pragma unroll
-            for (int j = CO_BLK - 1; j >= 0; --j) {
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    shift_in_gt(pp[v], d[v][j], hi[j]);
-                    shift_in_lt(pn[v], d[v][j], lo[j]);
-                }
-            }
+            ternarise_pass<V, CO_BLK>(d, (scalar_ptr)(uintptr_t)p.lo, (scalar_ptr)(uintptr_t)p.hi, cb,
+                                      co_left, p.c_out, pp, pn);
             const int sh = cb & 31;
 #pragma unroll
             for (int v = 0; v < V; ++v) { pos_w[v] |= pp[v] << sh; neg_w[v] |= pn[v] << sh; }

@@ -145,7 +145,8 @@ __device__ __forceinline__ void fetch_step(ActChunk<WC> (&A)[V], StepCursor& c, 
 // One step: accumulate CO_BLK channels from A0 (this step's activations) while fetching the next
 // step's activations into A1.  Software pipeline: while a channel group is being accumulated,
 // the scalar loads of the following group and the LDS reads of the next step are in flight.
-template <int WC, int V, int CO_BLK, bool TP>
+// INIT marks the first step of a pass, which sets the accumulators instead of adding to them.
+template <int WC, int V, int CO_BLK, bool TP, bool INIT = false>
 __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<WC> (&A1)[V], bool last,
                                           StepCursor& cur, const StepConsts& sc, int inc_c, int inc_b,
                                           int inc_a, WGroup<WC, GroupOf<CO_BLK>::value>& g0,
@@ -165,14 +166,14 @@ __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<
         if (gi == 0) fetch_step<WC, V, TP>(A1, cur, sc, inc_c, inc_b, inc_a, lane_lds, !last);
         load_wgroup<WC, KG>(g1, wcur + (gi + 1) * KG * 2 * WC);
         __builtin_amdgcn_sched_barrier(0);
-        mac_group<WC, V, CO_BLK, KG>(A0, g0, gi * KG, acc_m, acc_n);
+        mac_group<WC, V, CO_BLK, KG, INIT>(A0, g0, gi * KG, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
         settle<WC, KG>(g1);
         __builtin_amdgcn_sched_barrier(0);
         if (gi + 2 < NG) load_wgroup<WC, KG>(g0, wcur + (gi + 2) * KG * 2 * WC);
         else load_wgroup<WC, KG>(g0, wnext);
         __builtin_amdgcn_sched_barrier(0);
-        mac_group<WC, V, CO_BLK, KG>(A0, g1, (gi + 1) * KG, acc_m, acc_n);
+        mac_group<WC, V, CO_BLK, KG, INIT>(A0, g1, (gi + 1) * KG, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
     }
     wcur = wnext;
@@ -229,29 +230,42 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
                 for (int ch = 0; ch < t.nchunk; ++ch) {
                     for (int hz0 = 0; hz0 < t.hz; hz0 += FB) {
                         uint4 r[FB];
+                        // the second half of a batch is skipped as a whole (a wave-uniform
+                        // branch) when at most FB/2 planes are left, e.g. 4-plane tiles
+                        const bool both = t.hz - hz0 > FB / 2;
     #pragma unroll
-                        for (int j = 0; j < FB; ++j) {
-                            const int gz = gz0 + hz0 + j;
-                            const bool inb = xy_in && hz0 + j < t.hz && gz >= 0 && gz < p.d;
-                            r[j] = make_uint4(0u, 0u, 0u, 0u);
-                            if (inb) {
-                                const uint32_t* src = src_xy + (size_t)gz * zstride;
-                                if constexpr (WC == 2) {
-                                    const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
-                                    const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
-                                    r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
-                                } else {
-                                    r[j].x = src[ch];
-                                    r[j].y = src[wd + ch];
+                        for (int half = 0; half < 2; ++half) {
+                            if (half == 0 || both) {
+    #pragma unroll
+                                for (int j = half * (FB / 2); j < (half + 1) * (FB / 2); ++j) {
+                                    const int gz = gz0 + hz0 + j;
+                                    const bool inb = xy_in && hz0 + j < t.hz && gz >= 0 && gz < p.d;
+                                    r[j] = make_uint4(0u, 0u, 0u, 0u);
+                                    if (inb) {
+                                        const uint32_t* src = src_xy + (size_t)gz * zstride;
+                                        if constexpr (WC == 2) {
+                                            const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
+                                            const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
+                                            r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
+                                        } else {
+                                            r[j].x = src[ch];
+                                            r[j].y = src[wd + ch];
+                                        }
+                                    }
                                 }
                             }
                         }
     #pragma unroll
-                        for (int j = 0; j < FB; ++j) {
-                            if (hz0 + j < t.hz) {
-                                uint32_t* dst = dst_xy + (size_t)(hz0 + j) * plane * t.vstride;
-                                if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst + 4 * ch) = r[j];
-                                else *reinterpret_cast<uint2*>(dst + 2 * ch) = make_uint2(r[j].x, r[j].y);
+                        for (int half = 0; half < 2; ++half) {
+                            if (half == 0 || both) {
+    #pragma unroll
+                                for (int j = half * (FB / 2); j < (half + 1) * (FB / 2); ++j) {
+                                    if (hz0 + j < t.hz) {
+                                        uint32_t* dst = dst_xy + (size_t)(hz0 + j) * plane * t.vstride;
+                                        if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst + 4 * ch) = r[j];
+                                        else *reinterpret_cast<uint2*>(dst + 2 * ch) = make_uint2(r[j].x, r[j].y);
+                                    }
+                                }
                             }
                         }
                     }
@@ -371,36 +385,36 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
         const bool active = cb < co_end;
         if (!active && t.nks == 1) break;
         int32_t d[V][CO_BLK];   // accumulators of this pass
-        if (active) {
-            int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];
-#pragma unroll
-            for (int v = 0; v < V; ++v)
-#pragma unroll
-                for (int j = 0; j < CO_BLK; ++j) acc_m[v][j] = acc_n[v][j] = 0;
-
-            if (s_begin < s_end) {
-                scalar_ptr wcur = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC +
-                                  (size_t)s_begin * sc.step_words;
-                WGroup<WC, KG> g0, g1;
-                StepCursor cur = cur0;
-                ActChunk<WC> Aa[V], Ab[V];
-                fetch_step<WC, V, TP>(Aa, cur, sc, inc_c, inc_b, inc_a, lane_lds, false);
-                load_wgroup<WC, KG>(g0, wcur);
-                int step = s_begin;
-                for (; step + 2 <= s_end; step += 2) {   // two steps per trip: no register copies
-                    conv_step<WC, V, CO_BLK, TP>(Aa, Ab, false, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
-                                                 acc_m, acc_n);
-                    conv_step<WC, V, CO_BLK, TP>(Ab, Aa, step + 2 == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
-                                                 lane_lds, acc_m, acc_n);
-                }
-                if (step < s_end)
-                    conv_step<WC, V, CO_BLK, TP>(Aa, Ab, true, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
-                                                 acc_m, acc_n);
+        if (active && s_begin < s_end) {
+            int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];   // set by the pass's first step
+            scalar_ptr wcur = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC +
+                              (size_t)s_begin * sc.step_words;
+            WGroup<WC, KG> g0, g1;
+            StepCursor cur = cur0;
+            ActChunk<WC> Aa[V], Ab[V];
+            fetch_step<WC, V, TP>(Aa, cur, sc, inc_c, inc_b, inc_a, lane_lds, false);
+            load_wgroup<WC, KG>(g0, wcur);
+            int step = s_begin + 1;
+            conv_step<WC, V, CO_BLK, TP, true>(Aa, Ab, step == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                               lane_lds, acc_m, acc_n);
+            for (; step + 2 <= s_end; step += 2) {   // two steps per trip: no register copies
+                conv_step<WC, V, CO_BLK, TP>(Ab, Aa, false, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
+                                             acc_m, acc_n);
+                conv_step<WC, V, CO_BLK, TP>(Aa, Ab, step + 2 == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                             lane_lds, acc_m, acc_n);
             }
+            if (step < s_end)
+                conv_step<WC, V, CO_BLK, TP>(Ab, Aa, true, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
+                                             acc_m, acc_n);
 #pragma unroll
             for (int v = 0; v < V; ++v)
 #pragma unroll
                 for (int j = 0; j < CO_BLK; ++j) d[v][j] = acc_m[v][j] - 2 * acc_n[v][j];
+        } else if (active) {   // a tap share without steps (more shares than steps)
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+#pragma unroll
+                for (int j = 0; j < CO_BLK; ++j) d[v][j] = 0;
         }
 
         if (t.nks > 1) {
@@ -429,38 +443,10 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
         // ---- epilogue ----------------------------------------------------------------------
         const int co_left = co_end - cb;
         if constexpr (PACKED) {
-            // Cut points of this block: one bulk scalar fetch, then two decisions per
-            // (voxel, channel), highest channel first so that channel j ends up in bit j.
-            scalar_ptr thr_lo = (scalar_ptr)(uintptr_t)p.lo;
-            scalar_ptr thr_hi = (scalar_ptr)(uintptr_t)p.hi;
-            int32_t lo[CO_BLK], hi[CO_BLK];
-            if (co_left >= CO_BLK) {
-#pragma unroll
-                for (int j = 0; j < CO_BLK; ++j) {
-                    lo[j] = (int32_t)thr_lo[cb + j];
-                    hi[j] = (int32_t)thr_hi[cb + j];
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < CO_BLK; ++j) {
-                    const int cj = min(cb + j, p.c_out - 1);
-                    const int32_t l = (int32_t)thr_lo[cj], h = (int32_t)thr_hi[cj];
-                    // channels past c_out: cut points that never fire, i.e. zero bits
-                    lo[j] = j < co_left ? l : INT32_MIN;
-                    hi[j] = j < co_left ? h : INT32_MAX;
-                }
-            }
+            // Cut points of this block come through the scalar cache, a few channels at a time.
             uint32_t pp[V], pn[V];
-#pragma unroll
-            for (int v = 0; v < V; ++v) pp[v] = pn[v] = 0u;
-#pragma unroll
-            for (int j = CO_BLK - 1; j >= 0; --j) {
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    shift_in_gt(pp[v], d[v][j], hi[j]);   // +1 if acc > hi
-                    shift_in_lt(pn[v], d[v][j], lo[j]);   // -1 if acc < lo
-                }
-            }
+            ternarise_pass<V, CO_BLK>(d, (scalar_ptr)(uintptr_t)p.lo, (scalar_ptr)(uintptr_t)p.hi, cb,
+                                      co_left, p.c_out, pp, pn);
             const int sh = cb & 31;
 #pragma unroll
             for (int v = 0; v < V; ++v) { pos_w[v] |= pp[v] << sh; neg_w[v] |= pn[v] << sh; }
