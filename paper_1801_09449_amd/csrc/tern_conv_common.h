@@ -172,62 +172,81 @@ __device__ __forceinline__ void settle(const WGroup<WC, KG>& g)
 // operation is also the wait state the compiler itself puts between v_bitop3 and a reader of its
 // result.  The compiler assumes that an asm statement's outputs may need such a wait state and
 // puts an s_nop of its own in front of the next statement that touches one of them, which spoils
-// the spacing: hence four word pairs per statement, and two scratch registers taken in turn.
+// the spacing: hence four or eight word pairs per statement, and two scratch registers taken in turn.
 #ifndef TERN_MAC_PATTERN
 #define TERN_MAC_PATTERN 2
 #endif
 #if TERN_MAC_PATTERN == 1
-#define TERN_MAC_PAIR(P, ADD_M, ADD_N)                                              \
+#define TERN_MAC_PAIR(P, C, ADD_M, ADD_N)                                             \
     "v_and_b32 %[t], %[mw" P "], %[ma" P "]\n\t"                                   \
-    "v_bcnt_u32_b32 %[am" P "], %[t], " ADD_M "\n\t"                               \
+    "v_bcnt_u32_b32 %[am" C "], %[t], " ADD_M "\n\t"                               \
     "v_bitop3_b32 %[t], %[sa" P "], %[t], %[sw" P "] bitop3:0x48\n\t"              \
     "s_nop 0\n\t"                                                                  \
-    "v_bcnt_u32_b32 %[an" P "], %[t], " ADD_N "\n\t"
+    "v_bcnt_u32_b32 %[an" C "], %[t], " ADD_N "\n\t"
 #else
-#define TERN_MAC_PAIR(P, ADD_M, ADD_N)                                              \
+#define TERN_MAC_PAIR(P, C, ADD_M, ADD_N)                                             \
     "v_and_b32 %[t], %[mw" P "], %[ma" P "]\n\t"                                   \
     "s_nop 0\n\t"                                                                  \
-    "v_bcnt_u32_b32 %[am" P "], %[t], " ADD_M "\n\t"                               \
+    "v_bcnt_u32_b32 %[am" C "], %[t], " ADD_M "\n\t"                               \
     "v_bitop3_b32 %[t], %[sa" P "], %[t], %[sw" P "] bitop3:0x48\n\t"              \
     "s_nop 0\n\t"                                                                  \
-    "v_bcnt_u32_b32 %[an" P "], %[t], " ADD_N "\n\t"
+    "v_bcnt_u32_b32 %[an" C "], %[t], " ADD_N "\n\t"
 #endif
 #define TERN_MAC_IN(P, MA, SA, MW, SW) [ma##P] "v"(MA), [sa##P] "v"(SA), [mw##P] "s"(MW), [sw##P] "s"(SW)
 
-// Word q of channels jg .. jg+4/V-1 of group g for all V voxels of a lane (pair p = channel
-// p / V, voxel p % V).  SET: the accumulators hold nothing yet and are set instead of added to (a
-// pass's first step does that, so they are never cleared).
+// All WC words of channels jg .. jg+4/V-1 of group g for all V voxels of a lane: combination c =
+// (channel c / V, voxel c % V), 4 WC word pairs per statement.  SET: the accumulators hold
+// nothing yet; the first word sets them instead of adding to them (a pass's first step does that,
+// so they are never cleared).
 template <int WC, int V, int CO_BLK, int KG, bool SET>
-__device__ __forceinline__ void mac_quad(const ActChunk<WC> (&A)[V], const WGroup<WC, KG>& g, int q, int jg,
-                                         int j0, int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK],
+__device__ __forceinline__ void mac_quad(const ActChunk<WC> (&A)[V], const WGroup<WC, KG>& g, int jg, int j0,
+                                         int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK],
                                          uint32_t& t)
 {
-    static_assert(V == 1 || V == 2 || V == 4, "four (channel, voxel) pairs per statement");
+    static_assert(V == 1 || V == 2 || V == 4, "four (channel, voxel) combinations per statement");
+    static_assert(WC == 1 || WC == 2, "one or two words per chunk");
 #define TERN_C(P) (jg + (P) / V)
 #define TERN_X(P) ((P) % V)
-#define TERN_AM(P) acc_m[TERN_X(P)][j0 + TERN_C(P)]
-#define TERN_AN(P) acc_n[TERN_X(P)][j0 + TERN_C(P)]
-#define TERN_INS(P) TERN_MAC_IN(P, A[TERN_X(P)].m[q], A[TERN_X(P)].s[q], g.m[TERN_C(P)][q], g.s[TERN_C(P)][q])
-    if constexpr (SET) {
-        asm volatile(TERN_MAC_PAIR("0", "0", "0") TERN_MAC_PAIR("1", "0", "0") TERN_MAC_PAIR("2", "0", "0")
-                     TERN_MAC_PAIR("3", "0", "0")
-                     : [am0] "=&v"(TERN_AM(0)), [an0] "=&v"(TERN_AN(0)), [am1] "=&v"(TERN_AM(1)),
-                       [an1] "=&v"(TERN_AN(1)), [am2] "=&v"(TERN_AM(2)), [an2] "=&v"(TERN_AN(2)),
-                       [am3] "=&v"(TERN_AM(3)), [an3] "=&v"(TERN_AN(3)), [t] "+v"(t)
-                     : TERN_INS(0), TERN_INS(1), TERN_INS(2), TERN_INS(3));
+#define TERN_ACC_SET(C) [am##C] "=&v"(acc_m[TERN_X(C)][j0 + TERN_C(C)]), [an##C] "=&v"(acc_n[TERN_X(C)][j0 + TERN_C(C)])
+#define TERN_ACC_ADD(C) [am##C] "+v"(acc_m[TERN_X(C)][j0 + TERN_C(C)]), [an##C] "+v"(acc_n[TERN_X(C)][j0 + TERN_C(C)])
+#define TERN_INS(P, C, Q) TERN_MAC_IN(P, A[TERN_X(C)].m[Q], A[TERN_X(C)].s[Q], g.m[TERN_C(C)][Q], g.s[TERN_C(C)][Q])
+#define TERN_WORD0_SET TERN_MAC_PAIR("0", "0", "0", "0") TERN_MAC_PAIR("1", "1", "0", "0") \
+                       TERN_MAC_PAIR("2", "2", "0", "0") TERN_MAC_PAIR("3", "3", "0", "0")
+#define TERN_WORD0_ADD TERN_MAC_PAIR("0", "0", "%[am0]", "%[an0]") TERN_MAC_PAIR("1", "1", "%[am1]", "%[an1]") \
+                       TERN_MAC_PAIR("2", "2", "%[am2]", "%[an2]") TERN_MAC_PAIR("3", "3", "%[am3]", "%[an3]")
+#define TERN_WORD1_ADD TERN_MAC_PAIR("4", "0", "%[am0]", "%[an0]") TERN_MAC_PAIR("5", "1", "%[am1]", "%[an1]") \
+                       TERN_MAC_PAIR("6", "2", "%[am2]", "%[an2]") TERN_MAC_PAIR("7", "3", "%[am3]", "%[an3]")
+    if constexpr (WC == 2) {
+        if constexpr (SET) {
+            asm volatile(TERN_WORD0_SET TERN_WORD1_ADD
+                         : TERN_ACC_SET(0), TERN_ACC_SET(1), TERN_ACC_SET(2), TERN_ACC_SET(3), [t] "+v"(t)
+                         : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0),
+                           TERN_INS(4, 0, 1), TERN_INS(5, 1, 1), TERN_INS(6, 2, 1), TERN_INS(7, 3, 1));
+        } else {
+            asm volatile(TERN_WORD0_ADD TERN_WORD1_ADD
+                         : TERN_ACC_ADD(0), TERN_ACC_ADD(1), TERN_ACC_ADD(2), TERN_ACC_ADD(3), [t] "+v"(t)
+                         : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0),
+                           TERN_INS(4, 0, 1), TERN_INS(5, 1, 1), TERN_INS(6, 2, 1), TERN_INS(7, 3, 1));
+        }
     } else {
-        asm volatile(TERN_MAC_PAIR("0", "%[am0]", "%[an0]") TERN_MAC_PAIR("1", "%[am1]", "%[an1]")
-                     TERN_MAC_PAIR("2", "%[am2]", "%[an2]") TERN_MAC_PAIR("3", "%[am3]", "%[an3]")
-                     : [am0] "+v"(TERN_AM(0)), [an0] "+v"(TERN_AN(0)), [am1] "+v"(TERN_AM(1)),
-                       [an1] "+v"(TERN_AN(1)), [am2] "+v"(TERN_AM(2)), [an2] "+v"(TERN_AN(2)),
-                       [am3] "+v"(TERN_AM(3)), [an3] "+v"(TERN_AN(3)), [t] "+v"(t)
-                     : TERN_INS(0), TERN_INS(1), TERN_INS(2), TERN_INS(3));
+        if constexpr (SET) {
+            asm volatile(TERN_WORD0_SET
+                         : TERN_ACC_SET(0), TERN_ACC_SET(1), TERN_ACC_SET(2), TERN_ACC_SET(3), [t] "+v"(t)
+                         : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0));
+        } else {
+            asm volatile(TERN_WORD0_ADD
+                         : TERN_ACC_ADD(0), TERN_ACC_ADD(1), TERN_ACC_ADD(2), TERN_ACC_ADD(3), [t] "+v"(t)
+                         : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0));
+        }
     }
 #undef TERN_C
 #undef TERN_X
-#undef TERN_AM
-#undef TERN_AN
+#undef TERN_ACC_SET
+#undef TERN_ACC_ADD
 #undef TERN_INS
+#undef TERN_WORD0_SET
+#undef TERN_WORD0_ADD
+#undef TERN_WORD1_ADD
 }
 
 // Four VALU instructions per (word pair, voxel) (Eq. 9 as popcount(M) - 2 popcount(M & X), the
@@ -237,18 +256,16 @@ __device__ __forceinline__ void mac_group(const ActChunk<WC> (&A)[V], const WGro
                                           int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK])
 {
     // (The statements are volatile so that they stay in this order; the empty statement hands out
-    // two distinct scratch registers without an instruction.)
-    static_assert(KG % (4 / V) == 0 || V == 4, "whole statements");
+    // two distinct scratch registers without an instruction.  The compiler's own s_nop in front of
+    // a group's first statement, behind the scalar load of the next group's filter words, is
+    // welcome: without it the loop measured 2 % slower.)
+    constexpr int NCB = V == 4 ? 1 : 4 / V;   // channels per statement
+    static_assert(KG % NCB == 0, "whole statements");
     uint32_t t[2];
     asm volatile("" : "=v"(t[0]), "=v"(t[1]));
-    int k = 0;
 #pragma unroll
-    for (int q = 0; q < WC; ++q)
-#pragma unroll
-        for (int jg = 0; jg < KG; jg += (V == 4 ? 1 : 4 / V), ++k) {
-            if (INIT && q == 0) mac_quad<WC, V, CO_BLK, KG, true>(A, g, q, jg, j0, acc_m, acc_n, t[k & 1]);
-            else mac_quad<WC, V, CO_BLK, KG, false>(A, g, q, jg, j0, acc_m, acc_n, t[k & 1]);
-        }
+    for (int jg = 0, k = 0; jg < KG; jg += NCB, ++k)
+        mac_quad<WC, V, CO_BLK, KG, INIT>(A, g, jg, j0, acc_m, acc_n, t[k & 1]);
 }
 
 }  // namespace
