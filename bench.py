@@ -22,7 +22,7 @@ OPS_PER_MAC = 5.0 / 32.0                  # and, xor, and, 2 x popcount-accumula
 HBM_PEAK = 8.0e12
 # HBM bytes per launch of the config[1] kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
 # a 256 MiB copy under the same counters (profiles/conv3d_fused_config1.md).
-TRAFFIC_BYTES_CFG1 = 10.04e6
+TRAFFIC_BYTES_CFG1 = 10.09e6
 ALGORITHMIC_BYTES_CFG1 = 8.42e6
 
 
