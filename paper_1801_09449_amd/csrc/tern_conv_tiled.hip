@@ -58,6 +58,9 @@ struct TileParams {
     int32_t red_off;              // LDS word offset of the partial-sum area (nks > 1)
     int32_t vy;                   // 1: a lane's V voxels are 8 rows apart along y (single-plane
                                   // outputs); 0: consecutive along z
+    // flat halo fill: floor(e / d) = umulhi(e, m_d) with m_d = 0xffffffff / d + 1 for d = hx,
+    // hy * hx and nchunk (valid for e * d < 2^32 and d > 1; m_ch is unused when nchunk = 1)
+    uint32_t m_hx, m_pl, m_ch;
 };
 
 template <int WC>
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     // a wave pays one memory round trip per batch instead of one per voxel.  Deep tiles: a thread
     // owns plane positions i = tid, tid + nthreads, ... of the (hy, hx) halo plane and a batch is
     // FB planes of one position.  Flat tiles (few planes, many positions per thread, as for
-    // single-plane outputs): a batch is FB positions of one plane.
+    // single-plane outputs): a batch is FB (position, chunk) items of the whole tile.
     {
         constexpr int FB = 8;
         const int gx0 = ox0 * p.sw - p.pw, gy0 = oy0 * p.sh - p.ph, gz0 = oz0 * p.sd - p.pd;
@@ -272,45 +275,49 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
                 }
             }
         } else {
-            // floor(i / hx) = umulhi(i, magic) for every i * hx < 2^32 (i is an LDS position)
-            const uint32_t magic = 0xffffffffu / (uint32_t)t.hx + 1u;
-            for (int hz = 0; hz < t.hz; ++hz) {
-                const int gz = gz0 + hz;
-                const bool z_in = gz >= 0 && gz < p.d;
-                const uint32_t* src_z = in_n + (size_t)(z_in ? gz : 0) * zstride;
-                uint32_t* dst_z = lds + (size_t)hz * plane * t.vstride;
-                for (int ch = 0; ch < t.nchunk; ++ch) {
-                    for (int i0 = tid; i0 < plane; i0 += FB * nthreads) {
-                        uint4 r[FB];
+            // One index space over (plane, position, chunk), chunk fastest: neighbouring threads
+            // read neighbouring words of one voxel record and write neighbouring LDS words, and
+            // a thread's FB items are in flight together whatever plane and chunk they belong to
+            // (with a loop per plane and chunk a 512-channel tile took 16 round trips).
+            // The divisions are multiplications by host-made reciprocals; e is below the tile's
+            // LDS words.
+            const uint32_t nch = (uint32_t)t.nchunk;
+            const uint32_t m_hx = t.m_hx, m_pl = t.m_pl, m_ch = t.m_ch;
+            const uint32_t items = (uint32_t)t.hz * (uint32_t)plane * nch;
+            for (uint32_t e0 = tid; e0 < items; e0 += FB * nthreads) {
+                uint4 r[FB];
 #pragma unroll
-                        for (int j = 0; j < FB; ++j) {
-                            const int i = i0 + j * nthreads;
-                            const int hy = (int)__umulhi((uint32_t)i, magic);
-                            const int hxx = i - hy * t.hx;
-                            const int gy = gy0 + hy, gx = gx0 + hxx;
-                            const bool inb = z_in && i < plane && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
-                            r[j] = make_uint4(0u, 0u, 0u, 0u);
-                            if (inb) {
-                                const uint32_t* src = src_z + ((size_t)gy * p.w + gx) * 2u * wd;
-                                if constexpr (WC == 2) {
-                                    const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
-                                    const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
-                                    r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
-                                } else {
-                                    r[j].x = src[ch];
-                                    r[j].y = src[wd + ch];
-                                }
-                            }
+                for (int j = 0; j < FB; ++j) {
+                    const uint32_t e = e0 + j * nthreads;
+                    const uint32_t vox = nch > 1 ? __umulhi(e, m_ch) : e;   // plane * position index
+                    const uint32_t ch = e - vox * nch;
+                    const uint32_t hz = __umulhi(vox, m_pl);
+                    const uint32_t i = vox - hz * plane;
+                    const int hy = (int)__umulhi(i, m_hx);
+                    const int hxx = (int)i - hy * t.hx;
+                    const int gz = gz0 + (int)hz, gy = gy0 + hy, gx = gx0 + hxx;
+                    const bool inb = e < items && gz >= 0 && gz < p.d && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
+                    r[j] = make_uint4(0u, 0u, 0u, 0u);
+                    if (inb) {
+                        const uint32_t* src = in_n + (((size_t)gz * p.h + gy) * p.w + gx) * 2u * wd;
+                        if constexpr (WC == 2) {
+                            const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
+                            const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
+                            r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
+                        } else {
+                            r[j].x = src[ch];
+                            r[j].y = src[wd + ch];
                         }
+                    }
+                }
 #pragma unroll
-                        for (int j = 0; j < FB; ++j) {
-                            const int i = i0 + j * nthreads;
-                            if (i < plane) {
-                                uint32_t* dst = dst_z + (size_t)i * t.vstride;
-                                if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst + 4 * ch) = r[j];
-                                else *reinterpret_cast<uint2*>(dst + 2 * ch) = make_uint2(r[j].x, r[j].y);
-                            }
-                        }
+                for (int j = 0; j < FB; ++j) {
+                    const uint32_t e = e0 + j * nthreads;
+                    if (e < items) {
+                        const uint32_t vox = nch > 1 ? __umulhi(e, m_ch) : e;
+                        uint32_t* dst = lds + vox * t.vstride + (e - vox * nch) * (2 * WC);
+                        if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst) = r[j];
+                        else *reinterpret_cast<uint2*>(dst) = make_uint2(r[j].x, r[j].y);
                     }
                 }
             }
@@ -582,6 +589,9 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     t.tiles_x = cdiv(p.ow, 8 * t.nwx);
     t.tiles_y = cdiv(p.oh, 8 * vyx * t.nwy);
     t.tiles_z = cdiv(p.od, vzx * t.nwz);
+    t.m_hx = 0xffffffffu / (uint32_t)t.hx + 1u;
+    t.m_pl = 0xffffffffu / (uint32_t)(t.hx * t.hy) + 1u;
+    t.m_ch = t.nchunk > 1 ? 0xffffffffu / (uint32_t)t.nchunk + 1u : 0u;
     return true;
 }
 
