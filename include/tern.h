@@ -343,7 +343,7 @@ int tern_fold_batchnorm(const double* alpha, const double* gamma, const double* 
  * TERN_OPT_TAP_SPLIT: waves of one workgroup that share the kernel taps of one channel slice and
  * add their partial sums in LDS, 0 = choose, 1, 2, 4 or 8.  TERN_OPT_POINTWISE: 1 (default) = 1x1x1
  * convolutions with unit stride and no padding use the pointwise kernel when the input has 1, 2,
- * 4 or 8 words per plane, 0 = they go through the tiled kernel like any other.
+ * 3, 4, 5 or 8 words per plane, 0 = they go through the tiled kernel like any other.
  * Results never depend on options.  Returns TERN_EARG for an unknown option or
  * value. */
 typedef enum { TERN_OPT_LANE_DEPTH = 1, TERN_OPT_WAVES_Z = 2, TERN_OPT_CO_BLOCK = 3,

@@ -56,6 +56,13 @@ __global__ __launch_bounds__(kPointThreads) void conv_point_kernel(PointParams p
             uint2 r = *reinterpret_cast<const uint2*>(src);
             A[0][v].m[0] = live ? r.x : 0u;
             A[0][v].s[0] = live ? r.y : 0u;
+        } else if constexpr (WC == 1) {   // odd word counts: records are only 8-byte aligned
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const uint32_t m = src[ch], sg = src[WD + ch];
+                A[ch][v].m[0] = live ? m : 0u;
+                A[ch][v].s[0] = live ? sg : 0u;
+            }
         } else {
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
@@ -148,7 +155,7 @@ bool conv_point_applies(const ConvParams& p)
     if (p.kd * p.kh * p.kw != 1) return false;
     if (p.sd != 1 || p.sh != 1 || p.sw != 1 || p.pd != 0 || p.ph != 0 || p.pw != 0) return false;
     if (p.tp_slots != 0) return false;
-    return p.wd_in == 1 || p.wd_in == 2 || p.wd_in == 4 || p.wd_in == 8;
+    return p.wd_in == 1 || p.wd_in == 2 || p.wd_in == 3 || p.wd_in == 4 || p.wd_in == 5 || p.wd_in == 8;
 }
 
 int launch_conv_point(const ConvParams& c, hipStream_t s)
@@ -193,7 +200,9 @@ int launch_conv_point(const ConvParams& c, hipStream_t s)
     switch (c.wd_in) {
         case 1: if (co_blk == 32) TERN_POINT(1, 1, 32); else TERN_POINT(1, 1, 16); break;
         case 2: if (co_blk == 32) TERN_POINT(2, 1, 32); else TERN_POINT(2, 1, 16); break;
+        case 3: if (co_blk == 32) TERN_POINT(1, 3, 32); else TERN_POINT(1, 3, 16); break;
         case 4: if (co_blk == 32) TERN_POINT(2, 2, 32); else TERN_POINT(2, 2, 16); break;
+        case 5: if (co_blk == 32) TERN_POINT(1, 5, 32); else TERN_POINT(1, 5, 16); break;
         case 8: if (co_blk == 32) TERN_POINT(2, 4, 32); else TERN_POINT(2, 4, 16); break;
         default: return TERN_EARG;
     }

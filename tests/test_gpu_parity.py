@@ -362,12 +362,13 @@ def test_config2_fcn_full(G):
 
 POINTWISE = [(27, 16, (5, 7, 9), 1), (64, 64, (6, 5, 7), 2), (128, 40, (3, 5, 5), 3), (256, 96, (4, 4, 4), 1),
              (32, 33, (1, 1, 130), 2), (100, 70, (2, 9, 8), 2), (8, 200, (3, 3, 3), 1), (1, 1, (1, 1, 1), 1),
-             (64, 32, (16, 32, 40), 1)]
+             (64, 32, (16, 32, 40), 1), (135, 32, (3, 10, 13), 2), (160, 48, (2, 7, 9), 1), (80, 64, (5, 6, 7), 1),
+             (96, 17, (1, 3, 50), 3)]
 
 
 @pytest.mark.parametrize("ci,co,vol,n", POINTWISE, ids=[f"{a}-{b}-n{d}" for a, b, _, d in POINTWISE])
 def test_pointwise_kernel_and_tiled_route_agree_with_oracle(G, ci, co, vol, n):
-    """1x1x1 convolutions: 1, 2, 4 and 8 input words per plane, ragged voxel counts and channel
+    """1x1x1 convolutions: 1, 2, 3, 4, 5 and 8 input words per plane, ragged voxel counts and channel
     tails, batches; once through the pointwise kernel and once forced through the tiled one."""
     import paper_1801_09449_amd as T
     c = synth.conv_case("pw", n, ci, co, vol, k=1, pad=0, seed=ci + co)
