@@ -546,7 +546,13 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     t.nwx = 1; t.nwy = 1; t.nwz = g_waves_z > 0 ? g_waves_z : 1;
     // one voxel per lane: two waves share a halo tile from the start (along z, or along y for
     // single-plane outputs), which gives the same tile as one wave with two voxels per lane
-    if (V == 1 && g_waves_z == 0) { if (p.od > 1) t.nwz = 2; else t.nwy = 2; }
+    // (not for stacks of independent planes, kd = 1 with several output planes: stacking shares
+    // nothing there and only makes workgroups coarser; measured 7-8 % slower on the 2-D layers
+    // of a batch of 16)
+    if (V == 1 && g_waves_z == 0) {
+        if (p.od == 1) t.nwy = 2;
+        else if (p.kd > 1) t.nwz = 2;
+    }
     // Single-plane outputs (2-D convolutions): a lane's V voxels go along y instead of z.
     t.vy = p.od == 1 ? 1 : 0;
     const int vyx = t.vy ? V : 1, vzx = t.vy ? 1 : V;
@@ -671,8 +677,11 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
                                 (ks > 1 ? 2.0 * (ks - 1) * v * cb + 300.0 : 0.0);
         // waves of the fullest compute unit, spread over its four SIMDs
         const double per_simd = std::ceil(std::ceil(wgs / 256.0) * (nsp * nwc * ks) / 4.0);
-        // a SIMD issues a vector instruction in 78 % of its cycles with one wave, 90 % with two,
-        // 93 % with three, 95 % with four or more (measured with the instruction-mix probe)
+        // penalty for SIMDs with few waves.  The weights were the issue efficiency measured for
+        // one, two, three and four or more waves before the word-pair sequence was spaced by hand
+        // (it now loses less with few waves); they are kept because the choices they lead to
+        // still measure best on the mid-size layers tried (the gentler weights 0.89 / 0.95 /
+        // 0.98 / 1.0 picked a 50 % slower launch for 64 -> 64 channels on 32^3)
         const double eff = per_simd <= 1 ? 0.78 : per_simd <= 2 ? 0.90 : per_simd <= 3 ? 0.93 : 0.95;
         return per_simd * per_wave / eff;
     };
@@ -739,6 +748,10 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     if (nks > 1) { co_per_wave = co_blk; slices = cdiv(p.c_out, co_per_wave); }
     int nwc = 8 / (nsp * nks);
     if (nwc > slices) nwc = slices;
+    // Large launches: workgroups of four waves rather than eight.  Sharing a halo tile between
+    // more channel slices saves fills, but coarser workgroups fill the chip less evenly; measured
+    // equal on 3-D layers and 8 % faster on the large 2-D layers of a batch of 16.
+    if (nks == 1 && spatial_tiles * nsp * slices >= 4096 && nsp * nwc > 4) nwc = 4 / nsp;
     if (nwc < 1) nwc = 1;
     t.nwc = nwc;
     t.co_per_wave = co_per_wave;
