@@ -255,6 +255,9 @@ def main():
     result["roofline"]["measured_peak"] = probe_rate / 1e12
     result["roofline"]["frac_of_measured_peak"] = (lane_ops / probe_rate) if probe_rate > 0 else None
     result["roofline"]["issued_frac_of_measured_peak"] = (0.8 * lane_ops / probe_rate) if probe_rate > 0 else None
+    # the same instructions with no scalar instruction between them (what a compiler schedules)
+    ms_unspaced, _ = timed(lambda: T.tern_probe_valu(p_blocks, p_threads, p_iters, sink, 1), 3, 1, None)
+    result["roofline"]["measured_peak_unspaced"] = p_blocks * p_threads * p_iters * 65.0 / (ms_unspaced * 1e-3) / 1e12
 
     if args.extras:
         result["extras"] = extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, geom)

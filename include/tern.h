@@ -355,10 +355,13 @@ int tern_set_option(int option, int value);
  * convolution's instruction mix (16 word pairs = 64 integer vector instructions plus one add per
  * round and lane) on blocks x threads lanes with no memory traffic.  Timing it gives the sustained
  * lane-operation rate of the device, the measured ceiling for section 2's bit-count argument on
- * this hardware.  sink: device int32[1] (practically never written).  threads: multiple of 64,
- * at most 512.
+ * this hardware.  variant: 0 = the instruction order and spacing the convolution kernels use, 1 =
+ * the same instructions with no scalar instruction between them (for comparison).  sink: device
+ * int32[1] (practically never written).  threads: multiple of 64, at most 512.  TERN_EARG for
+ * anything else.
  */
-int tern_probe_valu(int32_t blocks, int32_t threads, int32_t iters, int32_t* sink, void* stream);
+int tern_probe_valu(int32_t blocks, int32_t threads, int32_t iters, int32_t variant, int32_t* sink,
+                    void* stream);
 
 #ifdef __cplusplus
 }

@@ -95,7 +95,7 @@ def lib():
     L.tern_fold_avgpool.argtypes = [P, I, I, I, I, I, C.POINTER(C.c_int32), P]
     L.tern_fold_avgpool.restype = C.c_int
     L.tern_set_option.argtypes = [C.c_int, C.c_int]; L.tern_set_option.restype = C.c_int
-    L.tern_probe_valu.argtypes = [I, I, I, P, P]; L.tern_probe_valu.restype = C.c_int
+    L.tern_probe_valu.argtypes = [I, I, I, I, P, P]; L.tern_probe_valu.restype = C.c_int
     _lib = L
     return L
 
@@ -362,10 +362,11 @@ def tern_fcn_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor,
     return out, views
 
 
-def tern_probe_valu(blocks: int, threads: int, iters: int, sink: torch.Tensor) -> None:
-    """Diagnostic: enqueue the instruction-mix probe (65 * iters vector instructions per lane)."""
+def tern_probe_valu(blocks: int, threads: int, iters: int, sink: torch.Tensor, variant: int = 0) -> None:
+    """Diagnostic: enqueue the instruction-mix probe (65 * iters vector instructions per lane);
+    variant 0 = the kernels' spaced sequence, 1 = the same instructions unspaced."""
     _dev(sink, torch.int32, "sink")
-    _check(lib().tern_probe_valu(int(blocks), int(threads), int(iters), _ptr(sink), _stream(sink)),
+    _check(lib().tern_probe_valu(int(blocks), int(threads), int(iters), int(variant), _ptr(sink), _stream(sink)),
            "tern_probe_valu")
 
 

@@ -157,13 +157,13 @@ __device__ __forceinline__ void settle(const WGroup<WC, KG>& g)
     }
 }
 
-// Eq. 9 for four (word pair, voxel) combinations: acc_m += popcount(ma & mw), acc_n +=
+// Eq. 9 for one (word pair, voxel) combination: acc_m += popcount(ma & mw), acc_n +=
 // popcount(ma & mw & (sa ^ sw)) -- and, popcount-accumulate, three-input bit operation (truth
 // table 0x48 = m & (sa ^ sw), index = sa<<2 | m<<1 | sw), popcount-accumulate; mw and sw are
 // wave-uniform.
 //
-// The sixteen instructions are one asm statement because their order and spacing decide the
-// issue rate on gfx950.  Measured with register-only loops of this mix (cycles per vector
+// Sixteen or thirty-two of these instructions make one asm statement (mac_quad below) because
+// their order and spacing decide the issue rate on gfx950.  Measured with register-only loops of this mix (cycles per vector
 // instruction at 2.4 GHz, four waves per SIMD): any order with no scalar instruction in between
 // 3.95-4.0, also with another vector instruction between producer and popcount; one scalar
 // instruction (s_nop 0 or any other) between the bit operation and its popcount 3.4; one between
@@ -173,25 +173,13 @@ __device__ __forceinline__ void settle(const WGroup<WC, KG>& g)
 // result.  The compiler assumes that an asm statement's outputs may need such a wait state and
 // puts an s_nop of its own in front of the next statement that touches one of them, which spoils
 // the spacing: hence four or eight word pairs per statement, and two scratch registers taken in turn.
-#ifndef TERN_MAC_PATTERN
-#define TERN_MAC_PATTERN 2
-#endif
-#if TERN_MAC_PATTERN == 1
-#define TERN_MAC_PAIR(P, C, ADD_M, ADD_N)                                             \
-    "v_and_b32 %[t], %[mw" P "], %[ma" P "]\n\t"                                   \
-    "v_bcnt_u32_b32 %[am" C "], %[t], " ADD_M "\n\t"                               \
-    "v_bitop3_b32 %[t], %[sa" P "], %[t], %[sw" P "] bitop3:0x48\n\t"              \
-    "s_nop 0\n\t"                                                                  \
-    "v_bcnt_u32_b32 %[an" C "], %[t], " ADD_N "\n\t"
-#else
-#define TERN_MAC_PAIR(P, C, ADD_M, ADD_N)                                             \
+#define TERN_MAC_PAIR(P, C, ADD_M, ADD_N)                                           \
     "v_and_b32 %[t], %[mw" P "], %[ma" P "]\n\t"                                   \
     "s_nop 0\n\t"                                                                  \
     "v_bcnt_u32_b32 %[am" C "], %[t], " ADD_M "\n\t"                               \
     "v_bitop3_b32 %[t], %[sa" P "], %[t], %[sw" P "] bitop3:0x48\n\t"              \
     "s_nop 0\n\t"                                                                  \
     "v_bcnt_u32_b32 %[an" C "], %[t], " ADD_N "\n\t"
-#endif
 #define TERN_MAC_IN(P, MA, SA, MW, SW) [ma##P] "v"(MA), [sa##P] "v"(SA), [mw##P] "s"(MW), [sw##P] "s"(SW)
 
 // All WC words of channels jg .. jg+4/V-1 of group g for all V voxels of a lane: combination c =
