@@ -92,6 +92,15 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 2, fake, need - 1, fake, C.byref(od), None, None) == -4
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 0, fake, need, fake, C.byref(od), None, None) == -3
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 2, None, need, fake, C.byref(od), None, None) == -1
+    # probe: null sink, launch shape and variant are checked before anything is launched
+    assert L.tern_probe_valu(4, 256, 10, 0, None, None) == -1
+    assert L.tern_probe_valu(4, 100, 10, 0, fake, None) == -3
+    assert L.tern_probe_valu(4, 256, 10, 2, fake, None) == -3
+    assert L.tern_probe_valu(0, 256, 10, 1, fake, None) == -3
+    # options: unknown option or value
+    assert L.tern_set_option(99, 0) == -3
+    assert L.tern_set_option(3, 24) == -3
+    assert L.tern_set_option(3, 0) == 0
     assert b"TERN_ESHAPE" in L.tern_status_string(-2)
 
 

@@ -526,3 +526,16 @@ def test_fcn_forward_replays_from_a_captured_graph(G):
         eager = T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(G.words(eager), G.words(out))
+
+
+@pytest.mark.gpu
+def test_instruction_mix_probe_runs_both_variants(G):
+    """The diagnostic kernel (no counterpart in the paper) launches in both variants and leaves
+    its sink alone."""
+    import torch
+    import paper_1801_09449_amd as T
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for variant in (0, 1):
+        T.tern_probe_valu(64, 256, 50, sink, variant)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0
