@@ -177,7 +177,9 @@ size_t tern_fcn_workspace_bytes(tern_dims in_dims, const tern_layer* layers /* h
  *               depth stride and dilation, the input region instead holds, per
  *               output voxel of layer 0, that voxel's kernel taps gathered into a bit string:
  *               Eq. 6 and the gathering run as one pass over the intensities and layer 0
- *               becomes a single-tap convolution.  Results are identical either way.)
+ *               becomes a single-tap convolution, which usually runs in that same pass on the
+ *               strings in registers; the region is then reserved but not written.  Results
+ *               are identical either way.)
  *               When layer_out (host array of n_layers pointers, may be NULL) is given,
  *               layer_out[i] receives the device address of layer i's packed output (inside
  *               workspace, or out_packed for the last layer) so that callers can inspect every

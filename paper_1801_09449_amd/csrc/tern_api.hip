@@ -372,6 +372,8 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
     // layer 0 becomes a single-tap convolution over those strings (its tap-packed filter bank is already in the
     // matching layout).  Otherwise: Eq. 6 on the raw intensities, packed, then layer 0 as is.
     const bool gathered = patch_pack_applies(in_dims.c, layers[0].g, o0);
+    PatchParams first = {};
+    bool fused = false;
     if (gathered) {
         const tern_dims patches = {o0.n, layers[0].g.k[0] * layers[0].g.k[1] * layers[0].g.k[2], o0.d, o0.h, o0.w};
         ws += (tern_packed_bytes(patches) + 255u) & ~(size_t)255u;
@@ -384,7 +386,11 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
         pp.sh = g.stride[1]; pp.sw = g.stride[2];
         pp.pd = g.pad[0]; pp.ph = g.pad[1]; pp.pw = g.pad[2];
         pp.dh = g.dil[1]; pp.dw = g.dil[2];
-        rc = launch_patch_pack_f32(pp, in_dims.n, (hipStream_t)stream);
+        // layer 0 runs behind the gathering in the same kernel (below) where that pays; the
+        // region reserved for the tap strings then stays unused
+        first = pp;
+        fused = patch_conv_pays(pp, in_dims.n);
+        rc = fused ? TERN_OK : launch_patch_pack_f32(pp, in_dims.n, (hipStream_t)stream);
     } else {
         ws += (tern_packed_bytes(in_dims) + 255u) & ~(size_t)255u;
         rc = tern_threshold_pack(in, TERN_SRC_F32, in_dims, in_lo, in_hi, cur_buf, stream);
@@ -401,13 +407,24 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
         } else {
             dst = out_packed;
         }
-        if (i == 0 && gathered) {
+        if (i == 0 && gathered && !fused) {
             const int32_t taps = layers[0].g.k[0] * layers[0].g.k[1] * layers[0].g.k[2];
             const tern_dims pin = {o.n, taps, o.d, o.h, o.w};
             const tern_conv_geom unit = {{1, 1, 1}, {1, 1, 1}, {0, 0, 0}, {1, 1, 1}};
+            if (!layers[0].w_bank || !layers[0].thr_lo || !layers[0].thr_hi) return TERN_ENULL;
+            if (!aligned16(layers[0].w_bank) || !aligned16(dst)) return TERN_EARG;
             rc = launch_conv3d(conv_params(cur_buf, pin, layers[0].w_bank, layers[0].c_out, unit, o,
                                            layers[0].thr_lo, layers[0].thr_hi, nullptr, dst),
                                (hipStream_t)stream);
+        } else if (i == 0 && gathered) {
+            if (!layers[0].w_bank || !layers[0].thr_lo || !layers[0].thr_hi) return TERN_ENULL;
+            if (!aligned16(layers[0].w_bank) || !aligned16(dst)) return TERN_EARG;
+            FirstConvParams fc;
+            fc.wgt = layers[0].w_bank; fc.lo = layers[0].thr_lo; fc.hi = layers[0].thr_hi;
+            fc.out_packed = dst;
+            fc.c_out = layers[0].c_out; fc.co_pad = (layers[0].c_out + 31) / 32 * 32;
+            fc.wd_out = tern_words(layers[0].c_out);
+            rc = launch_patch_conv_f32(first, fc, in_dims.n, (hipStream_t)stream);
         } else {
             rc = tern_conv3d(cur_buf, cur, layers[i].w_bank, layers[i].c_out, layers[i].g,
                              layers[i].thr_lo, layers[i].thr_hi, nullptr, dst, stream);
@@ -459,6 +476,8 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
     } else {
         off += region(in_dims);
     }
+    PatchParams first = {};
+    bool fused = false;
     if (w && w->run) {
         int rc;
         if (gathered) {
@@ -471,7 +490,11 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
             pp.sh = g.stride[1]; pp.sw = g.stride[2];
             pp.pd = g.pad[0]; pp.ph = g.pad[1]; pp.pw = g.pad[2];
             pp.dh = g.dil[1]; pp.dw = g.dil[2];
-            rc = launch_patch_pack_f32(pp, in_dims.n, w->stream);
+            // module 0 runs behind the gathering in the same kernel (below) where that pays; the
+            // region reserved for the tap strings then stays unused
+            first = pp;
+            fused = patch_conv_pays(pp, in_dims.n);
+            rc = fused ? TERN_OK : launch_patch_pack_f32(pp, in_dims.n, w->stream);
         } else {
             rc = tern_threshold_pack(w->in, TERN_SRC_F32, in_dims, w->in_lo, w->in_hi,
                                      (uint32_t*)(w->ws + in_off), w->stream);
@@ -524,7 +547,7 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
         off += region(o);
         if (w && w->run) {
             if (!m.w_bank || !m.thr_lo || !m.thr_hi) return TERN_ENULL;
-            if (i == 0 && gathered) {
+            if (i == 0 && gathered && !fused) {
                 // single-tap convolution over the gathered words
                 const int32_t taps = m.g.k[0] * m.g.k[1] * m.g.k[2];
                 const tern_dims pin = {o.n, taps, o.d, o.h, o.w};
@@ -534,6 +557,15 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
                                                o, m.thr_lo, m.thr_hi, nullptr,
                                                (uint32_t*)(w->ws + ooff[(size_t)i])),
                                    w->stream);
+            } else if (i == 0 && gathered) {
+                // gathering and single-tap convolution over the gathered words in one kernel
+                if (!aligned16(m.w_bank)) return TERN_EARG;
+                FirstConvParams fc;
+                fc.wgt = m.w_bank; fc.lo = m.thr_lo; fc.hi = m.thr_hi;
+                fc.out_packed = (uint32_t*)(w->ws + ooff[(size_t)i]);
+                fc.c_out = m.c_out; fc.co_pad = (m.c_out + 31) / 32 * 32;
+                fc.wd_out = tern_words(m.c_out);
+                rc = launch_patch_conv_f32(first, fc, in_dims.n, w->stream);
             } else {
                 rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
                                  m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);

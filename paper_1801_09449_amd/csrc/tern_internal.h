@@ -105,6 +105,17 @@ struct PatchParams {
 // that route.
 bool patch_pack_applies(int32_t c_in, const tern_conv_geom& g, const tern_dims& out);
 int launch_patch_pack_f32(const PatchParams& p, int32_t n, hipStream_t s);
+// Layer 0 behind the gathering, in the same kernel (PatchParams::dst unused): single-tap filter
+// bank over the gathered words, integer cut points, packed output [N][od][oh][ow][2][wd_out].
+struct FirstConvParams {
+    const uint32_t* wgt;    // [words of the tap string][co_pad][2][1]
+    const int32_t* lo;      // [c_out]
+    const int32_t* hi;
+    uint32_t* out_packed;
+    int32_t c_out, co_pad, wd_out;
+};
+int launch_patch_conv_f32(const PatchParams& p, const FirstConvParams& c, int32_t n, hipStream_t s);
+bool patch_conv_pays(const PatchParams& p, int32_t n);
 
 // Launchers implemented in the kernel translation units.  Each validates nothing (the entry
 // points did) and returns a tern_status.

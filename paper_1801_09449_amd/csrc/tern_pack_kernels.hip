@@ -5,6 +5,9 @@
 //     the hard activation of Eq. 6               (tern_threshold_pack)
 // All three are HBM-bound streams.  A thread owns VPT consecutive voxels of one batch item and
 // walks the channel words; for a fixed channel the lanes of a wave read consecutive addresses.
+#include <type_traits>
+
+#include "tern_conv_common.h"
 #include "tern_internal.h"
 
 namespace tern {
@@ -327,18 +330,14 @@ int launch_threshold_pack_f32(const float* src, tern_dims dims, const float* lo,
 namespace {
 
 // PZ = output planes per thread, WDP = words per plane of the gathered tap string.
+// Tap strings of output voxels (ox, oy, oz0 .. oz0+PZ-1) of batch item n: wm[t][q], ws[t][q].
 template <int KD, int KH, int KW, int PZ>
-__global__ __launch_bounds__(256) void patch_pack_f32_kernel(PatchParams p)
+__device__ __forceinline__ void gather_taps(const PatchParams& p, int n, int ox, int oy, int oz0,
+                                            uint32_t (&wm)[PZ][(KD * KH * KW + 31) / 32],
+                                            uint32_t (&ws)[PZ][(KD * KH * KW + 31) / 32])
 {
-    constexpr int kPatchZ = PZ;
     constexpr int NB = KH * KW;   // taps per input plane
     constexpr int WDP = (KD * NB + 31) / 32;
-    const int ox = blockIdx.x * 64 + threadIdx.x;
-    const int oy = blockIdx.y * 4 + threadIdx.y;
-    const int nseg = (p.od + kPatchZ - 1) / kPatchZ;
-    const int seg = blockIdx.z % nseg;
-    const int n = blockIdx.z / nseg;
-    if (ox >= p.ow || oy >= p.oh) return;
     const float lo = p.lo[0], hi = p.hi[0];
     const float* src_n = p.src + (size_t)n * p.d * p.h * p.w;
     const size_t plane = (size_t)p.h * p.w;
@@ -360,8 +359,7 @@ __global__ __launch_bounds__(256) void patch_pack_f32_kernel(PatchParams p)
 
     // All input planes this thread needs, fetched before any of them is used: one memory round
     // trip for the whole walk.  Planes outside the volume read plane 0 and are masked out.
-    constexpr int NP = kPatchZ + KD - 1;
-    const int oz0 = seg * kPatchZ;
+    constexpr int NP = PZ + KD - 1;
     float v[NP][NB];
 #pragma unroll
     for (int j = 0; j < NP; ++j) {
@@ -391,32 +389,138 @@ __global__ __launch_bounds__(256) void patch_pack_f32_kernel(PatchParams p)
         m[j] = P | N;
         s[j] = N;
     }
-    uint32_t* out = p.dst + ((((size_t)n * p.od + oz0) * p.oh + oy) * p.ow + ox) * 2u * WDP;
-    const size_t ostep = (size_t)p.oh * p.ow * 2u * WDP;
 #pragma unroll
-    for (int t = 0; t < kPatchZ; ++t) {
-        if (oz0 + t >= p.od) break;
+    for (int t = 0; t < PZ; ++t) {
         // plane a of the kernel occupies bits [a*NB, a*NB + NB) of the tap string
-        uint32_t wm[WDP], ws[WDP];
 #pragma unroll
-        for (int q = 0; q < WDP; ++q) wm[q] = ws[q] = 0u;
+        for (int q = 0; q < WDP; ++q) wm[t][q] = ws[t][q] = 0u;
 #pragma unroll
         for (int a = 0; a < KD; ++a) {
             constexpr int kNB = NB;
             const int word = (a * kNB) / 32, sh = (a * kNB) % 32;
-            wm[word] |= m[t + a] << sh;
-            ws[word] |= s[t + a] << sh;
+            wm[t][word] |= m[t + a] << sh;
+            ws[t][word] |= s[t + a] << sh;
             if (sh + kNB > 32) {
-                wm[word + 1] |= m[t + a] >> (32 - sh);
-                ws[word + 1] |= s[t + a] >> (32 - sh);
+                wm[t][word + 1] |= m[t + a] >> (32 - sh);
+                ws[t][word + 1] |= s[t + a] >> (32 - sh);
             }
         }
+    }
+}
+
+template <int KD, int KH, int KW, int PZ>
+__global__ __launch_bounds__(256) void patch_pack_f32_kernel(PatchParams p)
+{
+    constexpr int WDP = (KD * KH * KW + 31) / 32;
+    const int ox = blockIdx.x * 64 + threadIdx.x;
+    const int oy = blockIdx.y * 4 + threadIdx.y;
+    const int nseg = (p.od + PZ - 1) / PZ;
+    const int seg = blockIdx.z % nseg;
+    const int n = blockIdx.z / nseg;
+    if (ox >= p.ow || oy >= p.oh) return;
+    const int oz0 = seg * PZ;
+    uint32_t wm[PZ][WDP], ws[PZ][WDP];
+    gather_taps<KD, KH, KW, PZ>(p, n, ox, oy, oz0, wm, ws);
+    uint32_t* out = p.dst + ((((size_t)n * p.od + oz0) * p.oh + oy) * p.ow + ox) * 2u * WDP;
+    const size_t ostep = (size_t)p.oh * p.ow * 2u * WDP;
+#pragma unroll
+    for (int t = 0; t < PZ; ++t) {
+        if (oz0 + t >= p.od) break;
         uint32_t* o = out + (size_t)t * ostep;
         if constexpr (WDP == 1) {
-            *reinterpret_cast<uint2*>(o) = make_uint2(wm[0], ws[0]);
+            *reinterpret_cast<uint2*>(o) = make_uint2(wm[t][0], ws[t][0]);
         } else {
 #pragma unroll
-            for (int q = 0; q < WDP; ++q) { o[q] = wm[q]; o[WDP + q] = ws[q]; }
+            for (int q = 0; q < WDP; ++q) { o[q] = wm[t][q]; o[WDP + q] = ws[t][q]; }
+        }
+    }
+}
+
+// The same gathering with layer 0's convolution behind it: the tap strings stay in registers and
+// go straight through the word-pair sequence of the convolution kernels (Eq. 9 over the T
+// gathered "channels"), the cut points of layer 0's activation (Eq. 6) and the re-packing, so
+// that neither the ternarised input nor the tap strings ever reach memory.  Filter bank: the
+// single-tap bank over T channels [WDP][co_pad][2][1], which is the tap-packed bank of the
+// original kernel word for word.  VH voxels of a thread are convolved together (4 of the 8 planes
+// of a column, or the single one).
+template <int KD, int KH, int KW, int PZ>
+__global__ __launch_bounds__(256) void patch_conv_f32_kernel(PatchParams p, FirstConvParams c)
+{
+    constexpr int WDP = (KD * KH * KW + 31) / 32;
+    constexpr int VH = PZ >= 4 ? 4 : 1;
+    constexpr int CO_BLK = 16;
+    constexpr int KG = GroupOf<CO_BLK>::value;
+    constexpr int NG = CO_BLK / KG;
+    static_assert(PZ % VH == 0, "whole groups of voxels");
+    const int ox = blockIdx.x * 64 + threadIdx.x;
+    const int oy = blockIdx.y * 4 + threadIdx.y;
+    const int nseg = (p.od + PZ - 1) / PZ;
+    const int seg = blockIdx.z % nseg;
+    const int n = blockIdx.z / nseg;
+    if (ox >= p.ow || oy >= p.oh) return;   // (no cross-lane operation below)
+    const int oz0 = seg * PZ;
+    uint32_t wm[PZ][WDP], ws[PZ][WDP];
+    gather_taps<KD, KH, KW, PZ>(p, n, ox, oy, oz0, wm, ws);
+
+    const int step_words = c.co_pad * 2;   // filter-bank words per gathered word
+    const size_t ostep = (size_t)p.oh * p.ow * 2u * c.wd_out;
+    uint32_t* out = c.out_packed + ((((size_t)n * p.od + oz0) * p.oh + oy) * p.ow + ox) * 2u * c.wd_out;
+#pragma unroll
+    for (int h = 0; h < PZ / VH; ++h) {
+        ActChunk<1> A[WDP][VH];
+#pragma unroll
+        for (int q = 0; q < WDP; ++q)
+#pragma unroll
+            for (int v = 0; v < VH; ++v) { A[q][v].m[0] = wm[h * VH + v][q]; A[q][v].s[0] = ws[h * VH + v][q]; }
+        uint32_t pos_w[VH], neg_w[VH];
+#pragma unroll
+        for (int v = 0; v < VH; ++v) pos_w[v] = neg_w[v] = 0u;
+        for (int cb = 0; cb < c.c_out; cb += CO_BLK) {
+            int32_t acc_m[VH][CO_BLK], acc_n[VH][CO_BLK];   // set by the first word
+            scalar_ptr wbase = (scalar_ptr)(uintptr_t)c.wgt + (size_t)cb * 2;
+            WGroup<1, KG> g[2];
+            load_wgroup<1, KG>(g[0], wbase);
+            auto group_step = [&](int idx, auto init) {
+                const int q = idx / NG, gi = idx % NG;
+                settle<1, KG>(g[idx & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (idx + 1 < WDP * NG) {
+                    const int nq = (idx + 1) / NG, ngi = (idx + 1) % NG;
+                    load_wgroup<1, KG>(g[(idx + 1) & 1], wbase + (size_t)nq * step_words + ngi * KG * 2);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                mac_group<1, VH, CO_BLK, KG, decltype(init)::value>(A[q], g[idx & 1], gi * KG, acc_m, acc_n);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+#pragma unroll
+            for (int idx = 0; idx < NG; ++idx) group_step(idx, std::true_type{});
+#pragma unroll
+            for (int idx = NG; idx < WDP * NG; ++idx) group_step(idx, std::false_type{});
+
+            int32_t d[VH][CO_BLK];
+#pragma unroll
+            for (int v = 0; v < VH; ++v)
+#pragma unroll
+                for (int j = 0; j < CO_BLK; ++j) d[v][j] = acc_m[v][j] - 2 * acc_n[v][j];
+            uint32_t pp[VH], pn[VH];
+            ternarise_pass<VH, CO_BLK>(d, (scalar_ptr)(uintptr_t)c.lo, (scalar_ptr)(uintptr_t)c.hi, cb,
+                                       c.c_out - cb, c.c_out, pp, pn);
+            const int sh = cb & 31;
+#pragma unroll
+            for (int v = 0; v < VH; ++v) { pos_w[v] |= pp[v] << sh; neg_w[v] |= pn[v] << sh; }
+            if (((cb + CO_BLK) & 31) == 0 || cb + CO_BLK >= c.c_out) {
+                const int q = cb >> 5;
+#pragma unroll
+                for (int v = 0; v < VH; ++v) {
+                    const int t = h * VH + v;
+                    if (oz0 + t < p.od) {
+                        uint32_t* o = out + (size_t)t * ostep;
+                        o[q] = pos_w[v] | neg_w[v];
+                        o[c.wd_out + q] = neg_w[v] & ~pos_w[v];    // +1 wins if lo > hi
+                    }
+                    pos_w[v] = neg_w[v] = 0u;
+                }
+            }
         }
     }
 }
@@ -454,6 +558,31 @@ int launch_patch_pack_f32(const PatchParams& p, int32_t n, hipStream_t s)
         hipLaunchKernelGGL((patch_pack_f32_kernel<1, 3, 3, 8>), grid, block, 0, s, p);
     else
         hipLaunchKernelGGL((patch_pack_f32_kernel<15, 3, 3, 1>), grid, block, 0, s, p);
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
+
+// Whether layer 0 should run behind the gathering in one kernel.  The 15x3x3 variant holds 135
+// intensities per lane and fits only two waves per SIMD: good for one stack of slices (one launch
+// instead of two latency-bound ones), slower than gathering and convolving separately for many.
+bool patch_conv_pays(const PatchParams& p, int32_t n)
+{
+    if (p.kd != 15) return true;
+    return (int64_t)n * p.od * p.oh * p.ow <= 131072;
+}
+
+int launch_patch_conv_f32(const PatchParams& p, const FirstConvParams& c, int32_t n, hipStream_t s)
+{
+    const int pz = patch_planes_per_thread(p.kd, p.kh, p.kw);
+    if (pz == 0) return TERN_EARG;
+    const int nseg = (p.od + pz - 1) / pz;
+    const dim3 grid((unsigned)((p.ow + 63) / 64), (unsigned)((p.oh + 3) / 4), (unsigned)(nseg * n)), block(64, 4);
+    if (p.kd == 3)
+        hipLaunchKernelGGL((patch_conv_f32_kernel<3, 3, 3, 8>), grid, block, 0, s, p, c);
+    else if (p.kd == 1)
+        hipLaunchKernelGGL((patch_conv_f32_kernel<1, 3, 3, 8>), grid, block, 0, s, p, c);
+    else
+        hipLaunchKernelGGL((patch_conv_f32_kernel<15, 3, 3, 1>), grid, block, 0, s, p, c);
     TERN_HIP_CHECK(hipGetLastError());
     return TERN_OK;
 }

@@ -236,6 +236,13 @@ def test_unet_reduced(G):
     check_unet(G, synth.unet_table1(seed=6, n=1, width_div=3, size=(92, 100), slices=15))
 
 
+def test_unet_many_stacks_take_the_two_kernel_first_module(G):
+    """Four full-size stacks, narrow channels: module #1 has more output voxels than the fused
+    gather-and-convolve kernel is used for, so its taps are gathered to memory and convolved by the
+    pointwise kernel over five words (one stack takes the fused kernel, see the full-size test)."""
+    check_unet(G, synth.unet_table1(seed=7, n=4, width_div=8))
+
+
 def test_unet_table1_full_size(G):
     """The network at the paper's size (236 x 172 x 15 stack, full channel counts), one stack."""
     check_unet(G, synth.unet_table1(seed=0, n=1))
