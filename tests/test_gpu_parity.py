@@ -425,6 +425,28 @@ def test_fcn_first_layer_geometries(G, k, stride, pad, dil):
     assert len(np.unique(want[0])) == 3
 
 
+@pytest.mark.parametrize("k,pad,c_out", [((3, 3, 3), (1, 1, 1), 70), ((15, 3, 3), (0, 1, 0), 33),
+                                         ((1, 3, 3), (0, 0, 2), 97)], ids=["3x3x3-70", "15x3x3-33", "1x3x3-97"])
+def test_fcn_first_layer_more_than_one_output_word(G, k, pad, c_out):
+    """The fused first-layer kernel with more than 32 output channels (several packed words per
+    voxel, a ragged last pass), followed by a layer that reads them."""
+    vol = (17, 21, 70)
+    x = synth.gaussian((1, 1) + vol, 67, synth.T_F32)
+    in_lo, in_hi = np.array([-0.4], np.float32), np.array([0.4], np.float32)
+    layers, c_in = [], 1
+    for li, (co, kk, pd) in enumerate([(c_out, k, pad), (16, (1, 1, 1), (0, 0, 0))], start=1):
+        w = synth.ternary((co, c_in) + kk, 0.5, 67, synth.T_WGT + 8 * li)
+        lo, hi = synth.bn_like_thresholds(co, int(np.prod(kk)), c_in, 0.5, 0.6, 67, synth.T_THR + 8 * li)
+        layers.append(dict(w=w, k=kk, stride=(1, 1, 1), pad=pd, dil=(1, 1, 1), lo=lo, hi=hi))
+        c_in = co
+    f = synth.FcnCase("first-wide", x, in_lo, in_hi, layers)
+    got = fcn_run(G, f)
+    want = fcn_expect(f)
+    for i, ((w, dm), code) in enumerate(zip(got, want)):
+        assert tuple(dm) == code.shape, f"layer {i + 1}"
+        np.testing.assert_array_equal(w, oracle.pack(code), err_msg=f"layer {i + 1}")
+
+
 # ---- tensors above 4 GiB: byte offsets need 64 bits, voxel indices still fit 32 ---------------
 @pytest.mark.parametrize("c_in,c_out", [(1, 33), (17, 8)], ids=["tap-packed", "plain"])
 def test_volume_above_4gib_sampled(G, c_in, c_out):
