@@ -14,7 +14,8 @@ from .tern_oracle import (  # noqa: F401
     threshold,
     unpack,
 )
-from .prepare_oracle import activation_code, bn_affine, ternarize_filters  # noqa: F401,E402
+from .prepare_oracle import (activation_code, bn_affine, ternarize_filters,  # noqa: F401,E402
+                             ternarize_filters_sparse)
 from .unet_oracle import (  # noqa: F401,E402
     centre_crop,
     concat_channels,

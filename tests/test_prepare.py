@@ -60,6 +60,56 @@ def test_oracle_ternarize_invariants_and_gaussian_sparsity():
     assert np.all(np.abs(ab - want_alpha) < 0.02)
 
 
+def test_oracle_sparse_ternarize_hand_worked_and_properties():
+    # magnitudes 0.9 0.1 0.5 0.8 0.5 0.0: the three smallest are 0.0, 0.1 and the first of the 0.5s
+    w = np.array([[0.9, -0.1, 0.5, -0.8, -0.5, 0.0]])
+    codes, alpha = oracle.ternarize_filters_sparse(w, 3)
+    np.testing.assert_array_equal(codes, [[1, 0, 0, -1, -1, 0]])
+    assert alpha[0] == pytest.approx((0.9 + 0.8 + 0.5) / 3, rel=1e-15)
+    # nothing zeroed: plain signs (an exact zero has no sign); everything zeroed: alpha 0
+    codes, alpha = oracle.ternarize_filters_sparse(w, 0)
+    np.testing.assert_array_equal(codes, [[1, -1, 1, -1, -1, 0]])
+    assert alpha[0] == pytest.approx(2.8 / 5, rel=1e-15)
+    codes, alpha = oracle.ternarize_filters_sparse(w, 6)
+    assert not codes.any() and alpha[0] == 0.0
+    with pytest.raises(ValueError):
+        oracle.ternarize_filters_sparse(w, 7)
+    # continuous weights: exactly `zeros` zeros per filter, a threshold separates zeroed from kept
+    # magnitudes, kept entries carry their sign, alpha is their mean magnitude
+    g = synth.gaussian((6, 4, 3, 3, 3), 13, synth.T_F32).astype(np.float64)
+    per = g[0].size
+    for zeros in (0, 1, per // 2, per - 1):
+        codes, alpha = oracle.ternarize_filters_sparse(g, zeros)
+        flat, cf = np.abs(g).reshape(6, -1), codes.reshape(6, -1)
+        assert (np.sum(cf == 0, axis=1) == zeros).all()
+        for co in range(6):
+            z, k = flat[co][cf[co] == 0], flat[co][cf[co] != 0]
+            if z.size and k.size:
+                assert z.max() <= k.min()
+            np.testing.assert_array_equal(cf[co][cf[co] != 0], np.sign(g[co].reshape(-1))[cf[co] != 0])
+            assert alpha[co] == pytest.approx(k.mean() if k.size else 0.0, rel=1e-14)
+    # given the zero count that Eq. 4's own Delta produces, the rule reproduces Eq. 4 filter by filter
+    want_c, want_a = oracle.ternarize_filters(g)
+    for co in range(6):
+        z = int(np.sum(want_c[co] == 0))
+        c1, a1 = oracle.ternarize_filters_sparse(g[co:co + 1], z)
+        np.testing.assert_array_equal(c1[0], want_c[co])
+        assert a1[0] == pytest.approx(want_a[co], rel=1e-14)
+    # half of N(0,1) weights zeroed: the implied Delta is the median magnitude 0.6745, and
+    # alpha = E[|w| given |w| > median] = 2 * phi(0.6745) / 0.5
+    big = synth.gaussian((4, 1 << 16), 9, synth.T_F32).astype(np.float64)
+    cb, ab = oracle.ternarize_filters_sparse(big, 1 << 15)
+    kept_min = np.array([np.abs(big[i])[cb[i] != 0].min() for i in range(4)])
+    assert np.all(np.abs(kept_min - 0.6745) < 0.01)
+    want_alpha = 2 * math.exp(-0.6745 ** 2 / 2) / math.sqrt(2 * math.pi) / 0.5
+    assert np.all(np.abs(ab - want_alpha) < 0.01)
+    # sign symmetry and exact power-of-two scaling
+    c2, a2 = oracle.ternarize_filters_sparse(-4.0 * g, per // 2)
+    c1, a1 = oracle.ternarize_filters_sparse(g, per // 2)
+    np.testing.assert_array_equal(c2, -c1)
+    np.testing.assert_allclose(a2, 4.0 * a1, rtol=1e-15)
+
+
 def test_oracle_activation_code_is_eq6():
     acc = np.array([-3, -2, -1, 0, 1, 2, 3])
     # y = 0.5*acc: ties at acc = +-1 fall in the inclusive zero band
@@ -82,6 +132,25 @@ def test_ternarize_filters_matches_oracle(T):
     np.testing.assert_array_equal(codes, want_c)
     np.testing.assert_allclose(alpha, want_a, rtol=1e-12, atol=0)
     assert codes.dtype == np.int8 and codes.shape == w.shape
+
+
+def test_ternarize_filters_sparse_matches_oracle(T):
+    w = synth.gaussian((12, 8, 3, 3, 3), 17, synth.T_F32)
+    w[0] = 0.0
+    w[1, :3] = 0.25          # ties, also across the cut
+    w[1, 3:6] = -0.25
+    w[2] = np.round(w[2] * 4) / 4   # many equal magnitudes
+    per = w[0].size
+    for zeros in (0, 1, per // 2, per - 1, per):
+        codes, alpha = T.tern_ternarize_filters_sparse(w, zeros)
+        want_c, want_a = oracle.ternarize_filters_sparse(w, zeros)
+        np.testing.assert_array_equal(codes, want_c)
+        np.testing.assert_allclose(alpha, want_a, rtol=1e-12, atol=0)
+    assert codes.dtype == np.int8 and codes.shape == w.shape
+    with pytest.raises(Exception):
+        T.tern_ternarize_filters_sparse(w, per + 1)
+    with pytest.raises(Exception):
+        T.tern_ternarize_filters_sparse(w, -1)
 
 
 def rule(acc, lo, hi):
