@@ -314,6 +314,14 @@ int tern_fold_avgpool(const int8_t* w /* host */, int32_t c_out, int32_t c_in, i
  *   codes  : int8  [c_out][per_filter]  (ready for tern_pack_filters once copied to the device)
  *   alpha  : double[c_out]
  *
+ * tern_ternarize_filters_sparse -- the same with a prescribed sparsity (section 2, the remark
+ * after Eq. 9: Delta placed so that a given share of every kernel's entries, half in the paper's
+ * example, is zero).  Per output filter the `zeros` entries of smallest magnitude become 0 (equal
+ * magnitudes in index order), the others take their sign (an entry that is exactly 0 stays 0, so
+ * there can be more zeros than asked for); alpha = mean magnitude of the nonzero codes' entries.
+ * 0 <= zeros <= per_filter, else TERN_EARG.  Only the quantiser is provided: the convolution
+ * treats such filters like any others (the paper does not say how the bit-counts would halve).
+ *
  * tern_fold_thresholds -- integer cut points for the activation of Eq. 6 applied to
  * y = scale[c]*acc + shift[c] (scale and shift collect alpha and the batch-norm affine, which sit
  * between convolution and activation in a TernaryNet module, section 2).  For every integer acc
@@ -328,6 +336,8 @@ int tern_fold_avgpool(const int8_t* w /* host */, int32_t c_out, int32_t c_in, i
  */
 int tern_ternarize_filters(const float* w /* host */, int32_t c_out, int64_t per_filter,
                            int8_t* codes /* host */, double* alpha /* host */);
+int tern_ternarize_filters_sparse(const float* w /* host */, int32_t c_out, int64_t per_filter,
+                                  int64_t zeros, int8_t* codes /* host */, double* alpha /* host */);
 int tern_fold_thresholds(const double* scale /* host */, const double* shift /* host */, int32_t c,
                          int32_t acc_bound, int32_t* lo /* host */, int32_t* hi /* host */,
                          uint8_t* negate /* host */);

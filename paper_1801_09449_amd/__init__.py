@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     tern_fold_batchnorm,
     tern_fold_thresholds,
     tern_ternarize_filters,
+    tern_ternarize_filters_sparse,
     tern_pack,
     tern_pack_filters,
     tern_packed_bytes,

@@ -82,6 +82,8 @@ def lib():
                                    C.POINTER(C.c_void_p), P]
     L.tern_fcn_forward.restype = C.c_int
     L.tern_ternarize_filters.argtypes = [P, I, C.c_int64, P, P]; L.tern_ternarize_filters.restype = C.c_int
+    L.tern_ternarize_filters_sparse.argtypes = [P, I, C.c_int64, C.c_int64, P, P]
+    L.tern_ternarize_filters_sparse.restype = C.c_int
     L.tern_fold_thresholds.argtypes = [P, P, I, I, P, P, P]; L.tern_fold_thresholds.restype = C.c_int
     L.tern_fold_batchnorm.argtypes = [P, P, P, P, P, C.c_double, I, I, P, P, P]
     L.tern_fold_batchnorm.restype = C.c_int
@@ -578,6 +580,20 @@ def tern_ternarize_filters(w):
     alpha = np.empty(w.shape[0], dtype=np.float64)
     _check(lib().tern_ternarize_filters(_np_ptr(w), w.shape[0], w.size // w.shape[0], _np_ptr(codes),
                                         _np_ptr(alpha)), "tern_ternarize_filters")
+    return codes, alpha
+
+
+def tern_ternarize_filters_sparse(w, zeros: int):
+    """As tern_ternarize_filters, with `zeros` entries of every filter (those of smallest magnitude)
+    set to 0 instead of Eq. 4's threshold."""
+    import numpy as np
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    if w.ndim < 2:
+        raise ValueError("w must be [C_out][...]")
+    codes = np.empty(w.shape, dtype=np.int8)
+    alpha = np.empty(w.shape[0], dtype=np.float64)
+    _check(lib().tern_ternarize_filters_sparse(_np_ptr(w), w.shape[0], w.size // w.shape[0], int(zeros),
+                                               _np_ptr(codes), _np_ptr(alpha)), "tern_ternarize_filters_sparse")
     return codes, alpha
 
 

@@ -1,9 +1,12 @@
 // Host-side model preparation (runs on the CPU, touches no device memory): turning trained float
 // weights and batch-norm statistics into what the convolution kernels take -- ternary filter
-// codes plus one scale per output channel (Eq. 4), and two integer cut points per output channel
+// codes plus one scale per output channel (Eq. 4, or with a prescribed number of zeros per filter
+// as in the remark after Eq. 9), and two integer cut points per output channel
 // that reproduce the ternary activation (Eq. 6) applied after scale and batch-norm (section 2).
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <vector>
 
 #include "tern.h"
 
@@ -42,6 +45,39 @@ int tern_ternarize_filters(const float* w, int32_t c_out, int64_t per_filter, in
             else if (!(std::fabs(v) <= delta)) t = -1;
             out[i] = t;
             if (t != 0) { kept += std::fabs(v); ++n_kept; }
+        }
+        alpha[co] = n_kept ? kept / (double)n_kept : 0.0;
+    }
+    return TERN_OK;
+}
+
+int tern_ternarize_filters_sparse(const float* w, int32_t c_out, int64_t per_filter, int64_t zeros,
+                                  int8_t* codes, double* alpha)
+{
+    if (!w || !codes || !alpha) return TERN_ENULL;
+    if (c_out <= 0 || per_filter <= 0) return TERN_ESHAPE;
+    if (zeros < 0 || zeros > per_filter) return TERN_EARG;
+    std::vector<int64_t> order((size_t)per_filter);
+    for (int32_t co = 0; co < c_out; ++co) {
+        const float* row = w + (size_t)co * per_filter;
+        int8_t* out = codes + (size_t)co * per_filter;
+        for (int64_t i = 0; i < per_filter; ++i) order[(size_t)i] = i;
+        // the `zeros` entries of smallest magnitude, equal magnitudes in index order: only the cut
+        // matters, so a selection instead of a full sort
+        const auto smaller = [row](int64_t a, int64_t b) {
+            const float fa = std::fabs(row[a]), fb = std::fabs(row[b]);
+            return fa < fb || (fa == fb && a < b);
+        };
+        if (zeros > 0 && zeros < per_filter)
+            std::nth_element(order.begin(), order.begin() + zeros, order.end(), smaller);
+        double kept = 0.0;
+        int64_t n_kept = 0;
+        for (int64_t r = 0; r < per_filter; ++r) {
+            const int64_t i = order[(size_t)r];
+            int8_t t = 0;
+            if (r >= zeros) t = row[i] > 0.0f ? 1 : (row[i] < 0.0f ? -1 : 0);
+            out[i] = t;
+            if (t != 0) { kept += std::fabs((double)row[i]); ++n_kept; }
         }
         alpha[co] = n_kept ? kept / (double)n_kept : 0.0;
     }

@@ -219,11 +219,16 @@ def test_module_chain_float_reference_equals_folded_integer_path(T):
 
 
 @pytest.mark.gpu
-def test_prepared_module_on_gpu_matches_float_reference(T):
+@pytest.mark.parametrize("half_zero", [False, True], ids=["eq4", "half-zero"])
+def test_prepared_module_on_gpu_matches_float_reference(T, half_zero):
     import torch
     c_in, c_out, vol = 40, 48, (6, 9, 10)
     wf = synth.gaussian((c_out, c_in, 3, 3, 3), 19, synth.T_F32)
-    codes, alpha = T.tern_ternarize_filters(wf)
+    if half_zero:   # the paper's example of a prescribed sparsity: half of every filter zero
+        codes, alpha = T.tern_ternarize_filters_sparse(wf, wf[0].size // 2)
+        assert (np.sum(codes.reshape(c_out, -1) == 0, axis=1) == wf[0].size // 2).all()
+    else:
+        codes, alpha = T.tern_ternarize_filters(wf)
     act = synth.ternary((1, c_in) + vol, 0.4, 19, synth.T_ACT)
     u = synth.uniform01(4 * c_out, 19, 5).reshape(c_out, 4)
     gamma, beta, mean, var = (u[:, 0] - 0.3) * 2.0, u[:, 1] - 0.5, (u[:, 2] - 0.5) * 8.0, u[:, 3] * 25.0 + 0.1
