@@ -21,6 +21,7 @@ from .unet_oracle import (  # noqa: F401,E402
     concat_channels,
     conv3d_real,
     count_codes,
+    pool_digits,
     pool_sum,
     unet_forward,
     upsample_nearest,

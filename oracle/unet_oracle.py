@@ -17,9 +17,14 @@ Readings of the paper taken here (it names the operations but not their details)
 * Prediction layer: an ordinary cross-correlation of the ternary codes with real-valued weights
   plus a bias, evaluated in float64.
 
+* A window sum of at most four ternary codes can also be written with two ternary digits,
+  low + 3 * high (balanced ternary, unique on [-4, 4]); pool_digits() returns them.  Nothing in
+  the paper: it is this build's way of keeping pooled tensors in the 2-bit format.
+
 Pins: tests/test_unet_oracle.py (index-by-index brute force, hand-worked arrays, cross-check of
 the real-weight convolution against a library convolution, pooling folded into a strided
-convolution with repeated taps).
+convolution with repeated taps, digits: reconstruction of the sums and digit range on all 81
+windows of four codes).
 """
 from typing import Sequence, Tuple
 
@@ -38,6 +43,20 @@ def pool_sum(x: np.ndarray, window: Tuple[int, int, int]) -> np.ndarray:
             for e in range(pw):
                 out += x[:, :, a:od * pd:pd, b:oh * ph:ph, e:ow * pw:pw]
     return out.astype(x.dtype)
+
+
+def pool_digits(x: np.ndarray, window: Tuple[int, int, int]):
+    """Balanced-ternary digits of the window sums of ternary codes: (low, high) int8 tensors of
+    pool_sum's shape with low + 3 * high == pool_sum(x, window) and both in {-1, 0, +1}; defined
+    for windows of at most 4 voxels (sums in [-4, 4], where the representation exists and is
+    unique).  Written as the definition: the high digit is the sum divided by 3 and rounded to
+    the nearest integer, the low digit is what remains."""
+    if window[0] * window[1] * window[2] > 4:
+        raise ValueError("two digits cover sums in [-4, 4] only")
+    s = pool_sum(np.asarray(x, dtype=np.int64), window)
+    high = np.rint(s / 3.0).astype(np.int64)      # |s| <= 4: no ties at .5
+    low = s - 3 * high
+    return low.astype(np.int8), high.astype(np.int8)
 
 
 def upsample_nearest(x: np.ndarray, factor: Tuple[int, int, int]) -> np.ndarray:

@@ -165,3 +165,28 @@ def test_unet_table1_extents_where_the_table_is_consistent():
     printed = {1: (234, 170), 2: (232, 168), 9: (50, 34), 10: (48, 32), 11: (94, 62), 12: (92, 60)}
     for k, v in printed.items():
         assert sizes[k] == v
+
+
+def test_pool_digits_reconstruct_the_sums_on_every_window_of_four_codes():
+    """All 3^4 windows of four ternary codes: low + 3 * high is the window sum and both digits are
+    ternary; the representation is unique, so this pins the function completely."""
+    import itertools
+    combos = np.array(list(itertools.product((-1, 0, 1), repeat=4)), dtype=np.int8)     # [81][4]
+    x = combos.reshape(81, 1, 1, 2, 2)                                                # one 2x2 window each
+    low, high = oracle.pool_digits(x, (1, 2, 2))
+    assert low.shape == high.shape == (81, 1, 1, 1, 1)
+    s = combos.astype(np.int64).sum(axis=1)
+    np.testing.assert_array_equal(low.reshape(-1).astype(np.int64) + 3 * high.reshape(-1), s)
+    assert set(np.unique(low)) <= {-1, 0, 1} and set(np.unique(high)) <= {-1, 0, 1}
+    # hand-worked: 2 = -1 + 3, -4 = -1 - 3, 3 = 0 + 3, 1 = 1 + 0
+    for codes, want in [((1, 1, 0, 0), (-1, 1)), ((-1, -1, -1, -1), (-1, -1)), ((1, 1, 1, 0), (0, 1)),
+                        ((1, 0, 0, 0), (1, 0)), ((1, -1, 0, 0), (0, 0))]:
+        l, h = oracle.pool_digits(np.array(codes, np.int8).reshape(1, 1, 1, 2, 2), (1, 2, 2))
+        assert (int(l.item()), int(h.item())) == want
+    # other window shapes, several channels, trailing voxels dropped like pool_sum
+    x = synth.ternary((2, 5, 3, 5, 7), 0.3, 3, synth.T_ACT)
+    for win in [(1, 2, 2), (2, 2, 1), (1, 1, 3), (1, 1, 1), (2, 1, 2)]:
+        l, h = oracle.pool_digits(x, win)
+        np.testing.assert_array_equal(l.astype(np.int64) + 3 * h, oracle.pool_sum(x.astype(np.int64), win))
+    with pytest.raises(ValueError):
+        oracle.pool_digits(x, (2, 2, 2))
