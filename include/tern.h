@@ -220,6 +220,24 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
  * differs from exact arithmetic by at most (terms) * 2^-24 * (|bias| + sum |w| over the filter).
  * Meant for a handful of output channels (Table 1: 2); one thread per output voxel.
  *
+ * tern_pool_digits / tern_digits_weights / tern_conv3d_digits -- average pooling in front of a
+ * ternary convolution (Table 1: AvgPool 2x2 before modules 4, 6 and 8) at twice, not four times,
+ * the cost of the pooled convolution.  The sum of up to four ternary codes lies in [-4, 4] and has
+ * exactly one representation low + 3 * high with both digits in {-1, 0, +1} (balanced ternary).
+ * tern_pool_digits writes, for non-overlapping windows of at most 4 voxels (window[a] >= 1,
+ * product <= 4; trailing voxels that do not fill a window are dropped), the two digits of every
+ * window sum as a packed tensor [N][d/wd][h/wh][w/ww] with 64 * words(C) channels: word 2k of a
+ * plane holds the low digits of channels 32k .. 32k+31, word 2k+1 their high digits.
+ * tern_conv3d_digits is tern_conv3d on such a tensor (in_dims.c = that channel count, a multiple
+ * of 64) with the odd words counted three times, i.e. the exact convolution of the window sums;
+ * the cut points then refer to sums, not averages (scale them by the window volume).  Its filter
+ * bank is tern_pack_filters applied to the weights that tern_digits_weights (host arrays,
+ * launches nothing) makes from w [c_out][c_in][taps]: w_out [c_out][64 * words(c_in)][taps] with
+ * channel 64k + j and 64k + 32 + j both equal to channel 32k + j of w (zero past c_in).
+ * Limits as for tern_conv3d with k-volume * in_dims.c < 2^23.  TERN_ESHAPE also when the halo
+ * tile of a very large dilated kernel does not fit in LDS (the fallback kernel of tern_conv3d
+ * has no two-digit form).
+ *
  * tern_fold_avgpool (host arrays, launches nothing) -- average pooling between two ternary
  * modules, done exactly: pooling with window = stride = pool followed by a convolution with
  * kernel k, stride s, padding p, dilation 1 equals, up to the constant factor
@@ -245,6 +263,13 @@ int tern_concat(const tern_source* srcs /* host */, int32_t n_src, tern_dims out
 int tern_conv3d_real(const uint32_t* in_packed, tern_dims in_dims, const float* w,
                      const float* bias, int32_t c_out, tern_conv_geom g, float* out,
                      void* stream);
+int tern_pool_digits(const uint32_t* in_packed, tern_dims in_dims, const int32_t window[3] /* host */,
+                     uint32_t* out_packed, void* stream);
+int tern_digits_weights(const int8_t* w /* host */, int32_t c_out, int32_t c_in, int64_t taps,
+                        int8_t* w_out /* host */);
+int tern_conv3d_digits(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_bank,
+                       int32_t c_out, tern_conv_geom g, const int32_t* thr_lo, const int32_t* thr_hi,
+                       int32_t* out_acc, uint32_t* out_packed, void* stream);
 /*
  * tern_net_forward -- a network of ternary modules with skip connections (the baseline U-Net of
  * section 3 / Table 1, or any encoder-decoder of that kind), run as one call: Eq. 6 on the float

@@ -14,6 +14,8 @@ from .binding import (  # noqa: F401
     tern_count_codes,
     tern_conv3d_real,
     tern_fold_avgpool,
+    tern_pool_digits,
+    tern_digits_weights,
     tern_conv_out_dims,
     tern_fcn_forward,
     tern_net_forward,

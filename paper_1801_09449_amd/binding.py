@@ -76,6 +76,9 @@ def lib():
     L.tern_pack.argtypes = [P, Dims, P, P]; L.tern_pack.restype = C.c_int
     L.tern_pack_filters.argtypes = [P, I, I, I, I, I, P, P]; L.tern_pack_filters.restype = C.c_int
     L.tern_conv3d.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d.restype = C.c_int
+    L.tern_conv3d_digits.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d_digits.restype = C.c_int
+    L.tern_pool_digits.argtypes = [P, Dims, C.POINTER(C.c_int32), P, P]; L.tern_pool_digits.restype = C.c_int
+    L.tern_digits_weights.argtypes = [P, I, I, C.c_int64, P]; L.tern_digits_weights.restype = C.c_int
     L.tern_threshold_pack.argtypes = [P, C.c_int, Dims, P, P, P, P]; L.tern_threshold_pack.restype = C.c_int
     L.tern_fcn_workspace_bytes.argtypes = [Dims, C.POINTER(Layer), I]; L.tern_fcn_workspace_bytes.restype = S
     L.tern_fcn_forward.argtypes = [P, Dims, P, P, C.POINTER(Layer), I, P, S, P, C.POINTER(Dims),
@@ -217,9 +220,12 @@ def tern_pack_filters(w: torch.Tensor, out: Optional[torch.Tensor] = None) -> to
 def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out: int,
                 k=3, stride=1, pad=1, dil=1,
                 thr_lo: Optional[torch.Tensor] = None, thr_hi: Optional[torch.Tensor] = None,
-                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                out: Optional[torch.Tensor] = None, digits: bool = False) -> torch.Tensor:
     """Ternary convolution.  Without cut points: int32 accumulators [N][C_out][Do][Ho][Wo].
-    With thr_lo / thr_hi (int32 [C_out]): fused activation + re-pack, packed output."""
+    With thr_lo / thr_hi (int32 [C_out]): fused activation + re-pack, packed output.
+    digits=True: in_packed is the two-digit tensor of tern_pool_digits (c_in = its channel count,
+    a multiple of 64) and w_bank the bank of tern_digits_weights' output (tern_conv3d_digits)."""
+    entry = lib().tern_conv3d_digits if digits else lib().tern_conv3d
     _dev(in_packed, PACKED_DTYPE, "in_packed")
     _dev(w_bank, PACKED_DTYPE, "w_bank")
     if in_packed.dim() != 6 or in_packed.shape[4] != 2 or in_packed.shape[5] != tern_words(c_in):
@@ -243,17 +249,53 @@ def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out:
         _dev(out, PACKED_DTYPE, "out")
         if out.numel() * 4 != tern_packed_bytes((o.n, o.c, o.d, o.h, o.w)):
             raise ValueError("out has the wrong size")
-        rc = lib().tern_conv3d(_ptr(in_packed), in_dims, _ptr(w_bank), int(c_out), g, _ptr(thr_lo),
-                               _ptr(thr_hi), None, _ptr(out), _stream(in_packed))
+        rc = entry(_ptr(in_packed), in_dims, _ptr(w_bank), int(c_out), g, _ptr(thr_lo),
+                   _ptr(thr_hi), None, _ptr(out), _stream(in_packed))
     else:
         if out is None:
             out = torch.empty((o.n, o.c, o.d, o.h, o.w), dtype=torch.int32, device=in_packed.device)
         _dev(out, torch.int32, "out")
         if tuple(out.shape) != (o.n, o.c, o.d, o.h, o.w):
             raise ValueError("out has the wrong shape")
-        rc = lib().tern_conv3d(_ptr(in_packed), in_dims, _ptr(w_bank), int(c_out), g, None, None,
-                               _ptr(out), None, _stream(in_packed))
+        rc = entry(_ptr(in_packed), in_dims, _ptr(w_bank), int(c_out), g, None, None,
+                   _ptr(out), None, _stream(in_packed))
     _check(rc, "tern_conv3d")
+    return out
+
+
+def tern_pool_digits(in_packed: torch.Tensor, c: int, window, out: Optional[torch.Tensor] = None):
+    """Sums over non-overlapping windows (at most 4 voxels) of a packed tensor, as two balanced-
+    ternary digits: returns (packed [N][D'][H'][W'][2][2*words(c)], channel count 64*words(c))."""
+    _dev(in_packed, PACKED_DTYPE, "in_packed")
+    if in_packed.dim() != 6 or in_packed.shape[4] != 2 or in_packed.shape[5] != tern_words(c):
+        raise ValueError("in_packed must be [N][D][H][W][2][ceil(C/32)]")
+    win = _t3(window)
+    n, d, h, w = (int(x) for x in in_packed.shape[:4])
+    c2 = 64 * tern_words(c)
+    if min(win) < 1:
+        raise ValueError("window entries must be positive")
+    shape = (n, c2, d // win[0], h // win[1], w // win[2])
+    if out is None:
+        out = _empty_packed(shape, in_packed.device)
+    _dev(out, PACKED_DTYPE, "out")
+    if out.numel() * 4 != tern_packed_bytes(shape):
+        raise ValueError("out has the wrong size")
+    arr = (C.c_int32 * 3)(*win)
+    _check(lib().tern_pool_digits(_ptr(in_packed), Dims(n, int(c), d, h, w), arr, _ptr(out), _stream(in_packed)),
+           "tern_pool_digits")
+    return out, c2
+
+
+def tern_digits_weights(w):
+    """int8 host weights [C_out][C_in][...] -> [C_out][64*words(C_in)][...] for tern_conv3d(digits=True)."""
+    import numpy as np
+    w = np.ascontiguousarray(w, dtype=np.int8)
+    if w.ndim < 2:
+        raise ValueError("w must be [C_out][C_in][...]")
+    c_out, c_in = w.shape[:2]
+    taps = int(w.size // (c_out * c_in))
+    out = np.empty((c_out, 64 * tern_words(c_in)) + w.shape[2:], dtype=np.int8)
+    _check(lib().tern_digits_weights(_np_ptr(w), c_out, c_in, taps, _np_ptr(out)), "tern_digits_weights")
     return out
 
 

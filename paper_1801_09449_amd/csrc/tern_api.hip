@@ -104,6 +104,7 @@ static ConvParams conv_params(const uint32_t* in_packed, const tern_dims& in_dim
     p.co_pad = (c_out + 31) / 32 * 32;
     p.tp_slots = bs.tp_slots;
     p.tp_shift = bs.tp_shift;
+    p.digits = 0;
     return p;
 }
 
@@ -235,6 +236,41 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_
     const ConvParams p = conv_params(in_packed, in_dims, w_bank, c_out, g, o, thr_lo, thr_hi, out_acc,
                                      out_packed);
     return launch_conv3d(p, (hipStream_t)stream);
+}
+
+int tern_conv3d_digits(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_bank,
+                       int32_t c_out, tern_conv_geom g, const int32_t* thr_lo, const int32_t* thr_hi,
+                       int32_t* out_acc, uint32_t* out_packed, void* stream)
+{
+    if (!in_packed || !w_bank) return TERN_ENULL;
+    if ((out_acc == nullptr) == (out_packed == nullptr)) return TERN_EARG;
+    if (out_packed && (!thr_lo || !thr_hi)) return TERN_ENULL;
+    if (in_dims.c <= 0 || in_dims.c % 64 != 0) return TERN_EARG;   // whole (low, high) word pairs
+    tern_dims o;
+    int rc = geom_check(in_dims, c_out, g, &o);
+    if (rc != TERN_OK) return rc;
+    // accumulators reach 2 * k-volume * c (every digit pair can contribute 1 + 3)
+    if ((int64_t)g.k[0] * g.k[1] * g.k[2] * in_dims.c >= (1 << 23)) return TERN_ESHAPE;
+    if (!aligned16(in_packed) || !aligned16(w_bank)) return TERN_EARG;
+    if (out_packed && !aligned16(out_packed)) return TERN_EARG;
+    if (out_acc && ((uintptr_t)out_acc & 3u)) return TERN_EARG;
+    ConvParams p = conv_params(in_packed, in_dims, w_bank, c_out, g, o, thr_lo, thr_hi, out_acc, out_packed);
+    p.digits = 1;
+    return launch_conv3d(p, (hipStream_t)stream);
+}
+
+int tern_pool_digits(const uint32_t* in_packed, tern_dims in_dims, const int32_t window[3],
+                     uint32_t* out_packed, void* stream)
+{
+    if (!in_packed || !window || !out_packed) return TERN_ENULL;
+    if (!sizes_ok(in_dims)) return TERN_ESHAPE;
+    for (int a = 0; a < 3; ++a)
+        if (window[a] < 1 || window[a] > 4) return TERN_EARG;
+    if (window[0] * window[1] * window[2] > 4) return TERN_EARG;   // sums beyond +-4 need a third digit
+    if (!aligned16(in_packed) || !aligned16(out_packed)) return TERN_EARG;
+    const int64_t c2 = 64 * (int64_t)tern_words(in_dims.c);
+    if (c2 > INT32_MAX) return TERN_ESHAPE;
+    return launch_pool_digits(in_packed, in_dims, window, out_packed, (hipStream_t)stream);
 }
 
 int tern_concat(const tern_source* srcs, int32_t n_src, tern_dims out_dims, uint32_t* out_packed,

@@ -237,6 +237,69 @@ __device__ __forceinline__ void mac_quad(const ActChunk<WC> (&A)[V], const WGrou
 #undef TERN_WORD1_ADD
 }
 
+// Two-digit inputs (sums of up to four ternary codes written in balanced ternary, low digit in
+// the even word of a chunk and high digit, worth three, in the odd word): the same statement with
+// the odd word's popcounts going to accumulators of their own, acc2_m / acc2_n.
+template <int V, int CO_BLK, int KG, bool SET>
+__device__ __forceinline__ void mac_quad_digits(const ActChunk<2> (&A)[V], const WGroup<2, KG>& g, int jg, int j0,
+                                                int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK],
+                                                int32_t (&acc2_m)[V][CO_BLK], int32_t (&acc2_n)[V][CO_BLK],
+                                                uint32_t& t)
+{
+    static_assert(V == 1 || V == 2 || V == 4, "four (channel, voxel) combinations per statement");
+#define TERN_C(P) (jg + (P) / V)
+#define TERN_X(P) ((P) % V)
+#define TERN_ACC(C, K, A1, A2) [am##C] K(A1##_m[TERN_X(C)][j0 + TERN_C(C)]), [an##C] K(A1##_n[TERN_X(C)][j0 + TERN_C(C)]), \
+                               [bm##C] K(A2##_m[TERN_X(C)][j0 + TERN_C(C)]), [bn##C] K(A2##_n[TERN_X(C)][j0 + TERN_C(C)])
+#define TERN_INS(P, C, Q) TERN_MAC_IN(P, A[TERN_X(C)].m[Q], A[TERN_X(C)].s[Q], g.m[TERN_C(C)][Q], g.s[TERN_C(C)][Q])
+// the pair macro names its accumulators am<C> / an<C>; the odd word's pairs go through an alias
+#define TERN_MAC_PAIR_B(P, C, ADD_M, ADD_N)                                          \
+    "v_and_b32 %[t], %[mw" P "], %[ma" P "]\n\t"                                   \
+    "s_nop 0\n\t"                                                                  \
+    "v_bcnt_u32_b32 %[bm" C "], %[t], " ADD_M "\n\t"                               \
+    "v_bitop3_b32 %[t], %[sa" P "], %[t], %[sw" P "] bitop3:0x48\n\t"              \
+    "s_nop 0\n\t"                                                                  \
+    "v_bcnt_u32_b32 %[bn" C "], %[t], " ADD_N "\n\t"
+    if constexpr (SET) {
+        asm volatile(TERN_MAC_PAIR("0", "0", "0", "0") TERN_MAC_PAIR("1", "1", "0", "0")
+                     TERN_MAC_PAIR("2", "2", "0", "0") TERN_MAC_PAIR("3", "3", "0", "0")
+                     TERN_MAC_PAIR_B("4", "0", "0", "0") TERN_MAC_PAIR_B("5", "1", "0", "0")
+                     TERN_MAC_PAIR_B("6", "2", "0", "0") TERN_MAC_PAIR_B("7", "3", "0", "0")
+                     : TERN_ACC(0, "=&v", acc, acc2), TERN_ACC(1, "=&v", acc, acc2), TERN_ACC(2, "=&v", acc, acc2),
+                       TERN_ACC(3, "=&v", acc, acc2), [t] "+v"(t)
+                     : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0),
+                       TERN_INS(4, 0, 1), TERN_INS(5, 1, 1), TERN_INS(6, 2, 1), TERN_INS(7, 3, 1));
+    } else {
+        asm volatile(TERN_MAC_PAIR("0", "0", "%[am0]", "%[an0]") TERN_MAC_PAIR("1", "1", "%[am1]", "%[an1]")
+                     TERN_MAC_PAIR("2", "2", "%[am2]", "%[an2]") TERN_MAC_PAIR("3", "3", "%[am3]", "%[an3]")
+                     TERN_MAC_PAIR_B("4", "0", "%[bm0]", "%[bn0]") TERN_MAC_PAIR_B("5", "1", "%[bm1]", "%[bn1]")
+                     TERN_MAC_PAIR_B("6", "2", "%[bm2]", "%[bn2]") TERN_MAC_PAIR_B("7", "3", "%[bm3]", "%[bn3]")
+                     : TERN_ACC(0, "+v", acc, acc2), TERN_ACC(1, "+v", acc, acc2), TERN_ACC(2, "+v", acc, acc2),
+                       TERN_ACC(3, "+v", acc, acc2), [t] "+v"(t)
+                     : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0),
+                       TERN_INS(4, 0, 1), TERN_INS(5, 1, 1), TERN_INS(6, 2, 1), TERN_INS(7, 3, 1));
+    }
+#undef TERN_C
+#undef TERN_X
+#undef TERN_ACC
+#undef TERN_INS
+#undef TERN_MAC_PAIR_B
+}
+
+template <int V, int CO_BLK, int KG, bool INIT = false>
+__device__ __forceinline__ void mac_group_digits(const ActChunk<2> (&A)[V], const WGroup<2, KG>& g, int j0,
+                                                 int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK],
+                                                 int32_t (&acc2_m)[V][CO_BLK], int32_t (&acc2_n)[V][CO_BLK])
+{
+    constexpr int NCB = V == 4 ? 1 : 4 / V;
+    static_assert(KG % NCB == 0, "whole statements");
+    uint32_t t[2];
+    asm volatile("" : "=v"(t[0]), "=v"(t[1]));
+#pragma unroll
+    for (int jg = 0, k = 0; jg < KG; jg += NCB, ++k)
+        mac_quad_digits<V, CO_BLK, KG, INIT>(A, g, jg, j0, acc_m, acc_n, acc2_m, acc2_n, t[k & 1]);
+}
+
 // Four VALU instructions per (word pair, voxel) (Eq. 9 as popcount(M) - 2 popcount(M & X), the
 // subtraction deferred).  INIT: the accumulators of these channels hold nothing yet.
 template <int WC, int V, int CO_BLK, int KG, bool INIT = false>

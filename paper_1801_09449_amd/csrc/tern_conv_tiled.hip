@@ -149,13 +149,15 @@ __device__ __forceinline__ void fetch_step(ActChunk<WC> (&A)[V], StepCursor& c, 
 // step's activations into A1.  Software pipeline: while a channel group is being accumulated,
 // the scalar loads of the following group and the LDS reads of the next step are in flight.
 // INIT marks the first step of a pass, which sets the accumulators instead of adding to them.
-template <int WC, int V, int CO_BLK, bool TP, bool INIT = false>
+// DIG: two-digit input, the odd word of a chunk goes to the second accumulator set.
+template <int WC, int V, int CO_BLK, bool TP, bool DIG, bool INIT = false, typename Acc2>
 __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<WC> (&A1)[V], bool last,
                                           StepCursor& cur, const StepConsts& sc, int inc_c, int inc_b,
                                           int inc_a, WGroup<WC, GroupOf<CO_BLK>::value>& g0,
                                           WGroup<WC, GroupOf<CO_BLK>::value>& g1, scalar_ptr& wcur,
                                           const uint32_t* lane_lds,
-                                          int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK])
+                                          int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK],
+                                          Acc2& acc2_m, Acc2& acc2_n)
 {
     constexpr int KG = GroupOf<CO_BLK>::value;
     constexpr int NG = CO_BLK / KG;
@@ -169,20 +171,22 @@ __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<
         if (gi == 0) fetch_step<WC, V, TP>(A1, cur, sc, inc_c, inc_b, inc_a, lane_lds, !last);
         load_wgroup<WC, KG>(g1, wcur + (gi + 1) * KG * 2 * WC);
         __builtin_amdgcn_sched_barrier(0);
-        mac_group<WC, V, CO_BLK, KG, INIT>(A0, g0, gi * KG, acc_m, acc_n);
+        if constexpr (DIG) mac_group_digits<V, CO_BLK, KG, INIT>(A0, g0, gi * KG, acc_m, acc_n, acc2_m, acc2_n);
+        else mac_group<WC, V, CO_BLK, KG, INIT>(A0, g0, gi * KG, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
         settle<WC, KG>(g1);
         __builtin_amdgcn_sched_barrier(0);
         if (gi + 2 < NG) load_wgroup<WC, KG>(g0, wcur + (gi + 2) * KG * 2 * WC);
         else load_wgroup<WC, KG>(g0, wnext);
         __builtin_amdgcn_sched_barrier(0);
-        mac_group<WC, V, CO_BLK, KG, INIT>(A0, g1, (gi + 1) * KG, acc_m, acc_n);
+        if constexpr (DIG) mac_group_digits<V, CO_BLK, KG, INIT>(A0, g1, (gi + 1) * KG, acc_m, acc_n, acc2_m, acc2_n);
+        else mac_group<WC, V, CO_BLK, KG, INIT>(A0, g1, (gi + 1) * KG, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
     }
     wcur = wnext;
 }
 
-template <int WC, int V, int CO_BLK, bool PACKED, bool TP>
+template <int WC, int V, int CO_BLK, bool PACKED, bool TP, bool DIG = false>
 __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, TileParams t)
 {
     extern __shared__ __align__(16) uint32_t lds[];
@@ -394,6 +398,8 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
         int32_t d[V][CO_BLK];   // accumulators of this pass
         if (active && s_begin < s_end) {
             int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];   // set by the pass's first step
+            // second set for the high digits of a two-digit input (one dummy element otherwise)
+            int32_t acc2_m[DIG ? V : 1][DIG ? CO_BLK : 1], acc2_n[DIG ? V : 1][DIG ? CO_BLK : 1];
             scalar_ptr wcur = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC +
                               (size_t)s_begin * sc.step_words;
             WGroup<WC, KG> g0, g1;
@@ -402,21 +408,24 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
             fetch_step<WC, V, TP>(Aa, cur, sc, inc_c, inc_b, inc_a, lane_lds, false);
             load_wgroup<WC, KG>(g0, wcur);
             int step = s_begin + 1;
-            conv_step<WC, V, CO_BLK, TP, true>(Aa, Ab, step == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
-                                               lane_lds, acc_m, acc_n);
+            conv_step<WC, V, CO_BLK, TP, DIG, true>(Aa, Ab, step == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                               lane_lds, acc_m, acc_n, acc2_m, acc2_n);
             for (; step + 2 <= s_end; step += 2) {   // two steps per trip: no register copies
-                conv_step<WC, V, CO_BLK, TP>(Ab, Aa, false, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
-                                             acc_m, acc_n);
-                conv_step<WC, V, CO_BLK, TP>(Aa, Ab, step + 2 == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
-                                             lane_lds, acc_m, acc_n);
+                conv_step<WC, V, CO_BLK, TP, DIG>(Ab, Aa, false, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                                  lane_lds, acc_m, acc_n, acc2_m, acc2_n);
+                conv_step<WC, V, CO_BLK, TP, DIG>(Aa, Ab, step + 2 == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                             lane_lds, acc_m, acc_n, acc2_m, acc2_n);
             }
             if (step < s_end)
-                conv_step<WC, V, CO_BLK, TP>(Ab, Aa, true, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur, lane_lds,
-                                             acc_m, acc_n);
+                conv_step<WC, V, CO_BLK, TP, DIG>(Ab, Aa, true, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                                  lane_lds, acc_m, acc_n, acc2_m, acc2_n);
 #pragma unroll
             for (int v = 0; v < V; ++v)
 #pragma unroll
-                for (int j = 0; j < CO_BLK; ++j) d[v][j] = acc_m[v][j] - 2 * acc_n[v][j];
+                for (int j = 0; j < CO_BLK; ++j) {
+                    d[v][j] = acc_m[v][j] - 2 * acc_n[v][j];
+                    if constexpr (DIG) d[v][j] += 3 * (acc2_m[v][j] - 2 * acc2_n[v][j]);   // high digit
+                }
         } else if (active) {   // a tap share without steps (more shares than steps)
 #pragma unroll
             for (int v = 0; v < V; ++v)
@@ -507,11 +516,11 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     }
 }
 
-template <int WC, int V, int CO_BLK, bool PACKED, bool TP>
+template <int WC, int V, int CO_BLK, bool PACKED, bool TP, bool DIG = false>
 int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, dim3 grid,
                    int threads, hipStream_t s)
 {
-    auto kern = conv_tiled_kernel<WC, V, CO_BLK, PACKED, TP>;
+    auto kern = conv_tiled_kernel<WC, V, CO_BLK, PACKED, TP, DIG>;
     if (lds_bytes > 64 * 1024) {
         static thread_local int raised_on_device = -1;
         int dev = 0;
@@ -612,7 +621,7 @@ void set_pointwise(int v) { g_point = v ? 1 : 0; }
 
 int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 {
-    if (g_point && conv_point_applies(p_in)) return launch_conv_point(p_in, s);
+    if (g_point && !p_in.digits && conv_point_applies(p_in)) return launch_conv_point(p_in, s);
     ConvParams p = p_in;
     const bool packed = p.out_packed != nullptr;
     // A kernel of depth extent 1 with unit depth stride and no depth padding treats every input
@@ -712,10 +721,12 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         }
     }
     if (V == 2) V = lane_depth_for(co_blk);
+    if (p.digits) V = 1;   // the only variant built for two-digit inputs
     TileParams t;
     int64_t lds_bytes = 0;
     if (!plan_tiles(p, V, lds_limit, t, lds_bytes)) {
         if (V == 4 && plan_tiles(p, 2, lds_limit, t, lds_bytes)) V = 2;
+        else if (p.digits) return TERN_ESHAPE;   // the fallback kernel knows one-digit inputs only
         else return launch_conv3d_generic(p, s);
     }
     const int64_t spatial_tiles = (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n;
@@ -774,6 +785,13 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 #define TERN_LAUNCH(WC_, V_, CB_, TP_)                                                       \
     (packed ? launch_variant<WC_, V_, CB_, true, TP_>(p, t, lb, grid, threads, s)            \
             : launch_variant<WC_, V_, CB_, false, TP_>(p, t, lb, grid, threads, s))
+    if (p.digits) {   // two-digit input: one voxel per lane, two accumulator sets
+        if (co_blk == 32)
+            return packed ? launch_variant<2, 1, 32, true, false, true>(p, t, lb, grid, threads, s)
+                          : launch_variant<2, 1, 32, false, false, true>(p, t, lb, grid, threads, s);
+        return packed ? launch_variant<2, 1, 16, true, false, true>(p, t, lb, grid, threads, s)
+                      : launch_variant<2, 1, 16, false, false, true>(p, t, lb, grid, threads, s);
+    }
     if (tp) return co_blk == 32 ? TERN_LAUNCH(1, 2, 32, true) : TERN_LAUNCH(1, 2, 16, true);
     if (p.wc == 2) {
         if (V == 1) return co_blk == 32 ? TERN_LAUNCH(2, 1, 32, false) : TERN_LAUNCH(2, 1, 16, false);

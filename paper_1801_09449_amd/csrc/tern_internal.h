@@ -37,6 +37,7 @@ struct ConvParams {
     int32_t co_pad;         // c_out rounded up to a multiple of 32
     int32_t tp_slots;       // tap-packed filter bank: taps per word (0 = plain layout)
     int32_t tp_shift;       // tap-packed filter bank: bits per tap slot
+    int32_t digits;         // 1: two-digit input (tern_pool_digits): odd words count three times
 };
 
 // Filter-bank geometry for (c_in, taps): tap packing applies when a voxel is one word with at
@@ -129,6 +130,8 @@ int launch_conv3d(const ConvParams& p, hipStream_t s);
 bool conv_point_applies(const ConvParams& p);
 int launch_conv_point(const ConvParams& p, hipStream_t s);
 int launch_concat(const ConcatParams& p, hipStream_t s);
+int launch_pool_digits(const uint32_t* in, const tern_dims& in_dims, const int32_t window[3], uint32_t* out,
+                       hipStream_t s);
 int launch_real_conv(const RealConvParams& p, hipStream_t s);
 int launch_count_codes(const uint32_t* in, int64_t voxels, int32_t c, unsigned long long* nonzero,
                        unsigned long long* negative, hipStream_t s);

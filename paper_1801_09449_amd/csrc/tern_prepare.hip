@@ -84,6 +84,21 @@ int tern_ternarize_filters_sparse(const float* w, int32_t c_out, int64_t per_fil
     return TERN_OK;
 }
 
+int tern_digits_weights(const int8_t* w, int32_t c_out, int32_t c_in, int64_t taps, int8_t* w_out)
+{
+    if (!w || !w_out) return TERN_ENULL;
+    if (c_out <= 0 || c_in <= 0 || taps <= 0) return TERN_ESHAPE;
+    const int64_t wd = (c_in + 31) / 32;
+    for (int32_t co = 0; co < c_out; ++co)
+        for (int64_t c2 = 0; c2 < 64 * wd; ++c2) {
+            const int64_t src = 32 * (c2 / 64) + c2 % 32;   // both words of a pair hold the same channels
+            for (int64_t t = 0; t < taps; ++t)
+                w_out[((size_t)co * 64 * wd + c2) * taps + t] =
+                    src < c_in ? w[((size_t)co * c_in + src) * taps + t] : (int8_t)0;
+        }
+    return TERN_OK;
+}
+
 int tern_fold_thresholds(const double* scale, const double* shift, int32_t c, int32_t acc_bound,
                          int32_t* lo, int32_t* hi, uint8_t* negate)
 {

@@ -242,6 +242,79 @@ __global__ __launch_bounds__(kBlock) void count_codes_kernel(const uint32_t* __r
     }
 }
 
+// Sum pooling into two balanced-ternary digits.  The sum of up to four ternary codes lies in
+// [-4, 4] and has exactly one representation low + 3 * high with both digits in {-1, 0, +1}, so a
+// pooled tensor stays in the 2-bit format at twice the channel words (word 2k = low digits of
+// channels 32k.., word 2k+1 = their high digits) and the convolution behind an average pooling
+// (Table 1) costs two word pairs per pooled input word instead of one per unpooled voxel.
+// All 32 channels of a word at once, on bit planes: count the +1 and the -1 codes of the window
+// with one-bit adders (three-bit counts P and N), subtract, and read the digits off the 4-bit
+// two's-complement difference.
+struct PoolParams {
+    const uint32_t* in;     // [N][d][h][w][2][wd]
+    uint32_t* out;          // [N][od][oh][ow][2][2*wd]
+    int32_t d, h, w, od, oh, ow, wd;
+    int32_t pd, ph, pw;     // window, volume <= 4
+    int64_t total;          // N * od * oh * ow * wd
+};
+
+__device__ __forceinline__ void count4(const uint32_t (&b)[4], uint32_t& c0, uint32_t& c1, uint32_t& c2)
+{
+    const uint32_t s1 = b[0] ^ b[1] ^ b[2];
+    const uint32_t k1 = (b[0] & b[1]) | (b[2] & (b[0] ^ b[1]));   // carry of the first three
+    c0 = s1 ^ b[3];
+    const uint32_t k2 = s1 & b[3];
+    c1 = k1 ^ k2;
+    c2 = k1 & k2;
+}
+
+__global__ __launch_bounds__(kBlock) void pool_digits_kernel(PoolParams p)
+{
+    const int64_t gid = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (gid >= p.total) return;
+    const int k = (int)(gid % p.wd);
+    int64_t r = gid / p.wd;
+    const int ox = (int)(r % p.ow); r /= p.ow;
+    const int oy = (int)(r % p.oh); r /= p.oh;
+    const int oz = (int)(r % p.od);
+    const int64_t n = r / p.od;
+    uint32_t pos[4] = {0u, 0u, 0u, 0u}, neg[4] = {0u, 0u, 0u, 0u};
+    int idx = 0;
+    for (int a = 0; a < p.pd; ++a)
+        for (int b = 0; b < p.ph; ++b)
+            for (int c = 0; c < p.pw; ++c, ++idx) {
+                const size_t vox = (((size_t)n * p.d + (oz * p.pd + a)) * p.h + (oy * p.ph + b)) * p.w + (ox * p.pw + c);
+                const uint32_t m = p.in[vox * 2u * p.wd + k];
+                const uint32_t sg = p.in[vox * 2u * p.wd + p.wd + k];
+                // (idx < 4 by the launcher's check on the window volume)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (q == idx) { pos[q] = m & ~sg; neg[q] = m & sg; }
+            }
+    uint32_t p0, p1, p2, n0, n1, n2;
+    count4(pos, p0, p1, p2);
+    count4(neg, n0, n1, n2);
+    // s = P - N, four-bit two's complement, bit by bit with a borrow
+    const uint32_t s0 = p0 ^ n0;
+    const uint32_t b1 = ~p0 & n0;
+    const uint32_t s1 = p1 ^ n1 ^ b1;
+    const uint32_t b2 = (~p1 & n1) | (~(p1 ^ n1) & b1);
+    const uint32_t s2 = p2 ^ n2 ^ b2;
+    const uint32_t s3 = (~p2 & n2) | (~(p2 ^ n2) & b2);          // sign
+    // high digit: nonzero for |s| >= 2 (positive: 2, 3, 4; negative: everything but -1 = 1111)
+    const uint32_t hi_m = (~s3 & (s2 | s1)) | (s3 & ~(s2 & s1 & s0));
+    const uint32_t hi_s = s3 & hi_m;
+    // low digit s - 3 * high: zero for s in {-3, 0, 3} = {1101, 0000, 0011}, negative for
+    // s in {-4, -1, 2} = {1100, 1111, 0010}
+    const uint32_t z = (s3 & s2 & ~s1 & s0) | (~s3 & ~s2 & ~s1 & ~s0) | (~s3 & ~s2 & s1 & s0);
+    const uint32_t lo_m = ~z;
+    const uint32_t lo_s = (s3 & s2 & ~s1 & ~s0) | (s3 & s2 & s1 & s0) | (~s3 & ~s2 & s1 & ~s0);
+    const size_t ovox = (size_t)(gid / p.wd);
+    uint32_t* o = p.out + ovox * 4u * p.wd;     // 2 planes of 2*wd words
+    *reinterpret_cast<uint2*>(o + 2 * k) = make_uint2(lo_m, hi_m);
+    *reinterpret_cast<uint2*>(o + 2 * p.wd + 2 * k) = make_uint2(lo_s, hi_s);
+}
+
 __global__ void zero_counts_kernel(unsigned long long* a, unsigned long long* b, int32_t c)
 {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -261,6 +334,24 @@ int launch_count_codes(const uint32_t* in, int64_t voxels, int32_t c, unsigned l
     if (blocks > 2048) blocks = 2048;      // grid-stride: a few waves per SIMD, few atomics
     hipLaunchKernelGGL(count_codes_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, s, in, voxels, wd, c, nonzero,
                        negative);
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
+
+int launch_pool_digits(const uint32_t* in, const tern_dims& in_dims, const int32_t window[3], uint32_t* out,
+                       hipStream_t s)
+{
+    PoolParams p;
+    p.in = in; p.out = out;
+    p.d = in_dims.d; p.h = in_dims.h; p.w = in_dims.w;
+    p.pd = window[0]; p.ph = window[1]; p.pw = window[2];
+    p.od = in_dims.d / p.pd; p.oh = in_dims.h / p.ph; p.ow = in_dims.w / p.pw;
+    p.wd = (in_dims.c + 31) / 32;
+    p.total = (int64_t)in_dims.n * p.od * p.oh * p.ow * p.wd;
+    if (p.total == 0) return TERN_OK;
+    const int64_t blocks = (p.total + kBlock - 1) / kBlock;
+    if (blocks > 0x7fffffff) return TERN_ESHAPE;
+    hipLaunchKernelGGL(pool_digits_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, s, p);
     TERN_HIP_CHECK(hipGetLastError());
     return TERN_OK;
 }

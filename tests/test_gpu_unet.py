@@ -202,6 +202,70 @@ def test_count_codes_ignores_sign_under_clear_mask_and_repeats(G):
         np.testing.assert_array_equal(ng.cpu().numpy(), want_nz)     # every nonzero now reads as -1
 
 
+# ---- pooled convolutions through two balanced-ternary digits -----------------------------------------
+def digits_of(words, c):
+    """(low, high) int8 tensors [N][c][D][H][W] from a packed two-digit tensor (numpy words
+    [N][D][H][W][2][2*wd])."""
+    wd = (c + 31) // 32
+    m, s = words[..., 0, :], words[..., 1, :]
+    out = []
+    for which in (0, 1):
+        mm, ss = m[..., which::2], s[..., which::2]                      # [N][D][H][W][wd]
+        bits = np.arange(32, dtype=np.uint32)
+        mb = ((mm[..., None] >> bits) & 1).reshape(mm.shape[:-1] + (32 * wd,))[..., :c]
+        sb = ((ss[..., None] >> bits) & 1).reshape(ss.shape[:-1] + (32 * wd,))[..., :c]
+        code = mb.astype(np.int8) * (1 - 2 * sb.astype(np.int8))
+        out.append(np.moveaxis(code, -1, 1))
+    return out
+
+
+@pytest.mark.parametrize("c,vol,win", [(5, (3, 6, 8), (1, 2, 2)), (32, (1, 7, 9), (1, 2, 2)), (70, (4, 5, 6), (2, 2, 1)),
+                                       (64, (2, 4, 9), (1, 1, 3)), (33, (3, 3, 3), (1, 1, 1)), (96, (2, 8, 8), (2, 1, 2))])
+def test_pool_digits(G, c, vol, win):
+    import paper_1801_09449_amd as T
+    x = synth.ternary((2, c) + vol, 0.3, c + vol[0], synth.T_ACT)
+    got, c2 = T.tern_pool_digits(T.tern_pack(G.dev(x)), c, win)
+    assert c2 == 64 * ((c + 31) // 32)
+    words = G.words(got)
+    low, high = digits_of(words, c)
+    want_low, want_high = oracle.pool_digits(x, win)
+    np.testing.assert_array_equal(low, want_low)
+    np.testing.assert_array_equal(high, want_high)
+    # canonical packing: no sign bit without its mask bit, padding channels empty
+    assert not (words[..., 1, :] & ~words[..., 0, :]).any()
+    if c % 32:
+        assert not (words[..., 0, -2:] >> np.uint32(c % 32)).any()
+
+
+@pytest.mark.parametrize("ci,co,vol,k,win", [(64, 40, (1, 30, 26), (1, 3, 3), (1, 2, 2)), (40, 33, (6, 12, 10), (3, 3, 3), (1, 2, 2)),
+                                             (128, 64, (2, 21, 18), (1, 3, 3), (1, 2, 2)), (256, 48, (1, 16, 20), (1, 1, 1), (1, 2, 2)),
+                                             (32, 16, (4, 9, 9), (2, 3, 1), (2, 1, 2))])
+def test_conv_on_pooled_digits_equals_conv_on_window_sums(G, ci, co, vol, k, win):
+    """tern_pool_digits + tern_conv3d_digits against the oracle's convolution of the window sums:
+    int32 accumulators and fused packed output, both channel-block widths."""
+    import paper_1801_09449_amd as T
+    x = synth.ternary((2, ci) + vol, 0.35, ci + co, synth.T_ACT)
+    w = synth.ternary((co, ci) + k, 0.5, ci + co, synth.T_WGT)
+    pvol = win[0] * win[1] * win[2]
+    lo, hi = synth.bn_like_thresholds(co, int(np.prod(k)) * pvol, ci, 0.5, 0.65, ci, synth.T_THR)
+    pooled = np.ascontiguousarray(oracle.pool_sum(x, win))      # int8 sums in [-4, 4]
+    geom = ConvGeom(k, (1, 1, 1), (0, 0, 0), (1, 1, 1))
+    want_acc = oracle.conv3d(pooled, w, geom)
+    want_packed = oracle.pack(oracle.threshold(want_acc, lo, hi))
+    dig, c2 = T.tern_pool_digits(T.tern_pack(G.dev(x)), ci, win)
+    bank = T.tern_pack_filters(G.dev(T.tern_digits_weights(w)))
+    try:
+        for cb in (0, 16, 32):
+            T.tern_set_option(3, cb)
+            acc = T.tern_conv3d(dig, c2, bank, co, k=k, stride=1, pad=0, dil=1, digits=True)
+            packed = T.tern_conv3d(dig, c2, bank, co, k=k, stride=1, pad=0, dil=1, thr_lo=G.dev(lo),
+                                   thr_hi=G.dev(hi), digits=True)
+            np.testing.assert_array_equal(acc.cpu().numpy(), want_acc)
+            np.testing.assert_array_equal(G.words(packed), want_packed)
+    finally:
+        T.tern_set_option(3, 0)
+
+
 # ---- the whole network -----------------------------------------------------------------------------
 def run_unet(G, u):
     import torch
