@@ -144,7 +144,7 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
     # The paper's baseline U-Net (Table 1) on synthetic weights, whole forward pass, for one
     # stack of slices and for a batch of 16 stacks.  MACs in the paper's convention (a pooled
     # module counted at the pooled resolution) and as executed (pooling folded into the filters
-    # repeats every tap over the pooling window).
+    # repeats every tap over the pooling window: 4 x; pooling into two digits: 2 x).
     from paper_1801_09449_amd import unet
     for n in (1, 16):
         u = synth.unet_table1(seed=0, n=n)
@@ -152,11 +152,15 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
         ux = dev(u.x)
         pred, kept = unet.unet_forward(plan, ux, keep_layers=True)
         nominal = executed = 0
-        for L, (t, c) in zip(u.layers, kept):
+        chosen = plan.modules(ux.shape)
+        for L, (t, c), m in zip(u.layers, kept, chosen):
             vox = t.shape[0] * t.shape[1] * t.shape[2] * t.shape[3]
             taps = int(np.prod(L["k"]))
             nominal += vox * c * L["w"].shape[1] * taps
-            executed += vox * c * L["w"].shape[1] * taps * (int(np.prod(L["pool"])) if L["pool"] else 1)
+            if max(m.pool) > 1:      # two digits: the channel words double
+                executed += vox * c * 64 * ((L["w"].shape[1] + 31) // 32) * taps
+            else:
+                executed += vox * c * L["w"].shape[1] * taps * (int(np.prod(L["pool"])) if L["pool"] else 1)
         del kept
         ms_u, _ = timed(lambda: unet.unet_forward(plan, ux, out=pred), 20, 3, None)
         ugraph = torch.cuda.CUDAGraph()

@@ -276,8 +276,13 @@ int tern_conv3d_digits(const uint32_t* in_packed, tern_dims in_dims, const uint3
  * input, then for every module, in order, [nearest upsampling of the incoming tensor and
  * appending of an earlier module's centre-cropped output, via the tern_concat kernel] and a
  * fused tern_conv3d; optionally a float-weight prediction layer (tern_conv3d_real) on the last
- * module's output.  Average pooling is expressed through the module's filters and stride
- * (tern_fold_avgpool).  A chain without skips and upsampling is what tern_fcn_forward runs.
+ * module's output.  Average pooling in front of a module is expressed either through the
+ * module's filters and stride (tern_fold_avgpool; pool left at 1) or through pool[]: the
+ * incoming tensor (after upsampling and concatenation, if any) is sum-pooled over windows of
+ * pool[] voxels (product <= 4) into two digits (tern_pool_digits) and the convolution runs on
+ * those (tern_conv3d_digits: w_bank then is the bank of tern_digits_weights' output, the cut
+ * points refer to window sums).  A chain without skips and upsampling is what tern_fcn_forward
+ * runs.
  *   mods       : host array; module i reads the output of module i-1 (the packed input for
  *                i = 0), upsampled by up[] when any factor is > 1, followed channel-wise by the
  *                output of module skip_from (-1 = none; must be < i), centre-cropped to the
@@ -289,8 +294,8 @@ int tern_conv3d_digits(const uint32_t* in_packed, tern_dims in_dims, const uint3
  *   workspace  : device scratch of at least tern_net_workspace_bytes() bytes, 16-byte aligned;
  *                holds the packed input (or, as in tern_fcn_forward, the gathered taps of a
  *                one-channel input's first module), every module's output and every
- *                concatenated tensor, each in a region of its own (nothing is overwritten
- *                within a call).
+ *                concatenated or pooled tensor, each in a region of its own (nothing is
+ *                overwritten within a call).
  *   module_out / module_dims : optional host arrays of n_mods entries that receive the device
  *                address (inside workspace) and logical extents of every module's packed output.
  * Errors as for the calls it is made of; TERN_EARG for an invalid skip_from or crop,
@@ -305,6 +310,7 @@ typedef struct {
     const int32_t* thr_hi;
     int32_t skip_from;
     int32_t up[3];
+    int32_t pool[3];            /* {1,1,1} or all 0: none; else sum pooling through two digits */
 } tern_module;
 size_t tern_net_workspace_bytes(tern_dims in_dims, const tern_module* mods /* host */, int32_t n_mods);
 int tern_net_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,

@@ -48,7 +48,8 @@ class Source(C.Structure):
 
 class Module(C.Structure):
     _fields_ = [("c_out", C.c_int32), ("g", Geom), ("w_bank", C.c_void_p), ("thr_lo", C.c_void_p),
-                ("thr_hi", C.c_void_p), ("skip_from", C.c_int32), ("up", C.c_int32 * 3)]
+                ("thr_hi", C.c_void_p), ("skip_from", C.c_int32), ("up", C.c_int32 * 3),
+                ("pool", C.c_int32 * 3)]
 
 
 def lib_path() -> str:
@@ -494,22 +495,24 @@ def tern_conv3d_real(in_packed: torch.Tensor, c_in: int, w: torch.Tensor,
 class NetModule:
     """One module of tern_net_forward: a fused ternary convolution whose input is the previous
     module's output, optionally upsampled (`up`) and followed by the centre-cropped output of
-    module `skip_from`."""
+    module `skip_from`, optionally sum-pooled over `pool` (then w_bank is the bank of
+    tern_digits_weights' output and the cut points refer to window sums)."""
 
     def __init__(self, c_out: int, w_bank: torch.Tensor, thr_lo: torch.Tensor, thr_hi: torch.Tensor,
-                 k=3, stride=1, pad=0, dil=1, skip_from: int = -1, up=1):
+                 k=3, stride=1, pad=0, dil=1, skip_from: int = -1, up=1, pool=1):
         _dev(w_bank, PACKED_DTYPE, "w_bank")
         _dev(thr_lo, torch.int32, "thr_lo")
         _dev(thr_hi, torch.int32, "thr_hi")
         self.c_out, self.w_bank, self.thr_lo, self.thr_hi = int(c_out), w_bank, thr_lo, thr_hi
         self.k, self.stride, self.pad, self.dil = _t3(k), _t3(stride), _t3(pad), _t3(dil)
-        self.skip_from, self.up = int(skip_from), _t3(up)
+        self.skip_from, self.up, self.pool = int(skip_from), _t3(up), _t3(pool)
 
     def as_struct(self) -> Module:
         m = Module(self.c_out, _geom(self.k, self.stride, self.pad, self.dil), self.w_bank.data_ptr(),
                    self.thr_lo.data_ptr(), self.thr_hi.data_ptr(), self.skip_from)
         for a in range(3):
             m.up[a] = self.up[a]
+            m.pool[a] = self.pool[a]
         return m
 
 
@@ -592,6 +595,8 @@ def _net_dims(in_shape, mods):
         d, h, w = d * m.up[0], h * m.up[1], w * m.up[2]
         if m.skip_from >= 0:
             c += out[m.skip_from][1]
+        if max(m.pool) > 1:
+            c, d, h, w = 64 * tern_words(c), d // m.pool[0], h // m.pool[1], w // m.pool[2]
         cur = tern_conv_out_dims((n, c, d, h, w), m.c_out, m.k, m.stride, m.pad, m.dil)
         out.append(cur)
     return out

@@ -502,7 +502,8 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
     tern_dims o0 = in_dims;
     {
         const tern_module& m0 = mods[0];
-        const bool plain = m0.skip_from == -1 && m0.up[0] == 1 && m0.up[1] == 1 && m0.up[2] == 1;
+        const bool plain = m0.skip_from == -1 && m0.up[0] == 1 && m0.up[1] == 1 && m0.up[2] == 1 &&
+                           m0.pool[0] <= 1 && m0.pool[1] <= 1 && m0.pool[2] <= 1;
         if (plain && geom_check(in_dims, m0.c_out, m0.g, &o0) == TERN_OK)
             gathered = patch_pack_applies(in_dims.c, m0.g, o0);
     }
@@ -575,6 +576,26 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
             cur = cat;
             cur_off = cat_off;
         }
+        // sum pooling in front of the module: two balanced-ternary digits per channel
+        const bool pooled = m.pool[0] > 1 || m.pool[1] > 1 || m.pool[2] > 1;
+        if (pooled) {
+            for (int a = 0; a < 3; ++a)
+                if (m.pool[a] < 1 || m.pool[a] > 4) return TERN_EARG;
+            if (m.pool[0] * m.pool[1] * m.pool[2] > 4) return TERN_EARG;
+            const int64_t c2 = 64 * (int64_t)tern_words(cur.c);
+            if (c2 > INT32_MAX) return TERN_ESHAPE;
+            const tern_dims pd = {cur.n, (int32_t)c2, cur.d / m.pool[0], cur.h / m.pool[1], cur.w / m.pool[2]};
+            if (!sizes_ok(pd)) return TERN_ESHAPE;
+            const size_t pool_off = off;
+            off += region(pd);
+            if (w && w->run) {
+                const int rcp = tern_pool_digits((const uint32_t*)(w->ws + cur_off), cur, m.pool,
+                                                 (uint32_t*)(w->ws + pool_off), w->stream);
+                if (rcp != TERN_OK) return rcp;
+            }
+            cur = pd;
+            cur_off = pool_off;
+        }
         tern_dims o;
         int rc = geom_check(cur, m.c_out, m.g, &o);
         if (rc != TERN_OK) return rc;
@@ -602,6 +623,10 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
                 fc.c_out = m.c_out; fc.co_pad = (m.c_out + 31) / 32 * 32;
                 fc.wd_out = tern_words(m.c_out);
                 rc = launch_patch_conv_f32(first, fc, in_dims.n, w->stream);
+            } else if (pooled) {
+                rc = tern_conv3d_digits((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g,
+                                        m.thr_lo, m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]),
+                                        w->stream);
             } else {
                 rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
                                  m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
