@@ -92,6 +92,14 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 2, fake, need - 1, fake, C.byref(od), None, None) == -4
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 0, fake, need, fake, C.byref(od), None, None) == -3
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 2, None, need, fake, C.byref(od), None, None) == -1
+    # two-digit pooling and convolution
+    win = (C.c_int32 * 3)(1, 2, 2)
+    assert L.tern_pool_digits(None, d, win, fake, None) == -1
+    assert L.tern_pool_digits(fake, d, (C.c_int32 * 3)(2, 2, 2), fake, None) == -3
+    assert L.tern_pool_digits(fake, d, (C.c_int32 * 3)(1, 0, 2), fake, None) == -3
+    assert L.tern_conv3d_digits(fake, d, fake, 8, g, None, None, fake, None, None) == -3          # 32 channels: no digit pairs
+    assert L.tern_conv3d_digits(fake, Dims(1, 64, 4, 4, 4), None, 8, g, None, None, fake, None, None) == -1
+    assert L.tern_digits_weights(None, 4, 4, 27, None) == -1
     # probe: null sink, launch shape and variant are checked before anything is launched
     assert L.tern_probe_valu(4, 256, 10, 0, None, None) == -1
     assert L.tern_probe_valu(4, 100, 10, 0, fake, None) == -3
@@ -207,10 +215,11 @@ def test_net_forward_wiring_is_validated_on_the_host(T):
     fake = 0x1000
     p = C.c_void_p(fake)
 
-    def mod(c_out, k=3, stride=1, pad=1, skip=-1, up=(1, 1, 1), bank=fake):
+    def mod(c_out, k=3, stride=1, pad=1, skip=-1, up=(1, 1, 1), bank=fake, pool=(1, 1, 1)):
         m = Module(c_out, _geom(k, stride, pad, 1), bank, fake, fake, skip)
         for a in range(3):
             m.up[a] = up[a]
+            m.pool[a] = pool[a]
         return m
 
     d = Dims(1, 4, 4, 8, 8)
@@ -223,6 +232,13 @@ def test_net_forward_wiring_is_validated_on_the_host(T):
     assert L.tern_net_workspace_bytes(d, (Module * 2)(mod(8), mod(8, up=(0, 1, 1))), 2) == 0
     # the skipped tensor must be at least as large as the (upsampled) incoming one
     assert L.tern_net_workspace_bytes(d, (Module * 3)(mod(8, stride=2), mod(8), mod(8, skip=0, up=(4, 4, 4))), 3) == 0
+    # sum pooling in front of a module: a region for the two-digit tensor (64 channels per input
+    # word, here 8 channels -> 64, at the pooled extent 4x4x4) on top of input and two outputs
+    pooled = (Module * 2)(mod(8), mod(16, pool=(1, 2, 2)))
+    assert L.tern_net_workspace_bytes(d, pooled, 2) == 256 * 8 + 256 * 8 + 64 * 16 + 64 * 8
+    assert L.tern_net_workspace_bytes(d, (Module * 2)(mod(8), mod(16, pool=(2, 2, 2))), 2) == 0   # window above 4 voxels
+    assert L.tern_net_workspace_bytes(d, (Module * 2)(mod(8), mod(16, pool=(1, 5, 1))), 2) == 0
+    assert L.tern_net_workspace_bytes(d, (Module * 2)(mod(8), mod(16, pool=(1, -1, 2))), 2) == 0
     hg = _geom(1, 1, 0, 1)
     hd = Dims()
     args = lambda mods, n, ws_bytes, ws=p, head=None, hout=None: L.tern_net_forward(

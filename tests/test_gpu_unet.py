@@ -307,6 +307,16 @@ def test_unet_many_stacks_take_the_two_kernel_first_module(G):
     check_unet(G, synth.unet_table1(seed=7, n=4, width_div=8))
 
 
+def test_unet_reduced_with_every_pooled_module_through_two_digits(G, monkeypatch):
+    """The same narrow networks with the plan's size threshold at zero, so that modules 4, 6 and 8
+    all pool into two digits (tern_module.pool) instead of folding the window into their filters;
+    odd extents in front of the pooling drop their last row and column either way."""
+    from paper_1801_09449_amd import unet
+    monkeypatch.setattr(unet.UNetPlan, "DIGITS_FROM_MACS", 0.0)
+    check_unet(G, synth.unet_table1(seed=5, n=3, width_div=8, size=(84, 76), slices=5))
+    check_unet(G, synth.unet_table1(seed=6, n=1, width_div=3, size=(92, 100), slices=15))
+
+
 def test_unet_table1_full_size(G):
     """The network at the paper's size (236 x 172 x 15 stack, full channel counts), one stack."""
     check_unet(G, synth.unet_table1(seed=0, n=1))
