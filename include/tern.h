@@ -387,10 +387,16 @@ int tern_fold_batchnorm(const double* alpha, const double* gamma, const double* 
  * add their partial sums in LDS, 0 = choose, 1, 2, 4 or 8.  TERN_OPT_POINTWISE: 1 (default) = 1x1x1
  * convolutions with unit stride and no padding use the pointwise kernel when the input has 1, 2,
  * 3, 4, 5 or 8 words per plane, 0 = they go through the tiled kernel like any other.
+ * TERN_OPT_LANE_TILE: the block of 64 output voxels that one wave of the tiled kernel computes,
+ * 0 = choose (8 x 8 in a plane, or a smaller footprint over several planes where that wastes fewer
+ * lanes on the edges of a stack of independent planes), -1 = always 8 x 8, 100 * X + Y with X, Y in
+ * {1, 2, 4, 8} and X * Y >= 4 = X x Y voxels in 64 / (X * Y) planes wherever the output has more
+ * than one plane.
  * Results never depend on options.  Returns TERN_EARG for an unknown option or
  * value. */
 typedef enum { TERN_OPT_LANE_DEPTH = 1, TERN_OPT_WAVES_Z = 2, TERN_OPT_CO_BLOCK = 3,
-               TERN_OPT_CO_PER_WAVE = 4, TERN_OPT_TAP_SPLIT = 5, TERN_OPT_POINTWISE = 6 } tern_option;
+               TERN_OPT_CO_PER_WAVE = 4, TERN_OPT_TAP_SPLIT = 5, TERN_OPT_POINTWISE = 6,
+               TERN_OPT_LANE_TILE = 7 } tern_option;
 int tern_set_option(int option, int value);
 
 /*

@@ -416,7 +416,8 @@ def tern_probe_valu(blocks: int, threads: int, iters: int, sink: torch.Tensor, v
 
 
 def tern_set_option(option: int, value: int) -> None:
-    """Tuning override (1 = lane depth: 0 auto, 2, 4).  Results never depend on options."""
+    """Tuning override (option numbers and values as in tern_option of the C header).  Results never
+    depend on options."""
     _check(lib().tern_set_option(int(option), int(value)), "tern_set_option")
 
 

@@ -172,6 +172,13 @@ int tern_set_option(int option, int value)
         set_pointwise(value);
         return TERN_OK;
     }
+    if (option == TERN_OPT_LANE_TILE) {
+        const int lx = value / 100, ly = value % 100;
+        auto pow2 = [](int v) { return v == 1 || v == 2 || v == 4 || v == 8; };
+        if (value != 0 && value != -1 && !(pow2(lx) && pow2(ly) && lx * ly >= 4)) return TERN_EARG;
+        set_lane_tile(value);
+        return TERN_OK;
+    }
     if (option == TERN_OPT_WAVES_Z) {
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return TERN_EARG;
         set_waves_z(value);

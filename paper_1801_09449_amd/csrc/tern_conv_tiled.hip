@@ -59,8 +59,12 @@ struct TileParams {
     int32_t vy;                   // 1: a lane's V voxels are 8 rows apart along y (single-plane
                                   // outputs); 0: consecutive along z
     // flat halo fill: floor(e / d) = umulhi(e, m_d) with m_d = 0xffffffff / d + 1 for d = hx,
-    // hy * hx and nchunk (valid for e * d < 2^32 and d > 1; m_ch is unused when nchunk = 1)
+    // hy * hx and nchunk (valid for e * d < 2^32 and d > 1; m_ch is unused when nchunk = 1, m_hx
+    // when hx = 1)
     uint32_t m_hx, m_pl, m_ch;
+    // a wave's 64 lanes cover 2^lxb x 2^lyb x 64 / 2^(lxb + lyb) output voxels (x, y, z), x fastest
+    int32_t lxb, lyb;
+    int32_t flat;                 // 1: halo fill over one flat index space, 0: per plane position
 };
 
 template <int WC>
@@ -209,8 +213,9 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int tiz = bid % t.tiles_z;
     const int n = bid / t.tiles_z;
     // A lane's V output voxels are stacked along z, or (vy: single-plane outputs) along y.
-    const int ywave = t.vy ? 8 * V : 8, zwave = t.vy ? 1 : V;   // output extent of one wave
-    const int TX = 8 * t.nwx, TY = ywave * t.nwy, TZ = zwave * t.nwz;
+    const int LX = 1 << t.lxb, LY = 1 << t.lyb, LZ = 64 >> (t.lxb + t.lyb);   // lanes along x, y, z
+    const int ywave = t.vy ? LY * V : LY, zwave = t.vy ? 1 : LZ * V;   // output extent of one wave
+    const int TX = LX * t.nwx, TY = ywave * t.nwy, TZ = zwave * t.nwz;
     const int ox0 = tix * TX, oy0 = tiy * TY, oz0 = tiz * TZ;
 
     // ---- stage the halo tile -------------------------------------------------------------
@@ -226,7 +231,7 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
         const int wd = p.wd_in;
         const uint32_t* in_n = p.in + (size_t)n * p.d * p.h * p.w * 2u * wd;
         const size_t zstride = (size_t)p.h * p.w * 2u * wd;   // words between input planes
-        if (t.hz >= 4) {
+        if (!t.flat) {
             for (int i = tid; i < plane; i += nthreads) {
                 const int hy = i / t.hx;
                 const int hxx = i - hy * t.hx;
@@ -297,7 +302,7 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
                     const uint32_t ch = e - vox * nch;
                     const uint32_t hz = __umulhi(vox, m_pl);
                     const uint32_t i = vox - hz * plane;
-                    const int hy = (int)__umulhi(i, m_hx);
+                    const int hy = t.hx > 1 ? (int)__umulhi(i, m_hx) : (int)i;   // no 32-bit reciprocal of 1
                     const int hxx = (int)i - hy * t.hx;
                     const int gz = gz0 + (int)hz, gy = gy0 + hy, gx = gx0 + hxx;
                     const bool inb = e < items && gz >= 0 && gz < p.d && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
@@ -337,16 +342,17 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int wy = (wslot / t.nwx) % t.nwy;
     const int wz = (wslot / (t.nwx * t.nwy)) % t.nwz;
     const int wch = wslot / nsp;                      // channel slice of this wave
-    const int lx = lane & 7, ly = lane >> 3;
-    const int ox = ox0 + wx * 8 + lx;
+    const int lx = lane & (LX - 1), ly = (lane >> t.lxb) & (LY - 1);
+    const int lz = t.vy ? 0 : (lane >> (t.lxb + t.lyb)) * V;   // first of the lane's planes in the wave
+    const int ox = ox0 + wx * LX + lx;
     const int oy = oy0 + wy * ywave + ly;
-    const int ozb = oz0 + wz * zwave;
+    const int ozb = oz0 + wz * zwave + lz;
     const int row_words = t.hx * t.vstride;
     const int plane_words = t.hy * row_words;
     // LDS word offset of the tap-(0,0,0) input voxel of this lane's output voxel v = 0
-    const int lane_base = (wz * zwave * p.sd) * plane_words + (wy * ywave + ly) * p.sh * row_words +
-                          (wx * 8 + lx) * p.sw * t.vstride;
-    const int vstep = t.vy ? 8 * p.sh * row_words : p.sd * plane_words;  // between consecutive v
+    const int lane_base = ((wz * zwave + lz) * p.sd) * plane_words + (wy * ywave + ly) * p.sh * row_words +
+                          (wx * LX + lx) * p.sw * t.vstride;
+    const int vstep = t.vy ? LY * p.sh * row_words : p.sd * plane_words;  // between consecutive v
     const uint32_t* lane_lds = lds + lane_base;
 
     const int T = p.kd * p.kh * p.kw;
@@ -479,7 +485,7 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     const int oz = t.vy ? ozb : ozb + v;
-                    const int oyv = t.vy ? oy + 8 * v : oy;
+                    const int oyv = t.vy ? oy + LY * v : oy;
                     if (ox < p.ow && oyv < p.oh && oz < p.od) {
                         uint32_t* o = p.out_packed +
                                       ((((size_t)n * p.od + oz) * p.oh + oyv) * p.ow + ox) * 2u * p.wd_out;
@@ -502,7 +508,7 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const int oz = t.vy ? ozb : ozb + v;
-                const int oyv = t.vy ? oy + 8 * v : oy;
+                const int oyv = t.vy ? oy + LY * v : oy;
                 if (ox < p.ow && oyv < p.oh && oz < p.od) {
                     int32_t* o = p.out_acc + (size_t)n * p.c_out * cstride +
                                  ((size_t)oz * p.oh + oyv) * p.ow + ox;
@@ -545,11 +551,17 @@ int g_co_block = 0;     // tuning override: 0 = choose, 16 or 32 = channels per 
 int g_co_per_wave = 0;  // tuning override: 0 = choose, else channels per wave (multiple of 16)
 int g_tap_split = 0;    // tuning override: 0 = choose, else waves sharing the taps of one slice
 int g_point = 1;        // tuning override: 0 = never use the pointwise kernel
+int g_lane_tile = 0;    // tuning override: 0 = choose, else 100 * LX + LY lanes of a wave along x and y
 
-// Tile plan for a voxel depth V per lane; returns false if no halo tile fits in LDS.
-bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_t& lds_bytes)
+// Tile plan for a voxel depth V per lane and a wave of 2^lxb x 2^lyb x (64 / 2^(lxb + lyb)) lanes;
+// returns false if no halo tile fits in LDS.  Single-plane outputs need lxb + lyb = 6.
+bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_t& lds_bytes,
+                int lxb = 3, int lyb = 3)
 {
     const int wd = p.wd_in;
+    const int LX = 1 << lxb, LY = 1 << lyb, LZ = 64 >> (lxb + lyb);
+    t.lxb = lxb; t.lyb = lyb; t.flat = 1;
+    if (p.od == 1 && LZ != 1) return false;
     t.nchunk = wd / p.wc;
     t.vstride = 2 * wd + (wd >= 4 ? 4 : 0);
     t.nwx = 1; t.nwy = 1; t.nwz = g_waves_z > 0 ? g_waves_z : 1;
@@ -564,11 +576,11 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     }
     // Single-plane outputs (2-D convolutions): a lane's V voxels go along y instead of z.
     t.vy = p.od == 1 ? 1 : 0;
-    const int vyx = t.vy ? V : 1, vzx = t.vy ? 1 : V;
+    const int vyx = t.vy ? V : 1, vzx = t.vy ? 1 : V * LZ;
     auto halo = [](int tiles_out, int stride, int k, int dil) { return (tiles_out - 1) * stride + (k - 1) * dil + 1; };
     auto lds_for = [&](const TileParams& q) {
-        const int64_t hx = halo(8 * q.nwx, p.sw, p.kw, p.dw);
-        const int64_t hy = halo(8 * vyx * q.nwy, p.sh, p.kh, p.dh);
+        const int64_t hx = halo(LX * q.nwx, p.sw, p.kw, p.dw);
+        const int64_t hy = halo(LY * vyx * q.nwy, p.sh, p.kh, p.dh);
         const int64_t hz = halo(vzx * q.nwz, p.sd, p.kd, p.dd);
         return hx * hy * hz * q.vstride * 4;
     };
@@ -576,7 +588,7 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     // lowers LDS per wave the most) while the per-wave LDS share is too large for the waves a
     // compute unit is expected to hold: eight (20 KB each of the 160 KB) on a large problem,
     // fewer on a small one, where small tiles matter more because they give more workgroups.
-    const int64_t waves1 = (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8 * vyx) * cdiv(p.od, vzx) * p.n * cdiv(p.c_out, 16);
+    const int64_t waves1 = (int64_t)cdiv(p.ow, LX) * cdiv(p.oh, LY * vyx) * cdiv(p.od, vzx) * p.n * cdiv(p.c_out, 16);
     int per_cu = (int)((waves1 + 255) / 256);
     per_cu = per_cu < 1 ? 1 : (per_cu > 8 ? 8 : per_cu);
     const int64_t share_budget = (int64_t)(160 * 1024) / per_cu;
@@ -598,11 +610,11 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
     }
     lds_bytes = lds_for(t);
     if (lds_bytes > lds_limit) return false;
-    t.hx = halo(8 * t.nwx, p.sw, p.kw, p.dw);
-    t.hy = halo(8 * vyx * t.nwy, p.sh, p.kh, p.dh);
+    t.hx = halo(LX * t.nwx, p.sw, p.kw, p.dw);
+    t.hy = halo(LY * vyx * t.nwy, p.sh, p.kh, p.dh);
     t.hz = halo(vzx * t.nwz, p.sd, p.kd, p.dd);
-    t.tiles_x = cdiv(p.ow, 8 * t.nwx);
-    t.tiles_y = cdiv(p.oh, 8 * vyx * t.nwy);
+    t.tiles_x = cdiv(p.ow, LX * t.nwx);
+    t.tiles_y = cdiv(p.oh, LY * vyx * t.nwy);
     t.tiles_z = cdiv(p.od, vzx * t.nwz);
     t.m_hx = 0xffffffffu / (uint32_t)t.hx + 1u;
     t.m_pl = 0xffffffffu / (uint32_t)(t.hx * t.hy) + 1u;
@@ -618,6 +630,7 @@ void set_co_block(int v) { g_co_block = (v == 16 || v == 32) ? v : 0; }
 void set_co_per_wave(int v) { g_co_per_wave = (v > 0 && v % 16 == 0) ? v : 0; }
 void set_tap_split(int v) { g_tap_split = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
 void set_pointwise(int v) { g_point = v ? 1 : 0; }
+void set_lane_tile(int v) { g_lane_tile = v; }
 
 int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 {
@@ -722,10 +735,47 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     }
     if (V == 2) V = lane_depth_for(co_blk);
     if (p.digits) V = 1;   // the only variant built for two-digit inputs
+    // Shape of a wave's 64 output voxels.  8 x 8 in a plane by default.  Stacks of independent
+    // planes (kd = 1) start from 4 x 8 in two planes instead (measured equal to 9 % faster than
+    // 8 x 8 on the 2-D layers of a batch of 16, never slower), and where the extents leave much of
+    // the last tile of a row or column empty, a still smaller footprint over more planes
+    // (4 x 4 x 4, 2 x 8 x 4, ...) wastes fewer lanes at the price of a larger halo per output.
+    // Estimate: word-pair instructions of all waves plus about 32 instructions per halo item
+    // staged; another shape has to beat the starting one by 3 %.
+    int lxb = 3, lyb = 3;
+    if (p.od > 1 && g_lane_tile > 0) {
+        const int lx = g_lane_tile / 100, ly = g_lane_tile % 100;
+        for (int a = 0; a < 4; ++a)
+            for (int b = 0; b < 4; ++b)
+                if ((1 << a) == lx && (1 << b) == ly && a + b >= 2) { lxb = a; lyb = b; }
+    } else if (p.od > 1 && g_lane_tile == 0 && p.kd == 1 && p.tp_slots == 0) {
+        auto score = [&](int a, int b) -> double {
+            TileParams q;
+            int64_t bytes = 0;
+            if (!plan_tiles(p, V, lds_limit, q, bytes, a, b)) return 1e300;
+            const int nsp = q.nwx * q.nwy * q.nwz;
+            if (nsp > 8) return 1e300;
+            const int slices = cdiv(p.c_out, co_blk);
+            int nwc = 4 / nsp < 1 ? 1 : 4 / nsp;
+            if (nwc > slices) nwc = slices;
+            const double tiles = (double)q.tiles_x * q.tiles_y * q.tiles_z * p.n;
+            const double mac = tiles * nsp * steps_all * p.wc * 4.0 * V * slices * co_blk;
+            const double fill = tiles * cdiv(slices, nwc) * ((double)q.hx * q.hy * q.hz * q.nchunk / 64.0) * 32.0;
+            return mac + fill;
+        };
+        double best = score(2, 3);
+        if (best < 1e300) { lxb = 2; lyb = 3; best *= 0.97; }
+        for (int a = 0; a < 4; ++a)
+            for (int b = 0; b < 4; ++b) {
+                if (a + b < 2 || (a == 2 && b == 3)) continue;
+                const double e = score(a, b);
+                if (e < best) { best = e; lxb = a; lyb = b; }
+            }
+    }
     TileParams t;
     int64_t lds_bytes = 0;
-    if (!plan_tiles(p, V, lds_limit, t, lds_bytes)) {
-        if (V == 4 && plan_tiles(p, 2, lds_limit, t, lds_bytes)) V = 2;
+    if (!plan_tiles(p, V, lds_limit, t, lds_bytes, lxb, lyb)) {
+        if (V == 4 && plan_tiles(p, 2, lds_limit, t, lds_bytes, lxb, lyb)) V = 2;
         else if (p.digits) return TERN_ESHAPE;   // the fallback kernel knows one-digit inputs only
         else return launch_conv3d_generic(p, s);
     }
@@ -781,6 +831,16 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 
     const dim3 grid((unsigned)spatial_tiles, (unsigned)grid_y);
     const int threads = 64 * nsp * nwc * nks;
+    // Halo fill: per plane position (a thread fetches up to 8 planes of one position and chunk
+    // per round trip) for tiles of 4 planes or more, else over one flat index space.  Wave shapes
+    // with a small footprint have few positions per plane: they take whichever needs fewer trips.
+    t.flat = t.hz < 4 ? 1 : 0;
+    if (!(lxb == 3 && lyb == 3) && !t.flat) {
+        const int plane = t.hx * t.hy;
+        const int64_t deep_trips = (int64_t)cdiv(plane, threads) * t.nchunk * cdiv(t.hz, 8);
+        const int64_t flat_trips = ((int64_t)t.hz * plane * t.nchunk + 8 * threads - 1) / (8 * threads);
+        if (flat_trips < deep_trips) t.flat = 1;
+    }
     const size_t lb = (size_t)lds_bytes;
 #define TERN_LAUNCH(WC_, V_, CB_, TP_)                                                       \
     (packed ? launch_variant<WC_, V_, CB_, true, TP_>(p, t, lb, grid, threads, s)            \

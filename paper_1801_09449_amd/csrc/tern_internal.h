@@ -140,6 +140,7 @@ void set_waves_z(int v);
 void set_co_block(int v);
 void set_co_per_wave(int v);
 void set_tap_split(int v);
+void set_lane_tile(int v);
 void set_pointwise(int v);
 int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
                         int32_t kw, uint32_t* bank, hipStream_t s);

@@ -109,6 +109,10 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     assert L.tern_set_option(99, 0) == -3
     assert L.tern_set_option(3, 24) == -3
     assert L.tern_set_option(3, 0) == 0
+    for bad in (1, 303, 101, 102, 1608, 816, -2):      # wave shapes: powers of two up to 8, at least 4 lanes per plane
+        assert L.tern_set_option(7, bad) == -3
+    for good in (808, 408, 202, 401, -1, 0):
+        assert L.tern_set_option(7, good) == 0
     assert b"TERN_ESHAPE" in L.tern_status_string(-2)
 
 

@@ -226,6 +226,40 @@ def test_conv_kernel_variants_agree_with_oracle(G, opts):
             T.tern_set_option(key, 0)
 
 
+LANE_TILES = [-1, 804, 408, 404, 802, 208, 402, 204, 202, 801, 108, 104, 401]
+
+
+@pytest.mark.parametrize("tile", LANE_TILES, ids=[str(v) for v in LANE_TILES])
+@pytest.mark.parametrize("depth", [0, 2], ids=["auto", "v2"])
+def test_wave_shapes_agree_with_oracle(G, tile, depth):
+    """Every block of 64 output voxels a wave can be given (X x Y lanes in 64 / (X * Y) planes),
+    on 3-D convolutions, on stacks of independent planes (kernel depth 1, batch collapsed into
+    planes; extents that leave ragged tiles in x, y and z), with one and two voxels per lane, a
+    tap-packed case, a single-tap case, split taps and int32 output."""
+    import paper_1801_09449_amd as T
+    cases = [
+        synth.conv_case("w_3d", 1, 64, 48, (7, 13, 11), seed=301),
+        synth.conv_case("w_3d_s2", 2, 96, 32, (9, 12, 10), stride=2, seed=302),
+        synth.conv_case("w_stack", 5, 64, 64, (1, 21, 14), k=(1, 3, 3), pad=0, seed=303),
+        synth.conv_case("w_stack_c32", 3, 32, 40, (2, 11, 19), k=(1, 3, 3), pad=(0, 1, 1), seed=304),
+        synth.conv_case("w_stack_c512", 7, 512, 32, (1, 8, 9), k=(1, 3, 3), pad=0, seed=305),
+        synth.conv_case("w_stack_tp", 4, 8, 16, (1, 12, 12), k=(1, 3, 3), pad=(0, 1, 1), seed=306),
+        synth.conv_case("w_dil", 1, 64, 16, (6, 10, 10), pad=2, dil=2, seed=307),
+        # a single tap kept in the tiled kernel: halo tiles one voxel wide for X = 1
+        synth.conv_case("w_k1", 3, 128, 40, (3, 5, 5), k=1, pad=0, seed=308),
+    ]
+    try:
+        T.tern_set_option(7, tile)
+        T.tern_set_option(1, depth)
+        T.tern_set_option(6, 0)
+        for c in cases:
+            check_case(G, c)
+    finally:
+        T.tern_set_option(7, 0)
+        T.tern_set_option(1, 0)
+        T.tern_set_option(6, 1)
+
+
 def random_case(i):
     """Seeded random geometry: channels up to 300, extents up to 20, kernels up to 5 per axis with
     random stride, padding and dilation (kept valid), batch up to 3."""
