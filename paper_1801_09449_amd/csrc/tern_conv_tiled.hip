@@ -737,18 +737,20 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     if (p.digits) V = 1;   // the only variant built for two-digit inputs
     // Shape of a wave's 64 output voxels.  8 x 8 in a plane by default.  Stacks of independent
     // planes (kd = 1) start from 4 x 8 in two planes instead (measured equal to 9 % faster than
-    // 8 x 8 on the 2-D layers of a batch of 16, never slower), and where the extents leave much of
-    // the last tile of a row or column empty, a still smaller footprint over more planes
-    // (4 x 4 x 4, 2 x 8 x 4, ...) wastes fewer lanes at the price of a larger halo per output.
-    // Estimate: word-pair instructions of all waves plus about 32 instructions per halo item
-    // staged; another shape has to beat the starting one by 3 %.
+    // 8 x 8 on the 2-D layers of a batch of 16, never slower).  Where the extents leave much of
+    // the last tile of a row or column empty, a smaller footprint over more planes (8 x 4 x 2,
+    // 4 x 4 x 4, and for plane stacks also 2 x 8 x 4, ...) wastes fewer lanes at the price of a
+    // larger halo per output: 4-14 % faster on 3-D volumes of 100, 44 and 20 voxels per axis, no
+    // difference where 8 x 8 tiles fit.  Estimate: word-pair instructions of all waves plus about
+    // 32 instructions per halo item staged; another shape has to beat the starting one by 3 %.
     int lxb = 3, lyb = 3;
     if (p.od > 1 && g_lane_tile > 0) {
         const int lx = g_lane_tile / 100, ly = g_lane_tile % 100;
         for (int a = 0; a < 4; ++a)
             for (int b = 0; b < 4; ++b)
                 if ((1 << a) == lx && (1 << b) == ly && a + b >= 2) { lxb = a; lyb = b; }
-    } else if (p.od > 1 && g_lane_tile == 0 && p.kd == 1 && p.tp_slots == 0) {
+    } else if (p.od > 1 && g_lane_tile == 0 && p.tp_slots == 0) {
+        const bool planes = p.kd == 1;   // independent planes
         auto score = [&](int a, int b) -> double {
             TileParams q;
             int64_t bytes = 0;
@@ -763,11 +765,14 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
             const double fill = tiles * cdiv(slices, nwc) * ((double)q.hx * q.hy * q.hz * q.nchunk / 64.0) * 32.0;
             return mac + fill;
         };
-        double best = score(2, 3);
-        if (best < 1e300) { lxb = 2; lyb = 3; best *= 0.97; }
-        for (int a = 0; a < 4; ++a)
-            for (int b = 0; b < 4; ++b) {
-                if (a + b < 2 || (a == 2 && b == 3)) continue;
+        double best = planes ? score(2, 3) : score(3, 3);
+        if (best < 1e300) {
+            if (planes) { lxb = 2; lyb = 3; }
+            best *= 0.97;
+        }
+        for (int a = planes ? 0 : 2; a < 4; ++a)
+            for (int b = planes ? 0 : 2; b < 4; ++b) {
+                if (a + b < 2 || (a == lxb && b == lyb)) continue;
                 const double e = score(a, b);
                 if (e < best) { best = e; lxb = a; lyb = b; }
             }
