@@ -138,6 +138,28 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims,
                 int32_t* out_acc, uint32_t* out_packed, void* stream);
 
 /*
+ * tern_conv3d_mfma -- the same convolution, same arguments, same results bit for bit, with the
+ * inner products of section 2 (the sums that Eq. 9 evaluates by two bit-counts) taken by the
+ * int8 matrix instructions instead: activations stay packed in memory, a workgroup expands its
+ * halo tile to one byte per code in LDS and multiplies it with a byte filter bank.  Not the
+ * paper's scheme (which exists because CPUs count bits faster than they multiply); provided
+ * because on this device the matrix cores multiply faster than the vector units count.
+ *   byte_bank : tern_byte_bank_bytes(...) bytes, 16-byte aligned, made once per layer by
+ *               tern_expand_filters from the same int8 weights [C_out][C_in][kd][kh][kw] that
+ *               tern_pack_filters takes (layout [tap][word of 32 input channels][block of 32
+ *               filters][half of the word][filter][16 bytes], codes as 0x01 / 0xff / 0x00).
+ * Returns TERN_ESHAPE when the halo of an 8 x 8 x 8 block of outputs does not fit in LDS (large
+ * strides or dilations); tern_conv3d has no such limit.
+ */
+size_t tern_byte_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw);
+int tern_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                        int32_t kw, uint32_t* byte_bank, void* stream);
+int tern_conv3d_mfma(const uint32_t* in_packed, tern_dims in_dims,
+                     const uint32_t* byte_bank, int32_t c_out, tern_conv_geom g,
+                     const int32_t* thr_lo, const int32_t* thr_hi,
+                     int32_t* out_acc, uint32_t* out_packed, void* stream);
+
+/*
  * tern_threshold_pack -- the hard ternary activation of Eq. 6 followed by 2-bit packing, on a
  * tensor that is already in memory:  code = +1 if v > hi[c]; -1 if v < lo[c]; else 0.
  *   src    : contiguous [N][C][D][H][W] of type t (TERN_SRC_I32: int32 accumulators with int32

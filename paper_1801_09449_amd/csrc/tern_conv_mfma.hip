@@ -1,0 +1,364 @@
+// Ternary convolution on the matrix cores: the inner product of section 2 (the quantity that
+// Eq. 9 evaluates with two bit-counts) computed as an int8 matrix product.  Activations stay in
+// the packed two-plane layout in HBM; a workgroup expands its halo tile to one byte per code in
+// LDS (32 channels at a time) and contracts it with a byte filter bank through
+// v_mfma_i32_32x32x32_i8.  Same results as the bit-count kernels, bit for bit: every product is
+// an exact small integer and the accumulation is int32.
+//
+// Implicit matrix product: rows = output voxels, columns = output channels, inner index =
+// (kernel tap, input channel).  A wave owns 8 x 8 x 2 output voxels (four row blocks of 32:
+// plane p in {0, 1} x y-half h in {0, 1}, voxel i of a block at x = i % 8, y = 4 h + i / 8) and up
+// to 64 output channels (two column blocks), i.e. eight 32 x 32 accumulator tiles; four waves
+// stacked along z share a halo tile.  Per (tap, 32-channel word) a wave reads four row fragments
+// from LDS (one 16-byte read per lane each) and two column fragments from the filter bank
+// (16 bytes per lane, 1 KB contiguous per fragment, served by the vector cache) and issues eight
+// matrix instructions: LDS at half and the vector cache at half of what they can deliver.
+//
+// Operand layout of the instruction (inner extent 32 = two lane groups x 16 bytes): lane l of
+// the row operand holds row l % 32, lane l of the column operand holds column l % 32, and both
+// hold the inner indices of lane group l / 32 in the same byte order, so any consistent
+// assignment of (channel within the word) to (lane group, byte) gives the right sum; here
+// channel = 16 * (l / 32) + byte.  Result: lane l holds column l % 32, register v holds row
+// 8 * (v / 4) + 4 * (l / 32) + v % 4.
+#include "tern_internal.h"
+
+namespace tern {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kMaxWaves = 4;         // waves per workgroup (4, 2 or 1), stacked along z
+constexpr int kMaxThreads = 64 * kMaxWaves;
+constexpr int kTX = 8, kTY = 8;      // output voxels per workgroup: 8 x 8 x (2 per wave)
+constexpr int kRec = 48;             // LDS bytes per halo voxel: 32 channel bytes + 16 of padding
+constexpr int kFill = 4;             // halo items a thread keeps in flight
+
+struct MfmaPlan {
+    int32_t hx, hy, hz;              // halo extents in voxels
+    int32_t tiles_x, tiles_y, tiles_z;
+    int32_t nblk;                    // 32-channel column blocks in the filter bank
+    uint32_t m_hx, m_pl;             // floor(e / hx) = umulhi(e, m_hx), likewise hx * hy
+};
+
+// One byte per code from a word of 32 channels: +1 -> 0x01, -1 -> 0xff, 0 -> 0x00.
+// (nibble * 0x00204081) & 0x01010101 moves bit b of the nibble to bit 0 of byte b.
+__device__ __forceinline__ void expand_word(uint32_t m, uint32_t s, uint4& lo16, uint4& hi16)
+{
+    const uint32_t neg = m & s, pos = m & ~s;
+    uint32_t o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t pb = (((pos >> (4 * j)) & 15u) * 0x00204081u) & 0x01010101u;
+        const uint32_t nb = (((neg >> (4 * j)) & 15u) * 0x00204081u) & 0x01010101u;
+        o[j] = pb | (nb * 0xffu);
+    }
+    lo16 = make_uint4(o[0], o[1], o[2], o[3]);
+    hi16 = make_uint4(o[4], o[5], o[6], o[7]);
+}
+
+// Byte filter bank [tap][word][column block][lane group g][column j][16]: byte b of the entry is
+// the code of filter 32 * block + j at input channel 32 * word + 16 * g + b (0 past c_out or c_in).
+__global__ __launch_bounds__(256) void expand_filters_kernel(const int8_t* __restrict__ w, int32_t c_out,
+                                                             int32_t c_in, int32_t taps, int32_t wd,
+                                                             int32_t nblk, uint32_t* __restrict__ bank,
+                                                             int64_t dwords)
+{
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= dwords) return;
+    const int q = (int)(e & 3);                  // dword within the 16 bytes
+    const int j = (int)((e >> 2) & 31);
+    const int g = (int)((e >> 7) & 1);
+    int64_t r = e >> 8;                          // (tap * wd + word) * nblk + block
+    const int blk = (int)(r % nblk); r /= nblk;
+    const int word = (int)(r % wd);
+    const int tap = (int)(r / wd);
+    const int co = blk * 32 + j;
+    uint32_t out = 0u;
+    if (co < c_out) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int c = word * 32 + g * 16 + q * 4 + b;
+            if (c < c_in) {
+                const int v = w[((size_t)co * c_in + c) * taps + tap];
+                out |= (v > 0 ? 0x01u : v < 0 ? 0xffu : 0u) << (8 * b);
+            }
+        }
+    }
+    bank[e] = out;
+}
+
+// Eq. 6 on one 32 x 32 accumulator tile: register V of lane l is (row 8 (V / 4) + 4 (l / 32) +
+// V % 4, column l % 32).  A wave-wide comparison gives the 32 channel bits of two rows at once
+// (lanes 0-31: row r, lanes 32-63: row r + 4); they go to lanes r and r + 4 of posw / negw.
+template <int V>
+__device__ __forceinline__ void decide_rows(const v16i& acc, int32_t lo, int32_t hi, uint32_t& posw,
+                                            uint32_t& negw)
+{
+    if constexpr (V < 16) {
+        constexpr int r = (V >> 2) * 8 + (V & 3);
+        const unsigned long long bp = __ballot(acc[V] > hi);
+        const unsigned long long bn = __ballot(acc[V] < lo);
+        // The compiler does not see inside the statement: the wait states that a lane write
+        // needs after the comparisons wrote their scalar results are spelled out.
+        asm("s_nop 4\n\t"
+            "v_writelane_b32 %[p], %[pl], %[r0]\n\t"
+            "v_writelane_b32 %[p], %[ph], %[r1]\n\t"
+            "v_writelane_b32 %[n], %[nl], %[r0]\n\t"
+            "v_writelane_b32 %[n], %[nh], %[r1]"
+            : [p] "+v"(posw), [n] "+v"(negw)
+            : [pl] "s"((uint32_t)bp), [ph] "s"((uint32_t)(bp >> 32)), [nl] "s"((uint32_t)bn),
+              [nh] "s"((uint32_t)(bn >> 32)), [r0] "n"(r), [r1] "n"(r + 4));
+        decide_rows<V + 1>(acc, lo, hi, posw, negw);
+    }
+}
+
+template <int NB, bool PACKED>
+__global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv_mfma_kernel(ConvParams p, MfmaPlan t)
+{
+    extern __shared__ __align__(16) uint8_t lds8[];
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    int bid = blockIdx.x;
+    {   // contiguous runs of tiles per XCD (workgroups go to the 8 XCDs round-robin)
+        const int per_xcd = gridDim.x >> 3;
+        if (bid < (per_xcd << 3)) bid = (bid & 7) * per_xcd + (bid >> 3);
+    }
+    const int tix = bid % t.tiles_x; bid /= t.tiles_x;
+    const int tiy = bid % t.tiles_y; bid /= t.tiles_y;
+    const int tiz = bid % t.tiles_z;
+    const int n = bid / t.tiles_z;
+    const int ox0 = tix * kTX, oy0 = tiy * kTY, oz0 = tiz * (nthreads >> 5);   // two planes per wave
+    const int nb0 = blockIdx.y * NB;             // first column block of this workgroup
+
+    const int gx0 = ox0 * p.sw - p.pw, gy0 = oy0 * p.sh - p.ph, gz0 = oz0 * p.sd - p.pd;
+    const int plane = t.hx * t.hy;
+    const int nvox = plane * t.hz;
+    const int wd = p.wd_in;
+    const uint32_t* in_n = p.in + (size_t)n * p.d * p.h * p.w * 2u * wd;
+
+    const int i32 = lane & 31, g = lane >> 5;
+    const int xl = i32 & 7, yl = i32 >> 3;
+    const int row_b = t.hx * kRec, plane_b = t.hy * row_b;
+    const int lane_off = (wave * 2 * p.sd) * plane_b + (yl * p.sh) * row_b + (xl * p.sw) * kRec + g * 16;
+    int mboff[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) mboff[mb] = ((mb >> 1) * p.sd) * plane_b + ((mb & 1) * 4 * p.sh) * row_b;
+
+    const v4i* bank = reinterpret_cast<const v4i*>(p.wgt);
+    const int T = p.kd * p.kh * p.kw;
+
+    v16i acc[4][NB];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0;
+
+    for (int word = 0; word < wd; ++word) {
+        if (word > 0) __syncthreads();           // everyone is done reading the previous word's tile
+        // ---- stage the halo tile of this channel word, one byte per code ----
+        for (int e0 = tid; e0 < nvox; e0 += kFill * nthreads) {
+            uint32_t m[kFill], s[kFill];
+#pragma unroll
+            for (int k = 0; k < kFill; ++k) {
+                const uint32_t e = (uint32_t)(e0 + k * nthreads);
+                const uint32_t hz = __umulhi(e, t.m_pl);
+                const uint32_t r = e - hz * plane;
+                const int hy = (int)__umulhi(r, t.m_hx);
+                const int hxx = (int)r - hy * t.hx;
+                const int gz = gz0 + (int)hz, gy = gy0 + hy, gx = gx0 + hxx;
+                const bool inb = e < (uint32_t)nvox && gz >= 0 && gz < p.d && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
+                m[k] = s[k] = 0u;
+                if (inb) {
+                    const uint32_t vox = (uint32_t)((gz * p.h + gy) * p.w + gx);   // below 2^31 voxels per item
+                    const uint32_t* src = in_n + (size_t)vox * (2u * wd);
+                    m[k] = src[word];
+                    s[k] = src[wd + word];
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < kFill; ++k) {
+                const int e = e0 + k * nthreads;
+                if (e < nvox) {
+                    uint4 a, b;
+                    expand_word(m[k], s[k], a, b);
+                    uint4* dst = reinterpret_cast<uint4*>(lds8 + (size_t)e * kRec);
+                    dst[0] = a;
+                    dst[1] = b;
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- contract: all taps of this channel word ----
+        // Column fragments come from the vector cache, hundreds of cycles away: the next tap's
+        // are requested before this tap's matrix instructions are issued.
+        const uint8_t* lane_lds = lds8 + lane_off;
+        int tap = 0;
+        v4i Bn[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) Bn[nb] = bank[((size_t)word * t.nblk + nb0 + nb) * 64 + lane];
+        for (int a = 0; a < p.kd; ++a)
+            for (int b = 0; b < p.kh; ++b)
+                for (int c = 0; c < p.kw; ++c, ++tap) {
+                    const int toff = (a * p.dd) * plane_b + (b * p.dh) * row_b + (c * p.dw) * kRec;
+                    v4i A[4], B[NB];
+                    const int tnext = tap + 1 < T ? tap + 1 : tap;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        B[nb] = Bn[nb];
+                        Bn[nb] = bank[((size_t)(tnext * wd + word) * t.nblk + nb0 + nb) * 64 + lane];
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb)
+                        A[mb] = *reinterpret_cast<const v4i*>(lane_lds + toff + mboff[mb]);
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[mb], B[nb], acc[mb][nb], 0, 0, 0);
+                }
+    }
+
+    // ---- epilogue ----
+    // lane l holds column l % 32 (output channel) and, in register v, row 8 (v / 4) + 4 g + v % 4
+    // (voxel x = row % 8, y = row / 8 of the row block)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int co = (nb0 + nb) * 32 + i32;
+        if constexpr (PACKED) {
+            int32_t lo = INT32_MIN, hi = INT32_MAX;     // channels past c_out: code 0
+            if (co < p.c_out) { lo = p.lo[co]; hi = p.hi[co]; }
+            const int q = nb0 + nb;
+            if (q < p.wd_out) {
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb) {
+                    __builtin_amdgcn_sched_barrier(0);   // one tile at a time
+                    uint32_t posw = 0u, negw = 0u;      // lane r (< 32): words of the block's voxel r
+                    decide_rows<0>(acc[mb][nb], lo, hi, posw, negw);
+                    const int ox = ox0 + xl, oy = oy0 + (mb & 1) * 4 + yl, oz = oz0 + wave * 2 + (mb >> 1);
+                    if (g == 0 && ox < p.ow && oy < p.oh && oz < p.od) {
+                        uint32_t* o = p.out_packed + ((((size_t)n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
+                        o[q] = posw | negw;
+                        o[p.wd_out + q] = negw & ~posw;
+                    }
+                }
+            }
+        } else {
+            const size_t cstride = (size_t)p.od * p.oh * p.ow;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+                __builtin_amdgcn_sched_barrier(0);       // one tile at a time
+                const int oz = oz0 + wave * 2 + (mb >> 1);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = (v >> 2) * 8 + g * 4 + (v & 3);
+                    const int ox = ox0 + (r & 7), oy = oy0 + (mb & 1) * 4 + (r >> 3);
+                    if (co < p.c_out && ox < p.ow && oy < p.oh && oz < p.od)
+                        p.out_acc[((size_t)n * p.c_out + co) * cstride + ((size_t)oz * p.oh + oy) * p.ow + ox] =
+                            acc[mb][nb][v];
+                }
+            }
+        }
+    }
+}
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+template <int NB, bool PACKED>
+int launch_variant(const ConvParams& p, const MfmaPlan& t, size_t lds_bytes, dim3 grid, int threads,
+                   hipStream_t s)
+{
+    auto kern = conv_mfma_kernel<NB, PACKED>;
+    if (lds_bytes > 64 * 1024) {
+        static thread_local int raised_on_device = -1;
+        int dev = 0;
+        TERN_HIP_CHECK(hipGetDevice(&dev));
+        if (raised_on_device != dev) {
+            TERN_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+            raised_on_device = dev;
+        }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(threads), lds_bytes, s, p, t);
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
+
+}  // namespace
+
+size_t byte_bank_bytes(int32_t c_out, int32_t c_in, int32_t taps)
+{
+    const size_t wd = (size_t)(c_in + 31) / 32, nblk = (size_t)(c_out + 31) / 32;
+    return (size_t)taps * wd * nblk * 1024;
+}
+
+int launch_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t taps, uint32_t* bank,
+                          hipStream_t s)
+{
+    const int32_t wd = (c_in + 31) / 32, nblk = (c_out + 31) / 32;
+    const int64_t dwords = (int64_t)taps * wd * nblk * 256;
+    const int64_t blocks = (dwords + 255) / 256;
+    if (blocks > 0x7fffffff) return TERN_ESHAPE;
+    hipLaunchKernelGGL(expand_filters_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, c_out, c_in, taps, wd,
+                       nblk, bank, dwords);
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
+
+// p.wgt is the byte filter bank.  TERN_ESHAPE when the halo tile of even one wave's 8 x 8 x 2
+// output block does not fit in LDS (very large strides or dilations).
+int launch_conv3d_mfma(const ConvParams& p, hipStream_t s)
+{
+    MfmaPlan t;
+    auto halo = [](int out, int stride, int k, int dil) { return (out - 1) * stride + (k - 1) * dil + 1; };
+    t.hx = halo(kTX, p.sw, p.kw, p.dw);
+    t.hy = halo(kTY, p.sh, p.kh, p.dh);
+    // Waves per workgroup (each adds two output planes to the shared halo tile): the count that
+    // puts the most waves on a compute unit, LDS permitting (at most two per SIMD fit the
+    // registers), the larger tile on a tie.
+    const int64_t kLds = 160 * 1024;
+    int nw = 0, best_waves = 0;
+    for (int w = kMaxWaves; w >= 1; w /= 2) {
+        const int64_t bytes = (int64_t)t.hx * t.hy * halo(2 * w, p.sd, p.kd, p.dd) * kRec;
+        if (bytes > kLds) continue;
+        int64_t waves = w * (kLds / bytes);
+        if (waves > 8) waves = 8;
+        if (waves > best_waves) { best_waves = (int)waves; nw = w; }
+    }
+    if (nw == 0) return TERN_ESHAPE;
+    const int tz = 2 * nw;
+    t.hz = halo(tz, p.sd, p.kd, p.dd);
+    const int64_t lds = (int64_t)t.hx * t.hy * t.hz * kRec;
+    t.tiles_x = cdiv(p.ow, kTX);
+    t.tiles_y = cdiv(p.oh, kTY);
+    t.tiles_z = cdiv(p.od, tz);
+    t.nblk = (p.c_out + 31) / 32;
+    t.m_hx = 0xffffffffu / (uint32_t)t.hx + 1u;           // hx >= 8
+    t.m_pl = 0xffffffffu / (uint32_t)(t.hx * t.hy) + 1u;
+    const int64_t tiles = (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n;
+    if (tiles > 0x7fffffff) return TERN_ESHAPE;
+    const bool packed = p.out_packed != nullptr;
+    if (t.nblk == 1) {
+        const dim3 grid((unsigned)tiles, 1);
+        return packed ? launch_variant<1, true>(p, t, (size_t)lds, grid, 64 * nw, s)
+                      : launch_variant<1, false>(p, t, (size_t)lds, grid, 64 * nw, s);
+    }
+    // column blocks in pairs; an odd last block is paired with a block of zeros that the bank
+    // does not hold, so odd counts run one block per workgroup
+    if (t.nblk % 2 == 0) {
+        const dim3 grid((unsigned)tiles, (unsigned)(t.nblk / 2));
+        return packed ? launch_variant<2, true>(p, t, (size_t)lds, grid, 64 * nw, s)
+                      : launch_variant<2, false>(p, t, (size_t)lds, grid, 64 * nw, s);
+    }
+    const dim3 grid((unsigned)tiles, (unsigned)t.nblk);
+    return packed ? launch_variant<1, true>(p, t, (size_t)lds, grid, 64 * nw, s)
+                  : launch_variant<1, false>(p, t, (size_t)lds, grid, 64 * nw, s);
+}
+
+}  // namespace tern

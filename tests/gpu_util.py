@@ -15,18 +15,18 @@ def words(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy().view(np.uint32)
 
 
-def run_case(case, want_acc=True, want_packed=True):
-    """Run one single-layer case on the GPU.  Returns (acc int32 array or None, packed uint32
-    array or None)."""
+def run_case(case, want_acc=True, want_packed=True, mfma=False):
+    """Run one single-layer case on the GPU (mfma: through tern_conv3d_mfma and its byte filter
+    bank).  Returns (acc int32 array or None, packed uint32 array or None)."""
     act = T.tern_pack(dev(case.act))
-    bank = T.tern_pack_filters(dev(case.wgt))
+    bank = T.tern_expand_filters(dev(case.wgt)) if mfma else T.tern_pack_filters(dev(case.wgt))
     c_in, c_out = case.act.shape[1], case.wgt.shape[0]
     acc = packed = None
     if want_acc:
-        acc = T.tern_conv3d(act, c_in, bank, c_out, case.k, case.stride, case.pad, case.dil)
+        acc = T.tern_conv3d(act, c_in, bank, c_out, case.k, case.stride, case.pad, case.dil, mfma=mfma)
     if want_packed:
         packed = T.tern_conv3d(act, c_in, bank, c_out, case.k, case.stride, case.pad, case.dil,
-                               thr_lo=dev(case.lo), thr_hi=dev(case.hi))
+                               thr_lo=dev(case.lo), thr_hi=dev(case.hi), mfma=mfma)
     torch.cuda.synchronize()
     return (None if acc is None else acc.cpu().numpy(),
             None if packed is None else words(packed))

@@ -30,8 +30,8 @@ def expect(c):
     return acc, packed
 
 
-def check_case(G, c):
-    acc, packed = G.run_case(c)
+def check_case(G, c, mfma=False):
+    acc, packed = G.run_case(c, mfma=mfma)
     want_acc, want_packed = expect(c)
     assert acc.shape == want_acc.shape
     np.testing.assert_array_equal(acc, want_acc)
@@ -309,9 +309,9 @@ def sample_points(shape, count, seed):
     return np.concatenate([pts, extra])
 
 
-def check_sampled(G, c, count=20000):
+def check_sampled(G, c, count=20000, mfma=False):
     """Full-size run; the oracle computes a random sample of outputs one by one."""
-    acc, packed = G.run_case(c)
+    acc, packed = G.run_case(c, mfma=mfma)
     pts = sample_points(acc.shape, count, 97)
     want = oracle.conv3d_points(c.act, c.wgt, geom_of(c), pts)
     got = acc[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3], pts[:, 4]]
