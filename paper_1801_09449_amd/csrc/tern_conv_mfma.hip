@@ -159,41 +159,53 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0;
 
-    for (int word = 0; word < wd; ++word) {
-        if (word > 0) __syncthreads();           // everyone is done reading the previous word's tile
-        // ---- stage the halo tile of this channel word, one byte per code ----
-        for (int e0 = tid; e0 < nvox; e0 += kFill * nthreads) {
-            uint32_t m[kFill], s[kFill];
+    // Halo staging of one channel word: global loads (kFill voxels per thread in flight), then one
+    // byte per code into LDS.  A thread's first kFill voxels of the next word are requested
+    // before this word's contraction and stored after it.
+    auto halo_load = [&](int word, int e0, uint32_t (&m)[kFill], uint32_t (&s)[kFill]) {
 #pragma unroll
-            for (int k = 0; k < kFill; ++k) {
-                const uint32_t e = (uint32_t)(e0 + k * nthreads);
-                const uint32_t hz = __umulhi(e, t.m_pl);
-                const uint32_t r = e - hz * plane;
-                const int hy = (int)__umulhi(r, t.m_hx);
-                const int hxx = (int)r - hy * t.hx;
-                const int gz = gz0 + (int)hz, gy = gy0 + hy, gx = gx0 + hxx;
-                const bool inb = e < (uint32_t)nvox && gz >= 0 && gz < p.d && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
-                m[k] = s[k] = 0u;
-                if (inb) {
-                    const uint32_t vox = (uint32_t)((gz * p.h + gy) * p.w + gx);   // below 2^31 voxels per item
-                    const uint32_t* src = in_n + (size_t)vox * (2u * wd);
-                    m[k] = src[word];
-                    s[k] = src[wd + word];
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < kFill; ++k) {
-                const int e = e0 + k * nthreads;
-                if (e < nvox) {
-                    uint4 a, b;
-                    expand_word(m[k], s[k], a, b);
-                    uint4* dst = reinterpret_cast<uint4*>(lds8 + (size_t)e * kRec);
-                    dst[0] = a;
-                    dst[1] = b;
-                }
+        for (int k = 0; k < kFill; ++k) {
+            const uint32_t e = (uint32_t)(e0 + k * nthreads);
+            const uint32_t hz = __umulhi(e, t.m_pl);
+            const uint32_t r = e - hz * plane;
+            const int hy = (int)__umulhi(r, t.m_hx);
+            const int hxx = (int)r - hy * t.hx;
+            const int gz = gz0 + (int)hz, gy = gy0 + hy, gx = gx0 + hxx;
+            const bool inb = e < (uint32_t)nvox && gz >= 0 && gz < p.d && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
+            m[k] = s[k] = 0u;
+            if (inb) {
+                const uint32_t vox = (uint32_t)((gz * p.h + gy) * p.w + gx);   // below 2^31 voxels per item
+                const uint32_t* src = in_n + (size_t)vox * (2u * wd);
+                m[k] = src[word];
+                s[k] = src[wd + word];
             }
         }
+    };
+    auto halo_store = [&](int e0, const uint32_t (&m)[kFill], const uint32_t (&s)[kFill]) {
+#pragma unroll
+        for (int k = 0; k < kFill; ++k) {
+            const int e = e0 + k * nthreads;
+            if (e < nvox) {
+                uint4 a, b;
+                expand_word(m[k], s[k], a, b);
+                uint4* dst = reinterpret_cast<uint4*>(lds8 + (size_t)e * kRec);
+                dst[0] = a;
+                dst[1] = b;
+            }
+        }
+    };
+    uint32_t hm[kFill], hs[kFill];
+    halo_load(0, tid, hm, hs);
+    for (int word = 0; word < wd; ++word) {
+        if (word > 0) __syncthreads();           // everyone is done reading the previous word's tile
+        halo_store(tid, hm, hs);
+        for (int e0 = tid + kFill * nthreads; e0 < nvox; e0 += kFill * nthreads) {
+            uint32_t m2[kFill], s2[kFill];
+            halo_load(word, e0, m2, s2);
+            halo_store(e0, m2, s2);
+        }
         __syncthreads();
+        if (word + 1 < wd) halo_load(word + 1, tid, hm, hs);
 
         // ---- contract: all taps of this channel word ----
         // Column fragments come from the vector cache, hundreds of cycles away: the next tap's
