@@ -140,22 +140,30 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims,
 /*
  * tern_conv3d_mfma -- the same convolution, same arguments, same results bit for bit, with the
  * inner products of section 2 (the sums that Eq. 9 evaluates by two bit-counts) taken by the
- * int8 matrix instructions instead: activations stay packed in memory, a workgroup expands its
- * halo tile to one byte per code in LDS and multiplies it with a byte filter bank.  Not the
- * paper's scheme (which exists because CPUs count bits faster than they multiply); provided
- * because on this device the matrix cores multiply faster than the vector units count.
- *   byte_bank : tern_byte_bank_bytes(...) bytes, 16-byte aligned, made once per layer by
- *               tern_expand_filters from the same int8 weights [C_out][C_in][kd][kh][kw] that
- *               tern_pack_filters takes (layout [tap][word of 32 input channels][block of 32
- *               filters][half of the word][filter][16 bytes], codes as 0x01 / 0xff / 0x00).
- * Returns TERN_ESHAPE when the halo of an 8 x 8 x 8 block of outputs does not fit in LDS (large
- * strides or dilations); tern_conv3d has no such limit.
+ * matrix instructions instead: activations stay packed in memory, a workgroup expands its halo
+ * tile in LDS and multiplies it with an expanded filter bank.  Not the paper's scheme (which
+ * exists because CPUs count bits faster than they multiply); provided because on this device the
+ * matrix cores multiply faster than the vector units count.
+ *   kind        : TERN_MATRIX_I8 -- one byte per code (0x01 / 0xff / 0x00), int8 products, int32
+ *                 sums; TERN_MATRIX_F4 -- four bits per code (the E2M1 values +1, -1, 0), float
+ *                 sums, exact because every partial sum is an integer below 2^24 (TERN_ESHAPE if
+ *                 k-volume * C_in >= 2^24); twice the rate of the former.
+ *   matrix_bank : tern_matrix_bank_bytes(...) bytes, 16-byte aligned, made once per layer by
+ *                 tern_expand_filters from the same int8 weights [C_out][C_in][kd][kh][kw] that
+ *                 tern_pack_filters takes.  Layout [tap][step][block of 32 filters][half g]
+ *                 [filter j][16 bytes]; I8: step = word of 32 input channels, byte b = channel
+ *                 32 step + 16 g + b; F4: step = pair of words, 4-bit field c = channel
+ *                 64 step + 32 g + c.  Zero past C_out and C_in.
+ * Returns TERN_ESHAPE when the halo of an 8 x 8 x 2 block of outputs does not fit in LDS (very
+ * large strides or dilations); tern_conv3d has no such limit.
  */
-size_t tern_byte_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw);
+typedef enum { TERN_MATRIX_I8 = 0, TERN_MATRIX_F4 = 1 } tern_matrix_kind;
+size_t tern_matrix_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw,
+                              int32_t kind);
 int tern_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
-                        int32_t kw, uint32_t* byte_bank, void* stream);
+                        int32_t kw, int32_t kind, uint32_t* matrix_bank, void* stream);
 int tern_conv3d_mfma(const uint32_t* in_packed, tern_dims in_dims,
-                     const uint32_t* byte_bank, int32_t c_out, tern_conv_geom g,
+                     const uint32_t* matrix_bank, int32_t kind, int32_t c_out, tern_conv_geom g,
                      const int32_t* thr_lo, const int32_t* thr_hi,
                      int32_t* out_acc, uint32_t* out_packed, void* stream);
 

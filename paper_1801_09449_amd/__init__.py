@@ -23,7 +23,7 @@ from .binding import (  # noqa: F401
     NetModule,
     tern_fcn_workspace_bytes,
     tern_filter_bank_bytes,
-    tern_byte_bank_bytes,
+    tern_matrix_bank_bytes,
     tern_expand_filters,
     tern_fold_batchnorm,
     tern_fold_thresholds,

@@ -78,9 +78,9 @@ def lib():
     L.tern_pack_filters.argtypes = [P, I, I, I, I, I, P, P]; L.tern_pack_filters.restype = C.c_int
     L.tern_conv3d.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d.restype = C.c_int
     L.tern_conv3d_digits.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d_digits.restype = C.c_int
-    L.tern_conv3d_mfma.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d_mfma.restype = C.c_int
-    L.tern_byte_bank_bytes.argtypes = [I] * 5; L.tern_byte_bank_bytes.restype = S
-    L.tern_expand_filters.argtypes = [P, I, I, I, I, I, P, P]; L.tern_expand_filters.restype = C.c_int
+    L.tern_conv3d_mfma.argtypes = [P, Dims, P, I, I, Geom, P, P, P, P, P]; L.tern_conv3d_mfma.restype = C.c_int
+    L.tern_matrix_bank_bytes.argtypes = [I] * 6; L.tern_matrix_bank_bytes.restype = S
+    L.tern_expand_filters.argtypes = [P, I, I, I, I, I, I, P, P]; L.tern_expand_filters.restype = C.c_int
     L.tern_pool_digits.argtypes = [P, Dims, C.POINTER(C.c_int32), P, P]; L.tern_pool_digits.restype = C.c_int
     L.tern_digits_weights.argtypes = [P, I, I, C.c_int64, P]; L.tern_digits_weights.restype = C.c_int
     L.tern_threshold_pack.argtypes = [P, C.c_int, Dims, P, P, P, P]; L.tern_threshold_pack.restype = C.c_int
@@ -221,19 +221,22 @@ def tern_pack_filters(w: torch.Tensor, out: Optional[torch.Tensor] = None) -> to
     return out
 
 
-def tern_byte_bank_bytes(c_out: int, c_in: int, k) -> int:
+MATRIX_KINDS = {"i8": 0, "f4": 1}
+
+
+def tern_matrix_bank_bytes(c_out: int, c_in: int, k, kind: str = "i8") -> int:
     kd, kh, kw = _t3(k)
-    return int(lib().tern_byte_bank_bytes(int(c_out), int(c_in), kd, kh, kw))
+    return int(lib().tern_matrix_bank_bytes(int(c_out), int(c_in), kd, kh, kw, MATRIX_KINDS[kind]))
 
 
-def tern_expand_filters(w: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """int8 ternary [C_out][C_in][kd][kh][kw] -> byte filter bank of the matrix-core route (flat
-    int32 tensor)."""
+def tern_expand_filters(w: torch.Tensor, kind: str = "i8", out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """int8 ternary [C_out][C_in][kd][kh][kw] -> filter bank of the matrix-core route (flat int32
+    tensor); kind "i8" (a byte per code) or "f4" (four bits per code)."""
     _dev(w, torch.int8, "w")
     if w.dim() != 5:
         raise ValueError("w must be [C_out][C_in][kd][kh][kw]")
     co, ci, kd, kh, kw = (int(x) for x in w.shape)
-    nbytes = tern_byte_bank_bytes(co, ci, (kd, kh, kw))
+    nbytes = tern_matrix_bank_bytes(co, ci, (kd, kh, kw), kind)
     if nbytes == 0:
         raise TernError(-2, "tern_expand_filters")
     if out is None:
@@ -241,7 +244,8 @@ def tern_expand_filters(w: torch.Tensor, out: Optional[torch.Tensor] = None) -> 
     _dev(out, PACKED_DTYPE, "out")
     if out.numel() * 4 != nbytes:
         raise ValueError("out has the wrong size")
-    _check(lib().tern_expand_filters(_ptr(w), co, ci, kd, kh, kw, _ptr(out), _stream(w)), "tern_expand_filters")
+    _check(lib().tern_expand_filters(_ptr(w), co, ci, kd, kh, kw, MATRIX_KINDS[kind], _ptr(out), _stream(w)),
+           "tern_expand_filters")
     return out
 
 
@@ -249,15 +253,21 @@ def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out:
                 k=3, stride=1, pad=1, dil=1,
                 thr_lo: Optional[torch.Tensor] = None, thr_hi: Optional[torch.Tensor] = None,
                 out: Optional[torch.Tensor] = None, digits: bool = False,
-                mfma: bool = False) -> torch.Tensor:
+                mfma=False) -> torch.Tensor:
     """Ternary convolution.  Without cut points: int32 accumulators [N][C_out][Do][Ho][Wo].
     With thr_lo / thr_hi (int32 [C_out]): fused activation + re-pack, packed output.
     digits=True: in_packed is the two-digit tensor of tern_pool_digits (c_in = its channel count,
     a multiple of 64) and w_bank the bank of tern_digits_weights' output (tern_conv3d_digits).
-    mfma=True: w_bank is the byte bank of tern_expand_filters (tern_conv3d_mfma)."""
+    mfma="i8" / "f4" (True = "i8"): w_bank is the bank of tern_expand_filters for that kind
+    (tern_conv3d_mfma)."""
     if digits and mfma:
         raise ValueError("digits and mfma exclude each other")
-    entry = lib().tern_conv3d_digits if digits else lib().tern_conv3d_mfma if mfma else lib().tern_conv3d
+    kind = "i8" if mfma is True else mfma
+    if mfma:
+        def entry(a, d, b, *rest):
+            return lib().tern_conv3d_mfma(a, d, b, MATRIX_KINDS[kind], *rest)
+    else:
+        entry = lib().tern_conv3d_digits if digits else lib().tern_conv3d
     _dev(in_packed, PACKED_DTYPE, "in_packed")
     _dev(w_bank, PACKED_DTYPE, "w_bank")
     if in_packed.dim() != 6 or in_packed.shape[4] != 2 or in_packed.shape[5] != tern_words(c_in):
@@ -265,8 +275,9 @@ def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out:
     n, d, h, w = (int(x) for x in in_packed.shape[:4])
     in_dims = Dims(n, int(c_in), d, h, w)
     g = _geom(k, stride, pad, dil)
-    bank_bytes = tern_byte_bank_bytes if mfma else tern_filter_bank_bytes
-    if w_bank.numel() * 4 != bank_bytes(c_out, c_in, (g.k[0], g.k[1], g.k[2])):
+    kk = (g.k[0], g.k[1], g.k[2])
+    need = tern_matrix_bank_bytes(c_out, c_in, kk, kind) if mfma else tern_filter_bank_bytes(c_out, c_in, kk)
+    if w_bank.numel() * 4 != need:
         raise ValueError("w_bank size does not match (c_out, c_in, k)")
     o = Dims()
     _check(lib().tern_conv_out_dims(in_dims, int(c_out), g, C.byref(o)), "tern_conv3d")

@@ -245,26 +245,28 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_
     return launch_conv3d(p, (hipStream_t)stream);
 }
 
-size_t tern_byte_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw)
+size_t tern_matrix_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw, int32_t kind)
 {
-    if (!filter_shape_ok(c_out, c_in, kd, kh, kw)) return 0;
-    return byte_bank_bytes(c_out, c_in, kd * kh * kw);
+    if (!filter_shape_ok(c_out, c_in, kd, kh, kw) || (kind != TERN_MATRIX_I8 && kind != TERN_MATRIX_F4)) return 0;
+    return byte_bank_bytes(c_out, c_in, kd * kh * kw, kind);
 }
 
 int tern_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
-                        int32_t kw, uint32_t* byte_bank, void* stream)
+                        int32_t kw, int32_t kind, uint32_t* matrix_bank, void* stream)
 {
-    if (!w || !byte_bank) return TERN_ENULL;
+    if (!w || !matrix_bank) return TERN_ENULL;
+    if (kind != TERN_MATRIX_I8 && kind != TERN_MATRIX_F4) return TERN_EARG;
     if (!filter_shape_ok(c_out, c_in, kd, kh, kw)) return TERN_ESHAPE;
-    if (!aligned16(byte_bank)) return TERN_EARG;
-    return launch_expand_filters(w, c_out, c_in, kd * kh * kw, byte_bank, (hipStream_t)stream);
+    if (!aligned16(matrix_bank)) return TERN_EARG;
+    return launch_expand_filters(w, c_out, c_in, kd * kh * kw, kind, matrix_bank, (hipStream_t)stream);
 }
 
-int tern_conv3d_mfma(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* byte_bank,
+int tern_conv3d_mfma(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* byte_bank, int32_t kind,
                      int32_t c_out, tern_conv_geom g, const int32_t* thr_lo, const int32_t* thr_hi,
                      int32_t* out_acc, uint32_t* out_packed, void* stream)
 {
     if (!in_packed || !byte_bank) return TERN_ENULL;
+    if (kind != TERN_MATRIX_I8 && kind != TERN_MATRIX_F4) return TERN_EARG;
     if ((out_acc == nullptr) == (out_packed == nullptr)) return TERN_EARG;
     if (out_packed && (!thr_lo || !thr_hi)) return TERN_ENULL;
     tern_dims o;
@@ -275,7 +277,7 @@ int tern_conv3d_mfma(const uint32_t* in_packed, tern_dims in_dims, const uint32_
     if (out_acc && ((uintptr_t)out_acc & 3u)) return TERN_EARG;
     const ConvParams p = conv_params(in_packed, in_dims, byte_bank, c_out, g, o, thr_lo, thr_hi, out_acc,
                                      out_packed);
-    return launch_conv3d_mfma(p, (hipStream_t)stream);
+    return launch_conv3d_mfma(p, kind, (hipStream_t)stream);
 }
 
 int tern_conv3d_digits(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_bank,

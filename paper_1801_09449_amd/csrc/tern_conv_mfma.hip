@@ -1,25 +1,30 @@
 // Ternary convolution on the matrix cores: the inner product of section 2 (the quantity that
-// Eq. 9 evaluates with two bit-counts) computed as an int8 matrix product.  Activations stay in
-// the packed two-plane layout in HBM; a workgroup expands its halo tile to one byte per code in
-// LDS (32 channels at a time) and contracts it with a byte filter bank through
-// v_mfma_i32_32x32x32_i8.  Same results as the bit-count kernels, bit for bit: every product is
-// an exact small integer and the accumulation is int32.
+// Eq. 9 evaluates with two bit-counts) computed as a matrix product.  Activations stay in the
+// packed two-plane layout in HBM; a workgroup expands its halo tile in LDS, one inner step at a
+// time, and contracts it with an expanded filter bank.  Two kinds:
+//   int8: one byte per code, a step is a word of 32 channels, v_mfma_i32_32x32x32_i8, int32 sums;
+//   fp4:  four bits per code (E2M1: +1 = 0010, -1 = 1010), a step is a pair of words,
+//         v_mfma_scale_f32_32x32x64_f8f6f4 with both scales 2^0, float sums, exact because every
+//         partial sum is an integer below 2^24 (checked on the host); twice the rate.
+// Same results as the bit-count kernels, bit for bit.
 //
 // Implicit matrix product: rows = output voxels, columns = output channels, inner index =
 // (kernel tap, input channel).  A wave owns 8 x 8 x 2 output voxels (four row blocks of 32:
 // plane p in {0, 1} x y-half h in {0, 1}, voxel i of a block at x = i % 8, y = 4 h + i / 8) and up
-// to 64 output channels (two column blocks), i.e. eight 32 x 32 accumulator tiles; four waves
-// stacked along z share a halo tile.  Per (tap, 32-channel word) a wave reads four row fragments
-// from LDS (one 16-byte read per lane each) and two column fragments from the filter bank
-// (16 bytes per lane, 1 KB contiguous per fragment, served by the vector cache) and issues eight
-// matrix instructions: LDS at half and the vector cache at half of what they can deliver.
+// to 64 output channels (two column blocks), i.e. eight 32 x 32 accumulator tiles; up to four
+// waves stacked along z share a halo tile.  Per (tap, step) a wave reads four row fragments from
+// LDS (one 16-byte read per lane each) and two column fragments from the filter bank (16 bytes
+// per lane, 1 KB contiguous per fragment, served by the vector cache) and issues eight matrix
+// instructions: LDS at half and the vector cache at half of what they can deliver.
 //
-// Operand layout of the instruction (inner extent 32 = two lane groups x 16 bytes): lane l of
+// Operand layout of the instructions (two lane groups x 16 bytes of inner indices): lane l of
 // the row operand holds row l % 32, lane l of the column operand holds column l % 32, and both
-// hold the inner indices of lane group l / 32 in the same byte order, so any consistent
-// assignment of (channel within the word) to (lane group, byte) gives the right sum; here
-// channel = 16 * (l / 32) + byte.  Result: lane l holds column l % 32, register v holds row
-// 8 * (v / 4) + 4 * (l / 32) + v % 4.
+// hold the inner indices of lane group l / 32 in the same order, so any consistent assignment
+// of channels to (lane group, position) gives the right sum; here int8: channel 16 (l / 32) +
+// byte of the word, fp4: word l / 32 of the pair, channel = 4-bit field.  Result: lane l holds
+// column l % 32, register v holds row 8 (v / 4) + 4 (l / 32) + v % 4.
+#include <type_traits>
+
 #include "tern_internal.h"
 
 namespace tern {
@@ -27,6 +32,8 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kMaxWaves = 4;         // waves per workgroup (4, 2 or 1), stacked along z
 constexpr int kMaxThreads = 64 * kMaxWaves;
@@ -38,6 +45,7 @@ struct MfmaPlan {
     int32_t hx, hy, hz;              // halo extents in voxels
     int32_t tiles_x, tiles_y, tiles_z;
     int32_t nblk;                    // 32-channel column blocks in the filter bank
+    int32_t ksteps;                  // inner steps per tap: channel words (int8) or word pairs (fp4)
     uint32_t m_hx, m_pl;             // floor(e / hx) = umulhi(e, m_hx), likewise hx * hy
 };
 
@@ -57,10 +65,33 @@ __device__ __forceinline__ void expand_word(uint32_t m, uint32_t s, uint4& lo16,
     hi16 = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
+// Four bits per code (the E2M1 format of the scaled matrix instructions: +1 = 0010, -1 = 1010,
+// 0 = 0000) from a word of 32 channels, channel c in bits [4 c, 4 c + 4) of the 128.
+// spread(x) moves bit i of a byte to bit 4 i.
+__device__ __forceinline__ uint32_t spread8(uint32_t x)
+{
+    x = (x | (x << 12)) & 0x000f000fu;
+    x = (x | (x << 6)) & 0x03030303u;
+    x = (x | (x << 3)) & 0x11111111u;
+    return x;
+}
+__device__ __forceinline__ uint4 expand_word_f4(uint32_t m, uint32_t s)
+{
+    const uint32_t neg = m & s;
+    uint32_t o[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        o[j] = (spread8((m >> (8 * j)) & 0xffu) << 1) | (spread8((neg >> (8 * j)) & 0xffu) << 3);
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 // Byte filter bank [tap][word][column block][lane group g][column j][16]: byte b of the entry is
 // the code of filter 32 * block + j at input channel 32 * word + 16 * g + b (0 past c_out or c_in).
+// fp4 bank: [tap][word pair][column block][g][j][16 bytes], nibble c of the entry = code of filter
+// 32 * block + j at input channel 32 * (2 * pair + g) + c.
+template <bool F4>
 __global__ __launch_bounds__(256) void expand_filters_kernel(const int8_t* __restrict__ w, int32_t c_out,
-                                                             int32_t c_in, int32_t taps, int32_t wd,
+                                                             int32_t c_in, int32_t taps, int32_t ksteps,
                                                              int32_t nblk, uint32_t* __restrict__ bank,
                                                              int64_t dwords)
 {
@@ -69,19 +100,22 @@ __global__ __launch_bounds__(256) void expand_filters_kernel(const int8_t* __res
     const int q = (int)(e & 3);                  // dword within the 16 bytes
     const int j = (int)((e >> 2) & 31);
     const int g = (int)((e >> 7) & 1);
-    int64_t r = e >> 8;                          // (tap * wd + word) * nblk + block
+    int64_t r = e >> 8;                          // (tap * ksteps + step) * nblk + block
     const int blk = (int)(r % nblk); r /= nblk;
-    const int word = (int)(r % wd);
-    const int tap = (int)(r / wd);
+    const int ks = (int)(r % ksteps);
+    const int tap = (int)(r / ksteps);
     const int co = blk * 32 + j;
     uint32_t out = 0u;
     if (co < c_out) {
+        constexpr int PER = F4 ? 8 : 4;          // codes per dword
+        const int c0 = F4 ? (2 * ks + g) * 32 + q * 8 : ks * 32 + g * 16 + q * 4;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int c = word * 32 + g * 16 + q * 4 + b;
+        for (int b = 0; b < PER; ++b) {
+            const int c = c0 + b;
             if (c < c_in) {
                 const int v = w[((size_t)co * c_in + c) * taps + tap];
-                out |= (v > 0 ? 0x01u : v < 0 ? 0xffu : 0u) << (8 * b);
+                if constexpr (F4) out |= (v > 0 ? 0x2u : v < 0 ? 0xau : 0u) << (4 * b);
+                else out |= (v > 0 ? 0x01u : v < 0 ? 0xffu : 0u) << (8 * b);
             }
         }
     }
@@ -91,14 +125,15 @@ __global__ __launch_bounds__(256) void expand_filters_kernel(const int8_t* __res
 // Eq. 6 on one 32 x 32 accumulator tile: register V of lane l is (row 8 (V / 4) + 4 (l / 32) +
 // V % 4, column l % 32).  A wave-wide comparison gives the 32 channel bits of two rows at once
 // (lanes 0-31: row r, lanes 32-63: row r + 4); they go to lanes r and r + 4 of posw / negw.
-template <int V>
-__device__ __forceinline__ void decide_rows(const v16i& acc, int32_t lo, int32_t hi, uint32_t& posw,
+template <int V, typename Acc>
+__device__ __forceinline__ void decide_rows(const Acc& acc, int32_t lo, int32_t hi, uint32_t& posw,
                                             uint32_t& negw)
 {
     if constexpr (V < 16) {
         constexpr int r = (V >> 2) * 8 + (V & 3);
-        const unsigned long long bp = __ballot(acc[V] > hi);
-        const unsigned long long bn = __ballot(acc[V] < lo);
+        const int32_t d = (int32_t)acc[V];       // fp4 route: an exact integer held in a float
+        const unsigned long long bp = __ballot(d > hi);
+        const unsigned long long bn = __ballot(d < lo);
         // The compiler does not see inside the statement: the wait states that a lane write
         // needs after the comparisons wrote their scalar results are spelled out.
         asm("s_nop 4\n\t"
@@ -109,11 +144,11 @@ __device__ __forceinline__ void decide_rows(const v16i& acc, int32_t lo, int32_t
             : [p] "+v"(posw), [n] "+v"(negw)
             : [pl] "s"((uint32_t)bp), [ph] "s"((uint32_t)(bp >> 32)), [nl] "s"((uint32_t)bn),
               [nh] "s"((uint32_t)(bn >> 32)), [r0] "n"(r), [r1] "n"(r + 4));
-        decide_rows<V + 1>(acc, lo, hi, posw, negw);
+        decide_rows<V + 1, Acc>(acc, lo, hi, posw, negw);
     }
 }
 
-template <int NB, bool PACKED>
+template <int NB, bool PACKED, bool F4>
 __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv_mfma_kernel(ConvParams p, MfmaPlan t)
 {
     extern __shared__ __align__(16) uint8_t lds8[];
@@ -151,7 +186,9 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
     const v4i* bank = reinterpret_cast<const v4i*>(p.wgt);
     const int T = p.kd * p.kh * p.kw;
 
-    v16i acc[4][NB];
+    constexpr int KW = F4 ? 2 : 1;               // channel words per inner step
+    using Acc = typename std::conditional<F4, v16f, v16i>::type;
+    Acc acc[4][NB];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -159,10 +196,12 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0;
 
-    // Halo staging of one channel word: global loads (kFill voxels per thread in flight), then one
-    // byte per code into LDS.  A thread's first kFill voxels of the next word are requested
-    // before this word's contraction and stored after it.
-    auto halo_load = [&](int word, int e0, uint32_t (&m)[kFill], uint32_t (&s)[kFill]) {
+    // Halo staging of one inner step (a channel word, or a pair of them for fp4): global loads
+    // (kFill voxels per thread in flight), then one byte (or four bits) per code into LDS.  A
+    // thread's first kFill voxels of the next step are requested before this step's contraction
+    // and stored after it.
+    const int ksteps = t.ksteps;
+    auto halo_load = [&](int ks, int e0, uint32_t (&m)[kFill][KW], uint32_t (&s)[kFill][KW]) {
 #pragma unroll
         for (int k = 0; k < kFill; ++k) {
             const uint32_t e = (uint32_t)(e0 + k * nthreads);
@@ -172,49 +211,61 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
             const int hxx = (int)r - hy * t.hx;
             const int gz = gz0 + (int)hz, gy = gy0 + hy, gx = gx0 + hxx;
             const bool inb = e < (uint32_t)nvox && gz >= 0 && gz < p.d && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w;
-            m[k] = s[k] = 0u;
+#pragma unroll
+            for (int q = 0; q < KW; ++q) m[k][q] = s[k][q] = 0u;
             if (inb) {
                 const uint32_t vox = (uint32_t)((gz * p.h + gy) * p.w + gx);   // below 2^31 voxels per item
                 const uint32_t* src = in_n + (size_t)vox * (2u * wd);
-                m[k] = src[word];
-                s[k] = src[wd + word];
+#pragma unroll
+                for (int q = 0; q < KW; ++q) {
+                    const int word = ks * KW + q;
+                    if (word < wd) {                     // an odd word count leaves the last pair half empty
+                        m[k][q] = src[word];
+                        s[k][q] = src[wd + word];
+                    }
+                }
             }
         }
     };
-    auto halo_store = [&](int e0, const uint32_t (&m)[kFill], const uint32_t (&s)[kFill]) {
+    auto halo_store = [&](int e0, const uint32_t (&m)[kFill][KW], const uint32_t (&s)[kFill][KW]) {
 #pragma unroll
         for (int k = 0; k < kFill; ++k) {
             const int e = e0 + k * nthreads;
             if (e < nvox) {
-                uint4 a, b;
-                expand_word(m[k], s[k], a, b);
                 uint4* dst = reinterpret_cast<uint4*>(lds8 + (size_t)e * kRec);
-                dst[0] = a;
-                dst[1] = b;
+                if constexpr (F4) {
+                    dst[0] = expand_word_f4(m[k][0], s[k][0]);
+                    dst[1] = expand_word_f4(m[k][1], s[k][1]);
+                } else {
+                    uint4 a, b;
+                    expand_word(m[k][0], s[k][0], a, b);
+                    dst[0] = a;
+                    dst[1] = b;
+                }
             }
         }
     };
-    uint32_t hm[kFill], hs[kFill];
+    uint32_t hm[kFill][KW], hs[kFill][KW];
     halo_load(0, tid, hm, hs);
-    for (int word = 0; word < wd; ++word) {
-        if (word > 0) __syncthreads();           // everyone is done reading the previous word's tile
+    for (int ks = 0; ks < ksteps; ++ks) {
+        if (ks > 0) __syncthreads();             // everyone is done reading the previous step's tile
         halo_store(tid, hm, hs);
         for (int e0 = tid + kFill * nthreads; e0 < nvox; e0 += kFill * nthreads) {
-            uint32_t m2[kFill], s2[kFill];
-            halo_load(word, e0, m2, s2);
+            uint32_t m2[kFill][KW], s2[kFill][KW];
+            halo_load(ks, e0, m2, s2);
             halo_store(e0, m2, s2);
         }
         __syncthreads();
-        if (word + 1 < wd) halo_load(word + 1, tid, hm, hs);
+        if (ks + 1 < ksteps) halo_load(ks + 1, tid, hm, hs);
 
-        // ---- contract: all taps of this channel word ----
+        // ---- contract: all taps of this step ----
         // Column fragments come from the vector cache, hundreds of cycles away: the next tap's
         // are requested before this tap's matrix instructions are issued.
         const uint8_t* lane_lds = lds8 + lane_off;
         int tap = 0;
         v4i Bn[NB];
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) Bn[nb] = bank[((size_t)word * t.nblk + nb0 + nb) * 64 + lane];
+        for (int nb = 0; nb < NB; ++nb) Bn[nb] = bank[((size_t)ks * t.nblk + nb0 + nb) * 64 + lane];
         for (int a = 0; a < p.kd; ++a)
             for (int b = 0; b < p.kh; ++b)
                 for (int c = 0; c < p.kw; ++c, ++tap) {
@@ -224,7 +275,7 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb) {
                         B[nb] = Bn[nb];
-                        Bn[nb] = bank[((size_t)(tnext * wd + word) * t.nblk + nb0 + nb) * 64 + lane];
+                        Bn[nb] = bank[((size_t)(tnext * ksteps + ks) * t.nblk + nb0 + nb) * 64 + lane];
                     }
 #pragma unroll
                     for (int mb = 0; mb < 4; ++mb)
@@ -232,8 +283,18 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
                     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-                        for (int nb = 0; nb < NB; ++nb)
-                            acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[mb], B[nb], acc[mb][nb], 0, 0, 0);
+                        for (int nb = 0; nb < NB; ++nb) {
+                            if constexpr (F4) {
+                                // 4-bit operands occupy the first four of the eight operand registers;
+                                // both scales are 2^0 (E8M0 127 in every byte)
+                                const v8i a8 = __builtin_shufflevector(A[mb], A[mb], 0, 1, 2, 3, -1, -1, -1, -1);
+                                const v8i b8 = __builtin_shufflevector(B[nb], B[nb], 0, 1, 2, 3, -1, -1, -1, -1);
+                                acc[mb][nb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                                    a8, b8, acc[mb][nb], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                            } else {
+                                acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[mb], B[nb], acc[mb][nb], 0, 0, 0);
+                            }
+                        }
                 }
     }
 
@@ -252,7 +313,7 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
                 for (int mb = 0; mb < 4; ++mb) {
                     __builtin_amdgcn_sched_barrier(0);   // one tile at a time
                     uint32_t posw = 0u, negw = 0u;      // lane r (< 32): words of the block's voxel r
-                    decide_rows<0>(acc[mb][nb], lo, hi, posw, negw);
+                    decide_rows<0, Acc>(acc[mb][nb], lo, hi, posw, negw);
                     const int ox = ox0 + xl, oy = oy0 + (mb & 1) * 4 + yl, oz = oz0 + wave * 2 + (mb >> 1);
                     if (g == 0 && ox < p.ow && oy < p.oh && oz < p.od) {
                         uint32_t* o = p.out_packed + ((((size_t)n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
@@ -273,7 +334,7 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
                     const int ox = ox0 + (r & 7), oy = oy0 + (mb & 1) * 4 + (r >> 3);
                     if (co < p.c_out && ox < p.ow && oy < p.oh && oz < p.od)
                         p.out_acc[((size_t)n * p.c_out + co) * cstride + ((size_t)oz * p.oh + oy) * p.ow + ox] =
-                            acc[mb][nb][v];
+                            (int32_t)acc[mb][nb][v];
                 }
             }
         }
@@ -282,11 +343,11 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-template <int NB, bool PACKED>
+template <int NB, bool PACKED, bool F4>
 int launch_variant(const ConvParams& p, const MfmaPlan& t, size_t lds_bytes, dim3 grid, int threads,
                    hipStream_t s)
 {
-    auto kern = conv_mfma_kernel<NB, PACKED>;
+    auto kern = conv_mfma_kernel<NB, PACKED, F4>;
     if (lds_bytes > 64 * 1024) {
         static thread_local int raised_on_device = -1;
         int dev = 0;
@@ -304,29 +365,40 @@ int launch_variant(const ConvParams& p, const MfmaPlan& t, size_t lds_bytes, dim
 
 }  // namespace
 
-size_t byte_bank_bytes(int32_t c_out, int32_t c_in, int32_t taps)
+// kind 0: one byte per code, an inner step is one channel word; kind 1: four bits per code, an
+// inner step is a pair of channel words.  Either way a (tap, step, block of 32 filters) entry is
+// 64 lanes x 16 bytes.
+static int32_t steps_of(int32_t c_in, int kind) { return kind == 1 ? (c_in + 63) / 64 : (c_in + 31) / 32; }
+
+size_t byte_bank_bytes(int32_t c_out, int32_t c_in, int32_t taps, int kind)
 {
-    const size_t wd = (size_t)(c_in + 31) / 32, nblk = (size_t)(c_out + 31) / 32;
-    return (size_t)taps * wd * nblk * 1024;
+    const size_t nblk = (size_t)(c_out + 31) / 32;
+    return (size_t)taps * (size_t)steps_of(c_in, kind) * nblk * 1024;
 }
 
-int launch_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t taps, uint32_t* bank,
+int launch_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t taps, int kind, uint32_t* bank,
                           hipStream_t s)
 {
-    const int32_t wd = (c_in + 31) / 32, nblk = (c_out + 31) / 32;
-    const int64_t dwords = (int64_t)taps * wd * nblk * 256;
+    const int32_t ksteps = steps_of(c_in, kind), nblk = (c_out + 31) / 32;
+    const int64_t dwords = (int64_t)taps * ksteps * nblk * 256;
     const int64_t blocks = (dwords + 255) / 256;
     if (blocks > 0x7fffffff) return TERN_ESHAPE;
-    hipLaunchKernelGGL(expand_filters_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, c_out, c_in, taps, wd,
-                       nblk, bank, dwords);
+    if (kind == 1)
+        hipLaunchKernelGGL(expand_filters_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, s, w, c_out, c_in,
+                           taps, ksteps, nblk, bank, dwords);
+    else
+        hipLaunchKernelGGL(expand_filters_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, s, w, c_out, c_in,
+                           taps, ksteps, nblk, bank, dwords);
     TERN_HIP_CHECK(hipGetLastError());
     return TERN_OK;
 }
 
-// p.wgt is the byte filter bank.  TERN_ESHAPE when the halo tile of even one wave's 8 x 8 x 2
-// output block does not fit in LDS (very large strides or dilations).
-int launch_conv3d_mfma(const ConvParams& p, hipStream_t s)
+// p.wgt is the filter bank of that kind.  TERN_ESHAPE when the halo tile of even one wave's
+// 8 x 8 x 2 output block does not fit in LDS (very large strides or dilations), and for the 4-bit
+// kind when a sum could leave the integers a float holds exactly (k-volume * C_in >= 2^24).
+int launch_conv3d_mfma(const ConvParams& p, int kind, hipStream_t s)
 {
+    if (kind == 1 && (int64_t)p.kd * p.kh * p.kw * p.c_in >= (1 << 24)) return TERN_ESHAPE;
     MfmaPlan t;
     auto halo = [](int out, int stride, int k, int dil) { return (out - 1) * stride + (k - 1) * dil + 1; };
     t.hx = halo(kTX, p.sw, p.kw, p.dw);
@@ -355,22 +427,20 @@ int launch_conv3d_mfma(const ConvParams& p, hipStream_t s)
     t.m_pl = 0xffffffffu / (uint32_t)(t.hx * t.hy) + 1u;
     const int64_t tiles = (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n;
     if (tiles > 0x7fffffff) return TERN_ESHAPE;
+    t.ksteps = steps_of(p.c_in, kind);
     const bool packed = p.out_packed != nullptr;
-    if (t.nblk == 1) {
-        const dim3 grid((unsigned)tiles, 1);
-        return packed ? launch_variant<1, true>(p, t, (size_t)lds, grid, 64 * nw, s)
-                      : launch_variant<1, false>(p, t, (size_t)lds, grid, 64 * nw, s);
-    }
-    // column blocks in pairs; an odd last block is paired with a block of zeros that the bank
-    // does not hold, so odd counts run one block per workgroup
-    if (t.nblk % 2 == 0) {
-        const dim3 grid((unsigned)tiles, (unsigned)(t.nblk / 2));
-        return packed ? launch_variant<2, true>(p, t, (size_t)lds, grid, 64 * nw, s)
-                      : launch_variant<2, false>(p, t, (size_t)lds, grid, 64 * nw, s);
-    }
-    const dim3 grid((unsigned)tiles, (unsigned)t.nblk);
-    return packed ? launch_variant<1, true>(p, t, (size_t)lds, grid, 64 * nw, s)
-                  : launch_variant<1, false>(p, t, (size_t)lds, grid, 64 * nw, s);
+    // column blocks in pairs; an odd last block would be paired with a block the bank does not
+    // hold, so odd counts run one block per workgroup
+    const int nb = (t.nblk % 2 == 0) ? 2 : 1;
+    const dim3 grid((unsigned)tiles, (unsigned)(t.nblk / nb));
+    const int threads = 64 * nw;
+    const size_t lb = (size_t)lds;
+#define TERN_MFMA_LAUNCH(NB_, F4_)                                                    \
+    (packed ? launch_variant<NB_, true, F4_>(p, t, lb, grid, threads, s)               \
+            : launch_variant<NB_, false, F4_>(p, t, lb, grid, threads, s))
+    if (kind == 1) return nb == 2 ? TERN_MFMA_LAUNCH(2, true) : TERN_MFMA_LAUNCH(1, true);
+    return nb == 2 ? TERN_MFMA_LAUNCH(2, false) : TERN_MFMA_LAUNCH(1, false);
+#undef TERN_MFMA_LAUNCH
 }
 
 }  // namespace tern

@@ -130,10 +130,10 @@ int launch_conv3d(const ConvParams& p, hipStream_t s);
 bool conv_point_applies(const ConvParams& p);
 int launch_conv_point(const ConvParams& p, hipStream_t s);
 // Matrix-core route: byte filter bank and the convolution that takes it as p.wgt.
-size_t byte_bank_bytes(int32_t c_out, int32_t c_in, int32_t taps);
-int launch_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t taps, uint32_t* bank,
+size_t byte_bank_bytes(int32_t c_out, int32_t c_in, int32_t taps, int kind);
+int launch_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t taps, int kind, uint32_t* bank,
                           hipStream_t s);
-int launch_conv3d_mfma(const ConvParams& p, hipStream_t s);
+int launch_conv3d_mfma(const ConvParams& p, int kind, hipStream_t s);
 int launch_concat(const ConcatParams& p, hipStream_t s);
 int launch_pool_digits(const uint32_t* in, const tern_dims& in_dims, const int32_t window[3], uint32_t* out,
                        hipStream_t s);

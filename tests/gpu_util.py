@@ -16,10 +16,10 @@ def words(t: torch.Tensor) -> np.ndarray:
 
 
 def run_case(case, want_acc=True, want_packed=True, mfma=False):
-    """Run one single-layer case on the GPU (mfma: through tern_conv3d_mfma and its byte filter
-    bank).  Returns (acc int32 array or None, packed uint32 array or None)."""
+    """Run one single-layer case on the GPU (mfma = "i8" or "f4": through tern_conv3d_mfma and
+    its filter bank of that kind).  Returns (acc int32 array or None, packed uint32 array or None)."""
     act = T.tern_pack(dev(case.act))
-    bank = T.tern_expand_filters(dev(case.wgt)) if mfma else T.tern_pack_filters(dev(case.wgt))
+    bank = T.tern_expand_filters(dev(case.wgt), mfma) if mfma else T.tern_pack_filters(dev(case.wgt))
     c_in, c_out = case.act.shape[1], case.wgt.shape[0]
     acc = packed = None
     if want_acc:

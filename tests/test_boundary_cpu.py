@@ -73,15 +73,19 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     assert L.tern_threshold_pack(fake, 0, d, fake, fake, fake, None) == -3  # int8 source not accepted
     assert L.tern_threshold_pack(fake, 1, d, None, fake, fake, None) == -1
     # matrix-core route: same checks as tern_pack_filters / tern_conv3d
-    assert L.tern_expand_filters(None, 4, 4, 3, 3, 3, fake, None) == -1
-    assert L.tern_expand_filters(fake, 4, 4, 0, 3, 3, fake, None) == -2
-    assert L.tern_expand_filters(fake, 4, 4, 3, 3, 3, C.c_void_p(0x1004), None) == -3
-    assert L.tern_byte_bank_bytes(40, 70, 1, 3, 2) == 6 * 3 * 2 * 1024
-    assert L.tern_byte_bank_bytes(0, 70, 1, 3, 2) == 0
-    assert L.tern_conv3d_mfma(None, d, fake, 8, g, None, None, fake, None, None) == -1
-    assert L.tern_conv3d_mfma(fake, d, fake, 8, g, None, None, fake, fake, None) == -3      # both outputs
-    assert L.tern_conv3d_mfma(fake, d, fake, 8, g, None, None, None, fake, None) == -1      # no cut points
-    assert L.tern_conv3d_mfma(fake, Dims(1, 32, 4, 4, 0), fake, 8, g, None, None, fake, None, None) == -2
+    assert L.tern_expand_filters(None, 4, 4, 3, 3, 3, 0, fake, None) == -1
+    assert L.tern_expand_filters(fake, 4, 4, 0, 3, 3, 0, fake, None) == -2
+    assert L.tern_expand_filters(fake, 4, 4, 3, 3, 3, 2, fake, None) == -3                  # unknown kind
+    assert L.tern_expand_filters(fake, 4, 4, 3, 3, 3, 1, C.c_void_p(0x1004), None) == -3
+    assert L.tern_matrix_bank_bytes(40, 70, 1, 3, 2, 0) == 6 * 3 * 2 * 1024
+    assert L.tern_matrix_bank_bytes(40, 70, 1, 3, 2, 1) == 6 * 2 * 2 * 1024
+    assert L.tern_matrix_bank_bytes(0, 70, 1, 3, 2, 0) == 0
+    assert L.tern_matrix_bank_bytes(40, 70, 1, 3, 2, 5) == 0
+    assert L.tern_conv3d_mfma(None, d, fake, 0, 8, g, None, None, fake, None, None) == -1
+    assert L.tern_conv3d_mfma(fake, d, fake, 7, 8, g, None, None, fake, None, None) == -3     # unknown kind
+    assert L.tern_conv3d_mfma(fake, d, fake, 1, 8, g, None, None, fake, fake, None) == -3     # both outputs
+    assert L.tern_conv3d_mfma(fake, d, fake, 0, 8, g, None, None, None, fake, None) == -1     # no cut points
+    assert L.tern_conv3d_mfma(fake, Dims(1, 32, 4, 4, 0), fake, 0, 8, g, None, None, fake, None, None) == -2
     # conv: both or neither output, missing cut points, bad geometry
     assert L.tern_conv3d(fake, d, fake, 8, g, None, None, None, None, None) == -3
     assert L.tern_conv3d(fake, d, fake, 8, g, fake, fake, fake, fake, None) == -3

@@ -11,11 +11,15 @@ from tests.test_gpu_parity import G, SMALL, check_case, check_sampled, expect  #
 pytestmark = pytest.mark.gpu
 
 
+KINDS = ["i8", "f4"]
+
+
+@pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("spec", SMALL, ids=[s[0] for s in SMALL])
-def test_small_shapes(G, spec):
+def test_small_shapes(G, spec, kind):
     name, n, ci, co, vol, k, s, p, d = spec
     c = synth.conv_case(name, n, ci, co, vol, k, s, p, d, p0_w=0.5, p0_a=0.4, seed=61)
-    check_case(G, c, mfma=True)
+    check_case(G, c, mfma=kind)
 
 
 EXTRA = [
@@ -36,28 +40,43 @@ EXTRA = [
 ]
 
 
+@pytest.mark.parametrize("kind", KINDS)
 @pytest.mark.parametrize("c", EXTRA, ids=[c.name for c in EXTRA])
-def test_more_shapes(G, c):
-    check_case(G, c, mfma=True)
+def test_more_shapes(G, c, kind):
+    check_case(G, c, mfma=kind)
 
 
-def test_byte_bank_layout(G):
-    """[tap][word][block][half][filter][16 bytes], codes 0x01 / 0xff / 0x00, zero past c_out and c_in."""
+def test_matrix_bank_layouts(G):
+    """[tap][step][block][half g][filter j][16 bytes]; one byte per code (0x01 / 0xff / 0x00, a step
+    is a word of 32 channels) or four bits per code (0x2 / 0xa / 0x0, a step is a pair of words);
+    zero past c_out and c_in."""
     import paper_1801_09449_amd as T
     co, ci, k = 40, 70, (1, 3, 2)
     w = synth.ternary((co, ci) + k, 0.4, 77, synth.T_WGT)
-    bank = T.tern_expand_filters(G.dev(w)).cpu().numpy().view(np.uint8)
-    taps, wd, nblk = int(np.prod(k)), (ci + 31) // 32, (co + 31) // 32
-    assert bank.size == T.tern_byte_bank_bytes(co, ci, k) == taps * wd * nblk * 1024
-    want = np.zeros((taps, wd, nblk, 2, 32, 16), np.uint8)
+    taps, nblk = int(np.prod(k)), (co + 31) // 32
     flat = w.reshape(co, ci, taps)
+    bank = T.tern_expand_filters(G.dev(w), "i8").cpu().numpy().view(np.uint8)
+    wd = (ci + 31) // 32
+    assert bank.size == T.tern_matrix_bank_bytes(co, ci, k, "i8") == taps * wd * nblk * 1024
+    want = np.zeros((taps, wd, nblk, 2, 32, 16), np.uint8)
     for f in range(co):
         for c in range(ci):
             want[:, c // 32, f // 32, (c % 32) // 16, f % 32, c % 16] = flat[f, c].astype(np.uint8)
     np.testing.assert_array_equal(bank.reshape(want.shape), want)
+    bank4 = T.tern_expand_filters(G.dev(w), "f4").cpu().numpy().view(np.uint8)
+    pairs = (ci + 63) // 64
+    assert bank4.size == T.tern_matrix_bank_bytes(co, ci, k, "f4") == taps * pairs * nblk * 1024
+    nib = np.zeros((taps, pairs, nblk, 2, 32, 32), np.uint8)          # one entry per 4-bit field
+    code = {1: 0x2, -1: 0xA, 0: 0x0}
+    for f in range(co):
+        for c in range(ci):
+            nib[:, c // 64, f // 32, (c % 64) // 32, f % 32, c % 32] = np.vectorize(code.get)(flat[f, c])
+    want4 = (nib[..., 0::2] | (nib[..., 1::2] << 4)).astype(np.uint8)   # low field in the low half of a byte
+    np.testing.assert_array_equal(bank4.reshape(want4.shape), want4)
 
 
-def test_extreme_cut_points_and_empty_zero_band(G):
+@pytest.mark.parametrize("kind", KINDS)
+def test_extreme_cut_points_and_empty_zero_band(G, kind):
     c = synth.conv_case("m_cut", 1, 64, 40, (5, 9, 8), seed=409)
     i32 = np.iinfo(np.int32)
     j = np.arange(40)
@@ -65,26 +84,28 @@ def test_extreme_cut_points_and_empty_zero_band(G):
     c.hi = np.where(j % 4 == 0, i32.max, np.where(j % 4 == 1, i32.max, np.where(j % 4 == 2, i32.min, c.hi))).astype(np.int32)
     c.lo = np.minimum(c.lo, c.hi)
     c.lo[3::4] = c.hi[3::4] + 1          # empty zero band: every accumulator maps to -1 or +1
-    check_case(G, c, mfma=True)
+    check_case(G, c, mfma=kind)
 
 
-def test_config0_and_config1_full(G):
-    check_case(G, synth.config0(), mfma=True)
-    check_case(G, synth.config1(), mfma=True)
+@pytest.mark.parametrize("kind", KINDS)
+def test_config0_and_config1_full(G, kind):
+    check_case(G, synth.config0(), mfma=kind)
+    check_case(G, synth.config1(), mfma=kind)
 
 
-def test_config3_and_config4_full_size_sampled(G):
-    check_sampled(G, synth.config3(), mfma=True)
+@pytest.mark.parametrize("kind", KINDS)
+def test_config3_and_config4_full_size_sampled(G, kind):
+    check_sampled(G, synth.config3(), mfma=kind)
     for c in synth.config4_cases():
         if c.name in ("cfg4_k3_d1_pw0.5", "cfg4_k3_d3_pw0.7", "cfg4_k1_pw0.5"):
-            check_sampled(G, c, count=8000, mfma=True)
+            check_sampled(G, c, count=8000, mfma=kind)
 
 
 def test_oversized_halo_is_refused(G):
     """A dilation whose 8 x 8 x 2 halo tile exceeds LDS: TERN_ESHAPE, nothing launched."""
     import paper_1801_09449_amd as T
     c = synth.conv_case("m_big", 1, 32, 32, (40, 40, 40), pad=16, dil=16, seed=410)
-    act = T.tern_pack(G.dev(c.act)); bank = T.tern_expand_filters(G.dev(c.wgt))
+    act = T.tern_pack(G.dev(c.act)); bank = T.tern_expand_filters(G.dev(c.wgt), "i8")
     with pytest.raises(T.TernError) as e:
-        T.tern_conv3d(act, 32, bank, 32, pad=16, dil=16, mfma=True)
+        T.tern_conv3d(act, 32, bank, 32, pad=16, dil=16, mfma="i8")
     assert e.value.status == -2
