@@ -21,6 +21,7 @@ PEAK_LANE_OPS = 256 * 64 * 2.4e9          # 39.32e12 lane-ops/s
 OPS_PER_MAC = 5.0 / 32.0                  # and, xor, and, 2 x popcount-accumulate per 32 MACs
 HBM_PEAK = 8.0e12
 PEAK_MFMA_I8 = 5.0e15                     # dense int8 matrix operations per second (published)
+PEAK_MFMA_F4 = 10.1e15                    # dense 4-bit float matrix operations per second (published)
 # HBM bytes per launch of the config[1] kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
 # a 256 MiB copy under the same counters (profiles/conv3d_fused_config1.md).
 TRAFFIC_BYTES_CFG1 = 10.09e6
@@ -264,24 +265,27 @@ def main():
     ms_unspaced, _ = timed(lambda: T.tern_probe_valu(p_blocks, p_threads, p_iters, sink, 1), 3, 1, None)
     result["roofline"]["measured_peak_unspaced"] = p_blocks * p_threads * p_iters * 65.0 / (ms_unspaced * 1e-3) / 1e12
 
-    # The same convolution through the int8 matrix instructions (tern_conv3d_mfma): not the paper's
-    # bit-count scheme, reported beside it.  Roofline: 2 integer operations per MAC against the
-    # dense int8 matrix peak.
-    byte_bank = T.tern_expand_filters(dev(case.wgt), "i8")
-    out_mfma = torch.empty_like(out_packed)
-
-    def step_mfma():
-        T.tern_conv3d(act, c_in, byte_bank, c_out, thr_lo=lo, thr_hi=hi, out=out_mfma, mfma="i8", **geom)
-
-    ms_m, _ = timed(step_mfma, args.steps, args.warmup, None)
+    # The same convolution through the matrix instructions (tern_conv3d_mfma): not the paper's
+    # bit-count scheme, reported beside it.  Roofline: 2 operations per MAC against the dense
+    # matrix peak of the operand type.
     step()
     torch.cuda.synchronize()
-    result["mfma_route"] = {
-        "value": macs / (ms_m * 1e-3) / 1e12, "unit": "TMAC/s", "ms_per_step": ms_m,
-        "dtype": "int8 codes in LDS, int32 accumulate", "same_output_as_headline": bool(torch.equal(out_mfma, out_packed)),
-        "roofline": {"bound": "mfma", "achieved": 2.0 * macs / (ms_m * 1e-3) / 1e12, "peak": PEAK_MFMA_I8 / 1e12,
-                     "unit": "TOP/s (2 int8 operations per MAC)",
-                     "frac": 2.0 * macs / (ms_m * 1e-3) / PEAK_MFMA_I8, "traffic": None}}
+    result["mfma_route"] = {}
+    for kind, peak, dt in (("i8", PEAK_MFMA_I8, "int8 codes in LDS, int32 accumulate"),
+                           ("f4", PEAK_MFMA_F4, "4-bit float codes in LDS, float32 accumulate (exact integers)")):
+        m_bank = T.tern_expand_filters(dev(case.wgt), kind)
+        out_mfma = torch.empty_like(out_packed)
+
+        def step_mfma():
+            T.tern_conv3d(act, c_in, m_bank, c_out, thr_lo=lo, thr_hi=hi, out=out_mfma, mfma=kind, **geom)
+
+        ms_m, _ = timed(step_mfma, args.steps, args.warmup, None)
+        ops = 2.0 * macs / (ms_m * 1e-3)
+        result["mfma_route"][kind] = {
+            "value": macs / (ms_m * 1e-3) / 1e12, "unit": "TMAC/s", "ms_per_step": ms_m, "dtype": dt,
+            "same_output_as_headline": bool(torch.equal(out_mfma, out_packed)),
+            "roofline": {"bound": "mfma", "achieved": ops / 1e12, "peak": peak / 1e12,
+                         "unit": "TOP/s (2 operations per MAC)", "frac": ops / peak, "traffic": None}}
 
     if args.extras:
         result["extras"] = extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, geom)

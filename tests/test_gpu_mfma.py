@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import synth
-from tests.test_gpu_parity import G, SMALL, check_case, check_sampled, expect  # noqa: F401
+from tests.test_gpu_parity import G, SMALL, check_case, check_sampled, expect, random_case  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 
@@ -44,6 +44,18 @@ EXTRA = [
 @pytest.mark.parametrize("c", EXTRA, ids=[c.name for c in EXTRA])
 def test_more_shapes(G, c, kind):
     check_case(G, c, mfma=kind)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("i", range(32))
+def test_random_geometries(G, i, kind):
+    """The seeded random geometries of the bit-count route's test; a halo tile too large for LDS
+    (large strides or dilations) must be refused with TERN_ESHAPE, anything else must match."""
+    import paper_1801_09449_amd as T
+    try:
+        check_case(G, random_case(i), mfma=kind)
+    except T.TernError as e:
+        assert e.status == -2
 
 
 def test_matrix_bank_layouts(G):
