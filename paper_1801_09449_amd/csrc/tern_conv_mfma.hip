@@ -259,43 +259,66 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
         if (ks + 1 < ksteps) halo_load(ks + 1, tid, hm, hs);
 
         // ---- contract: all taps of this step ----
-        // Column fragments come from the vector cache, hundreds of cycles away: the next tap's
-        // are requested before this tap's matrix instructions are issued.
+        // Column fragments come from the vector cache, hundreds of cycles away: they are requested
+        // two taps ahead (three register sets in rotation); row fragments come from LDS at the
+        // start of their tap.
         const uint8_t* lane_lds = lds8 + lane_off;
-        int tap = 0;
-        v4i Bn[NB];
+        auto fetch_b = [&](v4i (&B)[NB], int tap) {
+            const int tq = tap < T ? tap : T - 1;        // past the end: a harmless repeat
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) Bn[nb] = bank[((size_t)ks * t.nblk + nb0 + nb) * 64 + lane];
-        for (int a = 0; a < p.kd; ++a)
-            for (int b = 0; b < p.kh; ++b)
-                for (int c = 0; c < p.kw; ++c, ++tap) {
-                    const int toff = (a * p.dd) * plane_b + (b * p.dh) * row_b + (c * p.dw) * kRec;
-                    v4i A[4], B[NB];
-                    const int tnext = tap + 1 < T ? tap + 1 : tap;
+            for (int nb = 0; nb < NB; ++nb)
+                B[nb] = bank[((size_t)(tq * ksteps + ks) * t.nblk + nb0 + nb) * 64 + lane];
+            __builtin_amdgcn_sched_barrier(0);           // keep the requests ahead of the matrix instructions
+        };
+        // LDS offset of the following tap (x fastest), as wave-uniform increments
+        const int inc_c = p.dw * kRec;
+        const int inc_b = p.dh * row_b - (p.kw - 1) * inc_c;
+        const int inc_a = p.dd * plane_b - (p.kh - 1) * p.dh * row_b - (p.kw - 1) * inc_c;
+        int tb = 0, tc = 0, toff = 0;
+        auto contract = [&](const v4i (&B)[NB]) {
+            v4i A[4];
 #pragma unroll
-                    for (int nb = 0; nb < NB; ++nb) {
-                        B[nb] = Bn[nb];
-                        Bn[nb] = bank[((size_t)(tnext * ksteps + ks) * t.nblk + nb0 + nb) * 64 + lane];
+            for (int mb = 0; mb < 4; ++mb)
+                A[mb] = *reinterpret_cast<const v4i*>(lane_lds + toff + mboff[mb]);
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    if constexpr (F4) {
+                        // 4-bit operands occupy the first four of the eight operand registers;
+                        // both scales are 2^0 (E8M0 127 in every byte)
+                        const v8i a8 = __builtin_shufflevector(A[mb], A[mb], 0, 1, 2, 3, -1, -1, -1, -1);
+                        const v8i b8 = __builtin_shufflevector(B[nb], B[nb], 0, 1, 2, 3, -1, -1, -1, -1);
+                        acc[mb][nb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                            a8, b8, acc[mb][nb], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+                    } else {
+                        acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[mb], B[nb], acc[mb][nb], 0, 0, 0);
                     }
-#pragma unroll
-                    for (int mb = 0; mb < 4; ++mb)
-                        A[mb] = *reinterpret_cast<const v4i*>(lane_lds + toff + mboff[mb]);
-#pragma unroll
-                    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                        for (int nb = 0; nb < NB; ++nb) {
-                            if constexpr (F4) {
-                                // 4-bit operands occupy the first four of the eight operand registers;
-                                // both scales are 2^0 (E8M0 127 in every byte)
-                                const v8i a8 = __builtin_shufflevector(A[mb], A[mb], 0, 1, 2, 3, -1, -1, -1, -1);
-                                const v8i b8 = __builtin_shufflevector(B[nb], B[nb], 0, 1, 2, 3, -1, -1, -1, -1);
-                                acc[mb][nb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                                    a8, b8, acc[mb][nb], 4, 4, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
-                            } else {
-                                acc[mb][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[mb], B[nb], acc[mb][nb], 0, 0, 0);
-                            }
-                        }
                 }
+            int inc = inc_c;                             // on to the next tap
+            if (++tc == p.kw) {
+                tc = 0;
+                inc = inc_b;
+                if (++tb == p.kh) { tb = 0; inc = inc_a; }
+            }
+            toff += inc;
+        };
+        v4i B0[NB], B1[NB], B2[NB];
+        fetch_b(B0, 0);
+        fetch_b(B1, 1);
+        int tap = 0;
+        for (; tap + 3 <= T; tap += 3) {
+            fetch_b(B2, tap + 2);
+            contract(B0);
+            fetch_b(B0, tap + 3);
+            contract(B1);
+            fetch_b(B1, tap + 4);
+            contract(B2);
+        }
+        if (tap < T) {
+            contract(B0);
+            if (tap + 1 < T) contract(B1);
+        }
     }
 
     // ---- epilogue ----
