@@ -174,6 +174,28 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
                                      "gmac_executed": executed / 1e9,
                                      "TMACs_executed": executed / (ms_u * 1e-3) / 1e12,
                                      "prediction_shape": list(pred.shape)}
+        if n == 16:
+            # the same network with its large modules on the matrix cores (not the paper's scheme)
+            plan_m = unet.UNetPlan(u.layers, u.head_w, u.head_b, u.in_lo, u.in_hi, matrix_kind="f4")
+            pred_m = unet.unet_forward(plan_m, ux).clone()
+            ms_m, _ = timed(lambda: unet.unet_forward(plan_m, ux, out=pred_m), 20, 3, None)
+            ex["unet_table1_n16_matrix_f4"] = {"ms": ms_m, "same_prediction": bool(torch.equal(pred_m, pred)),
+                                               "modules_on_matrix_cores": sum(
+                                                   1 for m in plan_m.modules(ux.shape) if m.matrix_bank is not None)}
+    # the other configurations through the matrix-core route
+    c4 = {c.name: c for c in synth.config4_cases()}
+    for name, c in (("cfg3", synth.config3()), ("cfg4_k3_d1_pw0.5", c4["cfg4_k3_d1_pw0.5"]),
+                    ("cfg4_k3_d3_pw0.5", c4["cfg4_k3_d3_pw0.5"])):
+        ci, co = c.act.shape[1], c.wgt.shape[0]
+        g = dict(k=c.k, stride=c.stride, pad=c.pad, dil=c.dil)
+        a_p = T.tern_pack(dev(c.act)); l_, h_ = dev(c.lo), dev(c.hi)
+        row = {}
+        for kind in ("i8", "f4"):
+            mb = T.tern_expand_filters(dev(c.wgt), kind)
+            o = T.tern_conv3d(a_p, ci, mb, co, thr_lo=l_, thr_hi=h_, mfma=kind, **g)
+            ms_k, _ = timed(lambda: T.tern_conv3d(a_p, ci, mb, co, thr_lo=l_, thr_hi=h_, mfma=kind, out=o, **g), 30, 5, None)
+            row[kind] = {"ms": ms_k, "TMACs": c.macs / (ms_k * 1e-3) / 1e12}
+        ex["mfma_" + name] = row
     return ex
 
 

@@ -341,6 +341,11 @@ typedef struct {
     int32_t skip_from;
     int32_t up[3];
     int32_t pool[3];            /* {1,1,1} or all 0: none; else sum pooling through two digits */
+    const uint32_t* matrix_bank;/* NULL, or the module's bank from tern_expand_filters: the module then
+                                   runs through tern_conv3d_mfma (same results); w_bank stays required
+                                   and is used when the matrix route refuses the geometry.  Ignored
+                                   for the first module of a one-channel input and for pooled modules. */
+    int32_t matrix_kind;        /* TERN_MATRIX_I8 or TERN_MATRIX_F4 when matrix_bank is given */
 } tern_module;
 size_t tern_net_workspace_bytes(tern_dims in_dims, const tern_module* mods /* host */, int32_t n_mods);
 int tern_net_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,

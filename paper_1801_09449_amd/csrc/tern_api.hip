@@ -644,6 +644,9 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
         odims[(size_t)i] = o;
         ooff[(size_t)i] = off;
         off += region(o);
+        if (m.matrix_bank && ((m.matrix_kind != TERN_MATRIX_I8 && m.matrix_kind != TERN_MATRIX_F4) ||
+                              !aligned16(m.matrix_bank)))
+            return TERN_EARG;
         if (w && w->run) {
             if (!m.w_bank || !m.thr_lo || !m.thr_hi) return TERN_ENULL;
             if (i == 0 && gathered && !fused) {
@@ -670,8 +673,14 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
                                         m.thr_lo, m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]),
                                         w->stream);
             } else {
-                rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
-                                 m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
+                rc = TERN_ESHAPE;
+                if (m.matrix_bank)
+                    rc = tern_conv3d_mfma((const uint32_t*)(w->ws + cur_off), cur, m.matrix_bank, m.matrix_kind,
+                                          m.c_out, m.g, m.thr_lo, m.thr_hi, nullptr,
+                                          (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
+                if (rc == TERN_ESHAPE)   // no matrix bank, or a halo tile the matrix route cannot hold
+                    rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
+                                     m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
             }
             if (rc != TERN_OK) return rc;
             if (w->module_out) w->module_out[i] = (uint32_t*)(w->ws + ooff[(size_t)i]);

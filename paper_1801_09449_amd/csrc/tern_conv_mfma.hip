@@ -427,9 +427,19 @@ int launch_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t 
 // p.wgt is the filter bank of that kind.  TERN_ESHAPE when the halo tile of even one wave's
 // 8 x 8 x 2 output block does not fit in LDS (very large strides or dilations), and for the 4-bit
 // kind when a sum could leave the integers a float holds exactly (k-volume * C_in >= 2^24).
-int launch_conv3d_mfma(const ConvParams& p, int kind, hipStream_t s)
+int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
 {
+    ConvParams p = p_in;
     if (kind == 1 && (int64_t)p.kd * p.kh * p.kw * p.c_in >= (1 << 24)) return TERN_ESHAPE;
+    // A kernel of depth extent 1 with unit depth stride and no depth padding treats every input
+    // plane by itself: batch items are just more planes, [N][D] collapses to [1][N*D], and a
+    // workgroup's eight planes may come from different batch items (stacks of 2-D slices have
+    // D = 1).  Packed output only: the int32 layout has the channel axis between N and D.
+    if (p.out_packed && p.n > 1 && p.kd == 1 && p.sd == 1 && p.pd == 0 && (int64_t)p.n * p.d <= INT32_MAX) {
+        p.d *= p.n;
+        p.od *= p.n;
+        p.n = 1;
+    }
     MfmaPlan t;
     auto halo = [](int out, int stride, int k, int dil) { return (out - 1) * stride + (k - 1) * dil + 1; };
     t.hx = halo(kTX, p.sw, p.kw, p.dw);
@@ -439,7 +449,9 @@ int launch_conv3d_mfma(const ConvParams& p, int kind, hipStream_t s)
     // registers), the larger tile on a tie.
     const int64_t kLds = 160 * 1024;
     int nw = 0, best_waves = 0;
-    for (int w = kMaxWaves; w >= 1; w /= 2) {
+    int w_max = kMaxWaves;
+    while (w_max > 1 && w_max >= p.od) w_max /= 2;   // no more waves than there are pairs of output planes
+    for (int w = w_max; w >= 1; w /= 2) {
         const int64_t nv = (int64_t)t.hx * t.hy * halo(2 * w, p.sd, p.kd, p.dd);
         const int64_t bytes = half_offset(nv) + nv * kRec;
         if (bytes > kLds) continue;
