@@ -132,26 +132,48 @@ __global__ __launch_bounds__(256) void expand_filters_kernel(const int8_t* __res
 // Eq. 6 on one 32 x 32 accumulator tile: register V of lane l is (row 8 (V / 4) + 4 (l / 32) +
 // V % 4, column l % 32).  A wave-wide comparison gives the 32 channel bits of two rows at once
 // (lanes 0-31: row r, lanes 32-63: row r + 4); they go to lanes r and r + 4 of posw / negw.
-template <int V, typename Acc>
-__device__ __forceinline__ void decide_rows(const Acc& acc, int32_t lo, int32_t hi, uint32_t& posw,
-                                            uint32_t& negw)
+// Four registers (one group of eight rows) per step: eight comparisons, then their sixteen lane
+// writes behind one wait.  Thr is the accumulators' own type (the fp4 route compares floats: its
+// sums are exact integers and the cut points are clamped to +-2^24, beyond every sum).
+template <int V0, typename Acc, typename Thr>
+__device__ __forceinline__ void decide_rows(const Acc& acc, Thr lo, Thr hi, uint32_t& posw, uint32_t& negw)
 {
-    if constexpr (V < 16) {
-        constexpr int r = (V >> 2) * 8 + (V & 3);
-        const int32_t d = (int32_t)acc[V];       // fp4 route: an exact integer held in a float
-        const unsigned long long bp = __ballot(d > hi);
-        const unsigned long long bn = __ballot(d < lo);
+    if constexpr (V0 < 16) {
+        constexpr int r = (V0 >> 2) * 8;         // rows r .. r + 3 from lane group 0, r + 4 .. r + 7 from group 1
+        unsigned long long bp[4], bn[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bp[j] = __ballot(acc[V0 + j] > hi);
+            bn[j] = __ballot(acc[V0 + j] < lo);
+        }
         // The compiler does not see inside the statement: the wait states that a lane write
-        // needs after the comparisons wrote their scalar results are spelled out.
+        // needs after a comparison wrote its scalar result are spelled out.
         asm("s_nop 4\n\t"
-            "v_writelane_b32 %[p], %[pl], %[r0]\n\t"
-            "v_writelane_b32 %[p], %[ph], %[r1]\n\t"
-            "v_writelane_b32 %[n], %[nl], %[r0]\n\t"
-            "v_writelane_b32 %[n], %[nh], %[r1]"
+            "v_writelane_b32 %[p], %[p0l], %[r0]\n\t"
+            "v_writelane_b32 %[p], %[p0h], %[r4]\n\t"
+            "v_writelane_b32 %[n], %[n0l], %[r0]\n\t"
+            "v_writelane_b32 %[n], %[n0h], %[r4]\n\t"
+            "v_writelane_b32 %[p], %[p1l], %[r1]\n\t"
+            "v_writelane_b32 %[p], %[p1h], %[r5]\n\t"
+            "v_writelane_b32 %[n], %[n1l], %[r1]\n\t"
+            "v_writelane_b32 %[n], %[n1h], %[r5]\n\t"
+            "v_writelane_b32 %[p], %[p2l], %[r2]\n\t"
+            "v_writelane_b32 %[p], %[p2h], %[r6]\n\t"
+            "v_writelane_b32 %[n], %[n2l], %[r2]\n\t"
+            "v_writelane_b32 %[n], %[n2h], %[r6]\n\t"
+            "v_writelane_b32 %[p], %[p3l], %[r3]\n\t"
+            "v_writelane_b32 %[p], %[p3h], %[r7]\n\t"
+            "v_writelane_b32 %[n], %[n3l], %[r3]\n\t"
+            "v_writelane_b32 %[n], %[n3h], %[r7]"
             : [p] "+v"(posw), [n] "+v"(negw)
-            : [pl] "s"((uint32_t)bp), [ph] "s"((uint32_t)(bp >> 32)), [nl] "s"((uint32_t)bn),
-              [nh] "s"((uint32_t)(bn >> 32)), [r0] "n"(r), [r1] "n"(r + 4));
-        decide_rows<V + 1, Acc>(acc, lo, hi, posw, negw);
+            : [p0l] "s"((uint32_t)bp[0]), [p0h] "s"((uint32_t)(bp[0] >> 32)), [n0l] "s"((uint32_t)bn[0]),
+              [n0h] "s"((uint32_t)(bn[0] >> 32)), [p1l] "s"((uint32_t)bp[1]), [p1h] "s"((uint32_t)(bp[1] >> 32)),
+              [n1l] "s"((uint32_t)bn[1]), [n1h] "s"((uint32_t)(bn[1] >> 32)), [p2l] "s"((uint32_t)bp[2]),
+              [p2h] "s"((uint32_t)(bp[2] >> 32)), [n2l] "s"((uint32_t)bn[2]), [n2h] "s"((uint32_t)(bn[2] >> 32)),
+              [p3l] "s"((uint32_t)bp[3]), [p3h] "s"((uint32_t)(bp[3] >> 32)), [n3l] "s"((uint32_t)bn[3]),
+              [n3h] "s"((uint32_t)(bn[3] >> 32)), [r0] "n"(r), [r1] "n"(r + 1), [r2] "n"(r + 2), [r3] "n"(r + 3),
+              [r4] "n"(r + 4), [r5] "n"(r + 5), [r6] "n"(r + 6), [r7] "n"(r + 7));
+        decide_rows<V0 + 4, Acc, Thr>(acc, lo, hi, posw, negw);
     }
 }
 
@@ -336,15 +358,24 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
     for (int nb = 0; nb < NB; ++nb) {
         const int co = (nb0 + nb) * 32 + i32;
         if constexpr (PACKED) {
-            int32_t lo = INT32_MIN, hi = INT32_MAX;     // channels past c_out: code 0
-            if (co < p.c_out) { lo = p.lo[co]; hi = p.hi[co]; }
+            int32_t lo_i = INT32_MIN, hi_i = INT32_MAX;  // channels past c_out: code 0
+            if (co < p.c_out) { lo_i = p.lo[co]; hi_i = p.hi[co]; }
+            using Thr = typename std::conditional<F4, float, int32_t>::type;
+            Thr lo, hi;
+            if constexpr (F4) {                          // |sum| < 2^24: clamping changes no decision
+                lo = (float)max(-(1 << 24), min(1 << 24, lo_i));
+                hi = (float)max(-(1 << 24), min(1 << 24, hi_i));
+            } else {
+                lo = lo_i;
+                hi = hi_i;
+            }
             const int q = nb0 + nb;
             if (q < p.wd_out) {
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb) {
                     __builtin_amdgcn_sched_barrier(0);   // one tile at a time
                     uint32_t posw = 0u, negw = 0u;      // lane r (< 32): words of the block's voxel r
-                    decide_rows<0, Acc>(acc[mb][nb], lo, hi, posw, negw);
+                    decide_rows<0, Acc, Thr>(acc[mb][nb], lo, hi, posw, negw);
                     const int ox = ox0 + xl, oy = oy0 + (mb & 1) * 4 + yl, oz = oz0 + wave * 2 + (mb >> 1);
                     if (g == 0 && ox < p.ow && oy < p.oh && oz < p.od) {
                         uint32_t* o = p.out_packed + ((((size_t)n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
