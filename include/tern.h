@@ -151,9 +151,10 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims,
  *   matrix_bank : tern_matrix_bank_bytes(...) bytes, 16-byte aligned, made once per layer by
  *                 tern_expand_filters from the same int8 weights [C_out][C_in][kd][kh][kw] that
  *                 tern_pack_filters takes.  Layout [tap][step][block of 32 filters][half g]
- *                 [filter j][16 bytes]; I8: step = word of 32 input channels, byte b = channel
- *                 32 step + 16 g + b; F4: step = pair of words, 4-bit field c = channel
- *                 64 step + 32 g + c.  Zero past C_out and C_in.
+ *                 [filter j][4 dwords q]; I8: step = word of 32 input channels, byte b of dword q
+ *                 = channel 32 step + (4 g + q) + 8 b; F4: step = pair of words, 4-bit field i of
+ *                 dword q = channel 32 (2 step + g) + 4 i + q (the order in which the kernel's
+ *                 expansion of an activation word leaves the channels).  Zero past C_out and C_in.
  * Returns TERN_ESHAPE when the halo of an 8 x 8 x 2 block of outputs does not fit in LDS (very
  * large strides or dilations); tern_conv3d has no such limit.
  */

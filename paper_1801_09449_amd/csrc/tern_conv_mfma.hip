@@ -20,8 +20,8 @@
 // Operand layout of the instructions (two lane groups x 16 bytes of inner indices): lane l of
 // the row operand holds row l % 32, lane l of the column operand holds column l % 32, and both
 // hold the inner indices of lane group l / 32 in the same order, so any consistent assignment
-// of channels to (lane group, position) gives the right sum; here int8: channel 16 (l / 32) +
-// byte of the word, fp4: word l / 32 of the pair, channel = 4-bit field.  Result: lane l holds
+// of channels to (lane group, position) gives the right sum; the one used is whatever makes the
+// 2-bit -> operand expansion cheapest (see expand_word, expand_word_f4).  Result: lane l holds
 // column l % 32, register v holds row 8 (v / 4) + 4 (l / 32) + v % 4.
 #include <type_traits>
 
@@ -56,46 +56,44 @@ struct MfmaPlan {
     int32_t half_off;                // LDS byte offset of the second region
 };
 
-// One byte per code from a word of 32 channels: +1 -> 0x01, -1 -> 0xff, 0 -> 0x00.
-// (nibble * 0x00204081) & 0x01010101 moves bit b of the nibble to bit 0 of byte b.
+// The inner index of the matrix product may be laid out in any order that row and column operands
+// share, so the expansions pick the order that costs the fewest instructions: bits are masked
+// where they stand instead of being gathered.
+//
+// One byte per code from a word of 32 channels: +1 -> 0x01, -1 -> 0xff, 0 -> 0x00.  Dword d
+// (0..7; lane group d / 4 reads dwords 4 (d / 4) .. + 3) holds channels d, d + 8, d + 16, d + 24 in
+// its bytes 0..3: (m >> d) & 0x01010101 is their magnitude byte, and 0xfe times the same of the
+// negative codes turns 0x01 into 0xff.
 __device__ __forceinline__ void expand_word(uint32_t m, uint32_t s, uint4& lo16, uint4& hi16)
 {
-    const uint32_t neg = m & s, pos = m & ~s;
+    const uint32_t neg = m & s;
     uint32_t o[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint32_t pb = (((pos >> (4 * j)) & 15u) * 0x00204081u) & 0x01010101u;
-        const uint32_t nb = (((neg >> (4 * j)) & 15u) * 0x00204081u) & 0x01010101u;
-        o[j] = pb | (nb * 0xffu);
-    }
+    for (int d = 0; d < 8; ++d)
+        o[d] = ((m >> d) & 0x01010101u) | (((neg >> d) & 0x01010101u) * 0xfeu);
     lo16 = make_uint4(o[0], o[1], o[2], o[3]);
     hi16 = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
 // Four bits per code (the E2M1 format of the scaled matrix instructions: +1 = 0010, -1 = 1010,
-// 0 = 0000) from a word of 32 channels, channel c in bits [4 c, 4 c + 4) of the 128.
-// spread(x) moves bit i of a byte to bit 4 i.
-__device__ __forceinline__ uint32_t spread8(uint32_t x)
-{
-    x = (x | (x << 12)) & 0x000f000fu;
-    x = (x | (x << 6)) & 0x03030303u;
-    x = (x | (x << 3)) & 0x11111111u;
-    return x;
-}
+// 0 = 0000) from a word of 32 channels.  Dword q (0..3) holds channels q, q + 4, ..., q + 28 in its
+// 4-bit fields 0..7: the magnitude bit of channel 4 i + q belongs at bit 4 i + 1 and its sign at
+// bit 4 i + 3, a shift by q - 1 and by q - 3 away from where the words have them.
 __device__ __forceinline__ uint4 expand_word_f4(uint32_t m, uint32_t s)
 {
     const uint32_t neg = m & s;
     uint32_t o[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        o[j] = (spread8((m >> (8 * j)) & 0xffu) << 1) | (spread8((neg >> (8 * j)) & 0xffu) << 3);
+    o[0] = ((m << 1) & 0x22222222u) | ((neg << 3) & 0x88888888u);
+    o[1] = (m & 0x22222222u) | ((neg << 2) & 0x88888888u);
+    o[2] = ((m >> 1) & 0x22222222u) | ((neg << 1) & 0x88888888u);
+    o[3] = ((m >> 2) & 0x22222222u) | (neg & 0x88888888u);
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-// Byte filter bank [tap][word][column block][lane group g][column j][16]: byte b of the entry is
-// the code of filter 32 * block + j at input channel 32 * word + 16 * g + b (0 past c_out or c_in).
-// fp4 bank: [tap][word pair][column block][g][j][16 bytes], nibble c of the entry = code of filter
-// 32 * block + j at input channel 32 * (2 * pair + g) + c.
+// Filter banks, [tap][step][column block][lane group g][column j][16 bytes], in the expansions'
+// channel order.  int8 (step = word): byte b of dword q = code of filter 32 * block + j at input
+// channel 32 * step + (4 g + q) + 8 b.  fp4 (step = pair of words): 4-bit field i of dword q = code
+// at input channel 32 * (2 * step + g) + 4 i + q.  Zero past c_out and c_in.
 template <bool F4>
 __global__ __launch_bounds__(256) void expand_filters_kernel(const int8_t* __restrict__ w, int32_t c_out,
                                                              int32_t c_in, int32_t taps, int32_t ksteps,
@@ -115,10 +113,9 @@ __global__ __launch_bounds__(256) void expand_filters_kernel(const int8_t* __res
     uint32_t out = 0u;
     if (co < c_out) {
         constexpr int PER = F4 ? 8 : 4;          // codes per dword
-        const int c0 = F4 ? (2 * ks + g) * 32 + q * 8 : ks * 32 + g * 16 + q * 4;
 #pragma unroll
         for (int b = 0; b < PER; ++b) {
-            const int c = c0 + b;
+            const int c = F4 ? (2 * ks + g) * 32 + 4 * b + q : ks * 32 + (4 * g + q) + 8 * b;
             if (c < c_in) {
                 const int v = w[((size_t)co * c_in + c) * taps + tap];
                 if constexpr (F4) out |= (v > 0 ? 0x2u : v < 0 ? 0xau : 0u) << (4 * b);

@@ -59,9 +59,10 @@ def test_random_geometries(G, i, kind):
 
 
 def test_matrix_bank_layouts(G):
-    """[tap][step][block][half g][filter j][16 bytes]; one byte per code (0x01 / 0xff / 0x00, a step
-    is a word of 32 channels) or four bits per code (0x2 / 0xa / 0x0, a step is a pair of words);
-    zero past c_out and c_in."""
+    """[tap][step][block][half g][filter j][4 dwords q].  int8: step = word of 32 channels, byte b
+    of dword q = channel (4 g + q) + 8 b of the word, codes 0x01 / 0xff / 0x00.  4-bit: step = pair
+    of words, field i of dword q = channel 4 i + q of word g of the pair, codes 0x2 / 0xa / 0x0.
+    Zero past c_out and c_in."""
     import paper_1801_09449_amd as T
     co, ci, k = 40, 70, (1, 3, 2)
     w = synth.ternary((co, ci) + k, 0.4, 77, synth.T_WGT)
@@ -70,20 +71,22 @@ def test_matrix_bank_layouts(G):
     bank = T.tern_expand_filters(G.dev(w), "i8").cpu().numpy().view(np.uint8)
     wd = (ci + 31) // 32
     assert bank.size == T.tern_matrix_bank_bytes(co, ci, k, "i8") == taps * wd * nblk * 1024
-    want = np.zeros((taps, wd, nblk, 2, 32, 16), np.uint8)
+    want = np.zeros((taps, wd, nblk, 2, 32, 4, 4), np.uint8)            # [...][g][j][q][b]
     for f in range(co):
         for c in range(ci):
-            want[:, c // 32, f // 32, (c % 32) // 16, f % 32, c % 16] = flat[f, c].astype(np.uint8)
+            d, b = (c % 32) % 8, (c % 32) // 8
+            want[:, c // 32, f // 32, d // 4, f % 32, d % 4, b] = flat[f, c].astype(np.uint8)
     np.testing.assert_array_equal(bank.reshape(want.shape), want)
-    bank4 = T.tern_expand_filters(G.dev(w), "f4").cpu().numpy().view(np.uint8)
+    bank4 = T.tern_expand_filters(G.dev(w), "f4").cpu().numpy().view(np.uint32)
     pairs = (ci + 63) // 64
-    assert bank4.size == T.tern_matrix_bank_bytes(co, ci, k, "f4") == taps * pairs * nblk * 1024
-    nib = np.zeros((taps, pairs, nblk, 2, 32, 32), np.uint8)          # one entry per 4-bit field
+    assert bank4.size * 4 == T.tern_matrix_bank_bytes(co, ci, k, "f4") == taps * pairs * nblk * 1024
+    want4 = np.zeros((taps, pairs, nblk, 2, 32, 4), np.uint32)          # [...][g][j][q]
     code = {1: 0x2, -1: 0xA, 0: 0x0}
     for f in range(co):
         for c in range(ci):
-            nib[:, c // 64, f // 32, (c % 64) // 32, f % 32, c % 32] = np.vectorize(code.get)(flat[f, c])
-    want4 = (nib[..., 0::2] | (nib[..., 1::2] << 4)).astype(np.uint8)   # low field in the low half of a byte
+            q, i = (c % 32) % 4, (c % 32) // 4
+            vals = np.array([code[int(v)] for v in flat[f, c]], np.uint32)
+            want4[:, c // 64, f // 32, (c % 64) // 32, f % 32, q] |= vals << np.uint32(4 * i)
     np.testing.assert_array_equal(bank4.reshape(want4.shape), want4)
 
 
