@@ -242,12 +242,19 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
             if (inb) {
                 const uint32_t vox = (uint32_t)((gz * p.h + gy) * p.w + gx);   // below 2^31 voxels per item
                 const uint32_t* src = in_n + (size_t)vox * (2u * wd);
+                if (F4 && (wd & 1) == 0) {               // both words of the pair with one load per plane
+                    const uint2 mm = *reinterpret_cast<const uint2*>(src + ks * 2);
+                    const uint2 ss = *reinterpret_cast<const uint2*>(src + wd + ks * 2);
+                    m[k][0] = mm.x; m[k][KW - 1] = mm.y;
+                    s[k][0] = ss.x; s[k][KW - 1] = ss.y;
+                } else {
 #pragma unroll
-                for (int q = 0; q < KW; ++q) {
-                    const int word = ks * KW + q;
-                    if (word < wd) {                     // an odd word count leaves the last pair half empty
-                        m[k][q] = src[word];
-                        s[k][q] = src[wd + word];
+                    for (int q = 0; q < KW; ++q) {
+                        const int word = ks * KW + q;
+                        if (word < wd) {                 // an odd word count leaves the last pair half empty
+                            m[k][q] = src[word];
+                            s[k][q] = src[wd + word];
+                        }
                     }
                 }
             }
