@@ -10,7 +10,7 @@ four times the word pairs of the pooled convolution); large ones pool into two b
 digits first (tern_pool_digits, one small launch) and convolve those (twice the word pairs).
 On request (matrix_kind) batches with at least four planes per convolution run their large
 modules on the matrix cores (tern_module.matrix_bank, pooling folded into the filters): same
-results, 16 stacks in 0.53 ms instead of 0.97 ms.  Not the default: the network then no longer
+results, 16 stacks in 0.47 ms instead of 0.97 ms.  Not the default: the network then no longer
 runs on the paper's bit-count scheme.
 """
 from typing import Dict, List, Sequence
