@@ -103,6 +103,20 @@ def test_extreme_cut_points_and_empty_zero_band(G, kind):
 
 
 @pytest.mark.parametrize("kind", KINDS)
+def test_cut_points_beyond_the_range_of_exact_floats(G, kind):
+    """Cut points at and past +-2^24 (the 4-bit kind compares floats and clamps them there: no sum
+    reaches that far, so every decision is the integer one)."""
+    c = synth.conv_case("m_far", 2, 96, 33, (4, 9, 10), seed=411)
+    far = np.array([2 ** 24, 2 ** 24 + 1, 2 ** 24 + 5, 2 ** 30, -(2 ** 24), -(2 ** 24) - 1, -(2 ** 24) - 7, -(2 ** 30),
+                    2 ** 24 - 1, -(2 ** 24) + 1, 0], np.int64)
+    c.lo = far[np.arange(33) % len(far)].astype(np.int32)
+    c.hi = far[(np.arange(33) * 5 + 3) % len(far)].astype(np.int32)
+    swap = c.lo > c.hi + 1                       # keep lo <= hi + 1 (the documented precondition)
+    c.lo[swap], c.hi[swap] = c.hi[swap], c.lo[swap]
+    check_case(G, c, mfma=kind)
+
+
+@pytest.mark.parametrize("kind", KINDS)
 def test_config0_and_config1_full(G, kind):
     check_case(G, synth.config0(), mfma=kind)
     check_case(G, synth.config1(), mfma=kind)
