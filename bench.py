@@ -26,6 +26,8 @@ PEAK_MFMA_F4 = 10.1e15                    # dense 4-bit float matrix operations 
 # a 256 MiB copy under the same counters (profiles/conv3d_fused_config1.md).
 TRAFFIC_BYTES_CFG1 = 10.09e6
 ALGORITHMIC_BYTES_CFG1 = 8.42e6
+# the same counters for the matrix-core kernels (profiles/conv3d_mfma_config1.md)
+TRAFFIC_BYTES_CFG1_MFMA = {"i8": 10.46e6, "f4": 10.05e6}
 
 
 def timed(fn, steps, warmup, stream_sync):
@@ -307,7 +309,8 @@ def main():
             "value": macs / (ms_m * 1e-3) / 1e12, "unit": "TMAC/s", "ms_per_step": ms_m, "dtype": dt,
             "same_output_as_headline": bool(torch.equal(out_mfma, out_packed)),
             "roofline": {"bound": "mfma", "achieved": ops / 1e12, "peak": peak / 1e12,
-                         "unit": "TOP/s (2 operations per MAC)", "frac": ops / peak, "traffic": None}}
+                         "unit": "TOP/s (2 operations per MAC)", "frac": ops / peak,
+                         "traffic": TRAFFIC_BYTES_CFG1_MFMA[kind]}}
 
     if args.extras:
         result["extras"] = extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, geom)
