@@ -208,6 +208,127 @@ __global__ __launch_bounds__(kBlock) void real_conv_lds_kernel(RealConvParams p,
     }
 }
 
+// The same convolution through partial-sum tables: for every (tap, group of four input channels)
+// LDS holds the 16 sums of the subsets of the group's four weights (per output channel of the
+// group CG), built by the workgroup from the staged weights.  A voxel's +1 codes of such a group
+// are a 4-bit index into the table and so are its -1 codes: two lookups, one addition and one
+// subtraction per output channel replace four multiply-adds and the unpacking of four codes.
+// A fixed order of operations again (table entries add their weights in channel order; the
+// accumulator takes "+ entry of the +1 codes, - entry of the -1 codes" group by group), but not
+// the order of real_conv_kernel: results agree within the rounding bound of a float sum of that
+// many terms, not bit for bit.  Used when weights and tables (five times the weights) fit in 64 KB.
+template <int CG>
+__global__ __launch_bounds__(kBlock) void real_conv_lut_kernel(RealConvParams p, int c_pad)
+{
+    extern __shared__ __align__(16) float wl[];
+    int64_t vox = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const bool active = vox < p.total;
+    if (!active) vox = p.total - 1;
+    const int64_t vox_out = vox;
+    const int x = (int)(vox % p.ow); vox /= p.ow;
+    const int y = (int)(vox % p.oh); vox /= p.oh;
+    const int z = (int)(vox % p.od);
+    const int n = (int)(vox / p.od);
+    const int T = p.kd * p.kh * p.kw;
+    const size_t per_filter = (size_t)p.c_in * T;
+    const size_t ospatial = (size_t)p.od * p.oh * p.ow;
+    const size_t sp = vox_out - (size_t)n * ospatial;
+    const int rows = T * c_pad;                  // (tap, channel) pairs, channels padded to fours
+    const int nq = c_pad / 4;                    // channel groups per tap
+    float* lut = wl + (size_t)rows * CG;         // [tap][group][16][CG]
+
+    for (int co0 = 0; co0 < p.c_out; co0 += CG) {
+        if (co0 > 0) __syncthreads();            // everyone is done with the previous group's tables
+        for (int i = threadIdx.x; i < rows * CG; i += kBlock) {
+            const int g = i % CG;
+            const int r = i / CG;
+            const int c = r % c_pad, tap = r / c_pad;
+            float wv = 0.0f;
+            if (c < p.c_in) wv = p.wgt[(size_t)min(co0 + g, p.c_out - 1) * per_filter + (size_t)c * T + tap];
+            wl[i] = wv;
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < T * nq * 16; i += kBlock) {
+            const int v = i & 15;
+            const float* w4 = wl + (size_t)(i >> 4) * 4 * CG;     // the group's four channels x CG
+#pragma unroll
+            for (int g = 0; g < CG; ++g) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    if ((v >> b) & 1) sum += w4[b * CG + g];
+                lut[(size_t)i * CG + g] = sum;
+            }
+        }
+        __syncthreads();
+        float acc[CG];
+#pragma unroll
+        for (int g = 0; g < CG; ++g) acc[g] = (p.bias && co0 + g < p.c_out) ? p.bias[co0 + g] : 0.0f;
+        // one tap's contribution from its voxel record (mask words, then sign words)
+        auto add_tap = [&](int tap, const uint32_t* rec_m, const uint32_t* rec_s, int nwords) {
+            const float* tt = lut + (size_t)tap * nq * 16 * CG;
+            for (int q = 0; q < nwords; ++q) {
+                const uint32_t m = rec_m[q];
+                const uint32_t neg = rec_s[q] & m;
+                const uint32_t pos = m & ~neg;
+                const int live = min(32, c_pad - 32 * q);     // multiple of 4
+                for (int j0 = 0; j0 < live; j0 += 4) {
+                    const float* grp = tt + (size_t)(8 * q + (j0 >> 2)) * 16 * CG;
+                    const float* ep = grp + ((pos >> j0) & 15u) * CG;
+                    const float* en = grp + ((neg >> j0) & 15u) * CG;
+#pragma unroll
+                    for (int g = 0; g < CG; ++g) acc[g] = (acc[g] + ep[g]) - en[g];
+                }
+            }
+        };
+        auto tap_source = [&](int tap, bool& inb) -> const uint32_t* {
+            const int c = tap % p.kw, r = tap / p.kw;
+            const int b = r % p.kh, a = r / p.kh;
+            const int iz = z * p.sd - p.pd + a * p.dd;
+            const int iy = y * p.sh - p.ph + b * p.dh;
+            const int ix = x * p.sw - p.pw + c * p.dw;
+            inb = iz >= 0 && iz < p.d && iy >= 0 && iy < p.h && ix >= 0 && ix < p.w;
+            return p.in + ((((size_t)n * p.d + (inb ? iz : 0)) * p.h + (inb ? iy : 0)) * p.w + (inb ? ix : 0)) *
+                              2u * p.wd_in;
+        };
+        if (p.wd_in == 2) {
+            // 16-byte records: the loads of up to nine taps are in flight together (one memory
+            // round trip per batch instead of one per tap)
+            constexpr int kBatch = 9;
+            for (int t0 = 0; t0 < T; t0 += kBatch) {
+                uint4 rec[kBatch];
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    rec[k] = make_uint4(0u, 0u, 0u, 0u);          // zero padding: every code is 0
+                    if (t0 + k < T) {
+                        bool inb;
+                        const uint32_t* v = tap_source(t0 + k, inb);
+                        if (inb) rec[k] = *reinterpret_cast<const uint4*>(v);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    if (t0 + k < T) {
+                        const uint32_t mw[2] = {rec[k].x, rec[k].y}, sw[2] = {rec[k].z, rec[k].w};
+                        add_tap(t0 + k, mw, sw, 2);
+                    }
+                }
+            }
+        } else {
+            for (int tap = 0; tap < T; ++tap) {
+                bool inb;
+                const uint32_t* v = tap_source(tap, inb);
+                if (inb) add_tap(tap, v, v + p.wd_in, p.wd_in);
+            }
+        }
+        if (active) {
+#pragma unroll
+            for (int g = 0; g < CG; ++g)
+                if (co0 + g < p.c_out) p.out[((size_t)n * p.c_out + co0 + g) * ospatial + sp] = acc[g];
+        }
+    }
+}
+
 // Per-channel code statistics of a packed tensor (the paper reports how sparse weights and
 // activations become, section 4).  A wave takes 64 voxels at a time; for every channel bit the
 // wave-wide vote of "this voxel's bit is set" is counted, lane j keeping the running nonzero
@@ -372,7 +493,12 @@ int launch_real_conv(const RealConvParams& p, hipStream_t s)
     const int cg = p.c_out <= 2 ? 2 : 4;
     const int c_pad = (p.c_in + 3) / 4 * 4;
     const int64_t lds = (int64_t)p.kd * p.kh * p.kw * c_pad * cg * 4;
-    if (lds <= 48 * 1024) {
+    if (5 * lds <= 64 * 1024) {      // weights + partial-sum tables
+        if (cg == 2)
+            hipLaunchKernelGGL(real_conv_lut_kernel<2>, dim3((unsigned)blocks), dim3(kBlock), (size_t)(5 * lds), s, p, c_pad);
+        else
+            hipLaunchKernelGGL(real_conv_lut_kernel<4>, dim3((unsigned)blocks), dim3(kBlock), (size_t)(5 * lds), s, p, c_pad);
+    } else if (lds <= 48 * 1024) {
         if (cg == 2)
             hipLaunchKernelGGL(real_conv_lds_kernel<2>, dim3((unsigned)blocks), dim3(kBlock), (size_t)lds, s, p, c_pad);
         else
