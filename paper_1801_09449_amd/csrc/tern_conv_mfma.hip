@@ -10,7 +10,8 @@
 //
 // Implicit matrix product: rows = output voxels, columns = output channels, inner index =
 // (kernel tap, input channel).  A wave owns 8 x 8 x 2 output voxels (four row blocks of 32:
-// plane p in {0, 1} x y-half h in {0, 1}, voxel i of a block at x = i % 8, y = 4 h + i / 8) and up
+// plane p in {0, 1} x y-half h in {0, 1}, voxel i of a block at x = i % 8, y = 4 h + i / 8; for a
+// single output plane 8 x 16 x 1, the row blocks being its four y-quarters) and up
 // to 64 output channels (two column blocks), i.e. eight 32 x 32 accumulator tiles; up to four
 // waves stacked along z share a halo tile.  Per (tap, step) a wave reads four row fragments from
 // LDS (one 16-byte read per lane each) and two column fragments from the filter bank (16 bytes
@@ -37,7 +38,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kMaxWaves = 4;         // waves per workgroup (4, 2 or 1), stacked along z
 constexpr int kMaxThreads = 64 * kMaxWaves;
-constexpr int kTX = 8, kTY = 8;      // output voxels per workgroup: 8 x 8 x (2 per wave)
+constexpr int kTX = 8;               // output voxels per wave: 8 x 8 x 2 planes, or 8 x 16 of a single plane
 // LDS tile: the two 16-byte halves of a halo voxel's 32 bytes (the row-fragment halves that lane
 // groups 0 and 1 read) live in two regions, voxel records 16 bytes apart in each, the second
 // region at an offset that is 64 modulo 128: eight lanes with neighbouring voxels read 128
@@ -54,6 +55,7 @@ struct MfmaPlan {
     int32_t ksteps;                  // inner steps per tap: channel words (int8) or word pairs (fp4)
     uint32_t m_hx, m_pl;             // floor(e / hx) = umulhi(e, m_hx), likewise hx * hy
     int32_t half_off;                // LDS byte offset of the second region
+    int32_t flat;                    // 1: single-plane output, a wave's four row blocks are y-quarters of 8 x 16
 };
 
 // The inner index of the matrix product may be laid out in any order that row and column operands
@@ -192,7 +194,9 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
     const int tiy = bid % t.tiles_y; bid /= t.tiles_y;
     const int tiz = bid % t.tiles_z;
     const int n = bid / t.tiles_z;
-    const int ox0 = tix * kTX, oy0 = tiy * kTY, oz0 = tiz * (nthreads >> 5);   // two planes per wave
+    const int flat = t.flat;                     // wave = 8 x 16 x 1 instead of 8 x 8 x 2
+    const int wplanes = flat ? 1 : 2;
+    const int ox0 = tix * kTX, oy0 = tiy * (flat ? 16 : 8), oz0 = tiz * (nthreads >> 6) * wplanes;
     const int nb0 = blockIdx.y * NB;             // first column block of this workgroup
 
     const int gx0 = ox0 * p.sw - p.pw, gy0 = oy0 * p.sh - p.ph, gz0 = oz0 * p.sd - p.pd;
@@ -204,10 +208,11 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
     const int i32 = lane & 31, g = lane >> 5;
     const int xl = i32 & 7, yl = i32 >> 3;
     const int row_b = t.hx * kRec, plane_b = t.hy * row_b;
-    const int lane_off = (wave * 2 * p.sd) * plane_b + (yl * p.sh) * row_b + (xl * p.sw) * kRec + g * t.half_off;
+    const int lane_off = (wave * wplanes * p.sd) * plane_b + (yl * p.sh) * row_b + (xl * p.sw) * kRec + g * t.half_off;
     int mboff[4];
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb) mboff[mb] = ((mb >> 1) * p.sd) * plane_b + ((mb & 1) * 4 * p.sh) * row_b;
+    for (int mb = 0; mb < 4; ++mb)
+        mboff[mb] = flat ? (mb * 4 * p.sh) * row_b : ((mb >> 1) * p.sd) * plane_b + ((mb & 1) * 4 * p.sh) * row_b;
 
     const v4i* bank = reinterpret_cast<const v4i*>(p.wgt);
     const int T = p.kd * p.kh * p.kw;
@@ -380,7 +385,8 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
                     __builtin_amdgcn_sched_barrier(0);   // one tile at a time
                     uint32_t posw = 0u, negw = 0u;      // lane r (< 32): words of the block's voxel r
                     decide_rows<0, Acc, Thr>(acc[mb][nb], lo, hi, posw, negw);
-                    const int ox = ox0 + xl, oy = oy0 + (mb & 1) * 4 + yl, oz = oz0 + wave * 2 + (mb >> 1);
+                    const int ox = ox0 + xl, oy = oy0 + (flat ? mb : (mb & 1)) * 4 + yl;
+                    const int oz = oz0 + wave * wplanes + (flat ? 0 : (mb >> 1));
                     if (g == 0 && ox < p.ow && oy < p.oh && oz < p.od) {
                         uint32_t* o = p.out_packed + ((((size_t)n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
                         o[q] = posw | negw;
@@ -393,11 +399,11 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb) {
                 __builtin_amdgcn_sched_barrier(0);       // one tile at a time
-                const int oz = oz0 + wave * 2 + (mb >> 1);
+                const int oz = oz0 + wave * wplanes + (flat ? 0 : (mb >> 1));
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int r = (v >> 2) * 8 + g * 4 + (v & 3);
-                    const int ox = ox0 + (r & 7), oy = oy0 + (mb & 1) * 4 + (r >> 3);
+                    const int ox = ox0 + (r & 7), oy = oy0 + (flat ? mb : (mb & 1)) * 4 + (r >> 3);
                     if (co < p.c_out && ox < p.ow && oy < p.oh && oz < p.od)
                         p.out_acc[((size_t)n * p.c_out + co) * cstride + ((size_t)oz * p.oh + oy) * p.ow + ox] =
                             (int32_t)acc[mb][nb][v];
@@ -478,7 +484,10 @@ int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
     MfmaPlan t;
     auto halo = [](int out, int stride, int k, int dil) { return (out - 1) * stride + (k - 1) * dil + 1; };
     t.hx = halo(kTX, p.sw, p.kw, p.dw);
-    t.hy = halo(kTY, p.sh, p.kh, p.dh);
+    // single-plane outputs: a wave takes 8 x 16 of the plane instead of 8 x 8 of two planes
+    t.flat = p.od == 1 ? 1 : 0;
+    const int wplanes = t.flat ? 1 : 2;
+    t.hy = halo(t.flat ? 16 : 8, p.sh, p.kh, p.dh);
     // Waves per workgroup (each adds two output planes to the shared halo tile): the count that
     // puts the most waves on a compute unit, LDS permitting (at most two per SIMD fit the
     // registers), the larger tile on a tie.
@@ -487,7 +496,7 @@ int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
     int w_max = kMaxWaves;
     while (w_max > 1 && w_max >= p.od) w_max /= 2;   // no more waves than there are pairs of output planes
     for (int w = w_max; w >= 1; w /= 2) {
-        const int64_t nv = (int64_t)t.hx * t.hy * halo(2 * w, p.sd, p.kd, p.dd);
+        const int64_t nv = (int64_t)t.hx * t.hy * halo(wplanes * w, p.sd, p.kd, p.dd);
         const int64_t bytes = half_offset(nv) + nv * kRec;
         if (bytes > kLds) continue;
         int64_t waves = w * (kLds / bytes);
@@ -495,13 +504,13 @@ int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
         if (waves > best_waves) { best_waves = (int)waves; nw = w; }
     }
     if (nw == 0) return TERN_ESHAPE;
-    const int tz = 2 * nw;
+    const int tz = wplanes * nw;
     t.hz = halo(tz, p.sd, p.kd, p.dd);
     const int64_t nvox = (int64_t)t.hx * t.hy * t.hz;
     t.half_off = (int32_t)half_offset(nvox);
     const int64_t lds = t.half_off + nvox * kRec;
     t.tiles_x = cdiv(p.ow, kTX);
-    t.tiles_y = cdiv(p.oh, kTY);
+    t.tiles_y = cdiv(p.oh, t.flat ? 16 : 8);
     t.tiles_z = cdiv(p.od, tz);
     t.nblk = (p.c_out + 31) / 32;
     t.m_hx = 0xffffffffu / (uint32_t)t.hx + 1u;           // hx >= 8

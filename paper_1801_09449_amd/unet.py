@@ -8,7 +8,7 @@ either way it is done here: small problems fold it into the filters of the modul
 (tern_fold_avgpool: taps repeated over the pooling window, stride multiplied: no extra launch,
 four times the word pairs of the pooled convolution); large ones pool into two balanced-ternary
 digits first (tern_pool_digits, one small launch) and convolve those (twice the word pairs).
-On request (matrix_kind) batches with at least four planes per convolution run their large
+On request (matrix_kind) batches with at least two planes per convolution run their large
 modules on the matrix cores (tern_module.matrix_bank, pooling folded into the filters): same
 results, 16 stacks in 0.47 ms instead of 0.97 ms.  Not the default: the network then no longer
 runs on the paper's bit-count scheme.
@@ -78,7 +78,7 @@ class UNetPlan:
     # A module behind the first runs on the matrix cores when its convolution sees at least this
     # many planes (a wave of that route covers two planes) and at least
     # this many ternary MACs (below it the launch is latency-bound either way).
-    MATRIX_FROM_PLANES = 4
+    MATRIX_FROM_PLANES = 2
     MATRIX_FROM_MACS = 1.0e9
 
     def modules(self, in_shape) -> List[B.NetModule]:

@@ -30,6 +30,9 @@ EXTRA = [
     synth.conv_case("m_c3", 1, 3, 20, (9, 8, 11), seed=403),
     # stack of 2-D planes, batch in front
     synth.conv_case("m_2d", 3, 128, 64, (1, 21, 14), k=(1, 3, 3), pad=0, seed=404),
+    # a single output plane (a wave takes 8 x 16 of it), ragged in both directions; with a stride
+    synth.conv_case("m_plane", 1, 64, 48, (1, 37, 21), k=(1, 3, 3), pad=(0, 1, 1), seed=412),
+    synth.conv_case("m_plane_s2", 1, 96, 32, (3, 30, 19), k=(3, 3, 3), stride=(1, 2, 2), pad=(0, 1, 1), seed=413),
     # halo tiles that only fit with fewer waves per workgroup: stride 2 and dilation 3 in 3-D
     synth.conv_case("m_s2", 1, 64, 64, (9, 12, 10), stride=2, seed=405),
     synth.conv_case("m_d3", 1, 64, 32, (10, 9, 12), pad=3, dil=3, seed=406),
