@@ -34,7 +34,7 @@ class UNetPlan:
         self._digit_mods: Dict[int, B.NetModule] = {}   # pooled modules in their two-digit form
         self._macs: Dict[int, float] = {}          # folded word-pair work per output voxel of such a module
         self._matrix_mods: Dict[int, B.NetModule] = {}  # modules behind the first with a matrix bank
-        self._work: Dict[int, float] = {}          # MACs per output voxel of a module as folded
+        self._module_macs: Dict[int, float] = {}          # MACs per output voxel of a module as folded
         for i, L in enumerate(layers):
             w = np.ascontiguousarray(L["w"], dtype=np.int8)
             stride = tuple(int(v) for v in (L.get("stride") or (1, 1, 1)))
@@ -58,7 +58,7 @@ class UNetPlan:
             kk = tuple(int(v) for v in w.shape[2:])
             self.mods.append(B.NetModule(int(w.shape[0]), bank, lo, hi, k=kk, stride=stride, pad=pad, dil=1,
                                          skip_from=skip, up=up))
-            self._work[i] = float(w.size)
+            self._module_macs[i] = float(w.size)
             if i > 0 and matrix_kind:
                 self._matrix_mods[i] = B.NetModule(int(w.shape[0]), bank, lo, hi, k=kk, stride=stride, pad=pad,
                                                    dil=1, skip_from=skip, up=up,
@@ -93,7 +93,7 @@ class UNetPlan:
                     mods[i] = m
             for i, m in self._matrix_mods.items():
                 n, _, d, h, w = dims[i]
-                if n * d >= self.MATRIX_FROM_PLANES and n * d * h * w * self._work[i] >= self.MATRIX_FROM_MACS:
+                if n * d >= self.MATRIX_FROM_PLANES and n * d * h * w * self._module_macs[i] >= self.MATRIX_FROM_MACS:
                     mods[i] = m
             self._chosen[key] = mods
         return self._chosen[key]
