@@ -144,6 +144,21 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
     ex["cfg2_fcn"]["layer_ms"] = per
     ms_in, _ = timed(lambda: T.tern_threshold_pack(x, ilo, ihi), 30, 5, None)
     ex["cfg2_fcn"]["input_threshold_pack_ms"] = ms_in
+    # the same encoder as a chain of tern_net_forward modules, on bit-counts and with int8 matrix
+    # banks on its two largest layers (2 and 3)
+    row = {}
+    for name, on_matrix in (("bitcount_ms", ()), ("matrix_i8_layers_2_3_ms", (1, 2))):
+        mods = []
+        for i, L in enumerate(f.layers):
+            w = dev(L["w"])
+            mods.append(T.NetModule(L["w"].shape[0], T.tern_pack_filters(w), dev(L["lo"]), dev(L["hi"]), k=L["k"],
+                                    stride=L["stride"], pad=L["pad"], dil=L["dil"],
+                                    matrix_bank=T.tern_expand_filters(w, "i8") if i in on_matrix else None,
+                                    matrix_kind="i8"))
+        ws_n = torch.empty((T.tern_net_workspace_bytes(x.shape, mods),), dtype=torch.uint8, device="cuda")
+        ms_n, _ = timed(lambda: T.tern_net_forward(x, ilo, ihi, mods, workspace=ws_n), 30, 5, None)
+        row[name] = ms_n
+    ex["cfg2_net_forward"] = row
 
     # The paper's baseline U-Net (Table 1) on synthetic weights, whole forward pass, for one
     # stack of slices and for a batch of 16 stacks.  MACs in the paper's convention (a pooled
