@@ -167,6 +167,18 @@ int tern_conv3d_mfma(const uint32_t* in_packed, tern_dims in_dims,
                      const uint32_t* matrix_bank, int32_t kind, int32_t c_out, tern_conv_geom g,
                      const int32_t* thr_lo, const int32_t* thr_hi,
                      int32_t* out_acc, uint32_t* out_packed, void* stream);
+/*
+ * tern_conv3d_mfma_digits -- tern_conv3d_digits (below) on the matrix cores: the convolution of
+ * the window sums that a two-digit tensor of tern_pool_digits holds (values -4 .. 4, all of them
+ * 4-bit float values), same results.  in_dims.c = 64 * words(C) as for tern_conv3d_digits;
+ * matrix_bank is the TERN_MATRIX_F4 bank of the layer's own weights [C_out][C][taps] (not the
+ * doubled ones of tern_digits_weights).  TERN_ESHAPE if 2 * k-volume * in_dims.c >= 2^24 or the
+ * halo tile does not fit.
+ */
+int tern_conv3d_mfma_digits(const uint32_t* in_packed, tern_dims in_dims,
+                            const uint32_t* matrix_bank, int32_t c_out, tern_conv_geom g,
+                            const int32_t* thr_lo, const int32_t* thr_hi,
+                            int32_t* out_acc, uint32_t* out_packed, void* stream);
 
 /*
  * tern_threshold_pack -- the hard ternary activation of Eq. 6 followed by 2-bit packing, on a
@@ -345,7 +357,9 @@ typedef struct {
     const uint32_t* matrix_bank;/* NULL, or the module's bank from tern_expand_filters: the module then
                                    runs through tern_conv3d_mfma (same results); w_bank stays required
                                    and is used when the matrix route refuses the geometry.  Ignored
-                                   for the first module of a one-channel input and for pooled modules. */
+                                   for the first module of a one-channel input.  A pooled module
+                                   takes the TERN_MATRIX_F4 bank of its own (undoubled) weights
+                                   (tern_conv3d_mfma_digits); an int8 bank is ignored there. */
     int32_t matrix_kind;        /* TERN_MATRIX_I8 or TERN_MATRIX_F4 when matrix_bank is given */
 } tern_module;
 size_t tern_net_workspace_bytes(tern_dims in_dims, const tern_module* mods /* host */, int32_t n_mods);

@@ -80,6 +80,7 @@ def lib():
     L.tern_conv3d_digits.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d_digits.restype = C.c_int
     L.tern_conv3d_mfma.argtypes = [P, Dims, P, I, I, Geom, P, P, P, P, P]; L.tern_conv3d_mfma.restype = C.c_int
     L.tern_matrix_bank_bytes.argtypes = [I] * 6; L.tern_matrix_bank_bytes.restype = S
+    L.tern_conv3d_mfma_digits.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d_mfma_digits.restype = C.c_int
     L.tern_expand_filters.argtypes = [P, I, I, I, I, I, I, P, P]; L.tern_expand_filters.restype = C.c_int
     L.tern_pool_digits.argtypes = [P, Dims, C.POINTER(C.c_int32), P, P]; L.tern_pool_digits.restype = C.c_int
     L.tern_digits_weights.argtypes = [P, I, I, C.c_int64, P]; L.tern_digits_weights.restype = C.c_int
@@ -260,10 +261,12 @@ def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out:
     a multiple of 64) and w_bank the bank of tern_digits_weights' output (tern_conv3d_digits).
     mfma="i8" / "f4" (True = "i8"): w_bank is the bank of tern_expand_filters for that kind
     (tern_conv3d_mfma)."""
-    if digits and mfma:
-        raise ValueError("digits and mfma exclude each other")
     kind = "i8" if mfma is True else mfma
-    if mfma:
+    if digits and mfma:
+        if kind != "f4":
+            raise ValueError("two-digit inputs go through the 4-bit kind")
+        entry = lib().tern_conv3d_mfma_digits
+    elif mfma:
         def entry(a, d, b, *rest):
             return lib().tern_conv3d_mfma(a, d, b, MATRIX_KINDS[kind], *rest)
     else:
@@ -276,7 +279,10 @@ def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out:
     in_dims = Dims(n, int(c_in), d, h, w)
     g = _geom(k, stride, pad, dil)
     kk = (g.k[0], g.k[1], g.k[2])
-    need = tern_matrix_bank_bytes(c_out, c_in, kk, kind) if mfma else tern_filter_bank_bytes(c_out, c_in, kk)
+    if digits and mfma:      # the bank of the undoubled weights: half the digit tensor's channels
+        need = tern_matrix_bank_bytes(c_out, c_in // 2, kk, kind)
+    else:
+        need = tern_matrix_bank_bytes(c_out, c_in, kk, kind) if mfma else tern_filter_bank_bytes(c_out, c_in, kk)
     if w_bank.numel() * 4 != need:
         raise ValueError("w_bank size does not match (c_out, c_in, k)")
     o = Dims()

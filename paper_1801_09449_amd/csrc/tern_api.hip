@@ -280,6 +280,25 @@ int tern_conv3d_mfma(const uint32_t* in_packed, tern_dims in_dims, const uint32_
     return launch_conv3d_mfma(p, kind, (hipStream_t)stream);
 }
 
+int tern_conv3d_mfma_digits(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* matrix_bank,
+                            int32_t c_out, tern_conv_geom g, const int32_t* thr_lo, const int32_t* thr_hi,
+                            int32_t* out_acc, uint32_t* out_packed, void* stream)
+{
+    if (!in_packed || !matrix_bank) return TERN_ENULL;
+    if ((out_acc == nullptr) == (out_packed == nullptr)) return TERN_EARG;
+    if (out_packed && (!thr_lo || !thr_hi)) return TERN_ENULL;
+    if (in_dims.c <= 0 || in_dims.c % 64 != 0) return TERN_EARG;   // whole (low, high) word pairs
+    tern_dims o;
+    int rc = geom_check(in_dims, c_out, g, &o);
+    if (rc != TERN_OK) return rc;
+    if (!aligned16(in_packed) || !aligned16(matrix_bank)) return TERN_EARG;
+    if (out_packed && !aligned16(out_packed)) return TERN_EARG;
+    if (out_acc && ((uintptr_t)out_acc & 3u)) return TERN_EARG;
+    ConvParams p = conv_params(in_packed, in_dims, matrix_bank, c_out, g, o, thr_lo, thr_hi, out_acc, out_packed);
+    p.digits = 1;
+    return launch_conv3d_mfma(p, TERN_MATRIX_F4, (hipStream_t)stream);
+}
+
 int tern_conv3d_digits(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_bank,
                        int32_t c_out, tern_conv_geom g, const int32_t* thr_lo, const int32_t* thr_hi,
                        int32_t* out_acc, uint32_t* out_packed, void* stream)
@@ -669,9 +688,15 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
                 fc.wd_out = tern_words(m.c_out);
                 rc = launch_patch_conv_f32(first, fc, in_dims.n, w->stream);
             } else if (pooled) {
-                rc = tern_conv3d_digits((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g,
-                                        m.thr_lo, m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]),
-                                        w->stream);
+                rc = TERN_ESHAPE;
+                if (m.matrix_bank && m.matrix_kind == TERN_MATRIX_F4)   // bank of the undoubled weights
+                    rc = tern_conv3d_mfma_digits((const uint32_t*)(w->ws + cur_off), cur, m.matrix_bank, m.c_out,
+                                                 m.g, m.thr_lo, m.thr_hi, nullptr,
+                                                 (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
+                if (rc == TERN_ESHAPE)
+                    rc = tern_conv3d_digits((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g,
+                                            m.thr_lo, m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]),
+                                            w->stream);
             } else {
                 rc = TERN_ESHAPE;
                 if (m.matrix_bank)

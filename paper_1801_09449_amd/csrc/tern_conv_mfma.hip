@@ -6,7 +6,10 @@
 //   fp4:  four bits per code (E2M1: +1 = 0010, -1 = 1010), a step is a pair of words,
 //         v_mfma_scale_f32_32x32x64_f8f6f4 with both scales 2^0, float sums, exact because every
 //         partial sum is an integer below 2^24 (checked on the host); twice the rate.
-// Same results as the bit-count kernels, bit for bit.
+// Same results as the bit-count kernels, bit for bit.  The fp4 kind also takes the two-digit tensors
+// of tern_pool_digits (window sums -4 .. 4 as low + 3 * high): every such sum is an E2M1 value, so
+// the staging turns a digit pair into the sum's code and the contraction is that of the pooled
+// tensor with the layer's own weights.
 //
 // Implicit matrix product: rows = output voxels, columns = output channels, inner index =
 // (kernel tap, input channel).  A wave owns 8 x 8 x 2 output voxels (four row blocks of 32:
@@ -89,6 +92,25 @@ __device__ __forceinline__ uint4 expand_word_f4(uint32_t m, uint32_t s)
     o[1] = (m & 0x22222222u) | ((neg << 2) & 0x88888888u);
     o[2] = ((m >> 1) & 0x22222222u) | ((neg << 1) & 0x88888888u);
     o[3] = ((m >> 2) & 0x22222222u) | (neg & 0x88888888u);
+    return make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// Two balanced-ternary digits per value (tern_pool_digits: value = low + 3 * high, -4 .. 4), to the
+// E2M1 code of the value (magnitudes 1, 2, 3, 4 = 0010, 0100, 0101, 0110), same field order as
+// expand_word_f4.  Bit planes of the code from the digits' masks and signs: the sign is the high
+// digit's where that is nonzero, else the low digit's; bit 2 says the high digit is nonzero; with
+// it, bit 1 says the low digit has the same sign (3 + 1) and bit 0 that the low digit is zero.
+__device__ __forceinline__ uint4 expand_digits_f4(uint32_t lm, uint32_t ls, uint32_t hm, uint32_t hs)
+{
+    const uint32_t b3 = (hm & hs) | (lm & ls & ~hm);
+    const uint32_t b2 = hm;
+    const uint32_t b1 = lm & ~(hm & (ls ^ hs));
+    const uint32_t b0 = hm & ~lm;
+    uint32_t o[4];
+    o[0] = (b0 & 0x11111111u) | ((b1 << 1) & 0x22222222u) | ((b2 << 2) & 0x44444444u) | ((b3 << 3) & 0x88888888u);
+    o[1] = ((b0 >> 1) & 0x11111111u) | (b1 & 0x22222222u) | ((b2 << 1) & 0x44444444u) | ((b3 << 2) & 0x88888888u);
+    o[2] = ((b0 >> 2) & 0x11111111u) | ((b1 >> 1) & 0x22222222u) | (b2 & 0x44444444u) | ((b3 << 1) & 0x88888888u);
+    o[3] = ((b0 >> 3) & 0x11111111u) | ((b1 >> 2) & 0x22222222u) | ((b2 >> 1) & 0x44444444u) | (b3 & 0x88888888u);
     return make_uint4(o[0], o[1], o[2], o[3]);
 }
 
@@ -176,7 +198,7 @@ __device__ __forceinline__ void decide_rows(const Acc& acc, Thr lo, Thr hi, uint
     }
 }
 
-template <int NB, bool PACKED, bool F4>
+template <int NB, bool PACKED, bool F4, bool DIG = false>
 __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void conv_mfma_kernel(ConvParams p, MfmaPlan t)
 {
     extern __shared__ __align__(16) uint8_t lds8[];
@@ -217,7 +239,10 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
     const v4i* bank = reinterpret_cast<const v4i*>(p.wgt);
     const int T = p.kd * p.kh * p.kw;
 
-    constexpr int KW = F4 ? 2 : 1;               // channel words per inner step
+    static_assert(F4 || !DIG, "two-digit inputs go through the 4-bit kind");
+    // input words per inner step: a channel word (int8), a pair (fp4), or the low and high digit
+    // words of a pair of channel words (two-digit input)
+    constexpr int KW = DIG ? 4 : F4 ? 2 : 1;
     using Acc = typename std::conditional<F4, v16f, v16i>::type;
     Acc acc[4][NB];
 #pragma unroll
@@ -247,11 +272,16 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
             if (inb) {
                 const uint32_t vox = (uint32_t)((gz * p.h + gy) * p.w + gx);   // below 2^31 voxels per item
                 const uint32_t* src = in_n + (size_t)vox * (2u * wd);
-                if (F4 && (wd & 1) == 0) {               // both words of the pair with one load per plane
+                if (DIG && (wd & 3) == 0) {              // the four digit words with one load per plane
+                    const uint4 mm = *reinterpret_cast<const uint4*>(src + ks * 4);
+                    const uint4 ss = *reinterpret_cast<const uint4*>(src + wd + ks * 4);
+                    m[k][0] = mm.x; m[k][1 % KW] = mm.y; m[k][2 % KW] = mm.z; m[k][3 % KW] = mm.w;
+                    s[k][0] = ss.x; s[k][1 % KW] = ss.y; s[k][2 % KW] = ss.z; s[k][3 % KW] = ss.w;
+                } else if (F4 && !DIG && (wd & 1) == 0) {   // both words of the pair with one load per plane
                     const uint2 mm = *reinterpret_cast<const uint2*>(src + ks * 2);
                     const uint2 ss = *reinterpret_cast<const uint2*>(src + wd + ks * 2);
-                    m[k][0] = mm.x; m[k][KW - 1] = mm.y;
-                    s[k][0] = ss.x; s[k][KW - 1] = ss.y;
+                    m[k][0] = mm.x; m[k][1 % KW] = mm.y;
+                    s[k][0] = ss.x; s[k][1 % KW] = ss.y;
                 } else {
 #pragma unroll
                     for (int q = 0; q < KW; ++q) {
@@ -272,9 +302,12 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
             if (e < nvox) {
                 uint4* dst0 = reinterpret_cast<uint4*>(lds8 + (size_t)e * kRec);
                 uint4* dst1 = reinterpret_cast<uint4*>(lds8 + t.half_off + (size_t)e * kRec);
-                if constexpr (F4) {
+                if constexpr (DIG) {          // words (low, high) of channel word 2 ks, then of 2 ks + 1
+                    *dst0 = expand_digits_f4(m[k][0], s[k][0], m[k][1 % KW], s[k][1 % KW]);
+                    *dst1 = expand_digits_f4(m[k][2 % KW], s[k][2 % KW], m[k][3 % KW], s[k][3 % KW]);
+                } else if constexpr (F4) {
                     *dst0 = expand_word_f4(m[k][0], s[k][0]);
-                    *dst1 = expand_word_f4(m[k][1], s[k][1]);
+                    *dst1 = expand_word_f4(m[k][1 % KW], s[k][1 % KW]);
                 } else {
                     uint4 a, b;
                     expand_word(m[k][0], s[k][0], a, b);
@@ -415,11 +448,11 @@ __global__ __launch_bounds__(kMaxThreads) __attribute__((amdgpu_waves_per_eu(2, 
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-template <int NB, bool PACKED, bool F4>
+template <int NB, bool PACKED, bool F4, bool DIG = false>
 int launch_variant(const ConvParams& p, const MfmaPlan& t, size_t lds_bytes, dim3 grid, int threads,
                    hipStream_t s)
 {
-    auto kern = conv_mfma_kernel<NB, PACKED, F4>;
+    auto kern = conv_mfma_kernel<NB, PACKED, F4, DIG>;
     if (lds_bytes > 64 * 1024) {
         static thread_local int raised_on_device = -1;
         int dev = 0;
@@ -468,10 +501,15 @@ int launch_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t 
 // p.wgt is the filter bank of that kind.  TERN_ESHAPE when the halo tile of even one wave's
 // 8 x 8 x 2 output block does not fit in LDS (very large strides or dilations), and for the 4-bit
 // kind when a sum could leave the integers a float holds exactly (k-volume * C_in >= 2^24).
+// p.digits: the input is a two-digit tensor (tern_pool_digits) and the bank that of the undoubled
+// weights, 4-bit kind.
 int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
 {
     ConvParams p = p_in;
     if (kind == 1 && (int64_t)p.kd * p.kh * p.kw * p.c_in >= (1 << 24)) return TERN_ESHAPE;
+    // two-digit input (p.digits): 4-bit kind only; p.c_in counts digit channels (two per value, each
+    // value up to 4 in magnitude), so a sum stays below 2 * k-volume * c_in
+    if (p.digits && (kind != 1 || 2 * (int64_t)p.kd * p.kh * p.kw * p.c_in >= (1 << 24))) return TERN_ESHAPE;
     // A kernel of depth extent 1 with unit depth stride and no depth padding treats every input
     // plane by itself: batch items are just more planes, [N][D] collapses to [1][N*D], and a
     // workgroup's eight planes may come from different batch items (stacks of 2-D slices have
@@ -517,7 +555,7 @@ int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
     t.m_pl = 0xffffffffu / (uint32_t)(t.hx * t.hy) + 1u;
     const int64_t tiles = (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n;
     if (tiles > 0x7fffffff) return TERN_ESHAPE;
-    t.ksteps = steps_of(p.c_in, kind);
+    t.ksteps = p.digits ? (p.wd_in + 3) / 4 : steps_of(p.c_in, kind);
     const bool packed = p.out_packed != nullptr;
     // column blocks in pairs; an odd last block would be paired with a block the bank does not
     // hold, so odd counts run one block per workgroup
@@ -528,6 +566,13 @@ int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
 #define TERN_MFMA_LAUNCH(NB_, F4_)                                                    \
     (packed ? launch_variant<NB_, true, F4_>(p, t, lb, grid, threads, s)               \
             : launch_variant<NB_, false, F4_>(p, t, lb, grid, threads, s))
+    if (p.digits) {
+        if (nb == 2)
+            return packed ? launch_variant<2, true, true, true>(p, t, lb, grid, threads, s)
+                          : launch_variant<2, false, true, true>(p, t, lb, grid, threads, s);
+        return packed ? launch_variant<1, true, true, true>(p, t, lb, grid, threads, s)
+                      : launch_variant<1, false, true, true>(p, t, lb, grid, threads, s);
+    }
     if (kind == 1) return nb == 2 ? TERN_MFMA_LAUNCH(2, true) : TERN_MFMA_LAUNCH(1, true);
     return nb == 2 ? TERN_MFMA_LAUNCH(2, false) : TERN_MFMA_LAUNCH(1, false);
 #undef TERN_MFMA_LAUNCH

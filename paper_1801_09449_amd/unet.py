@@ -9,8 +9,9 @@ either way it is done here: small problems fold it into the filters of the modul
 four times the word pairs of the pooled convolution); large ones pool into two balanced-ternary
 digits first (tern_pool_digits, one small launch) and convolve those (twice the word pairs).
 On request (matrix_kind) batches with at least two planes per convolution run their large
-modules on the matrix cores (tern_module.matrix_bank, pooling folded into the filters): same
-results, 16 stacks in 0.47 ms instead of 0.97 ms.  Not the default: the network then no longer
+modules on the matrix cores (tern_module.matrix_bank; pooled modules through two digits turned
+into 4-bit float codes of the window sums for the 4-bit kind, folded filters for int8): same
+results, 16 stacks in well under half the time.  Not the default: the network then no longer
 runs on the paper's bit-count scheme.
 """
 from typing import Dict, List, Sequence
@@ -43,11 +44,17 @@ class UNetPlan:
             up = tuple(L.get("up") or (1, 1, 1))
             lo, hi = dev(np.asarray(L["lo"], np.int32)), dev(np.asarray(L["hi"], np.int32))
             pool = tuple(int(v) for v in L["pool"]) if L.get("pool") else None
+            digits_matrix = None        # pooled module on the matrix cores: two digits -> 4-bit floats
             if pool and int(np.prod(pool)) <= 4 and max(pool) <= 4:
-                self._digit_mods[i] = B.NetModule(int(w.shape[0]), B.tern_pack_filters(dev(B.tern_digits_weights(w))),
-                                                  lo, hi, k=tuple(int(v) for v in w.shape[2:]), stride=stride,
+                dbank = B.tern_pack_filters(dev(B.tern_digits_weights(w)))
+                k0 = tuple(int(v) for v in w.shape[2:])
+                self._digit_mods[i] = B.NetModule(int(w.shape[0]), dbank, lo, hi, k=k0, stride=stride,
                                                   pad=pad, dil=1, skip_from=skip, up=up, pool=pool)
                 self._macs[i] = float(w.size) * float(np.prod(pool))
+                if i > 0 and matrix_kind == "f4":
+                    digits_matrix = B.NetModule(int(w.shape[0]), dbank, lo, hi, k=k0, stride=stride, pad=pad, dil=1,
+                                                skip_from=skip, up=up, pool=pool,
+                                                matrix_bank=B.tern_expand_filters(dev(w), "f4"), matrix_kind="f4")
             if pool:
                 # pooling window P before a convolution of stride s and padding p: filters with
                 # every tap repeated P times, stride s*P, padding p*P
@@ -59,7 +66,9 @@ class UNetPlan:
             self.mods.append(B.NetModule(int(w.shape[0]), bank, lo, hi, k=kk, stride=stride, pad=pad, dil=1,
                                          skip_from=skip, up=up))
             self._module_macs[i] = float(w.size)
-            if i > 0 and matrix_kind:
+            if digits_matrix is not None:
+                self._matrix_mods[i] = digits_matrix
+            elif i > 0 and matrix_kind:
                 self._matrix_mods[i] = B.NetModule(int(w.shape[0]), bank, lo, hi, k=kk, stride=stride, pad=pad,
                                                    dil=1, skip_from=skip, up=up,
                                                    matrix_bank=B.tern_expand_filters(dev(w), matrix_kind),

@@ -86,6 +86,9 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     assert L.tern_conv3d_mfma(fake, d, fake, 1, 8, g, None, None, fake, fake, None) == -3     # both outputs
     assert L.tern_conv3d_mfma(fake, d, fake, 0, 8, g, None, None, None, fake, None) == -1     # no cut points
     assert L.tern_conv3d_mfma(fake, Dims(1, 32, 4, 4, 0), fake, 0, 8, g, None, None, fake, None, None) == -2
+    assert L.tern_conv3d_mfma_digits(None, Dims(1, 64, 4, 4, 4), fake, 8, g, None, None, fake, None, None) == -1
+    assert L.tern_conv3d_mfma_digits(fake, d, fake, 8, g, None, None, fake, None, None) == -3     # 32 channels: no digit pairs
+    assert L.tern_conv3d_mfma_digits(fake, Dims(1, 64, 4, 4, 4), fake, 8, g, None, None, fake, fake, None) == -3
     # conv: both or neither output, missing cut points, bad geometry
     assert L.tern_conv3d(fake, d, fake, 8, g, None, None, None, None, None) == -3
     assert L.tern_conv3d(fake, d, fake, 8, g, fake, fake, fake, fake, None) == -3

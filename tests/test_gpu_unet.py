@@ -264,6 +264,14 @@ def test_conv_on_pooled_digits_equals_conv_on_window_sums(G, ci, co, vol, k, win
             np.testing.assert_array_equal(G.words(packed), want_packed)
     finally:
         T.tern_set_option(3, 0)
+    # the same through the matrix cores: the two digits of a value become its 4-bit float code,
+    # the bank is that of the undoubled weights
+    mbank = T.tern_expand_filters(G.dev(w), "f4")
+    acc = T.tern_conv3d(dig, c2, mbank, co, k=k, stride=1, pad=0, dil=1, digits=True, mfma="f4")
+    packed = T.tern_conv3d(dig, c2, mbank, co, k=k, stride=1, pad=0, dil=1, thr_lo=G.dev(lo), thr_hi=G.dev(hi),
+                           digits=True, mfma="f4")
+    np.testing.assert_array_equal(acc.cpu().numpy(), want_acc)
+    np.testing.assert_array_equal(G.words(packed), want_packed)
 
 
 # ---- the whole network -----------------------------------------------------------------------------
