@@ -5,7 +5,9 @@ counts that leave partial words and odd numbers of 32-filter blocks, batches, 2-
 import numpy as np
 import pytest
 
+import oracle
 import synth
+from oracle import ConvGeom
 from tests.test_gpu_parity import G, SMALL, check_case, check_sampled, expect, random_case  # noqa: F401
 
 pytestmark = pytest.mark.gpu
@@ -59,6 +61,43 @@ def test_random_geometries(G, i, kind):
         check_case(G, random_case(i), mfma=kind)
     except T.TernError as e:
         assert e.status == -2
+
+
+WINDOWS = [(1, 2, 2), (2, 1, 2), (2, 2, 1), (1, 1, 2), (1, 3, 1), (4, 1, 1), (1, 1, 1)]
+
+
+def test_random_geometries_on_pooled_digits(G):
+    """Sum pooling in front of 24 random geometries (stride, padding, dilation): the window sums as
+    two digits, through the bit-count kernel and through the 4-bit matrix route, against the
+    oracle's convolution of the sums.  Either route may refuse a halo too large for LDS with
+    TERN_ESHAPE (two-digit inputs have no direct fallback kernel); most cases must run."""
+    import paper_1801_09449_amd as T
+    ran = {False: 0, "f4": 0}
+    for i in range(24):
+        c = random_case(i)
+        win = WINDOWS[i % len(WINDOWS)]
+        n, ci = c.act.shape[:2]
+        co = c.wgt.shape[0]
+        vol = tuple(int(v) * f for v, f in zip(c.act.shape[2:], win))
+        x = synth.ternary((n, ci) + vol, 0.35, 8100 + i, synth.T_ACT)
+        pooled = np.ascontiguousarray(oracle.pool_sum(x, win))
+        want_acc = oracle.conv3d(pooled, c.wgt, ConvGeom(c.k, c.stride, c.pad, c.dil))
+        want_packed = oracle.pack(oracle.threshold(want_acc, c.lo, c.hi))
+        dig, c2 = T.tern_pool_digits(T.tern_pack(G.dev(x)), ci, win)
+        kw = dict(k=c.k, stride=c.stride, pad=c.pad, dil=c.dil, digits=True)
+        bank = T.tern_pack_filters(G.dev(T.tern_digits_weights(c.wgt)))
+        mbank = T.tern_expand_filters(G.dev(c.wgt), "f4")
+        for b, route in ((bank, False), (mbank, "f4")):
+            try:
+                acc = T.tern_conv3d(dig, c2, b, co, mfma=route, **kw)
+                packed = T.tern_conv3d(dig, c2, b, co, thr_lo=G.dev(c.lo), thr_hi=G.dev(c.hi), mfma=route, **kw)
+            except T.TernError as e:
+                assert e.status == -2, (i, route)
+                continue
+            np.testing.assert_array_equal(acc.cpu().numpy(), want_acc, err_msg=f"case {i} route {route}")
+            np.testing.assert_array_equal(G.words(packed), want_packed, err_msg=f"case {i} route {route}")
+            ran[route] += 1
+    assert ran[False] >= 20 and ran["f4"] >= 18, ran
 
 
 def test_matrix_bank_layouts(G):
