@@ -277,9 +277,7 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
  * bank is tern_pack_filters applied to the weights that tern_digits_weights (host arrays,
  * launches nothing) makes from w [c_out][c_in][taps]: w_out [c_out][64 * words(c_in)][taps] with
  * channel 64k + j and 64k + 32 + j both equal to channel 32k + j of w (zero past c_in).
- * Limits as for tern_conv3d with k-volume * in_dims.c < 2^23.  TERN_ESHAPE also when the halo
- * tile of a very large dilated kernel does not fit in LDS (the fallback kernel of tern_conv3d
- * has no two-digit form).
+ * Limits as for tern_conv3d with k-volume * in_dims.c < 2^23.
  *
  * tern_fold_avgpool (host arrays, launches nothing) -- average pooling between two ternary
  * modules, done exactly: pooling with window = stride = pool followed by a convolution with

@@ -13,6 +13,7 @@ __device__ __forceinline__ int32_t dot_at(const ConvParams& p, int n, int co, in
     const int Wd = p.wd_in;
     const int wc = p.wc, nchunk = Wd / wc;
     int32_t acc_m = 0, acc_n = 0;
+    int32_t high_m = 0, high_n = 0;   // odd words of a two-digit input: they count three times
     for (int a = 0; a < p.kd; ++a) {
         const int iz = z * p.sd - p.pd + a * p.dd;
         if (iz < 0 || iz >= p.d) continue;
@@ -43,13 +44,18 @@ __device__ __forceinline__ int32_t dot_at(const ConvParams& p, int n, int co, in
                         p.wgt + ((size_t)(tap * nchunk + q / wc) * p.co_pad + co) * 2u * wc + q % wc;
                     const uint32_t M = av[q] & wv[0];
                     const uint32_t N = M & (av[Wd + q] ^ wv[wc]);
-                    acc_m += __builtin_popcount(M);
-                    acc_n += __builtin_popcount(N);
+                    if (p.digits && (q & 1)) {
+                        high_m += __builtin_popcount(M);
+                        high_n += __builtin_popcount(N);
+                    } else {
+                        acc_m += __builtin_popcount(M);
+                        acc_n += __builtin_popcount(N);
+                    }
                 }
             }
         }
     }
-    return acc_m - 2 * acc_n;
+    return (acc_m - 2 * acc_n) + 3 * (high_m - 2 * high_n);
 }
 
 __global__ __launch_bounds__(256) void conv_generic_acc(ConvParams p, int64_t total)

@@ -781,7 +781,6 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     int64_t lds_bytes = 0;
     if (!plan_tiles(p, V, lds_limit, t, lds_bytes, lxb, lyb)) {
         if (V == 4 && plan_tiles(p, 2, lds_limit, t, lds_bytes, lxb, lyb)) V = 2;
-        else if (p.digits) return TERN_ESHAPE;   // the fallback kernel knows one-digit inputs only
         else return launch_conv3d_generic(p, s);
     }
     const int64_t spatial_tiles = (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n;

@@ -69,8 +69,8 @@ WINDOWS = [(1, 2, 2), (2, 1, 2), (2, 2, 1), (1, 1, 2), (1, 3, 1), (4, 1, 1), (1,
 def test_random_geometries_on_pooled_digits(G):
     """Sum pooling in front of 24 random geometries (stride, padding, dilation): the window sums as
     two digits, through the bit-count kernel and through the 4-bit matrix route, against the
-    oracle's convolution of the sums.  Either route may refuse a halo too large for LDS with
-    TERN_ESHAPE (two-digit inputs have no direct fallback kernel); most cases must run."""
+    oracle's convolution of the sums.  The matrix route may refuse a halo too large for LDS with
+    TERN_ESHAPE (the bit-count route then takes its direct kernel); most cases must run on it."""
     import paper_1801_09449_amd as T
     ran = {False: 0, "f4": 0}
     for i in range(24):
@@ -92,12 +92,12 @@ def test_random_geometries_on_pooled_digits(G):
                 acc = T.tern_conv3d(dig, c2, b, co, mfma=route, **kw)
                 packed = T.tern_conv3d(dig, c2, b, co, thr_lo=G.dev(c.lo), thr_hi=G.dev(c.hi), mfma=route, **kw)
             except T.TernError as e:
-                assert e.status == -2, (i, route)
+                assert route and e.status == -2, (i, route)
                 continue
             np.testing.assert_array_equal(acc.cpu().numpy(), want_acc, err_msg=f"case {i} route {route}")
             np.testing.assert_array_equal(G.words(packed), want_packed, err_msg=f"case {i} route {route}")
             ran[route] += 1
-    assert ran[False] >= 20 and ran["f4"] >= 18, ran
+    assert ran[False] == 24 and ran["f4"] >= 18, ran
 
 
 def test_matrix_bank_layouts(G):
