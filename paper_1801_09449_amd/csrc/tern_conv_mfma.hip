@@ -528,18 +528,21 @@ int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
     t.hy = halo(t.flat ? 16 : 8, p.sh, p.kh, p.dh);
     // Waves per workgroup (each adds two output planes to the shared halo tile): the count that
     // puts the most waves on a compute unit, LDS permitting (at most two per SIMD fit the
-    // registers), the larger tile on a tie.
+    // registers).  On a tie the larger tile where neighbouring waves read common input planes,
+    // else the smaller: waves that share nothing gain nothing from one workgroup and only wait
+    // for each other at its barriers.
     const int64_t kLds = 160 * 1024;
     int nw = 0, best_waves = 0;
     int w_max = kMaxWaves;
     while (w_max > 1 && w_max >= p.od) w_max /= 2;   // no more waves than there are pairs of output planes
+    const bool shares_z = (p.kd - 1) * p.dd + 1 > p.sd;   // neighbouring waves' input planes overlap
     for (int w = w_max; w >= 1; w /= 2) {
         const int64_t nv = (int64_t)t.hx * t.hy * halo(wplanes * w, p.sd, p.kd, p.dd);
         const int64_t bytes = half_offset(nv) + nv * kRec;
         if (bytes > kLds) continue;
         int64_t waves = w * (kLds / bytes);
         if (waves > 8) waves = 8;
-        if (waves > best_waves) { best_waves = (int)waves; nw = w; }
+        if (waves > best_waves || (waves == best_waves && !shares_z)) { best_waves = (int)waves; nw = w; }
     }
     if (nw == 0) return TERN_ESHAPE;
     const int tz = wplanes * nw;
