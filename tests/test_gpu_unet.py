@@ -274,6 +274,32 @@ def test_conv_on_pooled_digits_equals_conv_on_window_sums(G, ci, co, vol, k, win
     np.testing.assert_array_equal(G.words(packed), want_packed)
 
 
+def test_two_digit_input_through_the_direct_kernel(G):
+    """A dilation whose halo tile no LDS holds: tern_conv3d_digits runs on the direct kernel (odd
+    words count three times) and must still equal the convolution of the window sums; the matrix
+    route refuses such a halo."""
+    import paper_1801_09449_amd as T
+    ci, co, win, k = 40, 33, (1, 2, 2), (2, 3, 3)
+    x = synth.ternary((1, ci, 110, 18, 18), 0.35, 611, synth.T_ACT)
+    w = synth.ternary((co, ci) + k, 0.5, 612, synth.T_WGT)
+    lo, hi = synth.bn_like_thresholds(co, 18 * 4, ci, 0.5, 0.65, ci, synth.T_THR)
+    pooled = np.ascontiguousarray(oracle.pool_sum(x, win))
+    geom = ConvGeom(k, (1, 1, 1), (0, 1, 1), (100, 1, 1))
+    want_acc = oracle.conv3d(pooled, w, geom)
+    assert want_acc.shape == (1, co, 10, 9, 9)
+    want_packed = oracle.pack(oracle.threshold(want_acc, lo, hi))
+    dig, c2 = T.tern_pool_digits(T.tern_pack(G.dev(x)), ci, win)
+    bank = T.tern_pack_filters(G.dev(T.tern_digits_weights(w)))
+    kw = dict(k=k, stride=1, pad=(0, 1, 1), dil=(100, 1, 1), digits=True)
+    acc = T.tern_conv3d(dig, c2, bank, co, **kw)
+    packed = T.tern_conv3d(dig, c2, bank, co, thr_lo=G.dev(lo), thr_hi=G.dev(hi), **kw)
+    np.testing.assert_array_equal(acc.cpu().numpy(), want_acc)
+    np.testing.assert_array_equal(G.words(packed), want_packed)
+    with pytest.raises(T.TernError) as e:
+        T.tern_conv3d(dig, c2, T.tern_expand_filters(G.dev(w), "f4"), co, mfma="f4", **kw)
+    assert e.value.status == -2
+
+
 # ---- the whole network -----------------------------------------------------------------------------
 def run_unet(G, u, matrix_kind=None):
     import torch
