@@ -1,12 +1,16 @@
 """Compile the gfx950 library (csrc/*.hip -> paper_1801_09449_amd/libtern.so) with hipcc.
 
 hipcc cross-compiles without a GPU present.  The library is built in-tree so that it travels with
-the source tree; it is not installed anywhere.
+the source tree; it is not installed anywhere.  Every call recompiles every source (one hipcc
+process per file, side by side) and links the objects.
 """
 import glob
 import os
+import shutil
 import subprocess
 import sys
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -14,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtern.so")
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
@@ -25,25 +29,39 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    """Always recompiles (a few tens of seconds)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + FLAGS + ["-o", tmp] + sources()
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass warns that it does not know the packed-fp32 target feature: harmless
     out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
-        if os.path.exists(tmp):
-            os.remove(tmp)
-        raise RuntimeError("hipcc failed:\n" + out)
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + out)
     if verbose and out.strip():
-        print(out)
-    os.replace(tmp, LIB)
+        print(out, flush=True)
+
+
+def build(verbose: bool = False, jobs: int = 0) -> str:
+    """Always recompiles (under a minute with a few cores)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    tmpdir = tempfile.mkdtemp(prefix="tern_build_")
+    try:
+        objs = [os.path.join(tmpdir, os.path.basename(s)[:-4] + ".o") for s in sources()]
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            list(pool.map(lambda so: _run([hipcc] + FLAGS + ["-c", so[0], "-o", so[1]], verbose),
+                          zip(sources(), objs)))
+        tmp = LIB + ".tmp.%d" % os.getpid()
+        try:
+            _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs, verbose)
+            os.replace(tmp, LIB)
+        finally:
+            if os.path.exists(tmp):
+                os.remove(tmp)
+    finally:
+        shutil.rmtree(tmpdir, ignore_errors=True)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose="-q" not in sys.argv))
