@@ -11,7 +11,8 @@
  * General rules
  *   - Every data pointer is a DEVICE pointer owned by the caller unless a comment says "host".
  *     The library never allocates, frees or retains caller memory and keeps no state between
- *     calls except the last HIP error code (tern_last_hip_error).
+ *     calls except the last HIP error code (tern_last_hip_error) and the per-thread
+ *     tuning overrides of tern_tuning.h.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
  *     on that stream and return without synchronising.
  *   - Return value: TERN_OK (0) or a negative tern_status.  No call throws or aborts.  Arguments
@@ -30,7 +31,7 @@
  *   flag; the convolution result does not depend on the choice.)
  *   Packed buffers must be 16-byte aligned (any hipMalloc / torch allocation is).
  *
- * Filter banks (the ternary weights of one layer, "2 bits per weight", section 2) hold the same
+ * Filter banks (the ternary weights of one layer at two bits each, section 2) hold the same
  * two bit-planes but ordered for the convolution kernels, which fetch filter words through the
  * scalar cache one kernel tap at a time:
  *     uint32 [T * nchunk][co_pad][2][wc]
@@ -100,8 +101,8 @@ const char* tern_status_string(int status);
 int tern_pack(const int8_t* src, tern_dims dims, uint32_t* dst_packed, void* stream);
 
 /*
- * tern_pack_filters -- 2-bit encoding of a layer's ternary weights (section 2: "a trained model
- * can be stored using only 2 bits per weight") in the filter-bank layout described above.
+ * tern_pack_filters -- 2-bit encoding of a layer's ternary weights (section 2, last paragraph:
+ * two bits are all a trained weight needs) in the filter-bank layout described above.
  *   w    : int8 values in {-1, 0, +1}, contiguous [C_out][C_in][kd][kh][kw] (other values are
  *          treated as in tern_pack).
  *   bank : tern_filter_bank_bytes(...) bytes, 16-byte aligned.
@@ -136,49 +137,6 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims,
                 const uint32_t* w_bank, int32_t c_out, tern_conv_geom g,
                 const int32_t* thr_lo, const int32_t* thr_hi,
                 int32_t* out_acc, uint32_t* out_packed, void* stream);
-
-/*
- * tern_conv3d_mfma -- the same convolution, same arguments, same results bit for bit, with the
- * inner products of section 2 (the sums that Eq. 9 evaluates by two bit-counts) taken by the
- * matrix instructions instead: activations stay packed in memory, a workgroup expands its halo
- * tile in LDS and multiplies it with an expanded filter bank.  Not the paper's scheme (which
- * exists because CPUs count bits faster than they multiply); provided because on this device the
- * matrix cores multiply faster than the vector units count.
- *   kind        : TERN_MATRIX_I8 -- one byte per code (0x01 / 0xff / 0x00), int8 products, int32
- *                 sums; TERN_MATRIX_F4 -- four bits per code (the E2M1 values +1, -1, 0), float
- *                 sums, exact because every partial sum is an integer below 2^24 (TERN_ESHAPE if
- *                 k-volume * C_in >= 2^24); twice the rate of the former.
- *   matrix_bank : tern_matrix_bank_bytes(...) bytes, 16-byte aligned, made once per layer by
- *                 tern_expand_filters from the same int8 weights [C_out][C_in][kd][kh][kw] that
- *                 tern_pack_filters takes.  Layout [tap][step][block of 32 filters][half g]
- *                 [filter j][4 dwords q]; I8: step = word of 32 input channels, byte b of dword q
- *                 = channel 32 step + (4 g + q) + 8 b; F4: step = pair of words, 4-bit field i of
- *                 dword q = channel 32 (2 step + g) + 4 i + q (the order in which the kernel's
- *                 expansion of an activation word leaves the channels).  Zero past C_out and C_in.
- * Returns TERN_ESHAPE when the halo of an 8 x 8 x 2 block of outputs does not fit in LDS (very
- * large strides or dilations); tern_conv3d has no such limit.
- */
-typedef enum { TERN_MATRIX_I8 = 0, TERN_MATRIX_F4 = 1 } tern_matrix_kind;
-size_t tern_matrix_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw,
-                              int32_t kind);
-int tern_expand_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
-                        int32_t kw, int32_t kind, uint32_t* matrix_bank, void* stream);
-int tern_conv3d_mfma(const uint32_t* in_packed, tern_dims in_dims,
-                     const uint32_t* matrix_bank, int32_t kind, int32_t c_out, tern_conv_geom g,
-                     const int32_t* thr_lo, const int32_t* thr_hi,
-                     int32_t* out_acc, uint32_t* out_packed, void* stream);
-/*
- * tern_conv3d_mfma_digits -- tern_conv3d_digits (below) on the matrix cores: the convolution of
- * the window sums that a two-digit tensor of tern_pool_digits holds (values -4 .. 4, all of them
- * 4-bit float values), same results.  in_dims.c = 64 * words(C) as for tern_conv3d_digits;
- * matrix_bank is the TERN_MATRIX_F4 bank of the layer's own weights [C_out][C][taps] (not the
- * doubled ones of tern_digits_weights).  TERN_ESHAPE if 2 * k-volume * in_dims.c >= 2^24 or the
- * halo tile does not fit.
- */
-int tern_conv3d_mfma_digits(const uint32_t* in_packed, tern_dims in_dims,
-                            const uint32_t* matrix_bank, int32_t c_out, tern_conv_geom g,
-                            const int32_t* thr_lo, const int32_t* thr_hi,
-                            int32_t* out_acc, uint32_t* out_packed, void* stream);
 
 /*
  * tern_threshold_pack -- the hard ternary activation of Eq. 6 followed by 2-bit packing, on a
@@ -352,13 +310,6 @@ typedef struct {
     int32_t skip_from;
     int32_t up[3];
     int32_t pool[3];            /* {1,1,1} or all 0: none; else sum pooling through two digits */
-    const uint32_t* matrix_bank;/* NULL, or the module's bank from tern_expand_filters: the module then
-                                   runs through tern_conv3d_mfma (same results); w_bank stays required
-                                   and is used when the matrix route refuses the geometry.  Ignored
-                                   for the first module of a one-channel input.  A pooled module
-                                   takes the TERN_MATRIX_F4 bank of its own (undoubled) weights
-                                   (tern_conv3d_mfma_digits); an int8 bank is ignored there. */
-    int32_t matrix_kind;        /* TERN_MATRIX_I8 or TERN_MATRIX_F4 when matrix_bank is given */
 } tern_module;
 size_t tern_net_workspace_bytes(tern_dims in_dims, const tern_module* mods /* host */, int32_t n_mods);
 int tern_net_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
@@ -423,42 +374,6 @@ int tern_fold_thresholds(const double* scale /* host */, const double* shift /* 
 int tern_fold_batchnorm(const double* alpha, const double* gamma, const double* beta,
                         const double* mean, const double* var, double eps, int32_t c,
                         int32_t acc_bound, int32_t* lo, int32_t* hi, uint8_t* negate);
-
-/* Tuning overrides (process-wide, not thread-safe against concurrent launches; defaults are
- * chosen per call from the problem size).  TERN_OPT_LANE_DEPTH: output voxels per lane along z in
- * the tiled convolution kernel, 0 = choose automatically, 1, 2 or 4 = force (1 and 4 only
- * where that variant exists).  TERN_OPT_WAVES_Z: waves
- * stacked along z in one workgroup (sharing one LDS halo tile), 0 = choose, 1, 2, 4 or 8 = start
- * from that value.  TERN_OPT_CO_BLOCK: output channels per accumulation pass, 0 = choose, 16 or 32.
- * TERN_OPT_CO_PER_WAVE: output channels handled by one wave, 0 = choose, else a multiple of 16.
- * TERN_OPT_TAP_SPLIT: waves of one workgroup that share the kernel taps of one channel slice and
- * add their partial sums in LDS, 0 = choose, 1, 2, 4 or 8.  TERN_OPT_POINTWISE: 1 (default) = 1x1x1
- * convolutions with unit stride and no padding use the pointwise kernel when the input has 1, 2,
- * 3, 4, 5 or 8 words per plane, 0 = they go through the tiled kernel like any other.
- * TERN_OPT_LANE_TILE: the block of 64 output voxels that one wave of the tiled kernel computes,
- * 0 = choose (8 x 8 in a plane, or a smaller footprint over several planes where that wastes fewer
- * lanes on the edges of a stack of independent planes), -1 = always 8 x 8, 100 * X + Y with X, Y in
- * {1, 2, 4, 8} and X * Y >= 4 = X x Y voxels in 64 / (X * Y) planes wherever the output has more
- * than one plane.
- * Results never depend on options.  Returns TERN_EARG for an unknown option or
- * value. */
-typedef enum { TERN_OPT_LANE_DEPTH = 1, TERN_OPT_WAVES_Z = 2, TERN_OPT_CO_BLOCK = 3,
-               TERN_OPT_CO_PER_WAVE = 4, TERN_OPT_TAP_SPLIT = 5, TERN_OPT_POINTWISE = 6,
-               TERN_OPT_LANE_TILE = 7 } tern_option;
-int tern_set_option(int option, int value);
-
-/*
- * tern_probe_valu -- diagnostic, no counterpart in the paper: runs `iters` rounds of the
- * convolution's instruction mix (16 word pairs = 64 integer vector instructions plus one add per
- * round and lane) on blocks x threads lanes with no memory traffic.  Timing it gives the sustained
- * lane-operation rate of the device, the measured ceiling for section 2's bit-count argument on
- * this hardware.  variant: 0 = the instruction order and spacing the convolution kernels use, 1 =
- * the same instructions with no scalar instruction between them (for comparison).  sink: device
- * int32[1] (practically never written).  threads: multiple of 64, at most 512.  TERN_EARG for
- * anything else.
- */
-int tern_probe_valu(int32_t blocks, int32_t threads, int32_t iters, int32_t variant, int32_t* sink,
-                    void* stream);
 
 #ifdef __cplusplus
 }

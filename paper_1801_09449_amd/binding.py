@@ -49,7 +49,7 @@ class Source(C.Structure):
 class Module(C.Structure):
     _fields_ = [("c_out", C.c_int32), ("g", Geom), ("w_bank", C.c_void_p), ("thr_lo", C.c_void_p),
                 ("thr_hi", C.c_void_p), ("skip_from", C.c_int32), ("up", C.c_int32 * 3),
-                ("pool", C.c_int32 * 3), ("matrix_bank", C.c_void_p), ("matrix_kind", C.c_int32)]
+                ("pool", C.c_int32 * 3)]
 
 
 def lib_path() -> str:
@@ -457,8 +457,9 @@ def tern_fcn_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor,
 
 
 def tern_probe_valu(blocks: int, threads: int, iters: int, sink: torch.Tensor, variant: int = 0) -> None:
-    """Diagnostic: enqueue the instruction-mix probe (65 * iters vector instructions per lane);
-    variant 0 = the kernels' spaced sequence, 1 = the same instructions unspaced."""
+    """Diagnostic: enqueue the instruction probe (65 * iters vector instructions per lane);
+    variant 0 = the kernels' spaced sequence, 1 = the same instructions unspaced, 2-13 = single
+    opcodes and the binary word pair (see tern_tuning.h)."""
     _dev(sink, torch.int32, "sink")
     _check(lib().tern_probe_valu(int(blocks), int(threads), int(iters), int(variant), _ptr(sink), _stream(sink)),
            "tern_probe_valu")
@@ -549,17 +550,13 @@ class NetModule:
     tern_digits_weights' output and the cut points refer to window sums)."""
 
     def __init__(self, c_out: int, w_bank: torch.Tensor, thr_lo: torch.Tensor, thr_hi: torch.Tensor,
-                 k=3, stride=1, pad=0, dil=1, skip_from: int = -1, up=1, pool=1,
-                 matrix_bank: Optional[torch.Tensor] = None, matrix_kind: str = "f4"):
+                 k=3, stride=1, pad=0, dil=1, skip_from: int = -1, up=1, pool=1):
         _dev(w_bank, PACKED_DTYPE, "w_bank")
         _dev(thr_lo, torch.int32, "thr_lo")
         _dev(thr_hi, torch.int32, "thr_hi")
         self.c_out, self.w_bank, self.thr_lo, self.thr_hi = int(c_out), w_bank, thr_lo, thr_hi
         self.k, self.stride, self.pad, self.dil = _t3(k), _t3(stride), _t3(pad), _t3(dil)
         self.skip_from, self.up, self.pool = int(skip_from), _t3(up), _t3(pool)
-        if matrix_bank is not None:
-            _dev(matrix_bank, PACKED_DTYPE, "matrix_bank")
-        self.matrix_bank, self.matrix_kind = matrix_bank, MATRIX_KINDS[matrix_kind]
 
     def as_struct(self) -> Module:
         m = Module(self.c_out, _geom(self.k, self.stride, self.pad, self.dil), self.w_bank.data_ptr(),
@@ -567,8 +564,6 @@ class NetModule:
         for a in range(3):
             m.up[a] = self.up[a]
             m.pool[a] = self.pool[a]
-        m.matrix_bank = self.matrix_bank.data_ptr() if self.matrix_bank is not None else None
-        m.matrix_kind = self.matrix_kind
         return m
 
 

@@ -443,26 +443,17 @@ size_t tern_fcn_workspace_bytes(tern_dims in_dims, const tern_layer* layers, int
     return b;
 }
 
-int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
-                     const tern_layer* layers, int32_t n_layers, void* workspace,
-                     size_t workspace_bytes, uint32_t* out_packed, tern_dims* out_dims,
-                     uint32_t** layer_out, void* stream)
+// The chain behind tern_fcn_forward and tern_fcn_forward_static: everything validated, `workspace`
+// holds at least the bytes fcn_plan asks for.
+static int fcn_run(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
+                   const tern_layer* layers, int32_t n_layers, void* workspace, uint32_t* out_packed,
+                   uint32_t** layer_out, void* stream)
 {
-    if (!in || !in_lo || !in_hi || !layers || !workspace || !out_packed) return TERN_ENULL;
-    size_t need = 0;
-    tern_dims last;
-    int rc = fcn_plan(in_dims, layers, n_layers, &need, &last);
-    if (rc != TERN_OK) return rc;
-    for (int i = 0; i < n_layers; ++i)
-        if (!layers[i].w_bank || !layers[i].thr_lo || !layers[i].thr_hi) return TERN_ENULL;
-    if (workspace_bytes < need || !aligned16(workspace)) return TERN_EWORKSPACE;
-    if (!aligned16(out_packed)) return TERN_EARG;
-
     char* ws = (char*)workspace;
     uint32_t* cur_buf = (uint32_t*)ws;
     tern_dims cur = in_dims;
     tern_dims o0;
-    rc = geom_check(in_dims, layers[0].c_out, layers[0].g, &o0);
+    int rc = geom_check(in_dims, layers[0].c_out, layers[0].g, &o0);
     if (rc != TERN_OK) return rc;
     // A one-channel input with a 3x3x3, 1x3x3 or 15x3x3 first kernel: Eq. 6 and the gathering of
     // every output voxel's taps into a bit string happen in one pass over the intensities, and
@@ -508,13 +499,11 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
             const int32_t taps = layers[0].g.k[0] * layers[0].g.k[1] * layers[0].g.k[2];
             const tern_dims pin = {o.n, taps, o.d, o.h, o.w};
             const tern_conv_geom unit = {{1, 1, 1}, {1, 1, 1}, {0, 0, 0}, {1, 1, 1}};
-            if (!layers[0].w_bank || !layers[0].thr_lo || !layers[0].thr_hi) return TERN_ENULL;
             if (!aligned16(layers[0].w_bank) || !aligned16(dst)) return TERN_EARG;
             rc = launch_conv3d(conv_params(cur_buf, pin, layers[0].w_bank, layers[0].c_out, unit, o,
                                            layers[0].thr_lo, layers[0].thr_hi, nullptr, dst),
                                (hipStream_t)stream);
         } else if (i == 0 && gathered) {
-            if (!layers[0].w_bank || !layers[0].thr_lo || !layers[0].thr_hi) return TERN_ENULL;
             if (!aligned16(layers[0].w_bank) || !aligned16(dst)) return TERN_EARG;
             FirstConvParams fc;
             fc.wgt = layers[0].w_bank; fc.lo = layers[0].thr_lo; fc.hi = layers[0].thr_hi;
@@ -531,6 +520,25 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
         cur_buf = dst;
         cur = o;
     }
+    return TERN_OK;
+}
+
+int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
+                     const tern_layer* layers, int32_t n_layers, void* workspace,
+                     size_t workspace_bytes, uint32_t* out_packed, tern_dims* out_dims,
+                     uint32_t** layer_out, void* stream)
+{
+    if (!in || !in_lo || !in_hi || !layers || !workspace || !out_packed) return TERN_ENULL;
+    size_t need = 0;
+    tern_dims last;
+    int rc = fcn_plan(in_dims, layers, n_layers, &need, &last);
+    if (rc != TERN_OK) return rc;
+    for (int i = 0; i < n_layers; ++i)
+        if (!layers[i].w_bank || !layers[i].thr_lo || !layers[i].thr_hi) return TERN_ENULL;
+    if (workspace_bytes < need || !aligned16(workspace)) return TERN_EWORKSPACE;
+    if (!aligned16(out_packed)) return TERN_EARG;
+    rc = fcn_run(in, in_dims, in_lo, in_hi, layers, n_layers, workspace, out_packed, layer_out, stream);
+    if (rc != TERN_OK) return rc;
     if (out_dims) *out_dims = last;
     return TERN_OK;
 }
@@ -663,9 +671,6 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
         odims[(size_t)i] = o;
         ooff[(size_t)i] = off;
         off += region(o);
-        if (m.matrix_bank && ((m.matrix_kind != TERN_MATRIX_I8 && m.matrix_kind != TERN_MATRIX_F4) ||
-                              !aligned16(m.matrix_bank)))
-            return TERN_EARG;
         if (w && w->run) {
             if (!m.w_bank || !m.thr_lo || !m.thr_hi) return TERN_ENULL;
             if (i == 0 && gathered && !fused) {
@@ -688,24 +693,12 @@ int net_walk(tern_dims in_dims, const tern_module* mods, int32_t n_mods, NetWalk
                 fc.wd_out = tern_words(m.c_out);
                 rc = launch_patch_conv_f32(first, fc, in_dims.n, w->stream);
             } else if (pooled) {
-                rc = TERN_ESHAPE;
-                if (m.matrix_bank && m.matrix_kind == TERN_MATRIX_F4)   // bank of the undoubled weights
-                    rc = tern_conv3d_mfma_digits((const uint32_t*)(w->ws + cur_off), cur, m.matrix_bank, m.c_out,
-                                                 m.g, m.thr_lo, m.thr_hi, nullptr,
-                                                 (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
-                if (rc == TERN_ESHAPE)
-                    rc = tern_conv3d_digits((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g,
-                                            m.thr_lo, m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]),
-                                            w->stream);
+                rc = tern_conv3d_digits((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g,
+                                        m.thr_lo, m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]),
+                                        w->stream);
             } else {
-                rc = TERN_ESHAPE;
-                if (m.matrix_bank)
-                    rc = tern_conv3d_mfma((const uint32_t*)(w->ws + cur_off), cur, m.matrix_bank, m.matrix_kind,
-                                          m.c_out, m.g, m.thr_lo, m.thr_hi, nullptr,
-                                          (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
-                if (rc == TERN_ESHAPE)   // no matrix bank, or a halo tile the matrix route cannot hold
-                    rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
-                                     m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
+                rc = tern_conv3d((const uint32_t*)(w->ws + cur_off), cur, m.w_bank, m.c_out, m.g, m.thr_lo,
+                                 m.thr_hi, nullptr, (uint32_t*)(w->ws + ooff[(size_t)i]), w->stream);
             }
             if (rc != TERN_OK) return rc;
             if (w->module_out) w->module_out[i] = (uint32_t*)(w->ws + ooff[(size_t)i]);

@@ -459,7 +459,8 @@ int launch_variant(const ConvParams& p, const MfmaPlan& t, size_t lds_bytes, dim
         TERN_HIP_CHECK(hipGetDevice(&dev));
         if (raised_on_device != dev) {
             TERN_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               lds_limit_for_current_device()));
             raised_on_device = dev;
         }
     }
@@ -531,7 +532,8 @@ int launch_conv3d_mfma(const ConvParams& p_in, int kind, hipStream_t s)
     // registers).  On a tie the larger tile where neighbouring waves read common input planes,
     // else the smaller: waves that share nothing gain nothing from one workgroup and only wait
     // for each other at its barriers.
-    const int64_t kLds = 160 * 1024;
+    const int64_t kLds = lds_limit_for_current_device();   // what this device grants a workgroup
+    if (kLds <= 0) return TERN_EHIP;
     int nw = 0, best_waves = 0;
     int w_max = kMaxWaves;
     while (w_max > 1 && w_max >= p.od) w_max /= 2;   // no more waves than there are pairs of output planes

@@ -25,15 +25,11 @@ namespace tern {
 
 int launch_conv3d_generic(const ConvParams& p, hipStream_t s);
 
-namespace {
-
-constexpr int kMaxThreads = 512;         // 8 waves: at most 2 waves per SIMD, <= 256 VGPRs
-constexpr int kLdsLimit = 160 * 1024;    // LDS per compute unit / per workgroup on gfx950
-
 // Largest dynamic LDS allocation the current device grants one workgroup (queried once per
 // device; 0 on error).
 int lds_limit_for_current_device()
 {
+    constexpr int kLdsLimit = 160 * 1024;    // LDS per compute unit on gfx950
     static int cached[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
@@ -45,6 +41,10 @@ int lds_limit_for_current_device()
     }
     return cached[dev];
 }
+
+namespace {
+
+constexpr int kMaxThreads = 512;         // 8 waves: at most 2 waves per SIMD, <= 256 VGPRs
 
 struct TileParams {
     int32_t nwx, nwy, nwz;        // waves per workgroup along x, y, z
@@ -545,13 +545,15 @@ int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, d
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-int g_lane_depth = 0;   // tuning override: 0 = choose, 1, 2 or 4 = force that voxel depth per lane
-int g_waves_z = 0;      // tuning override: 0 = choose, else waves stacked along z per workgroup
-int g_co_block = 0;     // tuning override: 0 = choose, 16 or 32 = channels per accumulation pass
-int g_co_per_wave = 0;  // tuning override: 0 = choose, else channels per wave (multiple of 16)
-int g_tap_split = 0;    // tuning override: 0 = choose, else waves sharing the taps of one slice
-int g_point = 1;        // tuning override: 0 = never use the pointwise kernel
-int g_lane_tile = 0;    // tuning override: 0 = choose, else 100 * LX + LY lanes of a wave along x and y
+// Tuning overrides (tern_set_option).  Per host thread: a launch decision reads only values its
+// own thread has set, so no other thread can change the plan in the middle of it.
+thread_local int g_lane_depth = 0;   // 0 = choose, 1, 2 or 4 = force that voxel depth per lane
+thread_local int g_waves_z = 0;      // 0 = choose, else waves stacked along z per workgroup
+thread_local int g_co_block = 0;     // 0 = choose, 16 or 32 = channels per accumulation pass
+thread_local int g_co_per_wave = 0;  // 0 = choose, else channels per wave (multiple of 16)
+thread_local int g_tap_split = 0;    // 0 = choose, else waves sharing the taps of one slice
+thread_local int g_point = 1;        // 0 = never use the pointwise kernel
+thread_local int g_lane_tile = 0;    // 0 = choose, else 100 * LX + LY lanes of a wave along x and y
 
 // Tile plan for a voxel depth V per lane and a wave of 2^lxb x 2^lyb x (64 / 2^(lxb + lyb)) lanes;
 // returns false if no halo tile fits in LDS.  Single-plane outputs need lxb + lyb = 6.

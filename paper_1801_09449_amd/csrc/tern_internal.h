@@ -5,6 +5,8 @@
 #include <stdint.h>
 
 #include "tern.h"
+#include "tern_matrix.h"
+#include "tern_tuning.h"
 
 namespace tern {
 
@@ -117,6 +119,10 @@ struct FirstConvParams {
 };
 int launch_patch_conv_f32(const PatchParams& p, const FirstConvParams& c, int32_t n, hipStream_t s);
 bool patch_conv_pays(const PatchParams& p, int32_t n);
+
+// Largest dynamic LDS allocation the current device grants one workgroup, at most the 160 KB of a
+// gfx950 compute unit (queried once per device; 0 on error).
+int lds_limit_for_current_device();
 
 // Launchers implemented in the kernel translation units.  Each validates nothing (the entry
 // points did) and returns a tern_status.

@@ -1,10 +1,21 @@
-// Diagnostic: sustained issue rate of the convolution's instruction mix (and, popcount-accumulate,
-// three-input bit operation, popcount-accumulate with wave-uniform second operands) with no
-// memory traffic at all.  The benchmark uses it as the measured ceiling next to the nominal
-// 256 CU x 64 lanes x 2.4 GHz figure.  Variant 0 runs the kernels' own statement (a scalar no-op
-// between each producer and its popcount), variant 1 the same four instructions per word pair
-// in an order that needs no wait state and with no scalar instruction in between, which is what
-// a compiler's scheduler makes of them: the pair of figures shows what the spacing is worth.
+// Diagnostic: sustained issue rate of the convolution's vector instructions with no memory
+// traffic at all.  The benchmark uses variant 0 as the measured ceiling of the kernels' instruction
+// mix next to the nominal 256 CU x 64 lanes x 2.4 GHz figure; the other variants take the mix
+// apart (one opcode at a time, with and without a scalar instruction behind each vector
+// instruction) to show which part of it issues faster than one wave instruction per four cycles.
+//
+//   0  the kernels' own statement: and, s_nop, popcount-accumulate, three-input bit operation,
+//      s_nop, popcount-accumulate (a scalar no-op between each producer and its popcount)
+//   1  the same four vector instructions per word pair in an order that needs no wait state and
+//      with no scalar instruction in between (what a compiler's scheduler makes of them)
+//   2 / 3    v_and_b32 with a wave-uniform operand, alone / each followed by s_nop 0
+//   4 / 5    v_bcnt_u32_b32 accumulating into eight registers in turn, alone / with s_nop 0
+//   6 / 7    v_bitop3_b32, alone / with s_nop 0
+//   8 / 9    v_xor_b32 with a wave-uniform operand, alone / with s_nop 0
+//   10 / 11  the two-instruction word pair of the binary convolution (Eq. 8): xor, s_nop,
+//            popcount-accumulate / xor, popcount-accumulate
+//   12 / 13  v_add_u32 (a plain integer add, for reference), alone / with s_nop 0
+// Every variant issues 64 vector instructions plus one add per round and lane.
 #include "tern_conv_common.h"
 #include "tern_internal.h"
 
@@ -75,6 +86,70 @@ __global__ __launch_bounds__(512) void probe_unspaced_kernel(ProbeConsts c, int 
     if (r == 0x7fffffff) sink[0] = r;
 }
 
+// One opcode (or the binary word pair) at a time: eight instructions per statement on eight
+// registers r0..r7 taken in turn, eight statements per round.  OP: 0 and, 1 popcount-accumulate,
+// 2 three-input bit operation, 3 xor, 4 binary pair (xor into a scratch register, popcount of it
+// accumulated; four pairs per statement), 5 add.  NOP: s_nop 0 behind every vector instruction
+// (binary pair: between the xor and its popcount).
+#define TERN_P_AND(R, K)   "v_and_b32 %[r" R "], %[k" K "], %[a]\n\t"
+#define TERN_P_BCNT(R, K)  "v_bcnt_u32_b32 %[r" R "], %[a], %[r" R "]\n\t"
+#define TERN_P_BITOP(R, K) "v_bitop3_b32 %[r" R "], %[a], %[b], %[k" K "] bitop3:0x48\n\t"
+#define TERN_P_XOR(R, K)   "v_xor_b32 %[r" R "], %[k" K "], %[a]\n\t"
+#define TERN_P_ADD(R, K)   "v_add_u32 %[r" R "], %[k" K "], %[r" R "]\n\t"
+#define TERN_P_NOP "s_nop 0\n\t"
+#define TERN_P_EIGHT(I, S)                                                                      \
+    I("0", "0") S I("1", "1") S I("2", "2") S I("3", "3") S I("4", "0") S I("5", "1") S I("6", "2") S \
+        I("7", "3") S
+// binary pair: xor into t (registers r4..r7 serve as the scratch registers), popcount into r0..r3
+#define TERN_P_BIN(R, T, K, S) \
+    "v_xor_b32 %[r" T "], %[k" K "], %[a]\n\t" S "v_bcnt_u32_b32 %[r" R "], %[r" T "], %[r" R "]\n\t"
+#define TERN_P_BIN_FOUR(S) \
+    TERN_P_BIN("0", "4", "0", S) TERN_P_BIN("1", "5", "1", S) TERN_P_BIN("2", "6", "2", S) TERN_P_BIN("3", "7", "3", S)
+
+template <int OP, bool NOP>
+__global__ __launch_bounds__(512) void probe_opcode_kernel(ProbeConsts c, int iters, int32_t* sink)
+{
+    uint32_t a = threadIdx.x * 2654435761u + blockIdx.x, b = a ^ 0x9e3779b9u;
+    uint32_t r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = j;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+#define TERN_P_OPERANDS                                                                              \
+    : [r0] "+v"(r[0]), [r1] "+v"(r[1]), [r2] "+v"(r[2]), [r3] "+v"(r[3]), [r4] "+v"(r[4]), [r5] "+v"(r[5]), \
+      [r6] "+v"(r[6]), [r7] "+v"(r[7])                                                              \
+    : [a] "v"(a), [b] "v"(b), [k0] "s"(c.k[4 * (st & 3)]), [k1] "s"(c.k[4 * (st & 3) + 1]),        \
+      [k2] "s"(c.k[4 * (st & 3) + 2]), [k3] "s"(c.k[4 * (st & 3) + 3])
+            if constexpr (OP == 0) {
+                if constexpr (NOP) asm volatile(TERN_P_EIGHT(TERN_P_AND, TERN_P_NOP) TERN_P_OPERANDS);
+                else asm volatile(TERN_P_EIGHT(TERN_P_AND, "") TERN_P_OPERANDS);
+            } else if constexpr (OP == 1) {
+                if constexpr (NOP) asm volatile(TERN_P_EIGHT(TERN_P_BCNT, TERN_P_NOP) TERN_P_OPERANDS);
+                else asm volatile(TERN_P_EIGHT(TERN_P_BCNT, "") TERN_P_OPERANDS);
+            } else if constexpr (OP == 2) {
+                if constexpr (NOP) asm volatile(TERN_P_EIGHT(TERN_P_BITOP, TERN_P_NOP) TERN_P_OPERANDS);
+                else asm volatile(TERN_P_EIGHT(TERN_P_BITOP, "") TERN_P_OPERANDS);
+            } else if constexpr (OP == 3) {
+                if constexpr (NOP) asm volatile(TERN_P_EIGHT(TERN_P_XOR, TERN_P_NOP) TERN_P_OPERANDS);
+                else asm volatile(TERN_P_EIGHT(TERN_P_XOR, "") TERN_P_OPERANDS);
+            } else if constexpr (OP == 4) {
+                if constexpr (NOP) asm volatile(TERN_P_BIN_FOUR(TERN_P_NOP) TERN_P_OPERANDS);
+                else asm volatile(TERN_P_BIN_FOUR("") TERN_P_OPERANDS);
+            } else {
+                if constexpr (NOP) asm volatile(TERN_P_EIGHT(TERN_P_ADD, TERN_P_NOP) TERN_P_OPERANDS);
+                else asm volatile(TERN_P_EIGHT(TERN_P_ADD, "") TERN_P_OPERANDS);
+            }
+#undef TERN_P_OPERANDS
+        }
+        a += 0x01010101u;
+    }
+    uint32_t x = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) x += r[j];
+    if (x == 0x7fffffffu && b == 12345u) sink[0] = (int32_t)x;
+}
+
 }  // namespace
 }  // namespace tern
 
@@ -84,11 +159,21 @@ extern "C" int tern_probe_valu(int32_t blocks, int32_t threads, int32_t iters, i
     using namespace tern;
     if (!sink) return TERN_ENULL;
     if (blocks < 1 || threads < 64 || threads > 512 || threads % 64 || iters < 1) return TERN_EARG;
-    if (variant != 0 && variant != 1) return TERN_EARG;
+    if (variant < 0 || variant >= TERN_PROBE_VARIANTS) return TERN_EARG;
     ProbeConsts c;
     for (int i = 0; i < 32; ++i) c.k[i] = 0x9e3779b9u * (uint32_t)(i + 1);
-    hipLaunchKernelGGL(variant == 0 ? probe_kernel : probe_unspaced_kernel, dim3((unsigned)blocks),
-                       dim3((unsigned)threads), 0, (hipStream_t)stream, c, iters, sink);
+    typedef void (*kern_t)(ProbeConsts, int, int32_t*);
+    static const kern_t table[TERN_PROBE_VARIANTS] = {
+        probe_kernel, probe_unspaced_kernel,
+        probe_opcode_kernel<0, false>, probe_opcode_kernel<0, true>,
+        probe_opcode_kernel<1, false>, probe_opcode_kernel<1, true>,
+        probe_opcode_kernel<2, false>, probe_opcode_kernel<2, true>,
+        probe_opcode_kernel<3, false>, probe_opcode_kernel<3, true>,
+        probe_opcode_kernel<4, true>, probe_opcode_kernel<4, false>,
+        probe_opcode_kernel<5, false>, probe_opcode_kernel<5, true>,
+    };
+    hipLaunchKernelGGL(table[variant], dim3((unsigned)blocks), dim3((unsigned)threads), 0, (hipStream_t)stream, c,
+                       iters, sink);
     TERN_HIP_CHECK(hipGetLastError());
     return TERN_OK;
 }

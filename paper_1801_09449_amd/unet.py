@@ -8,11 +8,6 @@ either way it is done here: small problems fold it into the filters of the modul
 (tern_fold_avgpool: taps repeated over the pooling window, stride multiplied: no extra launch,
 four times the word pairs of the pooled convolution); large ones pool into two balanced-ternary
 digits first (tern_pool_digits, one small launch) and convolve those (twice the word pairs).
-On request (matrix_kind) batches with at least two planes per convolution run their large
-modules on the matrix cores (tern_module.matrix_bank; pooled modules through two digits turned
-into 4-bit float codes of the window sums for the 4-bit kind, folded filters for int8): same
-results, 16 stacks in well under half the time.  Not the default: the network then no longer
-runs on the paper's bit-count scheme.
 """
 from typing import Dict, List, Sequence
 
@@ -25,17 +20,13 @@ from . import binding as B
 class UNetPlan:
     """Device-resident parameters of the network, prepared once."""
 
-    def __init__(self, layers: Sequence[Dict], head_w, head_b, in_lo, in_hi, device="cuda", matrix_kind=None):
-        """matrix_kind: None (bit-count kernels throughout), or "f4" / "i8": large modules of large
-        batches take the matrix-core route."""
+    def __init__(self, layers: Sequence[Dict], head_w, head_b, in_lo, in_hi, device="cuda"):
         dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
         self.in_lo, self.in_hi = dev(np.asarray(in_lo, np.float32)), dev(np.asarray(in_hi, np.float32))
         saved: Dict[str, int] = {}
         self.mods: List[B.NetModule] = []          # pooling folded into the filters everywhere
         self._digit_mods: Dict[int, B.NetModule] = {}   # pooled modules in their two-digit form
         self._macs: Dict[int, float] = {}          # folded word-pair work per output voxel of such a module
-        self._matrix_mods: Dict[int, B.NetModule] = {}  # modules behind the first with a matrix bank
-        self._module_macs: Dict[int, float] = {}          # MACs per output voxel of a module as folded
         for i, L in enumerate(layers):
             w = np.ascontiguousarray(L["w"], dtype=np.int8)
             stride = tuple(int(v) for v in (L.get("stride") or (1, 1, 1)))
@@ -44,17 +35,12 @@ class UNetPlan:
             up = tuple(L.get("up") or (1, 1, 1))
             lo, hi = dev(np.asarray(L["lo"], np.int32)), dev(np.asarray(L["hi"], np.int32))
             pool = tuple(int(v) for v in L["pool"]) if L.get("pool") else None
-            digits_matrix = None        # pooled module on the matrix cores: two digits -> 4-bit floats
             if pool and int(np.prod(pool)) <= 4 and max(pool) <= 4:
                 dbank = B.tern_pack_filters(dev(B.tern_digits_weights(w)))
                 k0 = tuple(int(v) for v in w.shape[2:])
                 self._digit_mods[i] = B.NetModule(int(w.shape[0]), dbank, lo, hi, k=k0, stride=stride,
                                                   pad=pad, dil=1, skip_from=skip, up=up, pool=pool)
                 self._macs[i] = float(w.size) * float(np.prod(pool))
-                if i > 0 and matrix_kind == "f4":
-                    digits_matrix = B.NetModule(int(w.shape[0]), dbank, lo, hi, k=k0, stride=stride, pad=pad, dil=1,
-                                                skip_from=skip, up=up, pool=pool,
-                                                matrix_bank=B.tern_expand_filters(dev(w), "f4"), matrix_kind="f4")
             if pool:
                 # pooling window P before a convolution of stride s and padding p: filters with
                 # every tap repeated P times, stride s*P, padding p*P
@@ -65,14 +51,6 @@ class UNetPlan:
             kk = tuple(int(v) for v in w.shape[2:])
             self.mods.append(B.NetModule(int(w.shape[0]), bank, lo, hi, k=kk, stride=stride, pad=pad, dil=1,
                                          skip_from=skip, up=up))
-            self._module_macs[i] = float(w.size)
-            if digits_matrix is not None:
-                self._matrix_mods[i] = digits_matrix
-            elif i > 0 and matrix_kind:
-                self._matrix_mods[i] = B.NetModule(int(w.shape[0]), bank, lo, hi, k=kk, stride=stride, pad=pad,
-                                                   dil=1, skip_from=skip, up=up,
-                                                   matrix_bank=B.tern_expand_filters(dev(w), matrix_kind),
-                                                   matrix_kind=matrix_kind)
             if L.get("save"):
                 saved[L["save"]] = i
         self.head_w = dev(np.asarray(head_w, np.float32)) if head_w is not None else None
@@ -84,11 +62,6 @@ class UNetPlan:
     # two digits instead (half the word pairs for one more small launch; measured break-even
     # between 1 and 3 GMAC on MI355X).
     DIGITS_FROM_MACS = 1.5e9
-    # A module behind the first runs on the matrix cores when its convolution sees at least this
-    # many planes (a wave of that route covers two planes) and at least
-    # this many ternary MACs (below it the launch is latency-bound either way).
-    MATRIX_FROM_PLANES = 2
-    MATRIX_FROM_MACS = 1.0e9
 
     def modules(self, in_shape) -> List[B.NetModule]:
         """The module list for an input of this shape (cached)."""
@@ -99,10 +72,6 @@ class UNetPlan:
             for i, m in self._digit_mods.items():
                 n, _, d, h, w = dims[i]
                 if n * d * h * w * self._macs[i] >= self.DIGITS_FROM_MACS:
-                    mods[i] = m
-            for i, m in self._matrix_mods.items():
-                n, _, d, h, w = dims[i]
-                if n * d >= self.MATRIX_FROM_PLANES and n * d * h * w * self._module_macs[i] >= self.MATRIX_FROM_MACS:
                     mods[i] = m
             self._chosen[key] = mods
         return self._chosen[key]

@@ -192,19 +192,20 @@ class FcnCase:
 
 
 def config2(seed: int = 0, vol=(128, 128, 64), channels=(16, 32, 32, 64, 64, 128),
-            strides=(1, 2, 1, 2, 1, 2)) -> FcnCase:
+            strides=(1, 2, 1, 2, 1, 2), c0: int = 1) -> FcnCase:
     """Six 3^3 layers, channels 1-16-32-32-64-64-128, stride 2 at layers 2, 4, 6; N(0,1)
     intensities ternarised at +-0.5; weight zeros 0.5; cut points from bn_like_thresholds with
-    nonzero fractions 0.5 (weights) and 0.617 (activations)."""
-    x = gaussian((1, 1) + tuple(vol), seed, T_F32)
-    layers, c_in = [], 1
+    nonzero fractions 0.5 (weights) and 0.617 (activations).  c0: input channels (1 in the
+    configuration; more for tests of chains whose first layer sees several)."""
+    x = gaussian((1, c0) + tuple(vol), seed, T_F32)
+    layers, c_in = [], c0
     for li, (c_out, s) in enumerate(zip(channels, strides), start=1):
         w = ternary((c_out, c_in, 3, 3, 3), 0.5, seed, T_WGT + 8 * li)
         lo, hi = bn_like_thresholds(c_out, 27, c_in, 0.5, 0.617, seed, T_THR + 8 * li)
         layers.append(dict(w=w, k=(3, 3, 3), stride=(s,) * 3, pad=(1, 1, 1), dil=(1, 1, 1),
                            lo=lo, hi=hi))
         c_in = c_out
-    return FcnCase("cfg2", x, np.array([-0.5], np.float32), np.array([0.5], np.float32), layers)
+    return FcnCase("cfg2", x, np.full(c0, -0.5, np.float32), np.full(c0, 0.5, np.float32), layers)
 
 
 @dataclass

@@ -19,11 +19,15 @@ def T():
 
 
 def test_every_declared_symbol_is_exported(T):
-    hdr = open(os.path.join(ROOT, "include", "tern.h")).read()
-    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = set(re.findall(r"\b(tern_[a-z0-9_]+)\s*\(", hdr))
+    import glob
+    headers = sorted(glob.glob(os.path.join(ROOT, "include", "*.h")))
+    assert [os.path.basename(h) for h in headers] == ["tern.h", "tern_matrix.h", "tern_tuning.h"]
+    names = set()
+    for h in headers:
+        hdr = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        names |= set(re.findall(r"\b(tern_[a-z0-9_]+)\s*\(", hdr))
     assert {"tern_pack", "tern_conv3d", "tern_threshold_pack", "tern_fcn_forward",
-            "tern_pack_filters"} <= names
+            "tern_pack_filters", "tern_conv3d_mfma", "tern_set_option"} <= names
     L = T.lib()
     for n in sorted(names):
         assert hasattr(L, n), f"{n} declared in tern.h but not exported"
@@ -120,7 +124,8 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     # probe: null sink, launch shape and variant are checked before anything is launched
     assert L.tern_probe_valu(4, 256, 10, 0, None, None) == -1
     assert L.tern_probe_valu(4, 100, 10, 0, fake, None) == -3
-    assert L.tern_probe_valu(4, 256, 10, 2, fake, None) == -3
+    assert L.tern_probe_valu(4, 256, 10, 14, fake, None) == -3
+    assert L.tern_probe_valu(4, 256, 10, -1, fake, None) == -3
     assert L.tern_probe_valu(0, 256, 10, 1, fake, None) == -3
     # options: unknown option or value
     assert L.tern_set_option(99, 0) == -3

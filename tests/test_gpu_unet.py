@@ -301,18 +301,18 @@ def test_two_digit_input_through_the_direct_kernel(G):
 
 
 # ---- the whole network -----------------------------------------------------------------------------
-def run_unet(G, u, matrix_kind=None):
+def run_unet(G, u):
     import torch
     from paper_1801_09449_amd import unet
-    plan = unet.UNetPlan(u.layers, u.head_w, u.head_b, u.in_lo, u.in_hi, matrix_kind=matrix_kind)
+    plan = unet.UNetPlan(u.layers, u.head_w, u.head_b, u.in_lo, u.in_hi)
     pred, kept = unet.unet_forward(plan, G.dev(u.x), keep_layers=True)
     torch.cuda.synchronize()
     return pred.cpu().numpy(), [G.words(t) for t, _ in kept], kept, plan
 
 
-def check_unet(G, u, matrix_kind=None):
+def check_unet(G, u):
     """Runs the network and compares every module with the oracle; returns the plan."""
-    pred, kept, kept_dev, plan = run_unet(G, u, matrix_kind)
+    pred, kept, kept_dev, plan = run_unet(G, u)
     codes, want_pred = oracle.unet_forward(u.x, u.in_lo, u.in_hi, u.layers, u.head_w, u.head_b)
     assert len(kept) == len(codes) == 14
     for li, (got, want) in enumerate(zip(kept, codes), start=1):
@@ -351,30 +351,6 @@ def test_unet_reduced_with_every_pooled_module_through_two_digits(G, monkeypatch
     monkeypatch.setattr(unet.UNetPlan, "DIGITS_FROM_MACS", 0.0)
     check_unet(G, synth.unet_table1(seed=5, n=3, width_div=8, size=(84, 76), slices=5))
     check_unet(G, synth.unet_table1(seed=6, n=1, width_div=3, size=(92, 100), slices=15))
-
-
-@pytest.mark.parametrize("kind", ["f4", "i8"])
-def test_unet_reduced_with_modules_on_the_matrix_cores(G, monkeypatch, kind):
-    """The narrow networks with every module behind the first on the matrix-core route
-    (tern_module.matrix_bank, pooling folded into the filters): thresholds of the plan at zero.
-    The folded pooling modules (6 x 6 kernels, stride 2) and the one-stack case (a single plane per
-    convolution) go through it as well; every module's packed output, bit for bit."""
-    from paper_1801_09449_amd import unet
-    monkeypatch.setattr(unet.UNetPlan, "MATRIX_FROM_PLANES", 1)
-    monkeypatch.setattr(unet.UNetPlan, "MATRIX_FROM_MACS", 0.0)
-    monkeypatch.setattr(unet.UNetPlan, "DIGITS_FROM_MACS", 1e30)
-    check_unet(G, synth.unet_table1(seed=5, n=3, width_div=8, size=(84, 76), slices=5), matrix_kind=kind)
-    check_unet(G, synth.unet_table1(seed=6, n=1, width_div=3, size=(92, 100), slices=15), matrix_kind=kind)
-
-
-def test_unet_batch_of_eight_with_the_plans_own_rule_for_the_matrix_cores(G):
-    """Eight stacks, narrow channels, matrix kind given: the plan's size rule puts the large
-    modules on the matrix cores and leaves the small ones; results as from the oracle."""
-    from paper_1801_09449_amd import unet
-    u = synth.unet_table1(seed=8, n=8, width_div=2, size=(140, 132), slices=5)
-    plan = check_unet(G, u, matrix_kind="f4")
-    chosen = plan.modules(u.x.shape)
-    assert any(m.matrix_bank is not None for m in chosen) and any(m.matrix_bank is None for m in chosen[1:])
 
 
 def test_unet_table1_full_size(G):
