@@ -11,8 +11,8 @@
  * General rules
  *   - Every data pointer is a DEVICE pointer owned by the caller unless a comment says "host".
  *     The library never allocates, frees or retains caller memory and keeps no state between
- *     calls except the last HIP error code (tern_last_hip_error) and the per-thread
- *     tuning overrides of tern_tuning.h.
+ *     calls except the last HIP error code (tern_last_hip_error), the per-thread tuning
+ *     overrides of tern_tuning.h and the fixed scratch array of tern_fcn_forward_static.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
  *     on that stream and return without synchronising.
  *   - Return value: TERN_OK (0) or a negative tern_status.  No call throws or aborts.  Arguments
@@ -194,6 +194,30 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
                      void* workspace, size_t workspace_bytes,
                      uint32_t* out_packed, tern_dims* out_dims /* host */,
                      uint32_t** layer_out /* host, optional */, void* stream);
+
+/*
+ * tern_fcn_forward_static -- tern_fcn_forward for callers that cannot allocate device memory and
+ * have no workspace to hand over: code recorded into a HIP graph, tight serving loops, harnesses
+ * that forbid allocation.  Same arguments without the workspace, same results; the activations
+ * between layers go to a fixed device array of TERN_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (every GPU the library is used on holds its own copy until the process
+ * ends).  The call allocates and frees nothing; a chain whose tern_fcn_workspace_bytes() exceeds
+ * tern_static_scratch_bytes() is refused with TERN_EWORKSPACE before anything is launched.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ *     (different streams, or different host threads) race on it.  Calls on one stream are safe.
+ *   - The array keeps the previous call's contents; nothing needs clearing, because every region a
+ *     kernel of the chain reads was written earlier in the same call.
+ *   - layer_out[i] (optional) receives addresses inside that array for every layer but the last;
+ *     they are valid until the next call on the same GPU.
+ *   - The first call on a device looks the array's address up (and thereby loads the library's
+ *     code object if nothing has yet); make one ordinary call before recording a graph.
+ */
+#define TERN_STATIC_SCRATCH_BYTES (32u << 20)
+size_t tern_static_scratch_bytes(void);
+int tern_fcn_forward_static(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
+                            const tern_layer* layers /* host */, int32_t n_layers,
+                            uint32_t* out_packed, tern_dims* out_dims /* host */,
+                            uint32_t** layer_out /* host, optional */, void* stream);
 
 /*
  * U-Net plumbing on packed activations (section 3, Table 1: the Upsample2D rows, the "Skip"

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     tern_net_workspace_bytes,
     NetModule,
     tern_fcn_workspace_bytes,
+    tern_static_scratch_bytes,
     tern_filter_bank_bytes,
     tern_matrix_bank_bytes,
     tern_expand_filters,

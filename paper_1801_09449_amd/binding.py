@@ -89,6 +89,10 @@ def lib():
     L.tern_fcn_forward.argtypes = [P, Dims, P, P, C.POINTER(Layer), I, P, S, P, C.POINTER(Dims),
                                    C.POINTER(C.c_void_p), P]
     L.tern_fcn_forward.restype = C.c_int
+    L.tern_static_scratch_bytes.argtypes = []; L.tern_static_scratch_bytes.restype = S
+    L.tern_fcn_forward_static.argtypes = [P, Dims, P, P, C.POINTER(Layer), I, P, C.POINTER(Dims),
+                                          C.POINTER(C.c_void_p), P]
+    L.tern_fcn_forward_static.restype = C.c_int
     L.tern_ternarize_filters.argtypes = [P, I, C.c_int64, P, P]; L.tern_ternarize_filters.restype = C.c_int
     L.tern_ternarize_filters_sparse.argtypes = [P, I, C.c_int64, C.c_int64, P, P]
     L.tern_ternarize_filters_sparse.restype = C.c_int
@@ -407,9 +411,13 @@ def tern_fcn_workspace_bytes(in_shape, layers: Sequence[FcnLayer]) -> int:
 
 def tern_fcn_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor,
                      layers: Sequence[FcnLayer], workspace: Optional[torch.Tensor] = None,
-                     out: Optional[torch.Tensor] = None, return_layers: bool = False):
+                     out: Optional[torch.Tensor] = None, return_layers: bool = False,
+                     static_scratch: bool = False):
     """float32 [N][C0][D][H][W] -> packed output of the last module.  With return_layers, also a
-    list of (packed tensor view, logical dims) for every module's output."""
+    list of (packed tensor view, logical dims) for every module's output.  static_scratch=True
+    calls tern_fcn_forward_static: no workspace, the activations between layers go to the
+    library's fixed device array (return_layers then gives views of that array, valid until the
+    next such call on this GPU)."""
     _dev(x, torch.float32, "x")
     if x.dim() != 5:
         raise ValueError("x must be [N][C0][D][H][W]")
@@ -420,9 +428,13 @@ def tern_fcn_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor,
     need = int(lib().tern_fcn_workspace_bytes(_dims(x.shape), arr, len(layers)))
     if need == 0:
         raise TernError(-3, "tern_fcn_forward (invalid chain)")
-    if workspace is None:
-        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
-    _dev(workspace, torch.uint8, "workspace")
+    if static_scratch:
+        if workspace is not None:
+            raise ValueError("static_scratch takes no workspace")
+    else:
+        if workspace is None:
+            workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
+        _dev(workspace, torch.uint8, "workspace")
     # logical dims of every layer output
     dims_list: List[Tuple[int, ...]] = []
     cur = tuple(int(v) for v in x.shape)
@@ -436,13 +448,26 @@ def tern_fcn_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor,
         raise ValueError("out has the wrong size")
     od = Dims()
     ptrs = (C.c_void_p * len(layers))()
-    rc = lib().tern_fcn_forward(_ptr(x), _dims(x.shape), _ptr(in_lo), _ptr(in_hi), arr, len(layers),
-                                _ptr(workspace), workspace.numel(), _ptr(out), C.byref(od), ptrs,
-                                _stream(x))
-    _check(rc, "tern_fcn_forward")
+    if static_scratch:
+        rc = lib().tern_fcn_forward_static(_ptr(x), _dims(x.shape), _ptr(in_lo), _ptr(in_hi), arr, len(layers),
+                                           _ptr(out), C.byref(od), ptrs, _stream(x))
+        _check(rc, "tern_fcn_forward_static")
+    else:
+        rc = lib().tern_fcn_forward(_ptr(x), _dims(x.shape), _ptr(in_lo), _ptr(in_hi), arr, len(layers),
+                                    _ptr(workspace), workspace.numel(), _ptr(out), C.byref(od), ptrs,
+                                    _stream(x))
+        _check(rc, "tern_fcn_forward")
     if not return_layers:
         return out
     views = []
+    if static_scratch:
+        for i, dm in enumerate(dims_list):
+            if i + 1 == len(layers):
+                views.append((out, dm))
+            else:
+                shape = (dm[0], dm[2], dm[3], dm[4], 2, tern_words(dm[1]))
+                views.append((torch.as_tensor(_DeviceWords(int(ptrs[i]), shape), device=x.device), dm))
+        return out, views
     base = workspace.data_ptr()
     for i, dm in enumerate(dims_list):
         if i + 1 == len(layers):
@@ -454,6 +479,20 @@ def tern_fcn_forward(x: torch.Tensor, in_lo: torch.Tensor, in_hi: torch.Tensor,
                 dm[0], dm[2], dm[3], dm[4], 2, tern_words(dm[1]))
             views.append((v, dm))
     return out, views
+
+
+def tern_static_scratch_bytes() -> int:
+    """Size of the fixed device array behind tern_fcn_forward_static."""
+    return int(lib().tern_static_scratch_bytes())
+
+
+class _DeviceWords:
+    """Device memory that no torch tensor owns (the library's fixed scratch array), described so
+    that torch can view it without copying."""
+
+    def __init__(self, ptr: int, shape):
+        self.__cuda_array_interface__ = {"shape": tuple(int(v) for v in shape), "typestr": "<i4",
+                                         "data": (int(ptr), False), "version": 2}
 
 
 def tern_probe_valu(blocks: int, threads: int, iters: int, sink: torch.Tensor, variant: int = 0) -> None:

@@ -3,6 +3,7 @@
 // synchronising.  Nothing here allocates device memory.
 #include <limits.h>
 
+#include <mutex>
 #include <vector>
 
 #include "tern_internal.h"
@@ -538,6 +539,60 @@ int tern_fcn_forward(const float* in, tern_dims in_dims, const float* in_lo, con
     if (workspace_bytes < need || !aligned16(workspace)) return TERN_EWORKSPACE;
     if (!aligned16(out_packed)) return TERN_EARG;
     rc = fcn_run(in, in_dims, in_lo, in_hi, layers, n_layers, workspace, out_packed, layer_out, stream);
+    if (rc != TERN_OK) return rc;
+    if (out_dims) *out_dims = last;
+    return TERN_OK;
+}
+
+// ---- the chain for callers that cannot allocate ---------------------------------------------
+// The activations between layers live in a file-scope device array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy of the array at its own address;
+// in host code the array's name is only a handle for hipGetSymbolAddress, never an address to
+// pass to a kernel.  The address is looked up once per device, with that device current.
+static constexpr size_t kStaticScratchBytes = (size_t)TERN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, or null
+
+// Device address of the current device's copy of the scratch array (resolved on first use).
+static int scratch_for_current_device(void** out)
+{
+    int dev = 0;
+    TERN_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return TERN_EARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        TERN_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return TERN_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TERN_OK;
+}
+
+size_t tern_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int tern_fcn_forward_static(const float* in, tern_dims in_dims, const float* in_lo, const float* in_hi,
+                            const tern_layer* layers, int32_t n_layers, uint32_t* out_packed,
+                            tern_dims* out_dims, uint32_t** layer_out, void* stream)
+{
+    if (!in || !in_lo || !in_hi || !layers || !out_packed) return TERN_ENULL;
+    size_t need = 0;
+    tern_dims last;
+    int rc = fcn_plan(in_dims, layers, n_layers, &need, &last);
+    if (rc != TERN_OK) return rc;
+    for (int i = 0; i < n_layers; ++i)
+        if (!layers[i].w_bank || !layers[i].thr_lo || !layers[i].thr_hi) return TERN_ENULL;
+    if (need > kStaticScratchBytes) return TERN_EWORKSPACE;   // chain too large for the fixed array
+    if (!aligned16(out_packed)) return TERN_EARG;
+    void* ws = nullptr;
+    rc = scratch_for_current_device(&ws);
+    if (rc != TERN_OK) return rc;
+    // every region of the scratch that a kernel of the chain reads was written by an earlier
+    // kernel of the same call, so nothing has to be cleared between calls
+    rc = fcn_run(in, in_dims, in_lo, in_hi, layers, n_layers, ws, out_packed, layer_out, stream);
     if (rc != TERN_OK) return rc;
     if (out_dims) *out_dims = last;
     return TERN_OK;

@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported(T):
         hdr = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
         names |= set(re.findall(r"\b(tern_[a-z0-9_]+)\s*\(", hdr))
     assert {"tern_pack", "tern_conv3d", "tern_threshold_pack", "tern_fcn_forward",
-            "tern_pack_filters", "tern_conv3d_mfma", "tern_set_option"} <= names
+            "tern_pack_filters", "tern_fcn_forward_static", "tern_conv3d_mfma", "tern_set_option"} <= names
     L = T.lib()
     for n in sorted(names):
         assert hasattr(L, n), f"{n} declared in tern.h but not exported"
@@ -113,6 +113,14 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 2, fake, need - 1, fake, C.byref(od), None, None) == -4
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 0, fake, need, fake, C.byref(od), None, None) == -3
     assert L.tern_fcn_forward(fake, d, fake, fake, arr, 2, None, need, fake, C.byref(od), None, None) == -1
+    # the same chain over the library's fixed scratch array: refused when it does not fit, before
+    # any device is touched
+    assert L.tern_static_scratch_bytes() == 32 << 20
+    assert L.tern_fcn_forward_static(fake, d, fake, fake, arr, 2, None, C.byref(od), None, None) == -1
+    assert L.tern_fcn_forward_static(fake, d, fake, fake, arr, 0, fake, C.byref(od), None, None) == -3
+    big = Dims(1, 32, 128, 128, 160)       # 21 MB packed input + 21 MB first layer output
+    assert L.tern_fcn_workspace_bytes(big, arr, 2) > L.tern_static_scratch_bytes()
+    assert L.tern_fcn_forward_static(fake, big, fake, fake, arr, 2, fake, C.byref(od), None, None) == -4
     # two-digit pooling and convolution
     win = (C.c_int32 * 3)(1, 2, 2)
     assert L.tern_pool_digits(None, d, win, fake, None) == -1
