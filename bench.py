@@ -5,10 +5,16 @@ One step = one call of the fused ternary convolution (halo staging, masked-Hammi
 threshold + re-pack epilogue) on BASELINE config[1]: batch 1, C_in = C_out = 64, 64^3 volume, 3^3
 kernel, stride 1, pad 1, seeded synthetic ternary data already resident in HBM and already packed
 (as it is between layers of a network).  Prints ONE JSON line.
+
+Besides the headline the line carries: the roofline of the timed kernel (issued vector
+instructions against the issue rate of the same instruction sequence measured in this run), a
+check of the timed output against the CPU oracle, per-launch statistics, one compact row for each
+of the other BASELINE configurations, and the oracle timed on the host cores.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -16,23 +22,44 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# Roofline constants: 256 compute units x 64 32-bit integer lanes per clock x 2.4 GHz.
-PEAK_LANE_OPS = 256 * 64 * 2.4e9          # 39.32e12 lane-ops/s
-OPS_PER_MAC = 5.0 / 32.0                  # and, xor, and, 2 x popcount-accumulate per 32 MACs
-HBM_PEAK = 8.0e12
-PEAK_MFMA_I8 = 5.0e15                     # dense int8 matrix operations per second (published)
-PEAK_MFMA_F4 = 10.1e15                    # dense 4-bit float matrix operations per second (published)
-# HBM bytes per launch of the config[1] kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by
-# a 256 MiB copy under the same counters (profiles/conv3d_fused_config1.md).
+# Nominal vector-ALU rate: 256 compute units x 64 32-bit integer lanes per clock x 2.4 GHz (one
+# wave-wide instruction per SIMD every four cycles).
+NOMINAL_LANE_OPS = 256 * 64 * 2.4e9       # 39.32e12 lane-ops/s
+# The kernels issue four vector instructions per 32-bit word pair (32 MACs): and, popcount-
+# accumulate, three-input bit operation, popcount-accumulate.  Counted from the kernel's code: 94.5 %
+# of the instructions of a config[1] wave are these.
+ISSUED_OPS_PER_MAC = 4.0 / 32.0
+# The method as the paper writes it needs five operations per word pair (and, xor, and, two
+# popcount-accumulates): the figure the survey's roofline is quoted on.
+ALGORITHMIC_OPS_PER_MAC = 5.0 / 32.0
+# HBM bytes per launch of the config[1] kernel: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
+# a 256 MiB copy under the same counters (profiles/conv3d_fused_config1.md).  A profiler figure,
+# not measured by this script.
 TRAFFIC_BYTES_CFG1 = 10.09e6
 ALGORITHMIC_BYTES_CFG1 = 8.42e6
-# the same counters for the matrix-core kernels (profiles/conv3d_mfma_config1.md)
-TRAFFIC_BYTES_CFG1_MFMA = {"i8": 10.46e6, "f4": 10.05e6}
+SETTLE_MS = 40.0                          # GPU work in front of every timed region (clocks settle)
 
 
-def timed(fn, steps, warmup, stream_sync):
+def settle(fn, min_ms=SETTLE_MS):
+    """Run fn back to back for at least min_ms of GPU time, whatever --warmup says: a 2 ms timed
+    region right after an idle period measures the clock ramp, not the kernel."""
+    import torch
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    total = 0.0
+    while total < min_ms:
+        ev0.record()
+        for _ in range(20):
+            fn()
+        ev1.record()
+        torch.cuda.synchronize()
+        total += ev0.elapsed_time(ev1)
+
+
+def timed(fn, steps, warmup, stream_sync=None, settle_first=True):
     """Average milliseconds per call by events on the current stream, plus wall time."""
     import torch
+    if settle_first:
+        settle(fn)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -47,9 +74,21 @@ def timed(fn, steps, warmup, stream_sync):
     return ev0.elapsed_time(ev1) / steps, wall
 
 
+def per_launch(fn, count):
+    """Milliseconds of `count` single launches, each bracketed by its own pair of events."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(count)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in evs]
+
+
 def cpu_baseline(case, target_seconds=12.0):
     """The oracle, as it stands, timed on the host cores on a z-slab of the same workload sized
-    to about target_seconds."""
+    to about target_seconds.  Returns the JSON object and (accumulators, input planes used)."""
     import numpy as np
     import oracle
     from oracle import ConvGeom
@@ -71,7 +110,38 @@ def cpu_baseline(case, target_seconds=12.0):
         "value": macs / dt / 1e12, "unit": "TMAC/s", "cores": oracle.max_threads(), "kind": "oracle",
         "sample": f"z-slab of {planes} of {d} input planes of config[1] (same channels and kernel), "
                   f"1 repetition, {dt:.2f} s",
-    }
+    }, acc, planes
+
+
+def check_against_oracle(case, out_packed, acc_slab, planes):
+    """The timed call's packed output against the oracle.  With the accumulators of a z-slab of the
+    input (from cpu_baseline): every output plane whose taps lie inside the slab, all channels and
+    voxels.  Without: 4096 sampled outputs through the oracle's point evaluation."""
+    import numpy as np
+    import oracle
+    from oracle import ConvGeom
+    got = out_packed.cpu().numpy().view(np.uint32)            # [1][D][H][W][2][Wd]
+    d = case.act.shape[2]
+    if acc_slab is not None:
+        # an output plane z of the slab run equals the full run's when z + pad < planes (or the
+        # slab is the whole volume)
+        good = d if planes >= d else max(0, planes - case.pad[0] * case.dil[0])
+        want = oracle.pack(oracle.threshold(np.ascontiguousarray(acc_slab[:, :, :good]), case.lo, case.hi))
+        ok = bool(np.array_equal(got[:, :good], want))
+        return ok, f"{good} of {d} output planes, every voxel and channel, against oracle conv3d + threshold + pack"
+    rng = np.random.default_rng(0)
+    od, oh, ow = case.out_spatial
+    c_out = case.wgt.shape[0]
+    pts = np.stack([np.zeros(4096, np.int64), rng.integers(0, c_out, 4096), rng.integers(0, od, 4096),
+                    rng.integers(0, oh, 4096), rng.integers(0, ow, 4096)], axis=1).astype(np.int32)
+    acc = oracle.conv3d_points(case.act, case.wgt, ConvGeom(case.k, case.stride, case.pad, case.dil), pts)
+    code = np.where(acc > case.hi[pts[:, 1]], 1, np.where(acc < case.lo[pts[:, 1]], -1, 0))
+    w = got[0, pts[:, 2], pts[:, 3], pts[:, 4]]                # [P][2][Wd]
+    q, b = pts[:, 1] // 32, pts[:, 1] % 32
+    m = (w[np.arange(4096), 0, q] >> b.astype(np.uint32)) & 1
+    sg = (w[np.arange(4096), 1, q] >> b.astype(np.uint32)) & 1
+    got_code = np.where(m == 0, 0, np.where(sg == 1, -1, 1))
+    return bool(np.array_equal(got_code, code)), "4096 sampled outputs against oracle conv3d_points + Eq. 6"
 
 
 def conv_times(T, dev, c, steps=30, warmup=5):
@@ -144,21 +214,12 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
     ex["cfg2_fcn"]["layer_ms"] = per
     ms_in, _ = timed(lambda: T.tern_threshold_pack(x, ilo, ihi), 30, 5, None)
     ex["cfg2_fcn"]["input_threshold_pack_ms"] = ms_in
-    # the same encoder as a chain of tern_net_forward modules, on bit-counts and with int8 matrix
-    # banks on its two largest layers (2 and 3)
-    row = {}
-    for name, on_matrix in (("bitcount_ms", ()), ("matrix_i8_layers_2_3_ms", (1, 2))):
-        mods = []
-        for i, L in enumerate(f.layers):
-            w = dev(L["w"])
-            mods.append(T.NetModule(L["w"].shape[0], T.tern_pack_filters(w), dev(L["lo"]), dev(L["hi"]), k=L["k"],
-                                    stride=L["stride"], pad=L["pad"], dil=L["dil"],
-                                    matrix_bank=T.tern_expand_filters(w, "i8") if i in on_matrix else None,
-                                    matrix_kind="i8"))
-        ws_n = torch.empty((T.tern_net_workspace_bytes(x.shape, mods),), dtype=torch.uint8, device="cuda")
-        ms_n, _ = timed(lambda: T.tern_net_forward(x, ilo, ihi, mods, workspace=ws_n), 30, 5, None)
-        row[name] = ms_n
-    ex["cfg2_net_forward"] = row
+    # the same encoder as a chain of tern_net_forward modules
+    mods = [T.NetModule(L["w"].shape[0], T.tern_pack_filters(dev(L["w"])), dev(L["lo"]), dev(L["hi"]), k=L["k"],
+                        stride=L["stride"], pad=L["pad"], dil=L["dil"]) for L in f.layers]
+    ws_n = torch.empty((T.tern_net_workspace_bytes(x.shape, mods),), dtype=torch.uint8, device="cuda")
+    ms_n, _ = timed(lambda: T.tern_net_forward(x, ilo, ihi, mods, workspace=ws_n), 30, 5, None)
+    ex["cfg2_net_forward_ms"] = ms_n
 
     # The paper's baseline U-Net (Table 1) on synthetic weights, whole forward pass, for one
     # stack of slices and for a batch of 16 stacks.  MACs in the paper's convention (a pooled
@@ -191,17 +252,9 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
                                      "gmac_executed": executed / 1e9,
                                      "TMACs_executed": executed / (ms_u * 1e-3) / 1e12,
                                      "prediction_shape": list(pred.shape)}
-        if n == 16:
-            # the same network with its large modules on the matrix cores (not the paper's scheme)
-            plan_m = unet.UNetPlan(u.layers, u.head_w, u.head_b, u.in_lo, u.in_hi, matrix_kind="f4")
-            pred_m = unet.unet_forward(plan_m, ux).clone()
-            ms_m, _ = timed(lambda: unet.unet_forward(plan_m, ux, out=pred_m), 20, 3, None)
-            ex["unet_table1_n16_matrix_f4"] = {"ms": ms_m, "same_prediction": bool(torch.equal(pred_m, pred)),
-                                               "modules_on_matrix_cores": sum(
-                                                   1 for m in plan_m.modules(ux.shape) if m.matrix_bank is not None)}
-    # the other configurations through the matrix-core route
+    # the matrix-instruction experiment (include/tern_matrix.h), beside the contract's path
     c4 = {c.name: c for c in synth.config4_cases()}
-    for name, c in (("cfg3", synth.config3()), ("cfg4_k3_d1_pw0.5", c4["cfg4_k3_d1_pw0.5"]),
+    for name, c in (("cfg1", case), ("cfg3", synth.config3()), ("cfg4_k3_d1_pw0.5", c4["cfg4_k3_d1_pw0.5"]),
                     ("cfg4_k3_d3_pw0.5", c4["cfg4_k3_d3_pw0.5"])):
         ci, co = c.act.shape[1], c.wgt.shape[0]
         g = dict(k=c.k, stride=c.stride, pad=c.pad, dil=c.dil)
@@ -216,12 +269,48 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
     return ex
 
 
+def config_rows(T, synth, dev, peak_issue):
+    """One compact row per other BASELINE configuration (fused call, HBM-resident packed input)."""
+    import numpy as np
+    import torch
+    rows = {}
+
+    def row(c, steps=30):
+        f, a = conv_times(T, dev, c, steps=steps, warmup=3)
+        r = {"gmac": round(c.macs / 1e9, 3), "fused_ms": round(f, 5), "int32_out_ms": round(a, 5),
+             "TMACs": round(c.macs / (f * 1e-3) / 1e12, 2)}
+        if peak_issue:
+            r["issued_frac_of_measured_peak"] = round(ISSUED_OPS_PER_MAC * c.macs / (f * 1e-3) / peak_issue, 3)
+        return r
+
+    rows["config0"] = row(synth.config0(), steps=100)
+    f = synth.config2()
+    layers = [T.FcnLayer(L["w"].shape[1], L["w"].shape[0], T.tern_pack_filters(dev(L["w"])),
+                         dev(L["lo"]), dev(L["hi"]), L["k"], L["stride"], L["pad"], L["dil"])
+              for L in f.layers]
+    x, ilo, ihi = dev(f.x), dev(f.in_lo), dev(f.in_hi)
+    ws = torch.empty((T.tern_fcn_workspace_bytes(x.shape, layers),), dtype=torch.uint8, device="cuda")
+    out = T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws)
+    ms_fcn, _ = timed(lambda: T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws, out=out), 30, 3)
+    rows["config2"] = {"gmac": round(f.macs / 1e9, 3), "fused_ms": round(ms_fcn, 5),
+                       "TMACs": round(f.macs / (ms_fcn * 1e-3) / 1e12, 2),
+                       "what": "tern_fcn_forward: float input, Eq. 6, six fused layers"}
+    del x, ws, out, layers
+    rows["config3"] = row(synth.config3())
+    for c in synth.config4_cases():
+        if c.meta["p0_w"] == 0.5:
+            rows["config4_" + c.name[5:].replace("_pw0.5", "")] = row(c)
+    torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-configs", action="store_true", help="skip the rows of the other configurations")
     ap.add_argument("--extras", action="store_true", help="also time the other entry points")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference for HBM counters)")
@@ -265,25 +354,12 @@ def main():
     def step():
         T.tern_conv3d(act, c_in, bank, c_out, thr_lo=lo, thr_hi=hi, out=out_packed, **geom)
 
-    ms, wall_ms = timed(step, args.steps, args.warmup, None)
+    ms, wall_ms = timed(step, args.steps, args.warmup)
+    singles = per_launch(step, max(10, min(args.steps, 200)))
     macs = case.macs
     tmacs = macs / (ms * 1e-3) / 1e12
-    lane_ops = OPS_PER_MAC * macs / (ms * 1e-3)
-
-    result = {
-        "metric": "ternary MAC/s (TMAC/s) + ms per volume; % of int/popcount peak",
-        "value": tmacs, "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
-        "config": {"workload": "config[1]: fused ternary conv3d, N=1, C_in=C_out=64, 64^3, k=3^3, "
-                               "s=1, p=1, packed in -> packed out", "gmac": macs / 1e9,
-                   "wall_ms_per_step": wall_ms},
-        "roofline": {"bound": "alu", "achieved": lane_ops / 1e12, "peak": PEAK_LANE_OPS / 1e12,
-                     "unit": "T lane-op/s (algorithmic: 5 int32 VALU lane-ops per 32 MACs)",
-                     "frac": lane_ops / PEAK_LANE_OPS, "traffic": TRAFFIC_BYTES_CFG1,
-                     "algorithmic_bytes": ALGORITHMIC_BYTES_CFG1,
-                     "hbm_GBps": TRAFFIC_BYTES_CFG1 / (ms * 1e-3) / 1e9},
-    }
+    issued = ISSUED_OPS_PER_MAC * macs / (ms * 1e-3)
+    algorithmic = ALGORITHMIC_OPS_PER_MAC * macs / (ms * 1e-3)
 
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
@@ -292,47 +368,79 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # Sustained issue rate of the same instruction mix with no memory traffic (measured ceiling).
+    # Ceiling: the kernels' own instruction sequence in a register-only loop (no memory, four
+    # waves per SIMD), measured here and now; beside it the same four instructions with no scalar
+    # instruction between them, and a stream of one plain opcode (the nominal rate).
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-    p_blocks, p_threads, p_iters = 8192, 256, 2000
-    ms_probe, _ = timed(lambda: T.tern_probe_valu(p_blocks, p_threads, p_iters, sink), 3, 1, None)
-    probe_rate = p_blocks * p_threads * p_iters * 65.0 / (ms_probe * 1e-3)
-    result["roofline"]["measured_peak"] = probe_rate / 1e12
-    result["roofline"]["frac_of_measured_peak"] = (lane_ops / probe_rate) if probe_rate > 0 else None
-    result["roofline"]["issued_frac_of_measured_peak"] = (0.8 * lane_ops / probe_rate) if probe_rate > 0 else None
-    # the same instructions with no scalar instruction between them (what a compiler schedules)
-    ms_unspaced, _ = timed(lambda: T.tern_probe_valu(p_blocks, p_threads, p_iters, sink, 1), 3, 1, None)
-    result["roofline"]["measured_peak_unspaced"] = p_blocks * p_threads * p_iters * 65.0 / (ms_unspaced * 1e-3) / 1e12
+    p_blocks, p_threads, p_iters = 8192, 256, 1000
 
-    # The same convolution through the matrix instructions (tern_conv3d_mfma): not the paper's
-    # bit-count scheme, reported beside it.  Roofline: 2 operations per MAC against the dense
-    # matrix peak of the operand type.
-    step()
-    torch.cuda.synchronize()
-    result["mfma_route"] = {}
-    for kind, peak, dt in (("i8", PEAK_MFMA_I8, "int8 codes in LDS, int32 accumulate"),
-                           ("f4", PEAK_MFMA_F4, "4-bit float codes in LDS, float32 accumulate (exact integers)")):
-        m_bank = T.tern_expand_filters(dev(case.wgt), kind)
-        out_mfma = torch.empty_like(out_packed)
+    def probe_rate(variant):
+        ms_p, _ = timed(lambda: T.tern_probe_valu(p_blocks, p_threads, p_iters, sink, variant), 3, 1)
+        return p_blocks * p_threads * p_iters * 65.0 / (ms_p * 1e-3)
 
-        def step_mfma():
-            T.tern_conv3d(act, c_in, m_bank, c_out, thr_lo=lo, thr_hi=hi, out=out_mfma, mfma=kind, **geom)
+    peak = probe_rate(0)
+    result = {
+        "metric": "ternary MAC/s (TMAC/s) + ms per volume; % of int/popcount peak",
+        "value": tmacs, "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
+        "config": {"workload": "config[1]: fused ternary conv3d, N=1, C_in=C_out=64, 64^3, k=3^3, "
+                               "s=1, p=1, packed in -> packed out", "gmac": macs / 1e9,
+                   "wall_ms_per_step": wall_ms, "settle_ms_before_timing": SETTLE_MS},
+        "launch_ms": {"mean": ms, "median": statistics.median(singles), "min": min(singles),
+                      "single_launches": len(singles)},
+        "roofline": {
+            "bound": "alu", "achieved": issued / 1e12, "peak": peak / 1e12, "unit": "T lane-op/s",
+            "frac": issued / peak,
+            "basis": "achieved = 4 issued 32-bit vector lane-ops per 32 MACs (and, popcount-accumulate, "
+                     "three-input bit op, popcount-accumulate: the kernel's instructions per word pair) x "
+                     "MAC/s; peak = the same instruction sequence in a register-only loop, four waves per "
+                     "SIMD, measured in this run (tern_probe_valu variant 0)",
+            "nominal_peak": NOMINAL_LANE_OPS / 1e12,
+            "issued_frac_of_nominal_peak": issued / NOMINAL_LANE_OPS,
+            "algorithmic_5op": {"achieved": algorithmic / 1e12, "frac_of_nominal_peak": algorithmic / NOMINAL_LANE_OPS,
+                                "note": "the paper's five operations per word pair against 256 CU x 64 lanes x "
+                                        "2.4 GHz; above 1 because the kernel needs four instructions and "
+                                        "producer-popcount pairs issue faster than one instruction per four cycles"},
+            "traffic": TRAFFIC_BYTES_CFG1,
+            "traffic_basis": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel, profiles/conv3d_fused_config1.md "
+                             "(a profiler run of the same command, not this run)",
+            "algorithmic_bytes": ALGORITHMIC_BYTES_CFG1,
+            "hbm_GBps": TRAFFIC_BYTES_CFG1 / (ms * 1e-3) / 1e9,
+            "probe_T_lane_ops": {"kernel_sequence": peak / 1e12, "same_instructions_unspaced": probe_rate(1) / 1e12,
+                                 "v_and_b32_alone": probe_rate(2) / 1e12},
+        },
+    }
 
-        ms_m, _ = timed(step_mfma, args.steps, args.warmup, None)
-        ops = 2.0 * macs / (ms_m * 1e-3)
-        result["mfma_route"][kind] = {
-            "value": macs / (ms_m * 1e-3) / 1e12, "unit": "TMAC/s", "ms_per_step": ms_m, "dtype": dt,
-            "same_output_as_headline": bool(torch.equal(out_mfma, out_packed)),
-            "roofline": {"bound": "mfma", "achieved": ops / 1e12, "peak": peak / 1e12,
-                         "unit": "TOP/s (2 operations per MAC)", "frac": ops / peak,
-                         "traffic": TRAFFIC_BYTES_CFG1_MFMA[kind]}}
+    if not args.no_configs:
+        result["configs"] = config_rows(T, synth, dev, peak)
 
     if args.extras:
         result["extras"] = extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, geom)
 
+    # the timed call's output against the oracle
+    step()
+    torch.cuda.synchronize()
+    acc_slab, planes = None, 0
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(case)
+        result["cpu_baseline"], acc_slab, planes = cpu_baseline(case)
+        import oracle
+        c0 = synth.config0()
+        from oracle import ConvGeom
+        all_threads = oracle.max_threads()
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        oracle.conv3d(c0.act, c0.wgt, ConvGeom(c0.k, c0.stride, c0.pad, c0.dil))
+        dt0 = time.perf_counter() - t0
+        oracle.set_threads(all_threads)
+        result["cpu_baseline"]["config0_single_thread"] = {"seconds": dt0, "TMACs": c0.macs / dt0 / 1e12}
+    ok, how = check_against_oracle(case, out_packed, acc_slab, planes)
+    result["parity_checked"] = ok
+    result["parity_check"] = how
     print(json.dumps(result))
+    if not ok:
+        print("bench.py: the timed output differs from the oracle", file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

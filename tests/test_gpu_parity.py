@@ -63,6 +63,30 @@ def test_pack_unaligned_source_and_all_code_points(G):
     np.testing.assert_array_equal(got, oracle.pack(big))
 
 
+def tiled_ternary(c, spatial, seed, period=100003):
+    """[1][c][spatial] int8 ternary tensor for the large packer cases: a seeded block of `period`
+    voxels per channel (a prime, so that no power-of-two stride meets the same values) repeated
+    along the voxel axis; drawing hundreds of millions of values one by one would take minutes."""
+    base = synth.ternary((c, period), 0.4, seed, synth.T_ACT)
+    reps = -(-spatial // period)
+    return np.ascontiguousarray(np.tile(base, (1, reps))[:, :spatial]).reshape(1, c, spatial)
+
+
+# Every instantiation the packer's dispatch can select (voxels per thread x words held in
+# registers): 16 voxels per thread needs >= 4 194 304 voxels in multiples of 16 (int8 only); four
+# voxels per thread with all words in registers needs >= 262 144 voxels when there are four or
+# eight words (below that the words are split over threads).
+@pytest.mark.parametrize("c,vol", [(64, (128, 128, 256)), (128, (128, 128, 256)), (96, (128, 128, 256)),
+                                   (160, (64, 256, 256)), (128, (64, 64, 68)), (256, (64, 64, 68)),
+                                   (96, (64, 64, 68)), (64, (64, 64, 66))])
+def test_pack_large_inputs_reach_every_kernel_variant(G, c, vol):
+    import paper_1801_09449_amd as T
+    spatial = int(np.prod(vol))
+    x = tiled_ternary(c, spatial, 53 + c).reshape((1, c) + vol)
+    got = G.words(T.tern_pack(G.dev(x)))
+    np.testing.assert_array_equal(got, oracle.pack(x))
+
+
 # ---- a6: tern_threshold_pack ----------------------------------------------------------------
 @pytest.mark.parametrize("c,vol", [(3, (3, 5, 7)), (32, (4, 4, 4)), (45, (4, 6, 8)), (64, (5, 5, 5))])
 def test_threshold_pack_i32(G, c, vol):
@@ -92,6 +116,38 @@ def test_threshold_pack_f32_eq6_and_ties(G):
     x.reshape(-1)[:6] = [0.5, -0.5, np.nextafter(np.float32(0.5), np.float32(1)),
                          np.nextafter(np.float32(-0.5), np.float32(-1)), np.nan, 0.0]
     lo = np.full(3, -0.5, np.float32); hi = np.full(3, 0.5, np.float32)
+    got = G.words(T.tern_threshold_pack(G.dev(x), G.dev(lo), G.dev(hi)))
+    np.testing.assert_array_equal(got, oracle.pack(oracle.threshold(x, lo, hi)))
+
+
+@pytest.mark.parametrize("c,vol", [(64, (64, 64, 64)), (128, (64, 64, 68)), (256, (32, 64, 136)), (96, (40, 64, 64))])
+def test_threshold_pack_i32_at_full_size(G, c, vol):
+    """config[1]'s accumulator tensor size (64 channels on 64^3) and the four- and eight-word
+    variants above the size where words are no longer split over threads; values spread like
+    accumulators (within +-40), cut points in [-8, 8]."""
+    import paper_1801_09449_amd as T
+    spatial = int(np.prod(vol))
+    period = 100003
+    base = synth.uniform_int(c * period, -40, 40, 59 + c, synth.T_ACT).astype(np.int32).reshape(c, period)
+    v = np.ascontiguousarray(np.tile(base, (1, -(-spatial // period)))[:, :spatial]).reshape((1, c) + vol)
+    lo, hi = synth.threshold_pair(c, 59 + c)
+    got = G.words(T.tern_threshold_pack(G.dev(v), G.dev(lo), G.dev(hi)))
+    np.testing.assert_array_equal(got, oracle.pack(oracle.threshold(v, lo, hi)))
+
+
+@pytest.mark.parametrize("c,vol", [(64, (64, 64, 64)), (256, (32, 64, 136)), (1, (128, 128, 64))])
+def test_threshold_pack_f32_at_full_size(G, c, vol):
+    """The float source at config[1]'s tensor size, with eight words per plane, and at
+    config[2]'s input size (one channel of 128 x 128 x 64 intensities at +-0.5, Eq. 6)."""
+    import paper_1801_09449_amd as T
+    spatial = int(np.prod(vol))
+    period = 100003
+    base = synth.gaussian((c, period), 61 + c, synth.T_F32)
+    x = np.ascontiguousarray(np.tile(base, (1, -(-spatial // period)))[:, :spatial]).reshape((1, c) + vol)
+    u = synth.uniform01(2 * c, 61 + c, synth.T_THR).reshape(c, 2).astype(np.float32)
+    lo, hi = -0.25 - u[:, 0], 0.25 + u[:, 1]
+    if c == 1:
+        lo, hi = np.array([-0.5], np.float32), np.array([0.5], np.float32)
     got = G.words(T.tern_threshold_pack(G.dev(x), G.dev(lo), G.dev(hi)))
     np.testing.assert_array_equal(got, oracle.pack(oracle.threshold(x, lo, hi)))
 
@@ -338,16 +394,29 @@ def test_config3_reduced_full_and_full_size_sampled(G):
     check_sampled(G, synth.config3())
 
 
+def test_config3_full_size_every_output(G):
+    """All 33.5 M accumulators and codes of config[3] against the oracle (116 GMAC of scalar
+    work on the host cores: some tens of seconds)."""
+    check_case(G, synth.config3())
+
+
 def test_config4_reduced_full(G):
     for c in synth.config4_cases(vol=(12, 13, 20)):
         check_case(G, c)
 
 
 def test_config4_full_size_sampled(G):
+    """All twelve cases of the sweep at 96^3 (the oracle evaluates the sampled outputs only)."""
     cases = synth.config4_cases()
+    assert len(cases) == 12
     for c in cases:
-        if c.name in ("cfg4_k3_d1_pw0.5", "cfg4_k3_d3_pw0.7", "cfg4_k3_d2_pw0.3", "cfg4_k1_pw0.5"):
-            check_sampled(G, c, count=8000)
+        check_sampled(G, c, count=8000)
+
+
+def test_config4_pointwise_full_size_every_output(G):
+    """The 1^3 case at 96^3 element by element (3.6 GMAC for the oracle)."""
+    c = [c for c in synth.config4_cases() if c.name == "cfg4_k1_pw0.5"][0]
+    check_case(G, c)
 
 
 def fcn_run(G, f):
