@@ -304,6 +304,27 @@ def config_rows(T, synth, dev, peak_issue):
     return rows
 
 
+def binary_row(T, synth, dev, probe_rate):
+    """The binary special case (Eq. 8) at config[1]'s shape on inputs without zeros: two issued
+    vector instructions per word pair against the rate of that pair in a register-only loop."""
+    import torch
+    c = synth.conv_case("cfg1_binary", 1, 64, 64, 64, p0_w=0.0, p0_a=0.0, seed=0, thr_range=(-24, 24))
+    a = T.tern_pack(dev(c.act))
+    bank = T.tern_pack_filters_binary(dev(c.wgt))
+    lo, hi = dev(c.lo), dev(c.hi)
+    out = T.tern_conv3d_binary(a, 64, bank, 64, thr_lo=lo, thr_hi=hi)
+    ms, _ = timed(lambda: T.tern_conv3d_binary(a, 64, bank, 64, thr_lo=lo, thr_hi=hi, out=out), 100, 5)
+    peak = probe_rate(10)
+    issued = (2.0 / 32.0) * c.macs / (ms * 1e-3)
+    torch.cuda.synchronize()
+    return {"workload": "tern_conv3d_binary, config[1]'s shape, +-1 weights and activations, fused cut points",
+            "gmac": round(c.macs / 1e9, 3), "fused_ms": round(ms, 5), "TMACs": round(c.macs / (ms * 1e-3) / 1e12, 2),
+            "roofline": {"bound": "alu", "achieved": issued / 1e12, "peak": peak / 1e12, "unit": "T lane-op/s",
+                         "frac": issued / peak,
+                         "basis": "2 issued vector lane-ops per 32 MACs (three-input bit op, popcount-accumulate) "
+                                  "against the same pair in a register-only loop (tern_probe_valu variant 10)"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -414,6 +435,7 @@ def main():
 
     if not args.no_configs:
         result["configs"] = config_rows(T, synth, dev, peak)
+        result["binary_eq8"] = binary_row(T, synth, dev, probe_rate)
 
     if args.extras:
         result["extras"] = extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, geom)

@@ -139,6 +139,35 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims,
                 int32_t* out_acc, uint32_t* out_packed, void* stream);
 
 /*
+ * tern_pack_filters_binary / tern_conv3d_binary -- the binary special case, Eq. 8: with weights
+ * and activations in {-1, +1} the inner product of c-element vectors is c - 2 * popcount(I xor W),
+ * one xor and one bit count per word pair instead of the two of each that Eq. 9 needs.
+ *
+ * tern_conv3d_binary is tern_conv3d for filters without zeros.  The activations come in the same
+ * packed layout and their mask plane is honoured, so that zero padding (the ternary value 0) and
+ * any zero code drop out exactly as in Eq. 9:
+ *   acc[n][co][z][y][x] = sum over taps and channel words of
+ *        popcount(mask_a) - 2 * popcount(mask_a & (sign_a ^ sign_w)),
+ * which for an input without zeros, away from the padded border, is Eq. 8 with c = k-volume *
+ * C_in, and in general equals the integer inner product of the ternary patch with the +-1 filter.
+ * Output modes, cut points, limits and errors as for tern_conv3d (cut points with lo = hi + 1 give
+ * an output without zeros, i.e. the sign activation of a binary network).
+ *   w      : int8 [C_out][C_in][kd][kh][kw] with values -1 / +1 (not checked: a negative byte is
+ *            read as -1, anything else, 0 included, as +1).
+ *   bank   : tern_binary_bank_bytes(...) bytes, 16-byte aligned: uint32 [T * nchunk][co_pad][wc]
+ *            sign words (T, nchunk, wc, co_pad as for the ternary filter bank, always the plain
+ *            layout); bit j of word q is set where the weight of input channel 32q + j is -1;
+ *            filters co >= C_out and channels >= C_in are zero.
+ */
+size_t tern_binary_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw);
+int tern_pack_filters_binary(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                             int32_t kw, uint32_t* bank, void* stream);
+int tern_conv3d_binary(const uint32_t* in_packed, tern_dims in_dims,
+                       const uint32_t* w_bank, int32_t c_out, tern_conv_geom g,
+                       const int32_t* thr_lo, const int32_t* thr_hi,
+                       int32_t* out_acc, uint32_t* out_packed, void* stream);
+
+/*
  * tern_threshold_pack -- the hard ternary activation of Eq. 6 followed by 2-bit packing, on a
  * tensor that is already in memory:  code = +1 if v > hi[c]; -1 if v < lo[c]; else 0.
  *   src    : contiguous [N][C][D][H][W] of type t (TERN_SRC_I32: int32 accumulators with int32

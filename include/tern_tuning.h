@@ -46,7 +46,8 @@ int tern_set_option(int option, int value);
  *    2, 4, 6, 8, 12   one opcode alone: v_and_b32, v_bcnt_u32_b32, v_bitop3_b32, v_xor_b32,
  *       v_add_u32 (the last for reference);  3, 5, 7, 9, 13  the same with s_nop 0 behind every
  *       vector instruction;
- *   10  the word pair of the binary convolution (xor, s_nop 0, popcount-accumulate), 32 pairs;
+ *   10  the word pair of the binary convolution (three-input bit operation, s_nop 0, popcount-
+ *       accumulate), 32 pairs;
  *   11  the same without the no-op.
  * sink: device int32[1] (practically never written).  threads: multiple of 64, at most 512.
  * TERN_EARG for anything else.

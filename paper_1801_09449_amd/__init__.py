@@ -11,6 +11,9 @@ from .binding import (  # noqa: F401
     lib_path,
     tern_concat,
     tern_conv3d,
+    tern_conv3d_binary,
+    tern_pack_filters_binary,
+    tern_binary_bank_bytes,
     tern_count_codes,
     tern_conv3d_real,
     tern_fold_avgpool,

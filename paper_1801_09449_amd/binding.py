@@ -78,6 +78,9 @@ def lib():
     L.tern_pack_filters.argtypes = [P, I, I, I, I, I, P, P]; L.tern_pack_filters.restype = C.c_int
     L.tern_conv3d.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d.restype = C.c_int
     L.tern_conv3d_digits.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d_digits.restype = C.c_int
+    L.tern_binary_bank_bytes.argtypes = [I] * 5; L.tern_binary_bank_bytes.restype = S
+    L.tern_pack_filters_binary.argtypes = [P, I, I, I, I, I, P, P]; L.tern_pack_filters_binary.restype = C.c_int
+    L.tern_conv3d_binary.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d_binary.restype = C.c_int
     L.tern_conv3d_mfma.argtypes = [P, Dims, P, I, I, Geom, P, P, P, P, P]; L.tern_conv3d_mfma.restype = C.c_int
     L.tern_matrix_bank_bytes.argtypes = [I] * 6; L.tern_matrix_bank_bytes.restype = S
     L.tern_conv3d_mfma_digits.argtypes = [P, Dims, P, I, Geom, P, P, P, P, P]; L.tern_conv3d_mfma_digits.restype = C.c_int
@@ -226,6 +229,37 @@ def tern_pack_filters(w: torch.Tensor, out: Optional[torch.Tensor] = None) -> to
     return out
 
 
+def tern_binary_bank_bytes(c_out: int, c_in: int, k) -> int:
+    kd, kh, kw = _t3(k)
+    return int(lib().tern_binary_bank_bytes(int(c_out), int(c_in), kd, kh, kw))
+
+
+def tern_pack_filters_binary(w: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """int8 weights in {-1, +1} [C_out][C_in][kd][kh][kw] -> binary filter bank (flat int32 tensor)."""
+    _dev(w, torch.int8, "w")
+    if w.dim() != 5:
+        raise ValueError("w must be [C_out][C_in][kd][kh][kw]")
+    co, ci, kd, kh, kw = (int(x) for x in w.shape)
+    nbytes = tern_binary_bank_bytes(co, ci, (kd, kh, kw))
+    if nbytes == 0:
+        raise TernError(-2, "tern_pack_filters_binary")
+    if out is None:
+        out = torch.empty((nbytes // 4,), dtype=PACKED_DTYPE, device=w.device)
+    _dev(out, PACKED_DTYPE, "out")
+    if out.numel() * 4 != nbytes:
+        raise ValueError("out has the wrong size")
+    _check(lib().tern_pack_filters_binary(_ptr(w), co, ci, kd, kh, kw, _ptr(out), _stream(w)),
+           "tern_pack_filters_binary")
+    return out
+
+
+def tern_conv3d_binary(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out: int,
+                       k=3, stride=1, pad=1, dil=1, thr_lo: Optional[torch.Tensor] = None,
+                       thr_hi: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """tern_conv3d with the binary filter bank of tern_pack_filters_binary (Eq. 8)."""
+    return tern_conv3d(in_packed, c_in, w_bank, c_out, k, stride, pad, dil, thr_lo, thr_hi, out, binary=True)
+
+
 MATRIX_KINDS = {"i8": 0, "f4": 1}
 
 
@@ -258,7 +292,7 @@ def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out:
                 k=3, stride=1, pad=1, dil=1,
                 thr_lo: Optional[torch.Tensor] = None, thr_hi: Optional[torch.Tensor] = None,
                 out: Optional[torch.Tensor] = None, digits: bool = False,
-                mfma=False) -> torch.Tensor:
+                mfma=False, binary: bool = False) -> torch.Tensor:
     """Ternary convolution.  Without cut points: int32 accumulators [N][C_out][Do][Ho][Wo].
     With thr_lo / thr_hi (int32 [C_out]): fused activation + re-pack, packed output.
     digits=True: in_packed is the two-digit tensor of tern_pool_digits (c_in = its channel count,
@@ -266,7 +300,11 @@ def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out:
     mfma="i8" / "f4" (True = "i8"): w_bank is the bank of tern_expand_filters for that kind
     (tern_conv3d_mfma)."""
     kind = "i8" if mfma is True else mfma
-    if digits and mfma:
+    if binary and (digits or mfma):
+        raise ValueError("binary filters go with neither digits nor mfma")
+    if binary:
+        entry = lib().tern_conv3d_binary
+    elif digits and mfma:
         if kind != "f4":
             raise ValueError("two-digit inputs go through the 4-bit kind")
         entry = lib().tern_conv3d_mfma_digits
@@ -283,7 +321,9 @@ def tern_conv3d(in_packed: torch.Tensor, c_in: int, w_bank: torch.Tensor, c_out:
     in_dims = Dims(n, int(c_in), d, h, w)
     g = _geom(k, stride, pad, dil)
     kk = (g.k[0], g.k[1], g.k[2])
-    if digits and mfma:      # the bank of the undoubled weights: half the digit tensor's channels
+    if binary:
+        need = tern_binary_bank_bytes(c_out, c_in, kk)
+    elif digits and mfma:      # the bank of the undoubled weights: half the digit tensor's channels
         need = tern_matrix_bank_bytes(c_out, c_in // 2, kk, kind)
     else:
         need = tern_matrix_bank_bytes(c_out, c_in, kk, kind) if mfma else tern_filter_bank_bytes(c_out, c_in, kk)

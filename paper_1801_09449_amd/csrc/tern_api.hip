@@ -106,6 +106,7 @@ static ConvParams conv_params(const uint32_t* in_packed, const tern_dims& in_dim
     p.tp_slots = bs.tp_slots;
     p.tp_shift = bs.tp_shift;
     p.digits = 0;
+    p.binary = 0;
     return p;
 }
 
@@ -243,6 +244,42 @@ int tern_conv3d(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_
 
     const ConvParams p = conv_params(in_packed, in_dims, w_bank, c_out, g, o, thr_lo, thr_hi, out_acc,
                                      out_packed);
+    return launch_conv3d(p, (hipStream_t)stream);
+}
+
+size_t tern_binary_bank_bytes(int32_t c_out, int32_t c_in, int32_t kd, int32_t kh, int32_t kw)
+{
+    if (!filter_shape_ok(c_out, c_in, kd, kh, kw)) return 0;
+    const size_t co_pad = (size_t)(c_out + 31) / 32 * 32;
+    return (size_t)kd * kh * kw * (size_t)tern_words(c_in) * co_pad * sizeof(uint32_t);
+}
+
+int tern_pack_filters_binary(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                             int32_t kw, uint32_t* bank, void* stream)
+{
+    if (!w || !bank) return TERN_ENULL;
+    if (!filter_shape_ok(c_out, c_in, kd, kh, kw)) return TERN_ESHAPE;
+    if (!aligned16(bank)) return TERN_EARG;
+    return launch_pack_filters_binary(w, c_out, c_in, kd, kh, kw, bank, (hipStream_t)stream);
+}
+
+int tern_conv3d_binary(const uint32_t* in_packed, tern_dims in_dims, const uint32_t* w_bank,
+                       int32_t c_out, tern_conv_geom g, const int32_t* thr_lo, const int32_t* thr_hi,
+                       int32_t* out_acc, uint32_t* out_packed, void* stream)
+{
+    if (!in_packed || !w_bank) return TERN_ENULL;
+    if ((out_acc == nullptr) == (out_packed == nullptr)) return TERN_EARG;
+    if (out_packed && (!thr_lo || !thr_hi)) return TERN_ENULL;
+    tern_dims o;
+    int rc = geom_check(in_dims, c_out, g, &o);
+    if (rc != TERN_OK) return rc;
+    if (!aligned16(in_packed) || !aligned16(w_bank)) return TERN_EARG;
+    if (out_packed && !aligned16(out_packed)) return TERN_EARG;
+    if (out_acc && ((uintptr_t)out_acc & 3u)) return TERN_EARG;
+    ConvParams p = conv_params(in_packed, in_dims, w_bank, c_out, g, o, thr_lo, thr_hi, out_acc, out_packed);
+    p.binary = 1;
+    p.tp_slots = 0;    // the binary bank has the plain layout whatever C_in is
+    p.tp_shift = 0;
     return launch_conv3d(p, (hipStream_t)stream);
 }
 

@@ -319,5 +319,117 @@ __device__ __forceinline__ void mac_group(const ActChunk<WC> (&A)[V], const WGro
         mac_quad<WC, V, CO_BLK, KG, INIT>(A, g, jg, j0, acc_m, acc_n, t[k & 1]);
 }
 
+
+// ---- binary weights (Eq. 8) --------------------------------------------------------------------
+// With weights in {-1, +1} the filter has no mask plane: a group is KG channels x WC sign words.
+template <int WC, int KG>
+struct WGroupB {
+    uint32_t s[KG][WC];
+};
+
+// Binary filter bank: [step][co_pad][WC] sign words, the channels of a step contiguous.
+template <int WC, int KG>
+__device__ __forceinline__ void load_wgroup(WGroupB<WC, KG>& g, scalar_ptr wp)
+{
+#pragma unroll
+    for (int j = 0; j < KG; ++j)
+#pragma unroll
+        for (int q = 0; q < WC; ++q) g.s[j][q] = wp[j * WC + q];
+}
+
+template <int WC, int KG>
+__device__ __forceinline__ void settle(const WGroupB<WC, KG>& g)
+{
+    static_assert(KG % 8 == 0, "groups of 8 channels per asm statement");
+#pragma unroll
+    for (int j = 0; j < KG; j += 8) {
+        if constexpr (WC == 2) {
+            asm volatile("" ::"s"(g.s[j][0]), "s"(g.s[j][1]), "s"(g.s[j + 1][0]), "s"(g.s[j + 1][1]),
+                         "s"(g.s[j + 2][0]), "s"(g.s[j + 2][1]), "s"(g.s[j + 3][0]), "s"(g.s[j + 3][1]),
+                         "s"(g.s[j + 4][0]), "s"(g.s[j + 4][1]), "s"(g.s[j + 5][0]), "s"(g.s[j + 5][1]),
+                         "s"(g.s[j + 6][0]), "s"(g.s[j + 6][1]), "s"(g.s[j + 7][0]), "s"(g.s[j + 7][1]));
+        } else {
+            asm volatile("" ::"s"(g.s[j][0]), "s"(g.s[j + 1][0]), "s"(g.s[j + 2][0]), "s"(g.s[j + 3][0]),
+                         "s"(g.s[j + 4][0]), "s"(g.s[j + 5][0]), "s"(g.s[j + 6][0]), "s"(g.s[j + 7][0]));
+        }
+    }
+}
+
+// Eq. 8 with the activation's mask kept: for one (word pair, voxel) acc_n += popcount(ma & (sa ^
+// sw)) -- one three-input bit operation (the same truth table as in the ternary step, with the
+// activation mask in the place of M) and one popcount-accumulate, a scalar no-op between them.
+// The other half of the sum, popcount(ma), does not depend on the filter and is counted once
+// per voxel and step by the caller.  A zero activation (zero padding included) drops out
+// through its mask exactly as in Eq. 9; with no zeros the result is c - 2 popcount(I xor W).
+#define TERN_BIN_PAIR(P, C, ADD_N)                                                  \
+    "v_bitop3_b32 %[t], %[sa" P "], %[ma" P "], %[sw" P "] bitop3:0x48\n\t"        \
+    "s_nop 0\n\t"                                                                  \
+    "v_bcnt_u32_b32 %[an" C "], %[t], " ADD_N "\n\t"
+#define TERN_BIN_IN(P, MA, SA, SW) [ma##P] "v"(MA), [sa##P] "v"(SA), [sw##P] "s"(SW)
+
+template <int WC, int V, int CO_BLK, int KG, bool SET>
+__device__ __forceinline__ void mac_quad_bin(const ActChunk<WC> (&A)[V], const WGroupB<WC, KG>& g, int jg, int j0,
+                                             int32_t (&acc_n)[V][CO_BLK], uint32_t& t)
+{
+    static_assert(V == 1 || V == 2 || V == 4, "four (channel, voxel) combinations per statement");
+    static_assert(WC == 1 || WC == 2, "one or two words per chunk");
+#define TERN_C(P) (jg + (P) / V)
+#define TERN_X(P) ((P) % V)
+#define TERN_ACC_SET(C) [an##C] "=&v"(acc_n[TERN_X(C)][j0 + TERN_C(C)])
+#define TERN_ACC_ADD(C) [an##C] "+v"(acc_n[TERN_X(C)][j0 + TERN_C(C)])
+#define TERN_INS(P, C, Q) TERN_BIN_IN(P, A[TERN_X(C)].m[Q], A[TERN_X(C)].s[Q], g.s[TERN_C(C)][Q])
+#define TERN_WORD0_SET TERN_BIN_PAIR("0", "0", "0") TERN_BIN_PAIR("1", "1", "0") TERN_BIN_PAIR("2", "2", "0") \
+                       TERN_BIN_PAIR("3", "3", "0")
+#define TERN_WORD0_ADD TERN_BIN_PAIR("0", "0", "%[an0]") TERN_BIN_PAIR("1", "1", "%[an1]") \
+                       TERN_BIN_PAIR("2", "2", "%[an2]") TERN_BIN_PAIR("3", "3", "%[an3]")
+#define TERN_WORD1_ADD TERN_BIN_PAIR("4", "0", "%[an0]") TERN_BIN_PAIR("5", "1", "%[an1]") \
+                       TERN_BIN_PAIR("6", "2", "%[an2]") TERN_BIN_PAIR("7", "3", "%[an3]")
+    if constexpr (WC == 2) {
+        if constexpr (SET) {
+            asm volatile(TERN_WORD0_SET TERN_WORD1_ADD
+                         : TERN_ACC_SET(0), TERN_ACC_SET(1), TERN_ACC_SET(2), TERN_ACC_SET(3), [t] "+v"(t)
+                         : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0),
+                           TERN_INS(4, 0, 1), TERN_INS(5, 1, 1), TERN_INS(6, 2, 1), TERN_INS(7, 3, 1));
+        } else {
+            asm volatile(TERN_WORD0_ADD TERN_WORD1_ADD
+                         : TERN_ACC_ADD(0), TERN_ACC_ADD(1), TERN_ACC_ADD(2), TERN_ACC_ADD(3), [t] "+v"(t)
+                         : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0),
+                           TERN_INS(4, 0, 1), TERN_INS(5, 1, 1), TERN_INS(6, 2, 1), TERN_INS(7, 3, 1));
+        }
+    } else {
+        if constexpr (SET) {
+            asm volatile(TERN_WORD0_SET
+                         : TERN_ACC_SET(0), TERN_ACC_SET(1), TERN_ACC_SET(2), TERN_ACC_SET(3), [t] "+v"(t)
+                         : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0));
+        } else {
+            asm volatile(TERN_WORD0_ADD
+                         : TERN_ACC_ADD(0), TERN_ACC_ADD(1), TERN_ACC_ADD(2), TERN_ACC_ADD(3), [t] "+v"(t)
+                         : TERN_INS(0, 0, 0), TERN_INS(1, 1, 0), TERN_INS(2, 2, 0), TERN_INS(3, 3, 0));
+        }
+    }
+#undef TERN_C
+#undef TERN_X
+#undef TERN_ACC_SET
+#undef TERN_ACC_ADD
+#undef TERN_INS
+#undef TERN_WORD0_SET
+#undef TERN_WORD0_ADD
+#undef TERN_WORD1_ADD
+}
+
+// Two VALU instructions per (word pair, voxel).  INIT: the accumulators hold nothing yet.
+template <int WC, int V, int CO_BLK, int KG, bool INIT = false>
+__device__ __forceinline__ void mac_group_bin(const ActChunk<WC> (&A)[V], const WGroupB<WC, KG>& g, int j0,
+                                              int32_t (&acc_n)[V][CO_BLK])
+{
+    constexpr int NCB = V == 4 ? 1 : 4 / V;   // channels per statement
+    static_assert(KG % NCB == 0, "whole statements");
+    uint32_t t[2];
+    asm volatile("" : "=v"(t[0]), "=v"(t[1]));
+#pragma unroll
+    for (int jg = 0, k = 0; jg < KG; jg += NCB, ++k)
+        mac_quad_bin<WC, V, CO_BLK, KG, INIT>(A, g, jg, j0, acc_n, t[k & 1]);
+}
+
 }  // namespace
 }  // namespace tern

@@ -2,7 +2,8 @@
 // than LDS).  One thread computes one accumulator (int32 output) or one 32-channel output word
 // pair (packed output) straight from global memory.  Slow but general; same arithmetic as the
 // tiled kernel: Eq. 9 as popcount(M) - 2*popcount(M & X), M = mask_w & mask_a,
-// X = sign_w ^ sign_a, out-of-volume voxels contributing nothing.
+// X = sign_w ^ sign_a, out-of-volume voxels contributing nothing; with binary filters (Eq. 8)
+// M = mask_a.
 #include "tern_internal.h"
 
 namespace tern {
@@ -36,6 +37,16 @@ __device__ __forceinline__ int32_t dot_at(const ConvParams& p, int n, int co, in
                     const uint32_t N = M & (av[1] ^ (wv[1] >> sh));
                     acc_m += __builtin_popcount(M);
                     acc_n += __builtin_popcount(N);
+                    continue;
+                }
+                if (p.binary) {
+                    // binary filter bank: [tap * nchunk + chunk][co_pad][wc] sign words; every
+                    // nonzero activation counts, against the filter's sign (Eq. 8)
+                    for (int q = 0; q < Wd; ++q) {
+                        const uint32_t sw = p.wgt[((size_t)(tap * nchunk + q / wc) * p.co_pad + co) * wc + q % wc];
+                        acc_m += __builtin_popcount(av[q]);
+                        acc_n += __builtin_popcount(av[q] & (av[Wd + q] ^ sw));
+                    }
                     continue;
                 }
                 for (int q = 0; q < Wd; ++q) {

@@ -149,48 +149,75 @@ __device__ __forceinline__ void fetch_step(ActChunk<WC> (&A)[V], StepCursor& c, 
     }
 }
 
+// Filter-word group of a kernel variant: ternary filters carry mask and sign words (2 WC words per
+// channel in the bank), binary filters sign words only (WC words per channel, eight channels per
+// group: sixteen SGPRs at most).
+template <int WC, int CO_BLK, bool BIN>
+struct GroupType {
+    static constexpr int KG = GroupOf<CO_BLK>::value;
+    static constexpr int CW = 2 * WC;   // bank words per channel and step
+    using type = WGroup<WC, KG>;
+};
+template <int WC, int CO_BLK>
+struct GroupType<WC, CO_BLK, true> {
+    static constexpr int KG = 8;
+    static constexpr int CW = WC;
+    using type = WGroupB<WC, KG>;
+};
+
 // One step: accumulate CO_BLK channels from A0 (this step's activations) while fetching the next
 // step's activations into A1.  Software pipeline: while a channel group is being accumulated,
 // the scalar loads of the following group and the LDS reads of the next step are in flight.
 // INIT marks the first step of a pass, which sets the accumulators instead of adding to them.
 // DIG: two-digit input, the odd word of a chunk goes to the second accumulator set.
-template <int WC, int V, int CO_BLK, bool TP, bool DIG, bool INIT = false, typename Acc2>
+// BIN: binary filters (Eq. 8): only acc_n is used, and cnt collects popcount(mask_a) per voxel.
+template <int WC, int V, int CO_BLK, bool TP, bool DIG, bool BIN, bool INIT = false, typename Acc2>
 __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<WC> (&A1)[V], bool last,
                                           StepCursor& cur, const StepConsts& sc, int inc_c, int inc_b,
-                                          int inc_a, WGroup<WC, GroupOf<CO_BLK>::value>& g0,
-                                          WGroup<WC, GroupOf<CO_BLK>::value>& g1, scalar_ptr& wcur,
+                                          int inc_a, typename GroupType<WC, CO_BLK, BIN>::type& g0,
+                                          typename GroupType<WC, CO_BLK, BIN>::type& g1, scalar_ptr& wcur,
                                           const uint32_t* lane_lds,
                                           int32_t (&acc_m)[V][CO_BLK], int32_t (&acc_n)[V][CO_BLK],
-                                          Acc2& acc2_m, Acc2& acc2_n)
+                                          Acc2& acc2_m, Acc2& acc2_n, int32_t (&cnt)[V])
 {
-    constexpr int KG = GroupOf<CO_BLK>::value;
+    using GT = GroupType<WC, CO_BLK, BIN>;
+    constexpr int KG = GT::KG;
+    constexpr int CW = GT::CW;
     constexpr int NG = CO_BLK / KG;
     // after a wave's last step the prefetches re-read the same (valid) addresses and are dropped
     scalar_ptr wnext = last ? wcur : wcur + sc.step_words;
+    if constexpr (BIN) {
+#pragma unroll
+        for (int v = 0; v < V; ++v)
+#pragma unroll
+            for (int q = 0; q < WC; ++q) cnt[v] += __builtin_popcount(A0[v].m[q]);
+    }
 #pragma unroll
     for (int gi = 0; gi < NG; gi += 2) {
         settle<WC, KG>(g0);
         __builtin_amdgcn_sched_barrier(0);
         // issued behind the wait so that the LDS reads complete under the first group's arithmetic
         if (gi == 0) fetch_step<WC, V, TP>(A1, cur, sc, inc_c, inc_b, inc_a, lane_lds, !last);
-        load_wgroup<WC, KG>(g1, wcur + (gi + 1) * KG * 2 * WC);
+        load_wgroup<WC, KG>(g1, wcur + (gi + 1) * KG * CW);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (DIG) mac_group_digits<V, CO_BLK, KG, INIT>(A0, g0, gi * KG, acc_m, acc_n, acc2_m, acc2_n);
+        if constexpr (BIN) mac_group_bin<WC, V, CO_BLK, KG, INIT>(A0, g0, gi * KG, acc_n);
+        else if constexpr (DIG) mac_group_digits<V, CO_BLK, KG, INIT>(A0, g0, gi * KG, acc_m, acc_n, acc2_m, acc2_n);
         else mac_group<WC, V, CO_BLK, KG, INIT>(A0, g0, gi * KG, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
         settle<WC, KG>(g1);
         __builtin_amdgcn_sched_barrier(0);
-        if (gi + 2 < NG) load_wgroup<WC, KG>(g0, wcur + (gi + 2) * KG * 2 * WC);
+        if (gi + 2 < NG) load_wgroup<WC, KG>(g0, wcur + (gi + 2) * KG * CW);
         else load_wgroup<WC, KG>(g0, wnext);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (DIG) mac_group_digits<V, CO_BLK, KG, INIT>(A0, g1, (gi + 1) * KG, acc_m, acc_n, acc2_m, acc2_n);
+        if constexpr (BIN) mac_group_bin<WC, V, CO_BLK, KG, INIT>(A0, g1, (gi + 1) * KG, acc_n);
+        else if constexpr (DIG) mac_group_digits<V, CO_BLK, KG, INIT>(A0, g1, (gi + 1) * KG, acc_m, acc_n, acc2_m, acc2_n);
         else mac_group<WC, V, CO_BLK, KG, INIT>(A0, g1, (gi + 1) * KG, acc_m, acc_n);
         __builtin_amdgcn_sched_barrier(0);
     }
     wcur = wnext;
 }
 
-template <int WC, int V, int CO_BLK, bool PACKED, bool TP, bool DIG = false>
+template <int WC, int V, int CO_BLK, bool PACKED, bool TP, bool DIG = false, bool BIN = false>
 __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, TileParams t)
 {
     extern __shared__ __align__(16) uint32_t lds[];
@@ -368,7 +395,10 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     const int inc_c = p.dw * t.vstride;
     const int inc_b = p.dh * row_words - (p.kw - 1) * inc_c;
     const int inc_a = p.dd * plane_words - (p.kh - 1) * p.dh * row_words - (p.kw - 1) * inc_c;
-    sc.step_words = p.co_pad * 2 * WC;
+    using GT = GroupType<WC, CO_BLK, BIN>;
+    constexpr int CW = GT::CW;
+    static_assert(!BIN || (!TP && !DIG), "binary filters use the plain bank layout and one-digit inputs");
+    sc.step_words = p.co_pad * CW;
     sc.vstep = vstep;
     sc.slots = p.tp_slots; sc.shift = p.tp_shift;
     sc.slot_mask = TP ? ((1u << p.c_in) - 1u) : 0xffffffffu;
@@ -385,7 +415,7 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
         const int ta = r / p.kh;
         cur0.toff = ta * p.dd * plane_words + cur0.tb * p.dh * row_words + cur0.tc * inc_c;
     }
-    constexpr int KG = GroupOf<CO_BLK>::value;
+    constexpr int KG = GT::KG;
     constexpr int NG = CO_BLK / KG;
     static_assert(NG >= 2 && NG % 2 == 0, "CO_BLK must be a multiple of twice the group size");
     static_assert(CO_BLK <= 32 && 32 % CO_BLK == 0, "CO_BLK must divide 32");
@@ -406,30 +436,34 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
             int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];   // set by the pass's first step
             // second set for the high digits of a two-digit input (one dummy element otherwise)
             int32_t acc2_m[DIG ? V : 1][DIG ? CO_BLK : 1], acc2_n[DIG ? V : 1][DIG ? CO_BLK : 1];
-            scalar_ptr wcur = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * 2 * WC +
+            int32_t cnt[V];   // binary filters: nonzero activations met so far (the c of Eq. 8)
+#pragma unroll
+            for (int v = 0; v < V; ++v) cnt[v] = 0;
+            scalar_ptr wcur = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * CW +
                               (size_t)s_begin * sc.step_words;
-            WGroup<WC, KG> g0, g1;
+            typename GT::type g0, g1;
             StepCursor cur = cur0;
             ActChunk<WC> Aa[V], Ab[V];
             fetch_step<WC, V, TP>(Aa, cur, sc, inc_c, inc_b, inc_a, lane_lds, false);
             load_wgroup<WC, KG>(g0, wcur);
             int step = s_begin + 1;
-            conv_step<WC, V, CO_BLK, TP, DIG, true>(Aa, Ab, step == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
-                                               lane_lds, acc_m, acc_n, acc2_m, acc2_n);
+            conv_step<WC, V, CO_BLK, TP, DIG, BIN, true>(Aa, Ab, step == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1,
+                                                         wcur, lane_lds, acc_m, acc_n, acc2_m, acc2_n, cnt);
             for (; step + 2 <= s_end; step += 2) {   // two steps per trip: no register copies
-                conv_step<WC, V, CO_BLK, TP, DIG>(Ab, Aa, false, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
-                                                  lane_lds, acc_m, acc_n, acc2_m, acc2_n);
-                conv_step<WC, V, CO_BLK, TP, DIG>(Aa, Ab, step + 2 == s_end, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
-                                             lane_lds, acc_m, acc_n, acc2_m, acc2_n);
+                conv_step<WC, V, CO_BLK, TP, DIG, BIN>(Ab, Aa, false, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                                       lane_lds, acc_m, acc_n, acc2_m, acc2_n, cnt);
+                conv_step<WC, V, CO_BLK, TP, DIG, BIN>(Aa, Ab, step + 2 == s_end, cur, sc, inc_c, inc_b, inc_a, g0,
+                                                       g1, wcur, lane_lds, acc_m, acc_n, acc2_m, acc2_n, cnt);
             }
             if (step < s_end)
-                conv_step<WC, V, CO_BLK, TP, DIG>(Ab, Aa, true, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
-                                                  lane_lds, acc_m, acc_n, acc2_m, acc2_n);
+                conv_step<WC, V, CO_BLK, TP, DIG, BIN>(Ab, Aa, true, cur, sc, inc_c, inc_b, inc_a, g0, g1, wcur,
+                                                       lane_lds, acc_m, acc_n, acc2_m, acc2_n, cnt);
 #pragma unroll
             for (int v = 0; v < V; ++v)
 #pragma unroll
                 for (int j = 0; j < CO_BLK; ++j) {
-                    d[v][j] = acc_m[v][j] - 2 * acc_n[v][j];
+                    if constexpr (BIN) d[v][j] = cnt[v] - 2 * acc_n[v][j];   // c - 2 popcount, Eq. 8
+                    else d[v][j] = acc_m[v][j] - 2 * acc_n[v][j];
                     if constexpr (DIG) d[v][j] += 3 * (acc2_m[v][j] - 2 * acc2_n[v][j]);   // high digit
                 }
         } else if (active) {   // a tap share without steps (more shares than steps)
@@ -522,11 +556,11 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     }
 }
 
-template <int WC, int V, int CO_BLK, bool PACKED, bool TP, bool DIG = false>
+template <int WC, int V, int CO_BLK, bool PACKED, bool TP, bool DIG = false, bool BIN = false>
 int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, dim3 grid,
                    int threads, hipStream_t s)
 {
-    auto kern = conv_tiled_kernel<WC, V, CO_BLK, PACKED, TP, DIG>;
+    auto kern = conv_tiled_kernel<WC, V, CO_BLK, PACKED, TP, DIG, BIN>;
     if (lds_bytes > 64 * 1024) {
         static thread_local int raised_on_device = -1;
         int dev = 0;
@@ -636,7 +670,7 @@ void set_lane_tile(int v) { g_lane_tile = v; }
 
 int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 {
-    if (g_point && !p_in.digits && conv_point_applies(p_in)) return launch_conv_point(p_in, s);
+    if (g_point && !p_in.digits && !p_in.binary && conv_point_applies(p_in)) return launch_conv_point(p_in, s);
     ConvParams p = p_in;
     const bool packed = p.out_packed != nullptr;
     // A kernel of depth extent 1 with unit depth stride and no depth padding treats every input
@@ -697,7 +731,7 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         if (nwc > slices) nwc = slices;
         if (nwc < 1) nwc = 1;
         const double wgs = (double)q.tiles_x * q.tiles_y * q.tiles_z * p.n * cdiv(slices, nwc);
-        const double per_wave = (double)steps_all / ks * cb * p.wc * v * 4 + 5.0 * v * cb + 560.0 +
+        const double per_wave = (double)steps_all / ks * cb * p.wc * v * (p.binary ? 2 : 4) + 5.0 * v * cb + 560.0 +
                                 (ks > 1 ? 2.0 * (ks - 1) * v * cb + 300.0 : 0.0);
         // waves of the fullest compute unit, spread over its four SIMDs
         const double per_simd = std::ceil(std::ceil(wgs / 256.0) * (nsp * nwc * ks) / 4.0);
@@ -737,6 +771,7 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     }
     if (V == 2) V = lane_depth_for(co_blk);
     if (p.digits) V = 1;   // the only variant built for two-digit inputs
+    if (p.binary && V == 4) V = 2;   // binary filters: one or two voxels per lane
     // Shape of a wave's 64 output voxels.  8 x 8 in a plane by default.  Stacks of independent
     // planes (kd = 1) start from 4 x 8 in two planes instead (measured equal to 9 % faster than
     // 8 x 8 on the 2-D layers of a batch of 16, never slower).  Where the extents leave much of
@@ -857,6 +892,18 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
                           : launch_variant<2, 1, 32, false, false, true>(p, t, lb, grid, threads, s);
         return packed ? launch_variant<2, 1, 16, true, false, true>(p, t, lb, grid, threads, s)
                       : launch_variant<2, 1, 16, false, false, true>(p, t, lb, grid, threads, s);
+    }
+    if (p.binary) {   // Eq. 8: sign-only filter bank, two instructions per word pair
+#define TERN_LAUNCH_B(WC_, V_, CB_)                                                                     \
+    (packed ? launch_variant<WC_, V_, CB_, true, false, false, true>(p, t, lb, grid, threads, s)       \
+            : launch_variant<WC_, V_, CB_, false, false, false, true>(p, t, lb, grid, threads, s))
+        if (p.wc == 2) {
+            if (V == 1) return co_blk == 32 ? TERN_LAUNCH_B(2, 1, 32) : TERN_LAUNCH_B(2, 1, 16);
+            return co_blk == 32 ? TERN_LAUNCH_B(2, 2, 32) : TERN_LAUNCH_B(2, 2, 16);
+        }
+        if (V == 1) return TERN_LAUNCH_B(1, 1, 32);
+        return co_blk == 32 ? TERN_LAUNCH_B(1, 2, 32) : TERN_LAUNCH_B(1, 2, 16);
+#undef TERN_LAUNCH_B
     }
     if (tp) return co_blk == 32 ? TERN_LAUNCH(1, 2, 32, true) : TERN_LAUNCH(1, 2, 16, true);
     if (p.wc == 2) {

@@ -40,6 +40,7 @@ struct ConvParams {
     int32_t tp_slots;       // tap-packed filter bank: taps per word (0 = plain layout)
     int32_t tp_shift;       // tap-packed filter bank: bits per tap slot
     int32_t digits;         // 1: two-digit input (tern_pool_digits): odd words count three times
+    int32_t binary;         // 1: binary filters, bank [T*nchunk][co_pad][wc] of sign words (Eq. 8)
 };
 
 // Filter-bank geometry for (c_in, taps): tap packing applies when a voxel is one word with at
@@ -155,5 +156,7 @@ void set_lane_tile(int v);
 void set_pointwise(int v);
 int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
                         int32_t kw, uint32_t* bank, hipStream_t s);
+int launch_pack_filters_binary(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                               int32_t kw, uint32_t* bank, hipStream_t s);
 
 }  // namespace tern

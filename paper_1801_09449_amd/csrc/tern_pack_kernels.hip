@@ -638,6 +638,48 @@ __global__ __launch_bounds__(256) void pack_filters_kernel(const int8_t* __restr
 
 }  // namespace
 
+// Binary filter bank (weights in {-1, +1}, Eq. 8): uint32 [T*nchunk][co_pad][wc] sign words, plain
+// layout whatever C_in is; bit j of a word is set where the weight is negative.
+namespace {
+__global__ __launch_bounds__(256) void pack_filters_binary_kernel(const int8_t* __restrict__ w,
+                                                                  uint32_t* __restrict__ bank, int c_out, int c_in,
+                                                                  int T, int wc, int nchunk, int co_pad, int64_t total)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    int64_t r = gid;
+    const int q = (int)(r % wc); r /= wc;
+    const int co = (int)(r % co_pad); r /= co_pad;
+    const int step = (int)r;
+    uint32_t s = 0u;
+    if (co < c_out) {
+        const int tap = step / nchunk, chunk = step - tap * nchunk;
+        const int word = chunk * wc + q;
+        for (int j = 0; j < 32; ++j) {
+            const int ci = 32 * word + j;
+            if (ci >= c_in) break;
+            s |= (w[((size_t)co * c_in + ci) * T + tap] < 0 ? 1u : 0u) << j;
+        }
+    }
+    bank[gid] = s;
+}
+}  // namespace
+
+int launch_pack_filters_binary(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
+                               int32_t kw, uint32_t* bank, hipStream_t s)
+{
+    const int T = kd * kh * kw;
+    const int wd = (c_in + 31) / 32, wc = (wd % 2 == 0) ? 2 : 1, nchunk = wd / wc;
+    const int co_pad = (c_out + 31) / 32 * 32;
+    const int64_t total = (int64_t)T * nchunk * co_pad * wc;
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffff) return TERN_ESHAPE;
+    hipLaunchKernelGGL(pack_filters_binary_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, bank, c_out, c_in,
+                       T, wc, nchunk, co_pad, total);
+    TERN_HIP_CHECK(hipGetLastError());
+    return TERN_OK;
+}
+
 int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
                         int32_t kw, uint32_t* bank, hipStream_t s)
 {

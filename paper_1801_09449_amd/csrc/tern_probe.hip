@@ -12,8 +12,9 @@
 //   4 / 5    v_bcnt_u32_b32 accumulating into eight registers in turn, alone / with s_nop 0
 //   6 / 7    v_bitop3_b32, alone / with s_nop 0
 //   8 / 9    v_xor_b32 with a wave-uniform operand, alone / with s_nop 0
-//   10 / 11  the two-instruction word pair of the binary convolution (Eq. 8): xor, s_nop,
-//            popcount-accumulate / xor, popcount-accumulate
+//   10 / 11  the two-instruction word pair of the binary convolution (Eq. 8), 32 pairs per round:
+//            the kernels' own statement (three-input bit operation, s_nop, popcount-accumulate)
+//            / the same two instructions with no scalar instruction between them
 //   12 / 13  v_add_u32 (a plain integer add, for reference), alone / with s_nop 0
 // Every variant issues 64 vector instructions plus one add per round and lane.
 #include "tern_conv_common.h"
@@ -86,6 +87,31 @@ __global__ __launch_bounds__(512) void probe_unspaced_kernel(ProbeConsts c, int 
     if (r == 0x7fffffff) sink[0] = r;
 }
 
+// The binary convolution's own step: 32 word pairs = 64 vector instructions per round.
+__global__ __launch_bounds__(512) void probe_bin_kernel(ProbeConsts c, int iters, int32_t* sink)
+{
+    ActChunk<1> A[1];
+    A[0].m[0] = threadIdx.x * 2654435761u + blockIdx.x;
+    A[0].s[0] = A[0].m[0] ^ 0x9e3779b9u;
+    WGroupB<1, 8> g[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) g[h].s[j][0] = c.k[8 * h + j];
+    int32_t acc_n[1][32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) acc_n[0][j] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int h = 0; h < 4; ++h) mac_group_bin<1, 1, 32, 8>(A, g[h], 8 * h, acc_n);
+        A[0].m[0] += 0x01010101u;
+    }
+    int32_t r = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) r += acc_n[0][j];
+    if (r == 0x7fffffff) sink[0] = r;
+}
+
 // One opcode (or the binary word pair) at a time: eight instructions per statement on eight
 // registers r0..r7 taken in turn, eight statements per round.  OP: 0 and, 1 popcount-accumulate,
 // 2 three-input bit operation, 3 xor, 4 binary pair (xor into a scratch register, popcount of it
@@ -100,9 +126,9 @@ __global__ __launch_bounds__(512) void probe_unspaced_kernel(ProbeConsts c, int 
 #define TERN_P_EIGHT(I, S)                                                                      \
     I("0", "0") S I("1", "1") S I("2", "2") S I("3", "3") S I("4", "0") S I("5", "1") S I("6", "2") S \
         I("7", "3") S
-// binary pair: xor into t (registers r4..r7 serve as the scratch registers), popcount into r0..r3
+// binary pair: bit operation into t (registers r4..r7 serve as the scratch registers), popcount into r0..r3
 #define TERN_P_BIN(R, T, K, S) \
-    "v_xor_b32 %[r" T "], %[k" K "], %[a]\n\t" S "v_bcnt_u32_b32 %[r" R "], %[r" T "], %[r" R "]\n\t"
+    "v_bitop3_b32 %[r" T "], %[b], %[a], %[k" K "] bitop3:0x48\n\t" S "v_bcnt_u32_b32 %[r" R "], %[r" T "], %[r" R "]\n\t"
 #define TERN_P_BIN_FOUR(S) \
     TERN_P_BIN("0", "4", "0", S) TERN_P_BIN("1", "5", "1", S) TERN_P_BIN("2", "6", "2", S) TERN_P_BIN("3", "7", "3", S)
 
@@ -169,7 +195,7 @@ extern "C" int tern_probe_valu(int32_t blocks, int32_t threads, int32_t iters, i
         probe_opcode_kernel<1, false>, probe_opcode_kernel<1, true>,
         probe_opcode_kernel<2, false>, probe_opcode_kernel<2, true>,
         probe_opcode_kernel<3, false>, probe_opcode_kernel<3, true>,
-        probe_opcode_kernel<4, true>, probe_opcode_kernel<4, false>,
+        probe_bin_kernel, probe_opcode_kernel<4, false>,
         probe_opcode_kernel<5, false>, probe_opcode_kernel<5, true>,
     };
     hipLaunchKernelGGL(table[variant], dim3((unsigned)blocks), dim3((unsigned)threads), 0, (hipStream_t)stream, c,

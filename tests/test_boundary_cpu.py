@@ -101,6 +101,17 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     assert L.tern_conv3d(fake, d, fake, 0, g, None, None, fake, None, None) == -2
     assert L.tern_conv3d(fake, d, fake, 8, _geom(3, 1, 1, 0), None, None, fake, None, None) == -3
     assert L.tern_conv3d(fake, d, fake, 8, _geom(9, 1, 0, 1), None, None, fake, None, None) == -2
+    # binary filters (Eq. 8): same checks, own bank size
+    assert L.tern_binary_bank_bytes(64, 64, 3, 3, 3) == 27 * 2 * 64 * 4
+    assert L.tern_binary_bank_bytes(33, 1, 1, 3, 2) == 6 * 1 * 64 * 4        # no tap packing: one word per tap
+    assert L.tern_binary_bank_bytes(0, 4, 3, 3, 3) == 0
+    assert L.tern_pack_filters_binary(None, 4, 4, 3, 3, 3, fake, None) == -1
+    assert L.tern_pack_filters_binary(fake, 4, 4, 0, 3, 3, fake, None) == -2
+    assert L.tern_pack_filters_binary(fake, 4, 4, 3, 3, 3, C.c_void_p(0x1004), None) == -3
+    assert L.tern_conv3d_binary(fake, d, fake, 8, g, None, None, None, None, None) == -3
+    assert L.tern_conv3d_binary(fake, d, fake, 8, g, None, fake, None, fake, None) == -1
+    assert L.tern_conv3d_binary(fake, d, None, 8, g, None, None, fake, None, None) == -1
+    assert L.tern_conv3d_binary(fake, d, fake, 8, _geom(9, 1, 0, 1), None, None, fake, None, None) == -2
     # fcn: channel mismatch between layers, workspace too small
     arr = (Layer * 2)()
     arr[0] = Layer(32, 16, g, 0x1000, 0x1000, 0x1000)
