@@ -183,6 +183,30 @@ def test_fold_thresholds_exhaustive(T, bound):
     assert lo[5] == -bound - 1 and hi[5] == bound + 1   # constant 0
 
 
+def test_sparse_filters_leave_no_filter_words_to_skip(T):
+    """The remark after Eq. 9 (half of every kernel's entries zero would halve the bit counts)
+    gives no mechanism.  What a GPU kernel could skip is a filter word whose mask is all-zero,
+    and only where the skip is wave-uniform: a 32-channel word of one filter at one tap, the
+    64-channel chunk the kernel reads per step, or the four filters x chunk that one scalar fetch
+    brings in.  Measured on Gaussian filters through the library's prescribed-sparsity quantiser:
+    at 50 % zeros there is not a single all-zero word, at 90 % about 3 % of the words, 0.1 % of
+    the chunks and none of the fetch groups (independent zeros: 0.9^32 = 3.4 %, 0.9^64 = 0.1 %)."""
+    w = synth.gaussian((64, 64, 3, 3, 3), 0, synth.T_F32)
+    per = 64 * 27
+    seen = {}
+    for frac in (0.5, 0.7, 0.9):
+        codes, _ = T.tern_ternarize_filters_sparse(w, int(round(frac * per)))
+        nz = codes != 0
+        assert abs(1.0 - nz.mean() - frac) < 1e-3
+        words = nz.reshape(64, 2, 32, 27).any(axis=2)                 # [filter][word][tap]
+        chunks = words.any(axis=1)                                     # [filter][tap]
+        groups = chunks.reshape(16, 4, 27).any(axis=1)                 # four consecutive filters
+        seen[frac] = (1.0 - words.mean(), 1.0 - chunks.mean(), 1.0 - groups.mean())
+    assert seen[0.5] == (0.0, 0.0, 0.0)
+    assert seen[0.7][0] < 1e-3 and seen[0.7][1] == 0.0
+    assert 0.02 < seen[0.9][0] < 0.05 and seen[0.9][1] < 0.005 and seen[0.9][2] == 0.0
+
+
 def test_fold_rejects_bad_arguments(T):
     with pytest.raises(T.TernError):
         T.tern_fold_thresholds([np.nan], [0.0], 27)
