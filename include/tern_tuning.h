@@ -48,11 +48,15 @@ int tern_set_option(int option, int value);
  *       vector instruction;
  *   10  the word pair of the binary convolution (three-input bit operation, s_nop 0, popcount-
  *       accumulate), 32 pairs;
- *   11  the same without the no-op.
+ *   11  the same without the no-op;
+ *   14, 15  v_xor_b32 / v_bitop3_b32 with vector-register operands only;
+ *   16  v_and_b32 with a wave-uniform operand alternating with an independent v_add_u32 on
+ *       vector registers.
+ * (2, 6, 8, 12 give their opcode one wave-uniform operand, as the convolution's filter words are.)
  * sink: device int32[1] (practically never written).  threads: multiple of 64, at most 512.
  * TERN_EARG for anything else.
  */
-#define TERN_PROBE_VARIANTS 14
+#define TERN_PROBE_VARIANTS 17
 int tern_probe_valu(int32_t blocks, int32_t threads, int32_t iters, int32_t variant, int32_t* sink,
                     void* stream);
 

@@ -15,8 +15,21 @@
 //   10 / 11  the two-instruction word pair of the binary convolution (Eq. 8), 32 pairs per round:
 //            the kernels' own statement (three-input bit operation, s_nop, popcount-accumulate)
 //            / the same two instructions with no scalar instruction between them
-//   12 / 13  v_add_u32 (a plain integer add, for reference), alone / with s_nop 0
+//   12 / 13  v_add_u32 with a wave-uniform operand (a plain integer add, for reference), alone /
+//            with s_nop 0
+//   14       v_xor_b32 on vector registers only
+//   15       v_bitop3_b32 on vector registers only
+//   16       v_and_b32 with a wave-uniform operand alternating with an independent v_add_u32 on
+//            vector registers only
 // Every variant issues 64 vector instructions plus one add per round and lane.
+//
+// What the variants show on MI355X (cycles per wave instruction and SIMD at 2.4 GHz, four waves
+// per SIMD): an integer instruction whose operands are all vector registers retires in about two
+// cycles (14, 15: 2.1-2.3; 32 lanes per clock and SIMD, the rate behind the published fp32
+// vector peak), one that reads a wave-uniform (scalar register) operand in four (2, 6, 8, 12:
+// 4.0), and so does v_bcnt_u32_b32 whatever its operands (4: 4.07); a vector-only instruction
+// slips in beside a scalar-operand one (16: 2.15 on average).  A ternary word pair is therefore
+// 2 + 4 + 2 + 4 = 12 cycles at best, 3.0 per instruction; the kernels' sequence reaches 3.16.
 #include "tern_conv_common.h"
 #include "tern_internal.h"
 
@@ -114,14 +127,21 @@ __global__ __launch_bounds__(512) void probe_bin_kernel(ProbeConsts c, int iters
 
 // One opcode (or the binary word pair) at a time: eight instructions per statement on eight
 // registers r0..r7 taken in turn, eight statements per round.  OP: 0 and, 1 popcount-accumulate,
-// 2 three-input bit operation, 3 xor, 4 binary pair (xor into a scratch register, popcount of it
-// accumulated; four pairs per statement), 5 add.  NOP: s_nop 0 behind every vector instruction
+// 2 three-input bit operation, 3 xor, 4 binary pair (bit operation into a scratch register, popcount
+// of it accumulated; four pairs per statement), 5 add, each with one wave-uniform operand where the
+// opcode takes one; 6 xor and 7 bit operation on vector registers only; 8 scalar-operand and beside
+// an independent vector-only add.  NOP: s_nop 0 behind every vector instruction
 // (binary pair: between the xor and its popcount).
 #define TERN_P_AND(R, K)   "v_and_b32 %[r" R "], %[k" K "], %[a]\n\t"
 #define TERN_P_BCNT(R, K)  "v_bcnt_u32_b32 %[r" R "], %[a], %[r" R "]\n\t"
 #define TERN_P_BITOP(R, K) "v_bitop3_b32 %[r" R "], %[a], %[b], %[k" K "] bitop3:0x48\n\t"
 #define TERN_P_XOR(R, K)   "v_xor_b32 %[r" R "], %[k" K "], %[a]\n\t"
 #define TERN_P_ADD(R, K)   "v_add_u32 %[r" R "], %[k" K "], %[r" R "]\n\t"
+#define TERN_P_XORV(R, K)  "v_xor_b32 %[r" R "], %[a], %[r" R "]\n\t"
+#define TERN_P_BITOPV(R, K) "v_bitop3_b32 %[r" R "], %[a], %[b], %[r" R "] bitop3:0x48\n\t"
+// scalar-operand and into r4..r7 beside an independent vector-only add on r0..r3
+#define TERN_P_MIXED(R, T, K) "v_and_b32 %[r" T "], %[k" K "], %[a]\n\tv_add_u32 %[r" R "], %[b], %[r" R "]\n\t"
+#define TERN_P_MIXED_FOUR TERN_P_MIXED("0", "4", "0") TERN_P_MIXED("1", "5", "1") TERN_P_MIXED("2", "6", "2") TERN_P_MIXED("3", "7", "3")
 #define TERN_P_NOP "s_nop 0\n\t"
 #define TERN_P_EIGHT(I, S)                                                                      \
     I("0", "0") S I("1", "1") S I("2", "2") S I("3", "3") S I("4", "0") S I("5", "1") S I("6", "2") S \
@@ -162,9 +182,15 @@ __global__ __launch_bounds__(512) void probe_opcode_kernel(ProbeConsts c, int it
             } else if constexpr (OP == 4) {
                 if constexpr (NOP) asm volatile(TERN_P_BIN_FOUR(TERN_P_NOP) TERN_P_OPERANDS);
                 else asm volatile(TERN_P_BIN_FOUR("") TERN_P_OPERANDS);
-            } else {
+            } else if constexpr (OP == 5) {
                 if constexpr (NOP) asm volatile(TERN_P_EIGHT(TERN_P_ADD, TERN_P_NOP) TERN_P_OPERANDS);
                 else asm volatile(TERN_P_EIGHT(TERN_P_ADD, "") TERN_P_OPERANDS);
+            } else if constexpr (OP == 6) {
+                asm volatile(TERN_P_EIGHT(TERN_P_XORV, "") TERN_P_OPERANDS);
+            } else if constexpr (OP == 7) {
+                asm volatile(TERN_P_EIGHT(TERN_P_BITOPV, "") TERN_P_OPERANDS);
+            } else {
+                asm volatile(TERN_P_MIXED_FOUR TERN_P_OPERANDS);
             }
 #undef TERN_P_OPERANDS
         }
@@ -197,6 +223,7 @@ extern "C" int tern_probe_valu(int32_t blocks, int32_t threads, int32_t iters, i
         probe_opcode_kernel<3, false>, probe_opcode_kernel<3, true>,
         probe_bin_kernel, probe_opcode_kernel<4, false>,
         probe_opcode_kernel<5, false>, probe_opcode_kernel<5, true>,
+        probe_opcode_kernel<6, false>, probe_opcode_kernel<7, false>, probe_opcode_kernel<8, false>,
     };
     hipLaunchKernelGGL(table[variant], dim3((unsigned)blocks), dim3((unsigned)threads), 0, (hipStream_t)stream, c,
                        iters, sink);

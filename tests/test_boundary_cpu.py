@@ -143,7 +143,7 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     # probe: null sink, launch shape and variant are checked before anything is launched
     assert L.tern_probe_valu(4, 256, 10, 0, None, None) == -1
     assert L.tern_probe_valu(4, 100, 10, 0, fake, None) == -3
-    assert L.tern_probe_valu(4, 256, 10, 14, fake, None) == -3
+    assert L.tern_probe_valu(4, 256, 10, 17, fake, None) == -3
     assert L.tern_probe_valu(4, 256, 10, -1, fake, None) == -3
     assert L.tern_probe_valu(0, 256, 10, 1, fake, None) == -3
     # options: unknown option or value

@@ -654,13 +654,13 @@ def test_fcn_forward_replays_from_a_captured_graph(G):
 
 
 @pytest.mark.gpu
-def test_instruction_mix_probe_runs_both_variants(G):
-    """The diagnostic kernel (no counterpart in the paper) launches in both variants and leaves
-    its sink alone."""
+def test_instruction_mix_probe_runs_every_variant(G):
+    """The diagnostic kernels (no counterpart in the paper) launch in every variant and leave
+    their sink alone."""
     import torch
     import paper_1801_09449_amd as T
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
-    for variant in (0, 1):
+    for variant in range(17):
         T.tern_probe_valu(64, 256, 50, sink, variant)
     torch.cuda.synchronize()
     assert int(sink.item()) == 0
