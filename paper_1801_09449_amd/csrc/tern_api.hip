@@ -155,7 +155,7 @@ int tern_set_option(int option, int value)
         return TERN_OK;
     }
     if (option == TERN_OPT_CO_BLOCK) {
-        if (value != 0 && value != 16 && value != 32) return TERN_EARG;
+        if (value != 0 && value != 8 && value != 16 && value != 32) return TERN_EARG;
         set_co_block(value);
         return TERN_OK;
     }

@@ -108,10 +108,11 @@ __device__ __forceinline__ void ternarise_pass(const int32_t (&d)[V][CO_BLK], sc
 // being used, one arriving).  With 32 channels per pass KG = 4 keeps the filter words within 32
 // SGPRs, which leaves room for the loop's own scalars (8 per group made the compiler spill them);
 // with 16 channels per pass KG = 8 fits and halves the number of waits, which matters when a
-// SIMD holds a single wave and nothing else hides the scalar-cache latency.
+// SIMD holds a single wave and nothing else hides the scalar-cache latency; 8 channels per pass
+// are two groups of 4.
 template <int CO_BLK>
 struct GroupOf {
-    static constexpr int value = CO_BLK >= 32 ? 4 : 8;
+    static constexpr int value = (CO_BLK >= 32 || CO_BLK <= 8) ? 4 : 8;
 };
 
 template <int WC, int KG>

@@ -418,7 +418,7 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     constexpr int KG = GT::KG;
     constexpr int NG = CO_BLK / KG;
     static_assert(NG >= 2 && NG % 2 == 0, "CO_BLK must be a multiple of twice the group size");
-    static_assert(CO_BLK <= 32 && 32 % CO_BLK == 0, "CO_BLK must divide 32");
+    static_assert(CO_BLK <= 32 && 32 % CO_BLK == 0 && CO_BLK % 8 == 0, "CO_BLK must divide 32 in whole bytes");
 
     uint32_t pos_w[V], neg_w[V];  // packed mode: decision bits of the 32-channel word in progress
 #pragma unroll
@@ -508,14 +508,15 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
             for (int v = 0; v < V; ++v) { pos_w[v] |= pp[v] << sh; neg_w[v] |= pn[v] << sh; }
             const bool flush = ((cb + CO_BLK) & 31) == 0 || cb + CO_BLK >= co_end;
             if (flush) {
-                // This wave's bits of word q are [b0, b1).  A wave that owns only half of the
-                // word stores that half (16-bit store) so that the wave owning the other half can
-                // store its own without a read-modify-write; the low-half owner also stores the
-                // (zero) high half when no channel exists there.
+                // This wave's bits of word q are [b0, b1), whole bytes.  A wave that owns only part
+                // of the word stores that part (16- or 8-bit stores) so that the waves owning the
+                // rest can store theirs without a read-modify-write; the wave that owns the last
+                // existing channel of the word also stores the (zero) bytes behind it.
                 const int q = cb >> 5;
                 const int b0 = max(co_begin, q * 32) - q * 32;
                 const int b1 = min(co_begin + t.co_per_wave, q * 32 + 32) - q * 32;
-                const bool whole = b0 == 0 && (b1 == 32 || p.c_out <= q * 32 + 16);
+                const int B0 = b0 >> 3;
+                const int B1 = (q * 32 + b1 >= p.c_out) ? 4 : (b1 >> 3);
 #pragma unroll
                 for (int v = 0; v < V; ++v) {
                     const int oz = t.vy ? ozb : ozb + v;
@@ -525,13 +526,17 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
                                       ((((size_t)n * p.od + oz) * p.oh + oyv) * p.ow + ox) * 2u * p.wd_out;
                         const uint32_t mk = pos_w[v] | neg_w[v];      // nonzero mask
                         const uint32_t sg = neg_w[v] & ~pos_w[v];     // sign; +1 wins if lo > hi
-                        if (whole) {
+                        if (B0 == 0 && B1 == 4) {
                             o[q] = mk;
                             o[p.wd_out + q] = sg;
+                        } else if ((B0 & 1) == 0 && B1 - B0 == 2) {
+                            reinterpret_cast<uint16_t*>(o + q)[B0 >> 1] = (uint16_t)(mk >> (8 * B0));
+                            reinterpret_cast<uint16_t*>(o + p.wd_out + q)[B0 >> 1] = (uint16_t)(sg >> (8 * B0));
                         } else {
-                            const int half = b0 >> 4;
-                            reinterpret_cast<uint16_t*>(o + q)[half] = (uint16_t)(mk >> b0);
-                            reinterpret_cast<uint16_t*>(o + p.wd_out + q)[half] = (uint16_t)(sg >> b0);
+                            for (int B = B0; B < B1; ++B) {
+                                reinterpret_cast<uint8_t*>(o + q)[B] = (uint8_t)(mk >> (8 * B));
+                                reinterpret_cast<uint8_t*>(o + p.wd_out + q)[B] = (uint8_t)(sg >> (8 * B));
+                            }
                         }
                     }
                     pos_w[v] = neg_w[v] = 0u;
@@ -662,7 +667,7 @@ bool plan_tiles(const ConvParams& p, int V, int lds_limit, TileParams& t, int64_
 
 void set_lane_depth(int v) { g_lane_depth = (v == 1 || v == 2 || v == 4) ? v : 0; }
 void set_waves_z(int v) { g_waves_z = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
-void set_co_block(int v) { g_co_block = (v == 16 || v == 32) ? v : 0; }
+void set_co_block(int v) { g_co_block = (v == 8 || v == 16 || v == 32) ? v : 0; }
 void set_co_per_wave(int v) { g_co_per_wave = (v > 0 && v % 16 == 0) ? v : 0; }
 void set_tap_split(int v) { g_tap_split = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
 void set_pointwise(int v) { g_point = v ? 1 : 0; }
@@ -711,8 +716,10 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     // modules; -3 % with only 9 steps per wave, hence the step limit.
     const int steps_all = p.kd * p.kh * p.kw * (p.wd_in / p.wc);
     auto lane_depth_for = [&](int cb) {
-        const bool exists = p.tp_slots == 0 && (p.wc == 2 || cb == 32);
-        return (exists && (g_lane_depth == 1 || (g_lane_depth == 0 && steps_all >= 16))) ? 1 : 2;
+        const bool exists = p.tp_slots == 0 && (p.wc == 2 || cb == 32 || cb == 8);
+        // (8 channels per pass: two voxels per lane unless told otherwise, measured faster on
+        // every small launch tried but one)
+        return (exists && (g_lane_depth == 1 || (g_lane_depth == 0 && steps_all >= 16 && cb != 8))) ? 1 : 2;
     };
     // Estimated launch time in vector instructions of the busiest SIMD, for cb channels per pass
     // and the kernel taps split over ks waves: workgroups are dealt to the 256 compute units
@@ -747,6 +754,7 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     int V = 2, co_blk = 16;
     if (g_lane_depth == 4 && p.tp_slots == 0) { V = 4; co_blk = 16; }
     else if (g_co_block == 32) { V = 2; co_blk = 32; }
+    else if (g_co_block == 8 && p.tp_slots == 0 && !p.digits && !p.binary) { co_blk = 8; }
     else if (g_co_block == 0) {
         const int64_t tiles2 = p.od == 1 ? (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 16) * p.n
                                          : (int64_t)cdiv(p.ow, 8) * cdiv(p.oh, 8) * cdiv(p.od, 2) * p.n;
@@ -755,7 +763,14 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         // large launches: 32 channels per pass (half the passes over the LDS tile, half the fixed
         // cost); tiny ones: 16 (they need every wave they can get and split the taps besides);
         // in between the two differ in how evenly the workgroups fill the chip: estimate both
-        if (units >= 4096) {
+        // the smallest launches (fewer 16-channel slices of two-voxel tiles than SIMDs): 8 channels
+        // per pass.  They split the kernel taps over several waves anyway, and the partial sums
+        // that those waves exchange through LDS shrink with the pass width: twice the slices at
+        // half the split measured 8-23 % faster (24^3 x 32 channels 9.2 -> 7.1 us, 64 -> 128
+        // channels on 16 x 16 x 8 outputs 9.2 -> 7.6 us, the layers between 3-6 %).
+        if (tiles2 * cdiv(p.c_out, 16) < 1024 && p.tp_slots == 0 && !p.digits && !p.binary) {
+            co_blk = 8;
+        } else if (units >= 4096) {
             if (tail == 0 || tail > 16) co_blk = 32;
         } else if (units >= 512 && p.tp_slots == 0) {
             double best = 1e300;
@@ -843,7 +858,8 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     else if (nks_pref > 0) nks = nks_pref;
     else {
         const int64_t waves0 = spatial_tiles * nsp * slices;
-        while (nks * 2 * nsp <= 8 && waves0 * nks < 2048 && nsteps >= 4 * nks) nks *= 2;
+        // double the split while that keeps the launch within two waves per SIMD
+        while (nks * 2 * nsp <= 8 && waves0 * nks * 2 <= 2048 && nsteps >= 4 * nks) nks *= 2;
     }
     if (nks * nsp > 8) nks = 8 / nsp;
     if (nks < 1) nks = 1;
@@ -906,6 +922,11 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 #undef TERN_LAUNCH_B
     }
     if (tp) return co_blk == 32 ? TERN_LAUNCH(1, 2, 32, true) : TERN_LAUNCH(1, 2, 16, true);
+    if (co_blk == 8) {   // the finest channel slices: small launches
+        if (V == 4) V = 2;
+        if (p.wc == 2) return V == 1 ? TERN_LAUNCH(2, 1, 8, false) : TERN_LAUNCH(2, 2, 8, false);
+        return V == 1 ? TERN_LAUNCH(1, 1, 8, false) : TERN_LAUNCH(1, 2, 8, false);
+    }
     if (p.wc == 2) {
         if (V == 1) return co_blk == 32 ? TERN_LAUNCH(2, 1, 32, false) : TERN_LAUNCH(2, 1, 16, false);
         if (V == 4) return TERN_LAUNCH(2, 4, 16, false);

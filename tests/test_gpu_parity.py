@@ -256,6 +256,8 @@ VARIANTS = [
     (2, 4, 32, 64, 1), (2, 0, 16, 0, 2), (2, 0, 16, 0, 4), (2, 0, 32, 0, 8), (4, 0, 0, 0, 2),
     (2, 2, 16, 0, 4), (1, 0, 32, 32, 1), (1, 1, 32, 32, 1), (1, 2, 32, 64, 1), (1, 4, 32, 32, 1), (1, 0, 32, 0, 2), (1, 0, 16, 16, 1), (1, 2, 16, 32, 1), (1, 0, 16, 0, 4),
     (2, 0, 0, 0, 0),
+    # eight channels per pass: byte-granular stores of the packed words
+    (1, 0, 8, 0, 1), (2, 0, 8, 0, 1), (1, 0, 8, 0, 2), (2, 0, 8, 0, 4), (1, 2, 8, 16, 1), (2, 0, 8, 48, 1), (0, 0, 8, 0, 8),
 ]
 
 
