@@ -51,14 +51,18 @@ SETTLE_MS = 40.0                          # GPU work in front of every timed reg
 
 
 def settle(fn, min_ms=SETTLE_MS):
-    """Run fn back to back for at least min_ms of GPU time, whatever --warmup says: a 2 ms timed
-    region right after an idle period measures the clock ramp, not the kernel."""
+    """Run fn back to back for at least min_ms of GPU time, whatever --warmup says.  After an idle
+    period (input generation on the host) the shader clock takes about 15 ms of load to come
+    back: config[1] launches take 101 us at first and 91 us from the 150th on; a pause of a
+    millisecond does not undo that, one of 20 ms does.  A 2 ms timed region right after an idle
+    period measures that ramp, not the kernel.  Bursts of 100 launches with a synchronisation
+    between them: the pauses are tens of microseconds, and the launch queue stays short."""
     import torch
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     total = 0.0
     while total < min_ms:
         ev0.record()
-        for _ in range(20):
+        for _ in range(100):
             fn()
         ev1.record()
         torch.cuda.synchronize()
