@@ -183,6 +183,14 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
     ex = {}
     ms_acc, _ = timed(lambda: T.tern_conv3d(act, c_in, bank, c_out, out=out_acc, **geom), 50, 5, None)
     ex["cfg1_conv3d_int32_out_ms"] = ms_acc
+    # the persistent-workgroup form of the fused kernel (tuning option 8, off by default)
+    T.tern_set_option(8, 1)
+    try:
+        ms_pw, _ = timed(lambda: T.tern_conv3d(act, c_in, bank, c_out, thr_lo=lo, thr_hi=hi, out=out_packed, **geom),
+                         50, 5, None)
+    finally:
+        T.tern_set_option(8, 0)
+    ex["cfg1_conv3d_persistent_workgroups_ms"] = ms_pw
     ms_pack, _ = timed(lambda: T.tern_pack(act_i8, out=act), 50, 5, None)
     ex["cfg1_pack_i8_ms"] = ms_pack
     ex["cfg1_pack_i8_GBps"] = (act_i8.numel() + act.numel() * 4) / (ms_pack * 1e-3) / 1e9

@@ -28,12 +28,30 @@ extern "C" {
  * lanes on the edges of a stack of independent planes), -1 = always 8 x 8, 100 * X + Y with X, Y in
  * {1, 2, 4, 8} and X * Y >= 4 = X x Y voxels in 64 / (X * Y) planes wherever the output has more
  * than one plane.
+ * TERN_OPT_STREAM: 1 = large launches of the tiled kernel (one voxel per lane, 32 channels per
+ * pass, all output channels in one workgroup, at least eight tiles per compute unit) run as
+ * persistent workgroups, four per compute unit, each walking a run of consecutive tiles with the
+ * next halo tile loaded under the current tile's arithmetic; 0 (default) = one workgroup per tile.
+ * Measured 5-18 % slower than the default on every shape tried, kept as an option for comparison.
  * Results never depend on options.  Returns TERN_EARG for an unknown option or
  * value. */
 typedef enum { TERN_OPT_LANE_DEPTH = 1, TERN_OPT_WAVES_Z = 2, TERN_OPT_CO_BLOCK = 3,
                TERN_OPT_CO_PER_WAVE = 4, TERN_OPT_TAP_SPLIT = 5, TERN_OPT_POINTWISE = 6,
-               TERN_OPT_LANE_TILE = 7 } tern_option;
+               TERN_OPT_LANE_TILE = 7, TERN_OPT_STREAM = 8 } tern_option;
 int tern_set_option(int option, int value);
+
+/*
+ * tern_last_launch -- diagnostic: the plan of the calling thread's most recent convolution launch
+ * (tern_conv3d, tern_conv3d_binary, tern_conv3d_digits, or the last layer of a network call), so
+ * that a test can tell which kernel its input reached.  info (host, 8 values): [0] kernel, one of
+ * the TERN_KERNEL_ values (-1 before the thread's first launch); for the tiled and persistent
+ * kernels [1] output voxels per lane, [2] channels per pass, [3] waves sharing the taps of a slice,
+ * [4] threads per workgroup, [5], [6] grid extents, [7] LDS bytes per workgroup; zeros otherwise.
+ * TERN_ENULL for a NULL pointer.
+ */
+typedef enum { TERN_KERNEL_DIRECT = 0, TERN_KERNEL_TILED = 1, TERN_KERNEL_POINTWISE = 2,
+               TERN_KERNEL_PERSISTENT = 3 } tern_kernel;
+int tern_last_launch(int32_t info[8]);
 
 /*
  * tern_probe_valu -- diagnostic, no counterpart in the paper: runs `iters` rounds of 64 integer

@@ -113,6 +113,7 @@ def lib():
     L.tern_fold_avgpool.restype = C.c_int
     L.tern_set_option.argtypes = [C.c_int, C.c_int]; L.tern_set_option.restype = C.c_int
     L.tern_probe_valu.argtypes = [I, I, I, I, P, P]; L.tern_probe_valu.restype = C.c_int
+    L.tern_last_launch.argtypes = [C.POINTER(C.c_int32)]; L.tern_last_launch.restype = C.c_int
     _lib = L
     return L
 
@@ -548,6 +549,17 @@ def tern_set_option(option: int, value: int) -> None:
     """Tuning override (option numbers and values as in tern_option of the C header).  Results never
     depend on options."""
     _check(lib().tern_set_option(int(option), int(value)), "tern_set_option")
+
+
+KERNEL_DIRECT, KERNEL_TILED, KERNEL_POINTWISE, KERNEL_PERSISTENT = 0, 1, 2, 3
+
+
+def tern_last_launch() -> dict:
+    """Plan of this thread's most recent convolution launch (see tern_tuning.h)."""
+    info = (C.c_int32 * 8)()
+    _check(lib().tern_last_launch(info), "tern_last_launch")
+    keys = ("kernel", "voxels_per_lane", "channels_per_pass", "tap_split", "threads", "grid_x", "grid_y", "lds_bytes")
+    return dict(zip(keys, (int(v) for v in info)))
 
 
 # ---- U-Net plumbing ------------------------------------------------------------------------------

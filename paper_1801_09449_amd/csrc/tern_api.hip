@@ -181,12 +181,24 @@ int tern_set_option(int option, int value)
         set_lane_tile(value);
         return TERN_OK;
     }
+    if (option == TERN_OPT_STREAM) {
+        if (value != 0 && value != 1) return TERN_EARG;
+        set_stream(value);
+        return TERN_OK;
+    }
     if (option == TERN_OPT_WAVES_Z) {
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return TERN_EARG;
         set_waves_z(value);
         return TERN_OK;
     }
     return TERN_EARG;
+}
+
+int tern_last_launch(int32_t info[8])
+{
+    if (!info) return TERN_ENULL;
+    last_launch(info);
+    return TERN_OK;
 }
 
 int tern_pack(const int8_t* src, tern_dims dims, uint32_t* dst_packed, void* stream)

@@ -42,9 +42,24 @@ int lds_limit_for_current_device()
     return cached[dev];
 }
 
+// Compute units of the current device (queried once per device; 0 on error).
+static int compute_units_of_current_device()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cached[dev] = v;
+    }
+    return cached[dev];
+}
+
 namespace {
 
 constexpr int kMaxThreads = 512;         // 8 waves: at most 2 waves per SIMD, <= 256 VGPRs
+constexpr int kStreamItems = 2;          // persistent kernel: halo items a thread prefetches per tile
 
 struct TileParams {
     int32_t nwx, nwy, nwz;        // waves per workgroup along x, y, z
@@ -65,6 +80,7 @@ struct TileParams {
     // a wave's 64 lanes cover 2^lxb x 2^lyb x 64 / 2^(lxb + lyb) output voxels (x, y, z), x fastest
     int32_t lxb, lyb;
     int32_t flat;                 // 1: halo fill over one flat index space, 0: per plane position
+    int32_t tiles_per_wg;         // persistent kernel: consecutive tiles one workgroup walks
 };
 
 template <int WC>
@@ -561,6 +577,231 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
     }
 }
 
+// Persistent form of the kernel above for large launches of four-wave workgroups (one voxel per
+// lane, whole kernel per wave): a workgroup walks a run of consecutive tiles and holds two halo
+// tiles in LDS.  The global loads of the next tile are issued before the current tile's tap loop
+// and land in registers under it; they are written to the other LDS buffer after the loop, so
+// no wave waits for a halo fill except the very first.  Launched with as many workgroups as the
+// chip holds at once (four per compute unit), so every SIMD keeps the same four waves from start
+// to end and no second generation of workgroups has to ramp up.
+template <int WC, int CO_BLK, bool PACKED, bool BIN>
+__global__ __launch_bounds__(256) void conv_tiled_stream_kernel(ConvParams p, TileParams t)
+{
+    constexpr int V = 1;
+    constexpr int NI = kStreamItems;
+    extern __shared__ __align__(16) uint32_t lds[];
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // ---- this workgroup's run of tiles (contiguous per XCD, as above) -------------------------
+    int w = blockIdx.x;
+    {
+        const int per_xcd = gridDim.x >> 3;
+        if (w < (per_xcd << 3)) w = (w & 7) * per_xcd + (w >> 3);
+    }
+    const int ntiles = t.tiles_x * t.tiles_y * t.tiles_z * p.n;
+    const int first = w * t.tiles_per_wg;
+    const int last = min(ntiles, first + t.tiles_per_wg);
+    if (first >= last) return;   // whole workgroup
+
+    const int LX = 1 << t.lxb, LY = 1 << t.lyb, LZ = 64 >> (t.lxb + t.lyb);
+    const int TX = LX * t.nwx, TY = LY * t.nwy, TZ = LZ * t.nwz;
+    const int plane = t.hy * t.hx;
+    const int wd = p.wd_in;
+    const uint32_t nch = (uint32_t)t.nchunk;
+    const uint32_t items = (uint32_t)t.hz * (uint32_t)plane * nch;
+    const int buf_words = t.hz * plane * t.vstride;
+
+    struct Origin { int ox0, oy0, oz0, n; };
+    auto origin_of = [&](int tile) {
+        Origin o;
+        const int tix = tile % t.tiles_x; tile /= t.tiles_x;
+        const int tiy = tile % t.tiles_y; tile /= t.tiles_y;
+        const int tiz = tile % t.tiles_z;
+        o.n = tile / t.tiles_z;
+        o.ox0 = tix * TX; o.oy0 = tiy * TY; o.oz0 = tiz * TZ;
+        return o;
+    };
+    // Halo items e = tid + j * nthreads of one tile, (plane, position, chunk) with chunk fastest;
+    // out-of-volume voxels read as zero words.  Slots that no lane of the wave uses are skipped.
+    auto load_items = [&](const Origin& o, uint4 (&r)[NI]) {
+        const int gx0 = o.ox0 * p.sw - p.pw, gy0 = o.oy0 * p.sh - p.ph, gz0 = o.oz0 * p.sd - p.pd;
+        const uint32_t* in_n = p.in + (size_t)o.n * p.d * p.h * p.w * 2u * wd;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            r[j] = make_uint4(0u, 0u, 0u, 0u);
+            if ((uint32_t)(wave * 64 + j * nthreads) < items) {
+                const uint32_t e = tid + j * nthreads;
+                const uint32_t vox = nch > 1 ? __umulhi(e, t.m_ch) : e;
+                const uint32_t ch = e - vox * nch;
+                const uint32_t hz = __umulhi(vox, t.m_pl);
+                const uint32_t i = vox - hz * plane;
+                const int hy = t.hx > 1 ? (int)__umulhi(i, t.m_hx) : (int)i;
+                const int hxx = (int)i - hy * t.hx;
+                const int gz = gz0 + (int)hz, gy = gy0 + hy, gx = gx0 + hxx;
+                if (e < items && gz >= 0 && gz < p.d && gy >= 0 && gy < p.h && gx >= 0 && gx < p.w) {
+                    const uint32_t* src = in_n + (((size_t)gz * p.h + gy) * p.w + gx) * 2u * wd;
+                    if constexpr (WC == 2) {
+                        const uint2 m = *reinterpret_cast<const uint2*>(src + 2 * ch);
+                        const uint2 sg = *reinterpret_cast<const uint2*>(src + wd + 2 * ch);
+                        r[j] = make_uint4(m.x, m.y, sg.x, sg.y);
+                    } else {
+                        r[j].x = src[ch];
+                        r[j].y = src[wd + ch];
+                    }
+                }
+            }
+        }
+    };
+    auto store_items = [&](uint32_t* buf, const uint4 (&r)[NI]) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const uint32_t e = tid + j * nthreads;
+            if (e < items) {
+                const uint32_t vox = nch > 1 ? __umulhi(e, t.m_ch) : e;
+                uint32_t* dst = buf + vox * t.vstride + (e - vox * nch) * (2 * WC);
+                if constexpr (WC == 2) *reinterpret_cast<uint4*>(dst) = r[j];
+                else *reinterpret_cast<uint2*>(dst) = make_uint2(r[j].x, r[j].y);
+            }
+        }
+    };
+
+    // ---- this wave's voxels inside a tile, and its walk over the taps -------------------------
+    const int nsp = t.nwx * t.nwy * t.nwz;
+    const int wx = wave % t.nwx;
+    const int wy = (wave / t.nwx) % t.nwy;
+    const int wz = (wave / (t.nwx * t.nwy)) % t.nwz;
+    const int wch = wave / nsp;
+    const int lx = lane & (LX - 1), ly = (lane >> t.lxb) & (LY - 1);
+    const int lz = lane >> (t.lxb + t.lyb);
+    const int row_words = t.hx * t.vstride;
+    const int plane_words = t.hy * row_words;
+    const int lane_base = ((wz * LZ + lz) * p.sd) * plane_words + (wy * LY + ly) * p.sh * row_words +
+                          (wx * LX + lx) * p.sw * t.vstride;
+    const int T = p.kd * p.kh * p.kw;
+    const int co_begin = wch * t.co_per_wave;
+    const int co_end = min(p.c_out, co_begin + t.co_per_wave);
+    const int nsteps = T * t.nchunk;
+    StepConsts sc;
+    sc.kw = p.kw; sc.kh = p.kh; sc.nchunk = t.nchunk;
+    const int inc_c = p.dw * t.vstride;
+    const int inc_b = p.dh * row_words - (p.kw - 1) * inc_c;
+    const int inc_a = p.dd * plane_words - (p.kh - 1) * p.dh * row_words - (p.kw - 1) * inc_c;
+    using GT = GroupType<WC, CO_BLK, BIN>;
+    constexpr int CW = GT::CW;
+    constexpr int KG = GT::KG;
+    sc.step_words = p.co_pad * CW;
+    sc.vstep = 0;
+    sc.slots = 0; sc.shift = 0;
+    sc.slot_mask = 0xffffffffu;
+    sc.tap_end = T;
+
+    uint4 r[NI];
+    Origin here = origin_of(first);
+    load_items(here, r);
+    store_items(lds, r);
+    __syncthreads();
+
+    for (int tile = first, b = 0; tile < last; ++tile, b ^= 1) {
+        const bool more = tile + 1 < last;
+        Origin next = here;
+        if (more) {
+            next = origin_of(tile + 1);
+            load_items(next, r);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const uint32_t* lane_lds = lds + b * buf_words + lane_base;
+        const int ox = here.ox0 + wx * LX + lx;
+        const int oy = here.oy0 + wy * LY + ly;
+        const int oz = here.oz0 + wz * LZ + lz;
+
+        uint32_t pos_w = 0u, neg_w = 0u;
+        for (int cb = co_begin; cb < co_end; cb += CO_BLK) {
+            int32_t d[V][CO_BLK];
+            {
+                int32_t acc_m[V][CO_BLK], acc_n[V][CO_BLK];
+                int32_t acc2_m[1][1], acc2_n[1][1];
+                int32_t cnt[V] = {0};
+                scalar_ptr wcur = (scalar_ptr)(uintptr_t)p.wgt + (size_t)cb * CW;
+                typename GT::type g0, g1;
+                StepCursor cur = {0, 0, 0, 0, 0};
+                ActChunk<WC> Aa[V], Ab[V];
+                fetch_step<WC, V, false>(Aa, cur, sc, inc_c, inc_b, inc_a, lane_lds, false);
+                load_wgroup<WC, KG>(g0, wcur);
+                int step = 1;
+                conv_step<WC, V, CO_BLK, false, false, BIN, true>(Aa, Ab, step == nsteps, cur, sc, inc_c, inc_b,
+                                                                  inc_a, g0, g1, wcur, lane_lds, acc_m, acc_n,
+                                                                  acc2_m, acc2_n, cnt);
+                for (; step + 2 <= nsteps; step += 2) {
+                    conv_step<WC, V, CO_BLK, false, false, BIN>(Ab, Aa, false, cur, sc, inc_c, inc_b, inc_a, g0, g1,
+                                                                wcur, lane_lds, acc_m, acc_n, acc2_m, acc2_n, cnt);
+                    conv_step<WC, V, CO_BLK, false, false, BIN>(Aa, Ab, step + 2 == nsteps, cur, sc, inc_c, inc_b,
+                                                                inc_a, g0, g1, wcur, lane_lds, acc_m, acc_n, acc2_m,
+                                                                acc2_n, cnt);
+                }
+                if (step < nsteps)
+                    conv_step<WC, V, CO_BLK, false, false, BIN>(Ab, Aa, true, cur, sc, inc_c, inc_b, inc_a, g0, g1,
+                                                                wcur, lane_lds, acc_m, acc_n, acc2_m, acc2_n, cnt);
+#pragma unroll
+                for (int j = 0; j < CO_BLK; ++j) {
+                    if constexpr (BIN) d[0][j] = cnt[0] - 2 * acc_n[0][j];
+                    else d[0][j] = acc_m[0][j] - 2 * acc_n[0][j];
+                }
+            }
+            const int co_left = co_end - cb;
+            if constexpr (PACKED) {
+                uint32_t pp[V], pn[V];
+                ternarise_pass<V, CO_BLK>(d, (scalar_ptr)(uintptr_t)p.lo, (scalar_ptr)(uintptr_t)p.hi, cb,
+                                          co_left, p.c_out, pp, pn);
+                const int sh = cb & 31;
+                pos_w |= pp[0] << sh; neg_w |= pn[0] << sh;
+                const bool flush = ((cb + CO_BLK) & 31) == 0 || cb + CO_BLK >= co_end;
+                if (flush) {
+                    // whole bytes [B0, B1) of word q belong to this wave (see the kernel above)
+                    const int q = cb >> 5;
+                    const int b0 = max(co_begin, q * 32) - q * 32;
+                    const int b1 = min(co_begin + t.co_per_wave, q * 32 + 32) - q * 32;
+                    const int B0 = b0 >> 3;
+                    const int B1 = (q * 32 + b1 >= p.c_out) ? 4 : (b1 >> 3);
+                    if (ox < p.ow && oy < p.oh && oz < p.od) {
+                        uint32_t* o = p.out_packed +
+                                      ((((size_t)here.n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
+                        const uint32_t mk = pos_w | neg_w;
+                        const uint32_t sg = neg_w & ~pos_w;
+                        if (B0 == 0 && B1 == 4) {
+                            o[q] = mk;
+                            o[p.wd_out + q] = sg;
+                        } else {
+                            for (int B = B0; B < B1; ++B) {
+                                reinterpret_cast<uint8_t*>(o + q)[B] = (uint8_t)(mk >> (8 * B));
+                                reinterpret_cast<uint8_t*>(o + p.wd_out + q)[B] = (uint8_t)(sg >> (8 * B));
+                            }
+                        }
+                    }
+                    pos_w = neg_w = 0u;
+                }
+            } else {
+                const size_t cstride = (size_t)p.od * p.oh * p.ow;
+                if (ox < p.ow && oy < p.oh && oz < p.od) {
+                    int32_t* o = p.out_acc + (size_t)here.n * p.c_out * cstride + ((size_t)oz * p.oh + oy) * p.ow + ox;
+#pragma unroll
+                    for (int j = 0; j < CO_BLK; ++j)
+                        if (j < co_left) o[(size_t)(cb + j) * cstride] = d[0][j];
+                }
+            }
+        }
+        if (more) {
+            // the other buffer was last read before the barrier that ended the previous tile
+            store_items(lds + (b ^ 1) * buf_words, r);
+            __syncthreads();
+        }
+        here = next;
+    }
+}
+
 template <int WC, int V, int CO_BLK, bool PACKED, bool TP, bool DIG = false, bool BIN = false>
 int launch_variant(const ConvParams& p, const TileParams& t, size_t lds_bytes, dim3 grid,
                    int threads, hipStream_t s)
@@ -593,6 +834,14 @@ thread_local int g_co_per_wave = 0;  // 0 = choose, else channels per wave (mult
 thread_local int g_tap_split = 0;    // 0 = choose, else waves sharing the taps of one slice
 thread_local int g_point = 1;        // 0 = never use the pointwise kernel
 thread_local int g_lane_tile = 0;    // 0 = choose, else 100 * LX + LY lanes of a wave along x and y
+thread_local int g_stream = 0;       // 1 = persistent workgroups with prefetched halo tiles where they apply
+// plan of this thread's most recent convolution launch (tern_last_launch)
+thread_local int32_t g_last[8] = {-1, 0, 0, 0, 0, 0, 0, 0};
+void note_launch(int kind, int v, int cb, int nks, int threads, unsigned gx, unsigned gy, size_t lds)
+{
+    g_last[0] = kind; g_last[1] = v; g_last[2] = cb; g_last[3] = nks; g_last[4] = threads;
+    g_last[5] = (int32_t)gx; g_last[6] = (int32_t)gy; g_last[7] = (int32_t)lds;
+}
 
 // Tile plan for a voxel depth V per lane and a wave of 2^lxb x 2^lyb x (64 / 2^(lxb + lyb)) lanes;
 // returns false if no halo tile fits in LDS.  Single-plane outputs need lxb + lyb = 6.
@@ -672,10 +921,15 @@ void set_co_per_wave(int v) { g_co_per_wave = (v > 0 && v % 16 == 0) ? v : 0; }
 void set_tap_split(int v) { g_tap_split = (v == 1 || v == 2 || v == 4 || v == 8) ? v : 0; }
 void set_pointwise(int v) { g_point = v ? 1 : 0; }
 void set_lane_tile(int v) { g_lane_tile = v; }
+void set_stream(int v) { g_stream = v ? 1 : 0; }
+void last_launch(int32_t* info) { for (int i = 0; i < 8; ++i) info[i] = g_last[i]; }
 
 int launch_conv3d(const ConvParams& p_in, hipStream_t s)
 {
-    if (g_point && !p_in.digits && !p_in.binary && conv_point_applies(p_in)) return launch_conv_point(p_in, s);
+    if (g_point && !p_in.digits && !p_in.binary && conv_point_applies(p_in)) {
+        note_launch(TERN_KERNEL_POINTWISE, 0, 0, 0, 0, 0, 0, 0);
+        return launch_conv_point(p_in, s);
+    }
     ConvParams p = p_in;
     const bool packed = p.out_packed != nullptr;
     // A kernel of depth extent 1 with unit depth stride and no depth padding treats every input
@@ -833,7 +1087,10 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
     int64_t lds_bytes = 0;
     if (!plan_tiles(p, V, lds_limit, t, lds_bytes, lxb, lyb)) {
         if (V == 4 && plan_tiles(p, 2, lds_limit, t, lds_bytes, lxb, lyb)) V = 2;
-        else return launch_conv3d_generic(p, s);
+        else {
+            note_launch(TERN_KERNEL_DIRECT, 0, 0, 0, 0, 0, 0, 0);
+            return launch_conv3d_generic(p, s);
+        }
     }
     const int64_t spatial_tiles = (int64_t)t.tiles_x * t.tiles_y * t.tiles_z * p.n;
     if (spatial_tiles > 0x7fffffff) return TERN_ESHAPE;
@@ -899,6 +1156,31 @@ int launch_conv3d(const ConvParams& p_in, hipStream_t s)
         if (flat_trips < deep_trips) t.flat = 1;
     }
     const size_t lb = (size_t)lds_bytes;
+    // Persistent form: four-wave workgroups, one per (SIMD, wave slot) of the chip, each walking
+    // a run of tiles with the next halo tile prefetched under the current tile's arithmetic.
+    if (g_stream && V == 1 && co_blk == 32 && !tp && !p.digits && nks == 1 && grid_y == 1 && threads == 256 &&
+        (int64_t)t.hx * t.hy * t.hz * t.nchunk <= (int64_t)kStreamItems * threads && 2 * lds_bytes <= 64 * 1024) {
+        const int resident = 4 * compute_units_of_current_device();
+        if (resident > 0 && spatial_tiles >= 2 * (int64_t)resident) {
+            t.tiles_per_wg = (int32_t)((spatial_tiles + resident - 1) / resident);
+            const unsigned wgs = (unsigned)((spatial_tiles + t.tiles_per_wg - 1) / t.tiles_per_wg);
+            // at least a fifth of a compute unit's LDS per workgroup, so that no unit takes five
+            size_t sb = 2 * lb;
+            if (sb < 33 * 1024) sb = 33 * 1024;
+#define TERN_LAUNCH_S(WC_, BIN_)                                                                          \
+    do {                                                                                                  \
+        if (packed) hipLaunchKernelGGL((conv_tiled_stream_kernel<WC_, 32, true, BIN_>), dim3(wgs), dim3(threads), sb, s, p, t);   \
+        else hipLaunchKernelGGL((conv_tiled_stream_kernel<WC_, 32, false, BIN_>), dim3(wgs), dim3(threads), sb, s, p, t);        \
+    } while (0)
+            if (p.binary) { if (p.wc == 2) TERN_LAUNCH_S(2, true); else TERN_LAUNCH_S(1, true); }
+            else { if (p.wc == 2) TERN_LAUNCH_S(2, false); else TERN_LAUNCH_S(1, false); }
+#undef TERN_LAUNCH_S
+            TERN_HIP_CHECK(hipGetLastError());
+            note_launch(TERN_KERNEL_PERSISTENT, 1, 32, 1, threads, wgs, 1, sb);
+            return TERN_OK;
+        }
+    }
+    note_launch(TERN_KERNEL_TILED, V, co_blk, nks, threads, grid.x, grid.y, lb);
 #define TERN_LAUNCH(WC_, V_, CB_, TP_)                                                       \
     (packed ? launch_variant<WC_, V_, CB_, true, TP_>(p, t, lb, grid, threads, s)            \
             : launch_variant<WC_, V_, CB_, false, TP_>(p, t, lb, grid, threads, s))

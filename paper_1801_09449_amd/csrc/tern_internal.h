@@ -154,6 +154,8 @@ void set_co_per_wave(int v);
 void set_tap_split(int v);
 void set_lane_tile(int v);
 void set_pointwise(int v);
+void set_stream(int v);
+void last_launch(int32_t* info);
 int launch_pack_filters(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,
                         int32_t kw, uint32_t* bank, hipStream_t s);
 int launch_pack_filters_binary(const int8_t* w, int32_t c_out, int32_t c_in, int32_t kd, int32_t kh,

@@ -150,6 +150,11 @@ def test_null_and_bad_arguments_are_rejected_before_launch(T):
     assert L.tern_set_option(99, 0) == -3
     assert L.tern_set_option(3, 24) == -3
     assert L.tern_set_option(3, 0) == 0
+    assert L.tern_set_option(8, 2) == -3 and L.tern_set_option(8, 1) == 0 and L.tern_set_option(8, 0) == 0
+    # plan query: nothing launched by this thread yet
+    info = (C.c_int32 * 8)()
+    assert L.tern_last_launch(None) == -1
+    assert L.tern_last_launch(info) == 0 and info[0] == -1
     for bad in (1, 303, 101, 102, 1608, 816, -2):      # wave shapes: powers of two up to 8, at least 4 lanes per plane
         assert L.tern_set_option(7, bad) == -3
     for good in (808, 408, 202, 401, -1, 0):

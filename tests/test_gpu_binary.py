@@ -175,6 +175,18 @@ def test_binary_kernel_variants(G):
         T.tern_set_option(1, 0); T.tern_set_option(3, 0); T.tern_set_option(5, 0)
 
 
+def test_binary_persistent_workgroups(G):
+    """The persistent form of the tiled kernel on binary filters, at config[1]'s shape."""
+    import paper_1801_09449_amd as T
+    c = synth.conv_case("cfg1_binary", 1, 64, 64, 64, p0_w=0.0, p0_a=0.0, seed=5, thr_range=(-24, 24))
+    T.tern_set_option(8, 1)
+    try:
+        check_binary(G, c)
+        assert T.tern_last_launch()["kernel"] == T.KERNEL_PERSISTENT
+    finally:
+        T.tern_set_option(8, 0)
+
+
 def test_binary_oversized_halo_takes_the_direct_kernel(G):
     check_binary(G, binary_case("fallback", 1, 40, 33, (20, 21, 22), k=3, stride=1, pad=60, dil=60, seed=449))
 
