@@ -183,14 +183,24 @@ def extras(T, synth, dev, case, act_i8, act, bank, lo, hi, out_acc, out_packed, 
     ex = {}
     ms_acc, _ = timed(lambda: T.tern_conv3d(act, c_in, bank, c_out, out=out_acc, **geom), 50, 5, None)
     ex["cfg1_conv3d_int32_out_ms"] = ms_acc
-    # the persistent-workgroup form of the fused kernel (tuning option 8, off by default)
-    T.tern_set_option(8, 1)
-    try:
-        ms_pw, _ = timed(lambda: T.tern_conv3d(act, c_in, bank, c_out, thr_lo=lo, thr_hi=hi, out=out_packed, **geom),
-                         50, 5, None)
-    finally:
-        T.tern_set_option(8, 0)
-    ex["cfg1_conv3d_persistent_workgroups_ms"] = ms_pw
+    # the persistent-workgroup form of the tiled kernel (tuning option 8, off by default) beside
+    # the default launch, on the shapes it applies to
+    c4d1 = [c for c in synth.config4_cases() if c.name == "cfg4_k3_d1_pw0.5"][0]
+    pw = {}
+    for name, c in (("cfg1", case), ("cfg4_k3_d1", c4d1),
+                    ("batch3_48cubed_32_to_64", synth.conv_case("pw_b", 3, 32, 64, 48, seed=8, p0_a=0.4))):
+        row = {}
+        for label, opt in (("default", 0), ("persistent", 1)):
+            T.tern_set_option(8, opt)
+            try:
+                f, a = conv_times(T, dev, c, steps=50, warmup=5)
+                row[label + "_kernel"] = T.tern_last_launch()["kernel"]
+            finally:
+                T.tern_set_option(8, 0)
+            row[label + "_fused_ms"] = f
+            row[label + "_int32_ms"] = a
+        pw[name] = row
+    ex["persistent_workgroups"] = pw
     ms_pack, _ = timed(lambda: T.tern_pack(act_i8, out=act), 50, 5, None)
     ex["cfg1_pack_i8_ms"] = ms_pack
     ex["cfg1_pack_i8_GBps"] = (act_i8.numel() + act.numel() * 4) / (ms_pack * 1e-3) / 1e9
