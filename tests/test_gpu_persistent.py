@@ -55,6 +55,15 @@ def test_persistent_kernel_ragged_tiles_and_runs_across_batch_items(G, persisten
     assert T.tern_last_launch()["kernel"] == T.KERNEL_PERSISTENT
 
 
+def test_persistent_kernel_on_a_stack_of_planes(G, persistent):
+    """Kernel depth 1 on a batch of single-plane inputs: the batch collapses into planes, a wave
+    covers 4 x 8 voxels in two planes, and four waves of a workgroup take four channel slices."""
+    T = persistent
+    check_case(G, synth.conv_case("pw_planes", 32, 128, 128, (1, 116, 84), k=(1, 3, 3), pad=0, seed=614, p0_a=0.4))
+    plan = T.tern_last_launch()
+    assert plan["kernel"] == T.KERNEL_PERSISTENT, sorted(plan.items())
+
+
 def test_option_leaves_ineligible_launches_to_the_other_kernels(G, persistent):
     """Too few tiles, channel counts that need several workgroups per tile, single taps: the
     option changes nothing there."""
