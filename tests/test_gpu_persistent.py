@@ -82,3 +82,33 @@ def test_default_launch_of_config1_is_one_workgroup_per_tile(G):
     plan = T.tern_last_launch()
     assert plan == {"kernel": T.KERNEL_TILED, "voxels_per_lane": 1, "channels_per_pass": 32, "tap_split": 1,
                     "threads": 256, "grid_x": 2048, "grid_y": 1, "lds_bytes": 6400}
+
+
+def test_tuning_options_belong_to_the_calling_thread(G):
+    """An override set by one host thread changes neither the plan nor the options of another."""
+    import threading
+    import torch
+    import paper_1801_09449_amd as T
+    c = synth.conv_case("thr", 1, 64, 64, (32, 64, 64), seed=615)
+    a = T.tern_pack(G.dev(c.act))
+    bank = T.tern_pack_filters(G.dev(c.wgt))
+    lo, hi = G.dev(c.lo), G.dev(c.hi)
+    run = lambda: T.tern_conv3d(a, 64, bank, 64, thr_lo=lo, thr_hi=hi)
+    plans = {}
+
+    def worker():
+        plans["before"] = T.tern_last_launch()["kernel"]     # nothing launched by this thread yet
+        plans["other"] = (run(), T.tern_last_launch())[1]
+
+    T.tern_set_option(3, 16)      # TERN_OPT_CO_BLOCK
+    try:
+        mine_forced = (run(), T.tern_last_launch())[1]
+        th = threading.Thread(target=worker)
+        th.start(); th.join()
+    finally:
+        T.tern_set_option(3, 0)
+    mine_default = (run(), T.tern_last_launch())[1]
+    torch.cuda.synchronize()
+    assert plans["before"] == -1
+    assert mine_forced["channels_per_pass"] == 16
+    assert plans["other"]["channels_per_pass"] == 32 and plans["other"] == mine_default
