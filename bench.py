@@ -40,7 +40,7 @@ NOMINAL_LANE_OPS = 256 * 64 * 2.4e9       # 39.32e12: one wave instruction per S
 # of the instructions of a config[1] wave are these.
 ISSUED_OPS_PER_MAC = 4.0 / 32.0
 # The method as the paper writes it needs five operations per word pair (and, xor, and, two
-# popcount-accumulates): the figure the survey's roofline is quoted on.
+# popcount-accumulates); kept as a secondary figure beside the issued-instruction count.
 ALGORITHMIC_OPS_PER_MAC = 5.0 / 32.0
 # HBM bytes per launch of the config[1] kernel: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by
 # a 256 MiB copy under the same counters (profiles/conv3d_fused_config1.md).  A profiler figure,
