@@ -88,6 +88,26 @@ def timed(fn, steps, warmup, stream_sync=None, settle_first=True):
     return ev0.elapsed_time(ev1) / steps, wall
 
 
+def graph_ms(fn, calls=20, reps=30):
+    """Milliseconds of GPU time per call with `calls` calls recorded into one HIP graph and the
+    graph replayed: what a launch costs without the binding's host work per call."""
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(calls):
+            fn()
+    settle(g.replay)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(reps):
+        g.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / reps / calls
+
+
 def per_launch(fn, count):
     """Milliseconds of `count` single launches, each bracketed by its own pair of events."""
     import torch
@@ -316,6 +336,16 @@ def config_rows(T, synth, dev, peak_issue):
         return r
 
     rows["config0"] = row(synth.config0(), steps=100)
+    # config[0] is shorter than the binding's host work per call: GPU time per launch from a
+    # replayed graph of 20 calls
+    c0 = synth.config0()
+    a0, b0 = T.tern_pack(dev(c0.act)), T.tern_pack_filters(dev(c0.wgt))
+    l0, h0 = dev(c0.lo), dev(c0.hi)
+    g0 = dict(k=c0.k, stride=c0.stride, pad=c0.pad, dil=c0.dil)
+    o0 = T.tern_conv3d(a0, 32, b0, 32, thr_lo=l0, thr_hi=h0, **g0)
+    rows["config0"]["fused_graph_replay_ms"] = round(
+        graph_ms(lambda: T.tern_conv3d(a0, 32, b0, 32, thr_lo=l0, thr_hi=h0, out=o0, **g0)), 5)
+    del a0, b0, o0
     f = synth.config2()
     layers = [T.FcnLayer(L["w"].shape[1], L["w"].shape[0], T.tern_pack_filters(dev(L["w"])),
                          dev(L["lo"]), dev(L["hi"]), L["k"], L["stride"], L["pad"], L["dil"])
@@ -324,7 +354,9 @@ def config_rows(T, synth, dev, peak_issue):
     ws = torch.empty((T.tern_fcn_workspace_bytes(x.shape, layers),), dtype=torch.uint8, device="cuda")
     out = T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws)
     ms_fcn, _ = timed(lambda: T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws, out=out), 30, 3)
+    ms_fcn_g = graph_ms(lambda: T.tern_fcn_forward(x, ilo, ihi, layers, workspace=ws, out=out), calls=5)
     rows["config2"] = {"gmac": round(f.macs / 1e9, 3), "fused_ms": round(ms_fcn, 5),
+                       "fused_graph_replay_ms": round(ms_fcn_g, 5),
                        "TMACs": round(f.macs / (ms_fcn * 1e-3) / 1e12, 2),
                        "what": "tern_fcn_forward: float input, Eq. 6, six fused layers"}
     del x, ws, out, layers
