@@ -233,6 +233,77 @@ __device__ __forceinline__ void conv_step(const ActChunk<WC> (&A0)[V], ActChunk<
     wcur = wnext;
 }
 
+// End of one accumulation pass: channels [cb, cb + CO_BLK) of a wave whose slice is [co_begin,
+// co_end).  PACKED: Eq. 6 in integer form, the decision bits collected in pos_w / neg_w until a
+// 32-channel word (or the slice) is complete, then stored; else the raw accumulators (NCDHW).
+// A lane's V voxels are (ox, oy, ozb + v), or (ox, oy + LY * v, ozb) for single-plane outputs.
+template <int V, int CO_BLK, bool PACKED>
+__device__ __forceinline__ void finish_pass(const int32_t (&d)[V][CO_BLK], const ConvParams& p, const TileParams& t,
+                                            int cb, int co_begin, int co_end, int n, int ox, int oy, int ozb, int LY,
+                                            uint32_t (&pos_w)[V], uint32_t (&neg_w)[V])
+{
+    const int co_left = co_end - cb;
+    if constexpr (PACKED) {
+        // Cut points of this block come through the scalar cache, a few channels at a time.
+        uint32_t pp[V], pn[V];
+        ternarise_pass<V, CO_BLK>(d, (scalar_ptr)(uintptr_t)p.lo, (scalar_ptr)(uintptr_t)p.hi, cb,
+                                  co_left, p.c_out, pp, pn);
+        const int sh = cb & 31;
+#pragma unroll
+        for (int v = 0; v < V; ++v) { pos_w[v] |= pp[v] << sh; neg_w[v] |= pn[v] << sh; }
+        const bool flush = ((cb + CO_BLK) & 31) == 0 || cb + CO_BLK >= co_end;
+        if (flush) {
+            // This wave's bits of word q are [b0, b1), whole bytes.  A wave that owns only part
+            // of the word stores that part (16- or 8-bit stores) so that the waves owning the
+            // rest can store theirs without a read-modify-write; the wave that owns the last
+            // existing channel of the word also stores the (zero) bytes behind it.
+            const int q = cb >> 5;
+            const int b0 = max(co_begin, q * 32) - q * 32;
+            const int b1 = min(co_begin + t.co_per_wave, q * 32 + 32) - q * 32;
+            const int B0 = b0 >> 3;
+            const int B1 = (q * 32 + b1 >= p.c_out) ? 4 : (b1 >> 3);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const int oz = t.vy ? ozb : ozb + v;
+                const int oyv = t.vy ? oy + LY * v : oy;
+                if (ox < p.ow && oyv < p.oh && oz < p.od) {
+                    uint32_t* o = p.out_packed +
+                                  ((((size_t)n * p.od + oz) * p.oh + oyv) * p.ow + ox) * 2u * p.wd_out;
+                    const uint32_t mk = pos_w[v] | neg_w[v];      // nonzero mask
+                    const uint32_t sg = neg_w[v] & ~pos_w[v];     // sign; +1 wins if lo > hi
+                    if (B0 == 0 && B1 == 4) {
+                        o[q] = mk;
+                        o[p.wd_out + q] = sg;
+                    } else if ((B0 & 1) == 0 && B1 - B0 == 2) {
+                        reinterpret_cast<uint16_t*>(o + q)[B0 >> 1] = (uint16_t)(mk >> (8 * B0));
+                        reinterpret_cast<uint16_t*>(o + p.wd_out + q)[B0 >> 1] = (uint16_t)(sg >> (8 * B0));
+                    } else {
+                        for (int B = B0; B < B1; ++B) {
+                            reinterpret_cast<uint8_t*>(o + q)[B] = (uint8_t)(mk >> (8 * B));
+                            reinterpret_cast<uint8_t*>(o + p.wd_out + q)[B] = (uint8_t)(sg >> (8 * B));
+                        }
+                    }
+                }
+                pos_w[v] = neg_w[v] = 0u;
+            }
+        }
+    } else {
+        const size_t cstride = (size_t)p.od * p.oh * p.ow;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int oz = t.vy ? ozb : ozb + v;
+            const int oyv = t.vy ? oy + LY * v : oy;
+            if (ox < p.ow && oyv < p.oh && oz < p.od) {
+                int32_t* o = p.out_acc + (size_t)n * p.c_out * cstride +
+                             ((size_t)oz * p.oh + oyv) * p.ow + ox;
+#pragma unroll
+                for (int j = 0; j < CO_BLK; ++j)
+                    if (j < co_left) o[(size_t)(cb + j) * cstride] = d[v][j];
+            }
+        }
+    }
+}
+
 template <int WC, int V, int CO_BLK, bool PACKED, bool TP, bool DIG = false, bool BIN = false>
 __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, TileParams t)
 {
@@ -513,66 +584,7 @@ __global__ __launch_bounds__(kMaxThreads) void conv_tiled_kernel(ConvParams p, T
         }
 
         // ---- epilogue ----------------------------------------------------------------------
-        const int co_left = co_end - cb;
-        if constexpr (PACKED) {
-            // Cut points of this block come through the scalar cache, a few channels at a time.
-            uint32_t pp[V], pn[V];
-            ternarise_pass<V, CO_BLK>(d, (scalar_ptr)(uintptr_t)p.lo, (scalar_ptr)(uintptr_t)p.hi, cb,
-                                      co_left, p.c_out, pp, pn);
-            const int sh = cb & 31;
-#pragma unroll
-            for (int v = 0; v < V; ++v) { pos_w[v] |= pp[v] << sh; neg_w[v] |= pn[v] << sh; }
-            const bool flush = ((cb + CO_BLK) & 31) == 0 || cb + CO_BLK >= co_end;
-            if (flush) {
-                // This wave's bits of word q are [b0, b1), whole bytes.  A wave that owns only part
-                // of the word stores that part (16- or 8-bit stores) so that the waves owning the
-                // rest can store theirs without a read-modify-write; the wave that owns the last
-                // existing channel of the word also stores the (zero) bytes behind it.
-                const int q = cb >> 5;
-                const int b0 = max(co_begin, q * 32) - q * 32;
-                const int b1 = min(co_begin + t.co_per_wave, q * 32 + 32) - q * 32;
-                const int B0 = b0 >> 3;
-                const int B1 = (q * 32 + b1 >= p.c_out) ? 4 : (b1 >> 3);
-#pragma unroll
-                for (int v = 0; v < V; ++v) {
-                    const int oz = t.vy ? ozb : ozb + v;
-                    const int oyv = t.vy ? oy + LY * v : oy;
-                    if (ox < p.ow && oyv < p.oh && oz < p.od) {
-                        uint32_t* o = p.out_packed +
-                                      ((((size_t)n * p.od + oz) * p.oh + oyv) * p.ow + ox) * 2u * p.wd_out;
-                        const uint32_t mk = pos_w[v] | neg_w[v];      // nonzero mask
-                        const uint32_t sg = neg_w[v] & ~pos_w[v];     // sign; +1 wins if lo > hi
-                        if (B0 == 0 && B1 == 4) {
-                            o[q] = mk;
-                            o[p.wd_out + q] = sg;
-                        } else if ((B0 & 1) == 0 && B1 - B0 == 2) {
-                            reinterpret_cast<uint16_t*>(o + q)[B0 >> 1] = (uint16_t)(mk >> (8 * B0));
-                            reinterpret_cast<uint16_t*>(o + p.wd_out + q)[B0 >> 1] = (uint16_t)(sg >> (8 * B0));
-                        } else {
-                            for (int B = B0; B < B1; ++B) {
-                                reinterpret_cast<uint8_t*>(o + q)[B] = (uint8_t)(mk >> (8 * B));
-                                reinterpret_cast<uint8_t*>(o + p.wd_out + q)[B] = (uint8_t)(sg >> (8 * B));
-                            }
-                        }
-                    }
-                    pos_w[v] = neg_w[v] = 0u;
-                }
-            }
-        } else {
-            const size_t cstride = (size_t)p.od * p.oh * p.ow;
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const int oz = t.vy ? ozb : ozb + v;
-                const int oyv = t.vy ? oy + LY * v : oy;
-                if (ox < p.ow && oyv < p.oh && oz < p.od) {
-                    int32_t* o = p.out_acc + (size_t)n * p.c_out * cstride +
-                                 ((size_t)oz * p.oh + oyv) * p.ow + ox;
-#pragma unroll
-                    for (int j = 0; j < CO_BLK; ++j)
-                        if (j < co_left) o[(size_t)(cb + j) * cstride] = d[v][j];
-                }
-            }
-        }
+        finish_pass<V, CO_BLK, PACKED>(d, p, t, cb, co_begin, co_end, n, ox, oy, ozb, LY, pos_w, neg_w);
         if (t.nks > 1) break;
     }
 }
@@ -718,7 +730,7 @@ __global__ __launch_bounds__(256) void conv_tiled_stream_kernel(ConvParams p, Ti
         const int oy = here.oy0 + wy * LY + ly;
         const int oz = here.oz0 + wz * LZ + lz;
 
-        uint32_t pos_w = 0u, neg_w = 0u;
+        uint32_t pos_w[V] = {0u}, neg_w[V] = {0u};
         for (int cb = co_begin; cb < co_end; cb += CO_BLK) {
             int32_t d[V][CO_BLK];
             {
@@ -751,47 +763,7 @@ __global__ __launch_bounds__(256) void conv_tiled_stream_kernel(ConvParams p, Ti
                     else d[0][j] = acc_m[0][j] - 2 * acc_n[0][j];
                 }
             }
-            const int co_left = co_end - cb;
-            if constexpr (PACKED) {
-                uint32_t pp[V], pn[V];
-                ternarise_pass<V, CO_BLK>(d, (scalar_ptr)(uintptr_t)p.lo, (scalar_ptr)(uintptr_t)p.hi, cb,
-                                          co_left, p.c_out, pp, pn);
-                const int sh = cb & 31;
-                pos_w |= pp[0] << sh; neg_w |= pn[0] << sh;
-                const bool flush = ((cb + CO_BLK) & 31) == 0 || cb + CO_BLK >= co_end;
-                if (flush) {
-                    // whole bytes [B0, B1) of word q belong to this wave (see the kernel above)
-                    const int q = cb >> 5;
-                    const int b0 = max(co_begin, q * 32) - q * 32;
-                    const int b1 = min(co_begin + t.co_per_wave, q * 32 + 32) - q * 32;
-                    const int B0 = b0 >> 3;
-                    const int B1 = (q * 32 + b1 >= p.c_out) ? 4 : (b1 >> 3);
-                    if (ox < p.ow && oy < p.oh && oz < p.od) {
-                        uint32_t* o = p.out_packed +
-                                      ((((size_t)here.n * p.od + oz) * p.oh + oy) * p.ow + ox) * 2u * p.wd_out;
-                        const uint32_t mk = pos_w | neg_w;
-                        const uint32_t sg = neg_w & ~pos_w;
-                        if (B0 == 0 && B1 == 4) {
-                            o[q] = mk;
-                            o[p.wd_out + q] = sg;
-                        } else {
-                            for (int B = B0; B < B1; ++B) {
-                                reinterpret_cast<uint8_t*>(o + q)[B] = (uint8_t)(mk >> (8 * B));
-                                reinterpret_cast<uint8_t*>(o + p.wd_out + q)[B] = (uint8_t)(sg >> (8 * B));
-                            }
-                        }
-                    }
-                    pos_w = neg_w = 0u;
-                }
-            } else {
-                const size_t cstride = (size_t)p.od * p.oh * p.ow;
-                if (ox < p.ow && oy < p.oh && oz < p.od) {
-                    int32_t* o = p.out_acc + (size_t)here.n * p.c_out * cstride + ((size_t)oz * p.oh + oy) * p.ow + ox;
-#pragma unroll
-                    for (int j = 0; j < CO_BLK; ++j)
-                        if (j < co_left) o[(size_t)(cb + j) * cstride] = d[0][j];
-                }
-            }
+            finish_pass<V, CO_BLK, PACKED>(d, p, t, cb, co_begin, co_end, here.n, ox, oy, oz, LY, pos_w, neg_w);
         }
         if (more) {
             // the other buffer was last read before the barrier that ended the previous tile
