@@ -50,30 +50,49 @@ ALGORITHMIC_BYTES_CFG1 = 8.42e6
 SETTLE_MS = 40.0                          # GPU work in front of every timed region (clocks settle)
 
 
-def settle(fn, min_ms=SETTLE_MS):
-    """Run fn back to back for at least min_ms of GPU time, whatever --warmup says.  After an idle
-    period (input generation on the host) the shader clock takes about 15 ms of load to come
-    back: config[1] launches take 101 us at first and 91 us from the 150th on; a pause of a
-    millisecond does not undo that, one of 20 ms does.  A 2 ms timed region right after an idle
-    period measures that ramp, not the kernel.  Bursts of 100 launches with a synchronisation
-    between them: the pauses are tens of microseconds, and the launch queue stays short."""
+def settle(fn, min_ms=SETTLE_MS, max_ms=400.0):
+    """Run fn back to back until its time per launch has stopped falling: at least min_ms of GPU
+    time, whatever --warmup says, then on until four bursts in a row agree within 1 % (or max_ms).
+    After an idle period (input generation on the host) the shader clock comes back over tens of
+    milliseconds of load: config[1] launches take 101 us at first, 95 us after 45 ms on some
+    boxes, 88-91 us from then on; a pause of a millisecond does not undo that, one of 20 ms does.
+    A 2 ms timed region right after an idle period measures that ramp, not the kernel.  Bursts of
+    50 launches with a synchronisation between them: the pauses are tens of microseconds, and the
+    launch queue stays short."""
     import torch
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    total = 0.0
-    while total < min_ms:
+    total, per = 0.0, []
+    while total < max_ms:
         ev0.record()
-        for _ in range(100):
+        for _ in range(50):
             fn()
         ev1.record()
         torch.cuda.synchronize()
-        total += ev0.elapsed_time(ev1)
+        t = ev0.elapsed_time(ev1)
+        total += t
+        per.append(t)
+        if total >= min_ms and len(per) >= 4 and max(per[-4:]) <= 1.01 * min(per[-4:]):
+            break
+    return total
 
 
 def timed(fn, steps, warmup, stream_sync=None, settle_first=True):
     """Average milliseconds per call by events on the current stream, plus wall time."""
     import torch
     if settle_first:
-        settle(fn)
+        timed.last_settle_ms = settle(fn)
+        # One rehearsal of the timed region itself (synchronise, event, the same number of
+        # launches, event, synchronise), not counted: the first such region of a process has
+        # measured 5-40 us per launch longer than every later one (the host falls behind the GPU
+        # once while the queue is still empty), which a 20-launch region cannot absorb.
+        torch.cuda.synchronize()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        r0.record()
+        for _ in range(steps):
+            fn()
+        r1.record()
+        torch.cuda.synchronize()
+        r0.elapsed_time(r1)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -455,6 +474,7 @@ def main():
         T.tern_conv3d(act, c_in, bank, c_out, thr_lo=lo, thr_hi=hi, out=out_packed, **geom)
 
     ms, wall_ms = timed(step, args.steps, args.warmup)
+    settle_ms = timed.last_settle_ms
     singles = per_launch(step, max(10, min(args.steps, 200)))
     macs = case.macs
     tmacs = macs / (ms * 1e-3) / 1e12
@@ -486,7 +506,8 @@ def main():
         "dtype": "u32 bit-planes, int32 accumulate", "data": "synthetic",
         "config": {"workload": "config[1]: fused ternary conv3d, N=1, C_in=C_out=64, 64^3, k=3^3, "
                                "s=1, p=1, packed in -> packed out", "gmac": macs / 1e9,
-                   "wall_ms_per_step": wall_ms, "settle_ms_before_timing": SETTLE_MS},
+                   "wall_ms_per_step": wall_ms, "settle_ms_before_timing": round(settle_ms, 1),
+                   "settle_rule": "at least %g ms, then until four bursts of 50 launches agree within 1 %% (at most 400 ms)" % SETTLE_MS},
         "launch_ms": {"mean": ms, "median": statistics.median(singles), "min": min(singles),
                       "single_launches": len(singles)},
         "roofline": {
